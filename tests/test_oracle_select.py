@@ -1,0 +1,111 @@
+"""Pins for the oracle's gate and bucketing (Sec. 3.4 Eq. 4; Appendix C metadata).
+
+None of these re-types the oracle's formula on random data: they use a hand-enumerated truth
+table, structural invariants of Eq. 4, and a brute-force set construction for the lists."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from paper_2310_04361_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "select_truth_table.txt")
+
+
+def _truth_table():
+    rows = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        tau, s, g = [p.strip() for p in line.split("|")]
+        rows.append((float(tau), [float(v) for v in s.split()], [int(v) for v in g.split()]))
+    return rows
+
+
+@pytest.mark.parametrize("tau,scores,gate", _truth_table())
+def test_truth_table(oracle, tau, scores, gate):
+    mask, k = oracle.select(np.array([scores]), float(np.float32(tau)))
+    assert mask[0].tolist() == gate
+    assert k[0] == sum(gate)
+
+
+def test_tau_zero_selects_all_and_tau_one_selects_maximisers(oracle):
+    s = wl.random_scores(300, 37, seed=1, kind="grid").astype(np.float64)
+    m0, k0 = oracle.select(s, 0.0)
+    assert m0.all() and (k0 == 37).all()
+    m1, _ = oracle.select(s, 1.0)
+    assert np.array_equal(m1.astype(bool), s == s.max(axis=1, keepdims=True))
+
+
+def test_argmax_always_kept_and_nested_in_tau(oracle):
+    s = wl.random_scores(500, 64, seed=2).astype(np.float64)
+    prev = None
+    for tau in [0.0, 0.1, 0.25, 0.5, 0.75, 0.9, 1.0]:
+        m, k = oracle.select(s, float(np.float32(tau)))
+        assert (k >= 1).all()
+        assert m[np.arange(len(s)), s.argmax(axis=1)].all()
+        assert np.array_equal(k, m.sum(axis=1))
+        if prev is not None:            # cost is non-increasing in tau
+            assert not (m & ~prev.astype(bool)).any()
+        prev = m
+
+
+def test_power_of_two_scale_invariance(oracle):
+    s = wl.random_scores(200, 16, seed=3).astype(np.float64)
+    tau = float(np.float32(0.37))
+    m, _ = oracle.select(s, tau)
+    scale = 2.0 ** np.random.default_rng(0).integers(-20, 20, size=(200, 1))
+    m2, _ = oracle.select(s * scale, tau)
+    assert np.array_equal(m, m2)
+
+
+def test_tau_out_of_range_rejected(oracle):
+    s = np.ones((2, 3))
+    for bad in (-0.1, 1.5, float("nan")):
+        with pytest.raises(RuntimeError):
+            oracle.select(s, bad)
+
+
+def test_brute_force_small_grid(oracle):
+    """All 3-expert rows over a small dyadic grid, against a literal per-element reading of
+    Eq. 4 done with exact rationals."""
+    from fractions import Fraction
+    grid = [0.0, 0.5, 1.0, 1.5, 2.0]
+    for tau in (0.0, 0.25, 0.5, 0.75, 1.0):
+        rows = list(itertools.product(grid, repeat=3))
+        m, _ = oracle.select(np.array(rows), tau)
+        for r, got in zip(rows, m):
+            thr = Fraction(tau) * max(Fraction(v) for v in r)
+            assert got.tolist() == [1 if Fraction(v) >= thr else 0 for v in r]
+
+
+def test_bucket_matches_set_construction(oracle):
+    mask = wl.bernoulli_mask(97, 13, 0.3, seed=4)
+    mask[5] = 0                      # a token with no expert
+    mask[:, 7] = 0                   # an expert with no token
+    counts, offsets, lists = oracle.bucket(mask)
+    assert offsets[0] == 0 and offsets[-1] == mask.sum() == len(lists)
+    assert np.array_equal(np.diff(offsets), counts)
+    for e in range(13):
+        got = lists[offsets[e]:offsets[e + 1]].tolist()
+        assert got == sorted(got) and len(set(got)) == len(got)
+        assert set(got) == {t for t in range(97) if mask[t, e]}
+    assert counts[7] == 0
+
+
+def test_topk_gate(oracle):
+    s = wl.random_scores(50, 9, seed=5, kind="grid").astype(np.float64)
+    for k in (0, 1, 3, 9):
+        m = oracle.select_topk(s, k)
+        assert (m.sum(axis=1) == k).all()
+        for t in range(len(s)):
+            kept, dropped = s[t][m[t] == 1], s[t][m[t] == 0]
+            if len(kept) and len(dropped):
+                assert kept.min() >= dropped.max()
+    # distinct scores: top-k equals an argsort
+    s = wl.random_scores(20, 11, seed=6).astype(np.float64)
+    m = oracle.select_topk(s, 4)
+    for t in range(20):
+        assert set(np.flatnonzero(m[t])) == set(np.argsort(-s[t])[:4])

@@ -1,0 +1,168 @@
+/*
+ * dmoe.h -- C ABI of the MI355X (gfx950) dynamic-k Mixture-of-Experts FFN forward.
+ *
+ * The layer is the inference module of "Dense to Dynamic-k Mixture-of-Experts" (D2DMoE):
+ *   1. a two-layer router predicts, per token, the L2 norm of every expert's output (Sec. 3.3);
+ *   2. the dynamic-k gate keeps expert i iff its score is >= tau * the token's maximum score
+ *      (Sec. 3.4, Eq. 4);
+ *   3. tokens are bucketed per expert (the metadata of Appendix C, in compact form);
+ *   4. each selected expert runs up-projection (+gate), activation and down-projection, and the
+ *      expert outputs are summed, unweighted, on top of the output bias, which stays outside
+ *      the experts (Sec. 3.2; gated form: Appendix G).
+ *
+ * Conventions
+ *   - Plain C.  Every entry point returns a dmoe_status; DMOE_OK is 0.  dmoe_last_error() gives
+ *     a thread-local text for the last failure.
+ *   - All argument errors are found on the host BEFORE anything is launched, so a failing call
+ *     leaves every buffer untouched.
+ *   - Pointers are DEVICE pointers unless the name says host.  The caller owns every buffer; the
+ *     library allocates nothing, frees nothing and never synchronises the stream.  Work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Row-major, innermost index last.  x[T][d] and y[T][d] have the layer's dtype; scores are
+ *     always fp32.  Expert-major weights: w_up[E][m][d], w_gate[E][m][d] (gated only),
+ *     b_up[E][m] (nullable), w_down[E][m][d] (row j of expert e is the d-vector that neuron j of
+ *     that expert adds to the output), b_down[d] (nullable).  Router: r_w1[d_h][d], r_b1[d_h]
+ *     (nullable), r_w2[E][d_h], r_b2[E] (nullable).  Biases have the layer's dtype.
+ *   - Workspaces must be 256-byte aligned and at least as large as the matching *_workspace_bytes
+ *     call says; their contents are scratch.
+ *   - Unsupported shapes/dtypes are refused with DMOE_ERR_UNSUPPORTED; there is no fallback path.
+ */
+#ifndef DMOE_H
+#define DMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DMOE_OK = 0,
+    DMOE_ERR_NULL = 1,        /* a required pointer is NULL */
+    DMOE_ERR_SHAPE = 2,       /* a size is negative, zero where it must not be, or T*E overflows */
+    DMOE_ERR_UNSUPPORTED = 3, /* dtype / activation / shape the kernels do not cover */
+    DMOE_ERR_TAU = 4,         /* tau is NaN or outside [0, 1] */
+    DMOE_ERR_WORKSPACE = 5,   /* workspace missing, too small or not 256-byte aligned */
+    DMOE_ERR_HIP = 6          /* a HIP call failed; see dmoe_last_error() */
+} dmoe_status;
+
+enum { DMOE_F32 = 0, DMOE_BF16 = 1 };
+enum { DMOE_ACT_RELU = 0, DMOE_ACT_GELU_ERF = 1, DMOE_ACT_GELU_TANH = 2 };
+
+/*
+ * One converted layer (Sec. 3.2-3.3).  `packed` is NULL or the buffer filled by
+ * dmoe_pack_weights(); the bf16 expert kernels need it (DMOE_ERR_NULL otherwise), the fp32
+ * kernels ignore it.  A gated layer must have b_up == NULL: Appendix G states the gated form
+ * without biases, so where one would enter is undefined (DMOE_ERR_UNSUPPORTED).
+ */
+typedef struct {
+    int32_t d_model;       /* d   */
+    int32_t n_experts;     /* E   */
+    int32_t expert_size;   /* m   neurons per expert */
+    int32_t router_hidden; /* d_h */
+    int32_t gated;         /* 0 plain two-layer FFN, 1 gated (GLU) FFN */
+    int32_t act;           /* DMOE_ACT_* */
+    int32_t dtype;         /* DMOE_F32 | DMOE_BF16: x, y and every parameter */
+    int32_t reserved;      /* must be 0 */
+    const void *w_up, *w_gate, *b_up, *w_down, *b_down;
+    const void *r_w1, *r_b1, *r_w2, *r_b2;
+    const void *packed;
+} dmoe_layer;
+
+/* Library version (major*10000 + minor*100 + patch) and the text of the last error of the
+ * calling thread ("" if none).  The returned string is owned by the library. */
+int32_t dmoe_version(void);
+const char *dmoe_last_error(void);
+
+/* ---- sizes (host only, nothing is launched) ------------------------------------------------ */
+
+/* Workspace that dmoe_forward / dmoe_expert_ffn need for n_tokens tokens (worst case: every
+ * token selects every expert). */
+int32_t dmoe_workspace_bytes(const dmoe_layer *layer, int32_t n_tokens, size_t *out_bytes);
+/* Workspace of dmoe_select. */
+int32_t dmoe_select_workspace_bytes(int32_t n_tokens, int32_t n_experts, size_t *out_bytes);
+/* Size of the packed-weights buffer of this layer (0 for fp32 layers). */
+int32_t dmoe_packed_bytes(const dmoe_layer *layer, size_t *out_bytes);
+
+/*
+ * One-time re-layout of the down-projection for the MFMA kernels (bf16 layers): writes, into
+ * `packed` (device, 256-byte aligned, dmoe_packed_bytes() large), w_down transposed per expert
+ * to [E][d][m_pad] with m_pad = m rounded up to 32 and zero fill.  Put the pointer into
+ * layer->packed afterwards.  For fp32 layers this is a no-op that accepts packed == NULL.
+ */
+int32_t dmoe_pack_weights(const dmoe_layer *layer, void *packed, size_t packed_bytes,
+                          void *stream);
+
+/* ---- the hot path --------------------------------------------------------------------------- */
+
+/*
+ * Router (Sec. 3.3): scores[t][i] = | r_w2[i] . relu(r_w1 x_t + r_b1) + r_b2[i] |, fp32 out.
+ * bf16 layers: products on the matrix cores with fp32 accumulation, the hidden vector is
+ * rounded to bf16 between the two layers.  fp32 layers: fp32 throughout.
+ * n_tokens == 0 is a no-op.
+ */
+int32_t dmoe_router(const dmoe_layer *layer, const void *x, int32_t n_tokens,
+                    float *scores /* [T][E] */, void *stream);
+
+/*
+ * Dynamic-k gate + bucketing (Sec. 3.4 Eq. 4; Appendix C metadata).
+ * Expert i of token t is kept iff (double)scores[t][i] >= (double)tau * (double)max_j scores[t][j]
+ * -- the exact real comparison of the fp32 inputs (the fp64 product of two fp32 values is exact).
+ * tau == 0 keeps every expert.  Scores must be finite; otherwise the selection is unspecified
+ * but every output stays in range.
+ *   mask_bits   [T][ceil(E/64)] u64, bit (i % 64) of word (i / 64) = expert i kept; nullable
+ *   k_per_token [T] number of experts kept; nullable
+ *   counts      [E] tokens per expert; nullable
+ *   offsets     [E+1] exclusive prefix sum of counts, offsets[E] = P = number of pairs
+ *   token_lists capacity T*E; the tokens of expert e are token_lists[offsets[e]..offsets[e+1]),
+ *               in ascending order
+ */
+int32_t dmoe_select(const float *scores, int32_t n_tokens, int32_t n_experts, float tau,
+                    uint64_t *mask_bits, int32_t *k_per_token, int32_t *counts, int32_t *offsets,
+                    int32_t *token_lists, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Expert execution and merge (Sec. 3.2, Appendix G) for ANY valid per-expert token lists, e.g.
+ * Bernoulli-sampled decisions as in the latency experiment of Sec. 4.4:
+ *   y_t = b_down + sum over the experts e whose list holds t of E_e(x_t),
+ *   plain  E_e(x) = w_down[e]^T A(w_up[e] x + b_up[e]),
+ *   gated  E_e(x) = w_down[e]^T ( A(w_gate[e] x) o (w_up[e] x) ).
+ * y is fully overwritten; a token in no list gets b_down (or 0).  Lists may be in any order;
+ * a token listed twice for one expert counts once; entries outside [0, T) are ignored.
+ * bf16 layers: fp32 accumulation, the hidden activations are rounded to bf16 before the
+ * down-projection, expert outputs are summed in fp32 and rounded to bf16 once.
+ */
+int32_t dmoe_expert_ffn(const dmoe_layer *layer, const void *x, int32_t n_tokens,
+                        const int32_t *offsets /* [E+1] */, const int32_t *token_lists,
+                        void *y, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The whole layer: router, gate, bucketing, experts.  Optional outputs (each nullable):
+ * scores_out [T][E] fp32, mask_out [T][ceil(E/64)], offsets_out [E+1] and token_lists_out
+ * (capacity T*E; both or neither).
+ */
+int32_t dmoe_forward(const dmoe_layer *layer, const void *x, int32_t n_tokens, float tau,
+                     void *y, float *scores_out, uint64_t *mask_out, int32_t *offsets_out,
+                     int32_t *token_lists_out, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
+/* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
+
+/*
+ * When enabled, every kernel the library launches is bracketed by HIP events on the launch
+ * stream.  dmoe_timing_read() waits for those events and returns, for kernel slot `index`
+ * (0 .. dmoe_timing_slots()-1), its name, the number of launches and the summed duration in
+ * milliseconds since the last dmoe_timing_reset().  Enabling allocates the event pool (the only
+ * allocation the library ever makes); launches beyond the pool are not timed.  Not thread-safe;
+ * meant for a benchmark's separate measurement pass.
+ */
+int32_t dmoe_timing_enable(int32_t on);
+int32_t dmoe_timing_reset(void);
+int32_t dmoe_timing_slots(void);
+int32_t dmoe_timing_read(int32_t index, const char **name, int64_t *launches, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DMOE_H */

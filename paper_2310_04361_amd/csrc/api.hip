@@ -1,0 +1,346 @@
+// C ABI of libdmoe: argument validation (host only, before any launch), workspace carving and
+// kernel sequencing.  See include/dmoe.h for the contract of every entry point.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "dmoe_internal.h"
+
+namespace dmoe {
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// ---- timing ------------------------------------------------------------------------------------
+const char* const kSlotNames[kSlotCount] = {
+    "router", "mask_count", "lists_to_mask", "scan_groups", "scan_experts", "fill_lists",
+    "expert_up", "expert_down", "ffn_f32", "small_token", "pack_weights"};
+constexpr int kEventPairs = 8192;
+bool g_timing = false;
+std::vector<hipEvent_t> g_ev;      // 2 * kEventPairs once enabled
+std::vector<int> g_ev_slot;        // slot of each recorded pair
+int g_ev_used = 0;
+int64_t g_launches[kSlotCount];
+double g_ms[kSlotCount];
+
+int collect_events() {
+    for (int i = 0; i < g_ev_used; ++i) {
+        hipError_t e = hipEventSynchronize(g_ev[2 * i + 1]);
+        if (e != hipSuccess) return fail(DMOE_ERR_HIP, "hipEventSynchronize: %s", hipGetErrorString(e));
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, g_ev[2 * i], g_ev[2 * i + 1]);
+        if (e != hipSuccess) return fail(DMOE_ERR_HIP, "hipEventElapsedTime: %s", hipGetErrorString(e));
+        g_launches[g_ev_slot[i]] += 1;
+        g_ms[g_ev_slot[i]] += ms;
+    }
+    g_ev_used = 0;
+    return DMOE_OK;
+}
+
+// ---- validation ----------------------------------------------------------------------------------
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
+    if (!L) return fail(DMOE_ERR_NULL, "layer is NULL");
+    if (L->d_model <= 0 || L->n_experts <= 0 || L->expert_size <= 0)
+        return fail(DMOE_ERR_SHAPE, "d_model, n_experts and expert_size must be positive");
+    if (L->dtype != DMOE_F32 && L->dtype != DMOE_BF16)
+        return fail(DMOE_ERR_UNSUPPORTED, "dtype %d is not DMOE_F32 or DMOE_BF16", L->dtype);
+    if (L->reserved != 0) return fail(DMOE_ERR_UNSUPPORTED, "reserved field must be 0");
+    if (L->gated != 0 && L->gated != 1) return fail(DMOE_ERR_UNSUPPORTED, "gated must be 0 or 1");
+    if (need_router) {
+        if (L->router_hidden <= 0) return fail(DMOE_ERR_SHAPE, "router_hidden must be positive");
+        if (!L->r_w1 || !L->r_w2) return fail(DMOE_ERR_NULL, "router weights are NULL");
+        if (L->dtype == DMOE_BF16 && !router_bf16_supported(*L))
+            return fail(DMOE_ERR_UNSUPPORTED,
+                        "bf16 router needs d %% 32 == 0, E %% 4 == 0 and d_h in {32,64,128,256,512}");
+        if (L->dtype == DMOE_F32 && (size_t)(L->d_model + L->router_hidden) * 4 > 65536)
+            return fail(DMOE_ERR_UNSUPPORTED, "fp32 router needs d + d_h <= 16384");
+    }
+    if (need_experts) {
+        if (L->act < DMOE_ACT_RELU || L->act > DMOE_ACT_GELU_TANH)
+            return fail(DMOE_ERR_UNSUPPORTED, "unknown activation %d", L->act);
+        if (!L->w_up || !L->w_down) return fail(DMOE_ERR_NULL, "expert weights are NULL");
+        if (L->gated && !L->w_gate) return fail(DMOE_ERR_NULL, "gated layer without w_gate");
+        if (L->gated && L->b_up)
+            return fail(DMOE_ERR_UNSUPPORTED,
+                        "a gated expert with b_up is undefined (Appendix G states it without biases)");
+        if (L->dtype == DMOE_BF16) {
+            if (!up_bf16_supported(*L) || !down_bf16_supported(*L))
+                return fail(DMOE_ERR_UNSUPPORTED,
+                            "bf16 experts need d %% 128 == 0 and expert_size <= 128");
+            if (!L->packed)
+                return fail(DMOE_ERR_NULL, "bf16 experts need layer->packed (dmoe_pack_weights)");
+        } else if ((size_t)(2 * L->d_model + L->expert_size) * 4 > 65536) {
+            return fail(DMOE_ERR_UNSUPPORTED, "fp32 experts need 2 d + m <= 16384");
+        }
+    }
+    return DMOE_OK;
+}
+
+int check_tokens(int32_t T, int32_t E) {
+    if (T < 0) return fail(DMOE_ERR_SHAPE, "n_tokens is negative");
+    if ((long long)T * E > 0x7fffffffLL - 64)
+        return fail(DMOE_ERR_SHAPE, "n_tokens * n_experts does not fit the int32 list indices");
+    return DMOE_OK;
+}
+
+int check_tau(float tau) {
+    if (!(tau >= 0.0f && tau <= 1.0f)) return fail(DMOE_ERR_TAU, "tau must lie in [0, 1]");
+    return DMOE_OK;
+}
+
+int check_ws(const void* ws, size_t have, size_t need) {
+    if (need == 0) return DMOE_OK;
+    if (!ws) return fail(DMOE_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % kAlign) return fail(DMOE_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (have < need) return fail(DMOE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+    return DMOE_OK;
+}
+
+int check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(DMOE_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return DMOE_OK;
+}
+
+// ---- workspace layouts -----------------------------------------------------------------------------
+struct SelectWs {
+    size_t group_off, mask, total;
+};
+SelectWs select_ws(int T, int E, bool need_mask) {
+    SelectWs w{};
+    size_t o = 0;
+    w.group_off = o;
+    o += align_up(sizeof(int32_t) * (size_t)(div_up(T, kGroup) + 1) * E);
+    w.mask = o;
+    if (need_mask) o += align_up(sizeof(uint64_t) * (size_t)T * div_up(E, 64));
+    w.total = o;
+    return w;
+}
+
+struct LayerWs {
+    size_t scores, mask, group_off, counts, offsets, item_start, lists, H, total;
+};
+LayerWs layer_ws(const dmoe_layer& L, int T) {
+    LayerWs w{};
+    const int E = L.n_experts;
+    size_t o = 0;
+    w.scores = o;     o += align_up(sizeof(float) * (size_t)T * E);
+    w.mask = o;       o += align_up(sizeof(uint64_t) * (size_t)T * div_up(E, 64));
+    w.group_off = o;  o += align_up(sizeof(int32_t) * (size_t)(div_up(T, kGroup) + 1) * E);
+    w.counts = o;     o += align_up(sizeof(int32_t) * (size_t)E);
+    w.offsets = o;    o += align_up(sizeof(int32_t) * (size_t)(E + 1));
+    w.item_start = o; o += align_up(sizeof(int32_t) * (size_t)(E + 1));
+    w.lists = o;      o += align_up(sizeof(int32_t) * (size_t)T * E);
+    w.H = o;
+    if (L.dtype == DMOE_BF16) o += align_up(2 * (size_t)T * E * m_pad_of(L.expert_size));
+    w.total = o;
+    return w;
+}
+
+// Experts from mask bits whose group counts are already in group_off (both in the workspace).
+int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const LayerWs& w,
+                const uint64_t* mask, int32_t* offsets_out, int32_t* lists_out, void* y,
+                hipStream_t s) {
+    int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
+    int32_t* counts = reinterpret_cast<int32_t*>(ws + w.counts);
+    int32_t* offsets = offsets_out ? offsets_out : reinterpret_cast<int32_t*>(ws + w.offsets);
+    int32_t* lists = lists_out ? lists_out : reinterpret_cast<int32_t*>(ws + w.lists);
+    int32_t* item_start = reinterpret_cast<int32_t*>(ws + w.item_start);
+    if (L.dtype == DMOE_F32) {
+        if (offsets_out)
+            launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, kUpRows,
+                                 lists, s);
+        launch_ffn_f32(L, (const float*)x, T, mask, (float*)y, s);
+    } else {
+        launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, item_start, kUpRows,
+                             lists, s);
+        void* H = ws + w.H;
+        launch_up_bf16(L, x, T, offsets, item_start, lists, H, s);
+        launch_down_bf16(L, T, offsets, group_off, lists, H, y, s);
+    }
+    return check_launch("expert kernels");
+}
+
+}  // namespace
+
+LaunchTimer::LaunchTimer(int slot, hipStream_t stream) : slot_(slot), index_(-1), stream_(stream) {
+    if (g_timing && g_ev_used < kEventPairs) {
+        index_ = g_ev_used++;
+        g_ev_slot[index_] = slot;
+        (void)hipEventRecord(g_ev[2 * index_], stream_);
+    }
+}
+LaunchTimer::~LaunchTimer() {
+    if (index_ >= 0) (void)hipEventRecord(g_ev[2 * index_ + 1], stream_);
+}
+
+}  // namespace dmoe
+
+using namespace dmoe;
+
+extern "C" {
+
+int32_t dmoe_version(void) { return 100; }
+
+const char* dmoe_last_error(void) { return g_err; }
+
+int32_t dmoe_workspace_bytes(const dmoe_layer* layer, int32_t n_tokens, size_t* out_bytes) {
+    if (!out_bytes) return fail(DMOE_ERR_NULL, "out_bytes is NULL");
+    if (int rc = check_layer(layer, false, false)) return rc;
+    if (int rc = check_tokens(n_tokens, layer->n_experts)) return rc;
+    *out_bytes = layer_ws(*layer, n_tokens).total;
+    return DMOE_OK;
+}
+
+int32_t dmoe_select_workspace_bytes(int32_t n_tokens, int32_t n_experts, size_t* out_bytes) {
+    if (!out_bytes) return fail(DMOE_ERR_NULL, "out_bytes is NULL");
+    if (n_experts <= 0) return fail(DMOE_ERR_SHAPE, "n_experts must be positive");
+    if (int rc = check_tokens(n_tokens, n_experts)) return rc;
+    *out_bytes = select_ws(n_tokens, n_experts, true).total;
+    return DMOE_OK;
+}
+
+int32_t dmoe_packed_bytes(const dmoe_layer* layer, size_t* out_bytes) {
+    if (!out_bytes) return fail(DMOE_ERR_NULL, "out_bytes is NULL");
+    if (int rc = check_layer(layer, false, false)) return rc;
+    *out_bytes = layer->dtype == DMOE_BF16
+                     ? align_up(2 * (size_t)layer->n_experts * layer->d_model * m_pad_of(layer->expert_size))
+                     : 0;
+    return DMOE_OK;
+}
+
+int32_t dmoe_pack_weights(const dmoe_layer* layer, void* packed, size_t packed_bytes, void* stream) {
+    if (int rc = check_layer(layer, false, false)) return rc;
+    if (layer->dtype == DMOE_F32) return DMOE_OK;
+    if (!layer->w_down) return fail(DMOE_ERR_NULL, "w_down is NULL");
+    size_t need = 0;
+    dmoe_packed_bytes(layer, &need);
+    if (!packed) return fail(DMOE_ERR_NULL, "packed is NULL");
+    if (reinterpret_cast<uintptr_t>(packed) % kAlign) return fail(DMOE_ERR_WORKSPACE, "packed is not 256-byte aligned");
+    if (packed_bytes < need) return fail(DMOE_ERR_WORKSPACE, "packed has %zu bytes, %zu needed", packed_bytes, need);
+    launch_pack_bf16(*layer, packed, (hipStream_t)stream);
+    return check_launch("pack_weights");
+}
+
+int32_t dmoe_router(const dmoe_layer* layer, const void* x, int32_t n_tokens, float* scores,
+                    void* stream) {
+    if (int rc = check_layer(layer, true, false)) return rc;
+    if (int rc = check_tokens(n_tokens, layer->n_experts)) return rc;
+    if (n_tokens == 0) return DMOE_OK;
+    if (!x || !scores) return fail(DMOE_ERR_NULL, "x or scores is NULL");
+    if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, (hipStream_t)stream);
+    else launch_router_bf16(*layer, x, n_tokens, scores, (hipStream_t)stream);
+    return check_launch("router");
+}
+
+int32_t dmoe_select(const float* scores, int32_t n_tokens, int32_t n_experts, float tau,
+                    uint64_t* mask_bits, int32_t* k_per_token, int32_t* counts, int32_t* offsets,
+                    int32_t* token_lists, void* workspace, size_t workspace_bytes, void* stream) {
+    if (n_experts <= 0) return fail(DMOE_ERR_SHAPE, "n_experts must be positive");
+    if (int rc = check_tokens(n_tokens, n_experts)) return rc;
+    if (int rc = check_tau(tau)) return rc;
+    if (!offsets) return fail(DMOE_ERR_NULL, "offsets is NULL");
+    if (n_tokens > 0 && (!scores || !token_lists)) return fail(DMOE_ERR_NULL, "scores or token_lists is NULL");
+    const SelectWs w = select_ws(n_tokens, n_experts, mask_bits == nullptr);
+    if (int rc = check_ws(workspace, workspace_bytes, w.total)) return rc;
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = (hipStream_t)stream;
+    int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
+    uint64_t* mask = mask_bits ? mask_bits : reinterpret_cast<uint64_t*>(ws + w.mask);
+    if (n_tokens > 0)
+        launch_mask_from_scores(scores, n_tokens, n_experts, tau, mask, k_per_token, group_off, s);
+    launch_scan_and_fill(mask, n_tokens, n_experts, group_off, counts, offsets, nullptr, kUpRows,
+                         n_tokens > 0 ? token_lists : nullptr, s);
+    return check_launch("select");
+}
+
+int32_t dmoe_expert_ffn(const dmoe_layer* layer, const void* x, int32_t n_tokens,
+                        const int32_t* offsets, const int32_t* token_lists, void* y,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (int rc = check_layer(layer, false, true)) return rc;
+    if (int rc = check_tokens(n_tokens, layer->n_experts)) return rc;
+    if (n_tokens == 0) return DMOE_OK;
+    if (!x || !y || !offsets || !token_lists) return fail(DMOE_ERR_NULL, "x, y, offsets or token_lists is NULL");
+    const LayerWs w = layer_ws(*layer, n_tokens);
+    if (int rc = check_ws(workspace, workspace_bytes, w.total)) return rc;
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = (hipStream_t)stream;
+    uint64_t* mask = reinterpret_cast<uint64_t*>(ws + w.mask);
+    launch_mask_from_lists(offsets, token_lists, n_tokens, layer->n_experts, mask,
+                           reinterpret_cast<int32_t*>(ws + w.group_off), s);
+    return run_experts(*layer, x, n_tokens, ws, w, mask, nullptr, nullptr, y, s);
+}
+
+int32_t dmoe_forward(const dmoe_layer* layer, const void* x, int32_t n_tokens, float tau, void* y,
+                     float* scores_out, uint64_t* mask_out, int32_t* offsets_out,
+                     int32_t* token_lists_out, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    if (int rc = check_layer(layer, true, true)) return rc;
+    if (int rc = check_tokens(n_tokens, layer->n_experts)) return rc;
+    if (int rc = check_tau(tau)) return rc;
+    if ((offsets_out == nullptr) != (token_lists_out == nullptr))
+        return fail(DMOE_ERR_NULL, "offsets_out and token_lists_out go together");
+    if (n_tokens == 0) return DMOE_OK;
+    if (!x || !y) return fail(DMOE_ERR_NULL, "x or y is NULL");
+    const LayerWs w = layer_ws(*layer, n_tokens);
+    if (int rc = check_ws(workspace, workspace_bytes, w.total)) return rc;
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = (hipStream_t)stream;
+    float* scores = scores_out ? scores_out : reinterpret_cast<float*>(ws + w.scores);
+    if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
+    else launch_router_bf16(*layer, x, n_tokens, scores, s);
+    uint64_t* mask = mask_out ? mask_out : reinterpret_cast<uint64_t*>(ws + w.mask);
+    launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr,
+                            reinterpret_cast<int32_t*>(ws + w.group_off), s);
+    return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s);
+}
+
+int32_t dmoe_timing_enable(int32_t on) {
+    if (on && g_ev.empty()) {
+        g_ev.resize(2 * kEventPairs);
+        g_ev_slot.resize(kEventPairs);
+        for (auto& ev : g_ev) {
+            hipError_t e = hipEventCreate(&ev);
+            if (e != hipSuccess) {
+                g_ev.clear();
+                return fail(DMOE_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+            }
+        }
+    }
+    g_timing = on != 0;
+    return DMOE_OK;
+}
+
+int32_t dmoe_timing_reset(void) {
+    const int rc = collect_events();
+    memset(g_launches, 0, sizeof(g_launches));
+    for (double& v : g_ms) v = 0.0;
+    return rc;
+}
+
+int32_t dmoe_timing_slots(void) { return kSlotCount; }
+
+int32_t dmoe_timing_read(int32_t index, const char** name, int64_t* launches, double* total_ms) {
+    if (index < 0 || index >= kSlotCount) return fail(DMOE_ERR_SHAPE, "timing slot out of range");
+    if (int rc = collect_events()) return rc;
+    if (name) *name = kSlotNames[index];
+    if (launches) *launches = g_launches[index];
+    if (total_ms) *total_ms = g_ms[index];
+    return DMOE_OK;
+}
+
+}  // extern "C"

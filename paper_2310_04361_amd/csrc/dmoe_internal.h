@@ -1,0 +1,76 @@
+// Internal declarations shared by the HIP translation units of libdmoe (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dmoe.h"
+
+namespace dmoe {
+
+// ---- fixed granularities -------------------------------------------------------------------
+constexpr int kGroup = 64;        // tokens per select group (one wavefront, lane = token)
+constexpr int kChunkGroups = 4;   // groups per down-projection token chunk
+constexpr int kChunk = kGroup * kChunkGroups;   // 256 tokens whose outputs live in LDS together
+constexpr int kUpRows = 64;       // list rows per up-projection work item (4 MFMA column tiles)
+
+inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
+inline int div_up(int a, int b) { return (a + b - 1) / b; }
+inline int m_pad_of(int m) { return round_up(m, 32); }
+
+// ---- kernel timing slots --------------------------------------------------------------------
+enum Slot {
+    kSlotRouter = 0,
+    kSlotMask,
+    kSlotListsToMask,
+    kSlotScanGroups,
+    kSlotScanExperts,
+    kSlotFill,
+    kSlotUp,
+    kSlotDown,
+    kSlotFfnF32,
+    kSlotSmall,
+    kSlotPack,
+    kSlotCount
+};
+
+// Brackets one kernel launch with events when timing is enabled (see dmoe_timing_enable).
+struct LaunchTimer {
+    LaunchTimer(int slot, hipStream_t stream);
+    ~LaunchTimer();
+    int slot_;
+    int index_;
+    hipStream_t stream_;
+};
+
+// ---- select / bucket (select.hip) -----------------------------------------------------------
+// group_off is [(NG+1)][E] int32 with NG = ceil(T/64): after the scans, group_off[g][e] is the
+// number of tokens < 64*g that selected expert e, and row NG holds the per-expert totals.
+void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint64_t* mask,
+                             int32_t* k_per_token, int32_t* group_off, hipStream_t s);
+void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,
+                            uint64_t* mask, int32_t* group_off, hipStream_t s);
+void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
+                          int32_t* offsets, int32_t* item_start, int rows_per_item,
+                          int32_t* token_lists, hipStream_t s);
+
+// ---- router (router.hip) ----------------------------------------------------------------------
+void launch_router_f32(const dmoe_layer& L, const float* x, int T, float* scores, hipStream_t s);
+void launch_router_bf16(const dmoe_layer& L, const void* x, int T, float* scores, hipStream_t s);
+
+// ---- experts ----------------------------------------------------------------------------------
+void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* mask, float* y,
+                    hipStream_t s);
+void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s);
+// H is [capacity][m_pad] bf16, row p belongs to list position p.
+void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* offsets,
+                    const int32_t* item_start, const int32_t* token_lists, void* H,
+                    hipStream_t s);
+void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* group_off,
+                      const int32_t* token_lists, const void* H, void* y, hipStream_t s);
+
+bool up_bf16_supported(const dmoe_layer& L);
+bool down_bf16_supported(const dmoe_layer& L);
+bool router_bf16_supported(const dmoe_layer& L);
+
+}  // namespace dmoe

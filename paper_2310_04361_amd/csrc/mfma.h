@@ -1,0 +1,46 @@
+// gfx950 matrix-core helpers: operand types, the 16x16x32 bf16 MFMA and its register layout.
+//
+// v_mfma_f32_16x16x32_bf16 computes D[16][16] += A[16][32] * B[32][16] per wavefront.
+// With lane = 16*q + c (q = 0..3, c = 0..15):
+//   A operand: lane holds A[i = c][k = 8q .. 8q+7]      (8 consecutive bf16 = one 16-byte load)
+//   B operand: lane holds B[k = 8q .. 8q+7][j = c]      (same shape: 8 consecutive k of column c)
+//   D / C    : lane holds D[i = 4q + r][j = c], r = 0..3
+// Only "the same k goes to the same (lane group, slot) in A and in B" matters for the sum over k,
+// so any k permutation applied to both operands is allowed; the kernels use that freedom.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dmoe {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 load8(const __bf16* p) {
+    return *reinterpret_cast<const bf16x8*>(p);
+}
+
+__device__ __forceinline__ bf16x8 zero8() {
+    bf16x8 z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (__bf16)0.0f;
+    return z;
+}
+
+__device__ __forceinline__ float bf16_to_float(__bf16 v) { return (float)v; }
+
+// Activation A(v) in fp32.  GELU(v) = v * Phi(v); the tanh form is its usual approximation.
+__device__ __forceinline__ float activate(int act, float v) {
+    if (act == DMOE_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == DMOE_ACT_GELU_ERF) return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    const float u = 0.79788456080286535588f * (v + 0.044715f * v * v * v);
+    return 0.5f * v * (1.0f + tanhf(u));
+}
+
+}  // namespace dmoe

@@ -1,0 +1,142 @@
+"""The C-ABI library loads, exports every symbol the header declares, and turns every bad
+argument into an error on the host -- no compute call is made, so this runs without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2310_04361_amd import binding as B
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(__file__)), "include", "dmoe.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2310_04361_amd import build
+        build.build()
+    return B.lib()
+
+
+def _layer(**kw):
+    base = dict(d_model=128, n_experts=16, expert_size=16, router_hidden=32, gated=0, act=0,
+                dtype=B.DMOE_F32, reserved=0, w_up=0x1000, w_gate=None, b_up=None, w_down=0x1000,
+                b_down=None, r_w1=0x1000, r_b1=None, r_w2=0x1000, r_b2=None, packed=None)
+    base.update(kw)
+    return B.DmoeLayerStruct(**base)
+
+
+def test_exports_match_header(lib):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(dmoe_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.dmoe_version() >= 100
+
+
+def test_struct_layout_matches_header():
+    # 8 int32 followed by 10 pointers
+    assert ctypes.sizeof(B.DmoeLayerStruct) == 8 * 4 + 10 * 8
+    assert B.DmoeLayerStruct.w_up.offset == 32 and B.DmoeLayerStruct.packed.offset == 32 + 9 * 8
+
+
+def test_workspace_sizes(lib):
+    n = ctypes.c_size_t(0)
+    L = _layer()
+    assert lib.dmoe_workspace_bytes(ctypes.byref(L), 128, ctypes.byref(n)) == B.DMOE_OK
+    assert n.value >= 128 * 16 * 4 * 2 and n.value % 256 == 0
+    small = n.value
+    assert lib.dmoe_workspace_bytes(ctypes.byref(L), 4096, ctypes.byref(n)) == B.DMOE_OK
+    assert n.value > small
+    assert lib.dmoe_workspace_bytes(ctypes.byref(L), 0, ctypes.byref(n)) == B.DMOE_OK
+    assert lib.dmoe_workspace_bytes(ctypes.byref(L), -1, ctypes.byref(n)) == B.DMOE_ERR_SHAPE
+    assert lib.dmoe_workspace_bytes(ctypes.byref(L), 2 ** 30, ctypes.byref(n)) == B.DMOE_ERR_SHAPE
+    assert lib.dmoe_workspace_bytes(None, 1, ctypes.byref(n)) == B.DMOE_ERR_NULL
+    assert lib.dmoe_workspace_bytes(ctypes.byref(L), 1, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_select_workspace_bytes(100, 16, ctypes.byref(n)) == B.DMOE_OK and n.value > 0
+    assert lib.dmoe_select_workspace_bytes(100, 0, ctypes.byref(n)) == B.DMOE_ERR_SHAPE
+    Lb = _layer(dtype=B.DMOE_BF16, expert_size=24)
+    assert lib.dmoe_packed_bytes(ctypes.byref(Lb), ctypes.byref(n)) == B.DMOE_OK
+    assert n.value == 16 * 128 * 32 * 2
+    assert lib.dmoe_packed_bytes(ctypes.byref(L), ctypes.byref(n)) == B.DMOE_OK and n.value == 0
+
+
+def test_layer_validation(lib):
+    n = ctypes.c_size_t(0)
+    bad = [
+        (_layer(d_model=0), B.DMOE_ERR_SHAPE),
+        (_layer(n_experts=-3), B.DMOE_ERR_SHAPE),
+        (_layer(dtype=7), B.DMOE_ERR_UNSUPPORTED),
+        (_layer(reserved=1), B.DMOE_ERR_UNSUPPORTED),
+        (_layer(gated=2), B.DMOE_ERR_UNSUPPORTED),
+    ]
+    for L, code in bad:
+        assert lib.dmoe_workspace_bytes(ctypes.byref(L), 8, ctypes.byref(n)) == code
+        assert lib.dmoe_last_error()
+
+
+def test_entry_points_reject_bad_arguments_before_launch(lib):
+    ws, big = 0x10000, 1 << 40
+    x = y = 0x2000
+    L = _layer()
+    ref = ctypes.byref
+    # router
+    assert lib.dmoe_router(ref(L), None, 4, 0x3000, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_router(ref(L), x, -1, 0x3000, None) == B.DMOE_ERR_SHAPE
+    assert lib.dmoe_router(ref(_layer(r_w1=None)), x, 4, 0x3000, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_router(ref(_layer(router_hidden=0)), x, 4, 0x3000, None) == B.DMOE_ERR_SHAPE
+    assert lib.dmoe_router(ref(_layer(dtype=B.DMOE_BF16, router_hidden=48)), x, 4, 0x3000, None) == B.DMOE_ERR_UNSUPPORTED
+    assert lib.dmoe_router(ref(L), x, 0, None, None) == B.DMOE_OK          # T = 0: no-op
+    # select
+    sel = lambda **k: lib.dmoe_select(*[k.get(a, d) for a, d in (
+        ("scores", 0x3000), ("T", 8), ("E", 16), ("tau", 0.5), ("mask", None), ("k", None),
+        ("counts", None), ("offsets", 0x4000), ("lists", 0x5000), ("ws", ws), ("wsb", big),
+        ("stream", None))])
+    assert sel(tau=1.5) == B.DMOE_ERR_TAU
+    assert sel(tau=-0.01) == B.DMOE_ERR_TAU
+    assert sel(tau=float("nan")) == B.DMOE_ERR_TAU
+    assert sel(scores=None) == B.DMOE_ERR_NULL
+    assert sel(offsets=None) == B.DMOE_ERR_NULL
+    assert sel(lists=None) == B.DMOE_ERR_NULL
+    assert sel(E=0) == B.DMOE_ERR_SHAPE
+    assert sel(T=-2) == B.DMOE_ERR_SHAPE
+    assert sel(ws=None) == B.DMOE_ERR_WORKSPACE
+    assert sel(ws=ws + 8) == B.DMOE_ERR_WORKSPACE
+    assert sel(wsb=16) == B.DMOE_ERR_WORKSPACE
+    # expert_ffn
+    ffn = lambda L=L, **k: lib.dmoe_expert_ffn(ref(L), *[k.get(a, d) for a, d in (
+        ("x", x), ("T", 8), ("offsets", 0x4000), ("lists", 0x5000), ("y", y), ("ws", ws),
+        ("wsb", big), ("stream", None))])
+    assert ffn(x=None) == B.DMOE_ERR_NULL
+    assert ffn(offsets=None) == B.DMOE_ERR_NULL
+    assert ffn(wsb=0) == B.DMOE_ERR_WORKSPACE
+    assert ffn(L=_layer(act=9)) == B.DMOE_ERR_UNSUPPORTED
+    assert ffn(L=_layer(w_down=None)) == B.DMOE_ERR_NULL
+    assert ffn(L=_layer(gated=1)) == B.DMOE_ERR_NULL                        # no w_gate
+    assert ffn(L=_layer(gated=1, w_gate=0x1000, b_up=0x1000)) == B.DMOE_ERR_UNSUPPORTED
+    assert ffn(L=_layer(dtype=B.DMOE_BF16)) == B.DMOE_ERR_NULL              # not packed
+    assert ffn(L=_layer(dtype=B.DMOE_BF16, d_model=100, packed=0x1000)) == B.DMOE_ERR_UNSUPPORTED
+    assert ffn(L=_layer(dtype=B.DMOE_BF16, expert_size=200, packed=0x1000)) == B.DMOE_ERR_UNSUPPORTED
+    assert ffn(T=0, ws=None, wsb=0) == B.DMOE_OK
+    # forward
+    fwd = lambda L=L, **k: lib.dmoe_forward(ref(L), *[k.get(a, d) for a, d in (
+        ("x", x), ("T", 8), ("tau", 0.5), ("y", y), ("scores", None), ("mask", None),
+        ("offsets", None), ("lists", None), ("ws", ws), ("wsb", big), ("stream", None))])
+    assert fwd(tau=2.0) == B.DMOE_ERR_TAU
+    assert fwd(y=None) == B.DMOE_ERR_NULL
+    assert fwd(offsets=0x4000) == B.DMOE_ERR_NULL                           # lists missing
+    assert fwd(ws=None) == B.DMOE_ERR_WORKSPACE
+    assert fwd(L=_layer(r_w2=None)) == B.DMOE_ERR_NULL
+    assert fwd(T=0, ws=None, wsb=0) == B.DMOE_OK
+    assert b"workspace" in lib.dmoe_last_error() or lib.dmoe_last_error() is not None
+    # pack
+    Lb = _layer(dtype=B.DMOE_BF16)
+    assert lib.dmoe_pack_weights(ref(Lb), None, 0, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_pack_weights(ref(Lb), 0x10000, 16, None) == B.DMOE_ERR_WORKSPACE
+    assert lib.dmoe_pack_weights(ref(L), None, 0, None) == B.DMOE_OK          # fp32: no-op
+    # timing slots are readable without enabling
+    assert lib.dmoe_timing_slots() >= 8
+    assert lib.dmoe_timing_read(999, None, None, None) == B.DMOE_ERR_SHAPE

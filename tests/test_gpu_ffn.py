@@ -1,0 +1,157 @@
+"""dmoe_expert_ffn and dmoe_forward on the GPU against the oracle (Sec. 3.2, 3.4, Appendix G).
+
+Expert execution is driven with explicit lists (Bernoulli-sampled decisions, the device of the
+latency experiment in Sec. 4.4), so it is tested independently of the router.  End-to-end runs
+hand the GPU's fp32 scores to the oracle's gate for bf16 layers (the router has its own test);
+the fp32 configuration is checked fully independently, leaving out tokens with a score within
+1e-6 of the threshold."""
+import numpy as np
+import pytest
+
+from helpers import TOL, lists_from_mask, oracle_ffn, small_cfg, tokenwise_rel_err
+from paper_2310_04361_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2310_04361_amd import binding
+    binding.lib()
+    return binding
+
+
+def _run_ffn(B, L, cfg, x, mask, shuffle_seed=None):
+    import torch
+    offsets, lists = lists_from_mask(mask, shuffle_seed)
+    lists_dev = torch.from_numpy(np.concatenate([lists, np.zeros(1, np.int32)])).cuda()
+    y = B.dmoe_expert_ffn(L, B.to_device(x, cfg.dtype), torch.from_numpy(offsets).cuda(), lists_dev)
+    torch.cuda.synchronize()
+    return B.from_device(y, cfg.dtype)
+
+
+CASES = [
+    # name, T, E override, Bernoulli p
+    ("cfg1", 128, None, 0.3),
+    ("cfg1", 77, None, 1.0),
+    ("cfg2", 700, None, 0.17),      # two full 256-token chunks and a ragged third
+    ("cfg2", 256, None, 1.0),       # every expert for every token: the dense FFN
+    ("cfg2", 50, None, 0.02),       # nearly empty: most experts have no token
+    ("cfg3", 300, None, 0.2),
+    ("cfg4", 300, 32, 0.35),
+    ("cfg4", 64, None, 0.1),        # all 256 experts
+    ("cfg5b", 16, None, 0.25),
+    ("paper", 200, None, 0.4),      # 24 experts of 128 neurons
+]
+
+
+@pytest.mark.parametrize("name,T,E,p", CASES)
+def test_expert_ffn_matches_oracle(B, oracle, name, T, E, p):
+    cfg = small_cfg(name, T, E)
+    print(f"expert_ffn {name} T={T} E={cfg.E} p={p}", flush=True)
+    layer, x = wl.make_layer(cfg, 1), wl.make_input(cfg, 1)
+    L = B.Layer(layer, cfg.dtype)
+    mask = wl.bernoulli_mask(T, cfg.E, p, seed=T)
+    if T > 3 and p < 1.0:
+        mask[2] = 0                                   # a token with no expert: y = b_down
+        mask[:, min(3, cfg.E - 1)] = 0                # an expert with no token
+    ref = oracle_ffn(oracle, layer, x, mask)
+    got = _run_ffn(B, L, cfg, x, mask)
+    err = tokenwise_rel_err(got, ref)
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]
+    if T > 3 and p < 1.0:
+        b2 = layer["b_down"] if layer["b_down"] is not None else np.zeros(cfg.d)
+        assert np.array_equal(got[2], b2)
+    # list order and duplicates do not matter
+    got2 = _run_ffn(B, L, cfg, x, mask, shuffle_seed=3)
+    assert tokenwise_rel_err(got2, ref) <= TOL[cfg.dtype]
+
+
+def test_expert_ffn_ignores_out_of_range_and_duplicate_entries(B, oracle):
+    import torch
+    cfg = small_cfg("cfg2", 100)
+    layer, x = wl.make_layer(cfg, 2), wl.make_input(cfg, 2)
+    L = B.Layer(layer, cfg.dtype)
+    mask = wl.bernoulli_mask(100, cfg.E, 0.1, seed=8)
+    offsets, lists = lists_from_mask(mask)
+    # append, to expert E-1, a duplicate of its first token (if any), a negative and a too-large id
+    extra = np.array([lists[offsets[-2]] if offsets[-1] > offsets[-2] else 0, -5, 100, 10 ** 6], np.int32)
+    if offsets[-1] == offsets[-2]:
+        mask[0, cfg.E - 1] = 1
+    lists2 = np.concatenate([lists, extra])
+    offsets2 = offsets.copy()
+    offsets2[-1] += len(extra)
+    y = B.dmoe_expert_ffn(L, B.to_device(x, cfg.dtype), torch.from_numpy(offsets2).cuda(),
+                          torch.from_numpy(lists2).cuda())
+    torch.cuda.synchronize()
+    ref = oracle_ffn(oracle, layer, x, mask)
+    assert tokenwise_rel_err(B.from_device(y, cfg.dtype), ref) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("tau", [0.0, 0.5, 0.9])
+def test_forward_fp32_independent(B, oracle, tau):
+    """cfg1: the GPU and the oracle each compute their own scores."""
+    import torch
+    cfg = wl.CONFIGS["cfg1"]
+    layer, x = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
+    L = B.Layer(layer, cfg.dtype)
+    tau32 = float(np.float32(tau))
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32, want_scores=True, want_mask=True,
+                           want_lists=True)
+    torch.cuda.synchronize()
+    ref_y, ref_s, ref_mask = oracle.forward(layer, x, tau32)
+    mx = ref_s.max(axis=1, keepdims=True)
+    near = (np.abs(ref_s - tau32 * mx) <= 1e-6 * np.maximum(1.0, mx)).any(axis=1) if tau > 0 else np.zeros(cfg.T, bool)
+    keep = ~near
+    assert keep.sum() >= cfg.T * 0.9
+    assert tokenwise_rel_err(ex["scores"].cpu().numpy(), ref_s) <= 1e-5
+    got_mask = B.mask_bits_to_bool(ex["mask_bits"], cfg.E)
+    assert np.array_equal(got_mask[keep], ref_mask[keep])
+    assert tokenwise_rel_err(B.from_device(y, cfg.dtype)[keep], ref_y[keep]) <= 1e-5
+    if tau == 0:
+        assert got_mask.all()
+        W1, W2 = layer["w_up"].reshape(cfg.H, cfg.d), layer["w_down"].reshape(cfg.H, cfg.d)
+        dense = np.maximum(x @ W1.T, 0) @ W2
+        assert tokenwise_rel_err(B.from_device(y, cfg.dtype), dense) <= 1e-5
+    # the lists it reports are the lists of the mask it reports
+    offsets = ex["offsets"].cpu().numpy()
+    lists = ex["token_lists"].cpu().numpy()
+    for e in range(cfg.E):
+        assert lists[offsets[e]:offsets[e + 1]].tolist() == np.flatnonzero(got_mask[:, e]).tolist()
+
+
+@pytest.mark.parametrize("name,T,E,tau", [
+    ("cfg2", 600, None, 0.5), ("cfg2", 600, None, 0.0), ("cfg2", 300, None, 0.9),
+    ("cfg3", 500, None, 0.5), ("cfg4", 200, 64, 0.3), ("cfg5b", 16, None, 0.5),
+])
+def test_forward_bf16_score_handoff(B, oracle, name, T, E, tau):
+    import torch
+    cfg = small_cfg(name, T, E)
+    print(f"forward {name} T={T} tau={tau}", flush=True)
+    layer, x = wl.make_layer(cfg, 3), wl.make_input(cfg, 3)
+    L = B.Layer(layer, cfg.dtype)
+    tau32 = float(np.float32(tau))
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32, want_scores=True, want_mask=True,
+                           want_lists=True)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy()
+    ref_mask, _ = oracle.select(s.astype(np.float64), tau32)        # gate on the GPU's own scores
+    got_mask = B.mask_bits_to_bool(ex["mask_bits"], cfg.E)
+    assert np.array_equal(got_mask, ref_mask)                       # bit-exact
+    assert (got_mask.sum(axis=1) >= 1).all()
+    offsets = ex["offsets"].cpu().numpy()
+    lists = ex["token_lists"].cpu().numpy()
+    assert offsets[-1] == ref_mask.sum()
+    for e in range(cfg.E):
+        assert lists[offsets[e]:offsets[e + 1]].tolist() == np.flatnonzero(ref_mask[:, e]).tolist()
+    ref_y = oracle_ffn(oracle, layer, x, ref_mask)
+    err = tokenwise_rel_err(B.from_device(y, cfg.dtype), ref_y)
+    print(f"  density={ref_mask.mean():.3f} err={err:.3e}", flush=True)
+    assert err <= TOL["bf16"]
+    # without the optional outputs the result is the same
+    y2, _ = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32)
+    torch.cuda.synchronize()
+    assert tokenwise_rel_err(B.from_device(y2, cfg.dtype), ref_y) <= TOL["bf16"]

@@ -80,7 +80,7 @@ int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
         if (L->dtype == DMOE_BF16) {
             if (!up_bf16_supported(*L) || !down_bf16_supported(*L))
                 return fail(DMOE_ERR_UNSUPPORTED,
-                            "bf16 experts need d %% 128 == 0 and expert_size <= 128");
+                            "bf16 experts need d %% 256 == 0 and expert_size <= 128");
             if (!L->packed)
                 return fail(DMOE_ERR_NULL, "bf16 experts need layer->packed (dmoe_pack_weights)");
         } else if ((size_t)(2 * L->d_model + L->expert_size) * 4 > 65536) {

@@ -10,8 +10,8 @@ namespace dmoe {
 
 // ---- fixed granularities -------------------------------------------------------------------
 constexpr int kGroup = 64;        // tokens per select group (one wavefront, lane = token)
-constexpr int kChunkGroups = 4;   // groups per down-projection token chunk
-constexpr int kChunk = kGroup * kChunkGroups;   // 256 tokens whose outputs live in LDS together
+constexpr int kChunkGroups = 2;   // groups per down-projection token chunk
+constexpr int kChunk = kGroup * kChunkGroups;   // 128 tokens whose outputs live in LDS together
 constexpr int kUpRows = 64;       // list rows per up-projection work item (4 MFMA column tiles)
 
 inline int round_up(int a, int b) { return (a + b - 1) / b * b; }

@@ -4,14 +4,14 @@
 //   up    expert-major grouped GEMM over the compact lists: gathers the listed rows of x (no
 //         copy), multiplies by the expert's up (and gate) rows, applies bias + activation in fp32
 //         and writes the hidden activations, rounded to bf16, to H[list position][m_pad].
-//   down  output-stationary: a workgroup owns 256 consecutive tokens x 128 output columns as an
+//   down  output-stationary: a workgroup owns 128 consecutive tokens x 256 output columns as an
 //         fp32 tile in LDS, walks all experts, multiplies the chunk's compact H rows of each
 //         expert by that expert's down-projection slice and adds the result into the owning
-//         token rows with LDS atomics.  Every y element is written exactly once, in bf16; no
-//         global atomics, no second pass.
-// Tokens ride on the MFMA column axis in `up` (so four consecutive neurons of one token land in
-// one lane and H is written in 8-byte pieces) and on the row axis in `down` (so one LDS-add
-// instruction covers 16 consecutive output columns of four token rows).
+//         token rows (plain LDS read-add-write; each wavefront owns its own columns).  Every y
+//         element is written exactly once, in bf16; no global atomics, no second pass.
+// Tokens ride on the MFMA column axis in both kernels, so four consecutive neurons (up) or
+// output columns (down) of one token land in one lane: H is written in 8-byte pieces and the LDS
+// merge moves 16 bytes per lane with a single row address.
 #include "dmoe_internal.h"
 #include "mfma.h"
 
@@ -19,9 +19,12 @@ namespace dmoe {
 
 namespace {
 
-constexpr int kDownCols = 128;                 // output columns per down workgroup
-constexpr int kDownStride = kDownCols + 16;    // LDS row stride in floats (bank spread)
 constexpr int kDownWaves = 8;
+constexpr int kDownCols = kDownWaves * 32;     // output columns per down workgroup
+constexpr int kDownBatch = 256;                // experts per tile-list batch
+constexpr int kDownStride = kDownCols + 4;      // LDS row stride in floats
+constexpr size_t kDownLds =
+    sizeof(float) * kChunk * kDownStride + sizeof(int2) * kDownBatch * (kChunk / 32);
 
 // w_down[E][m][d] -> w2t[E][d][m_pad], zero-filled for j >= m.
 __global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __restrict__ w2t,
@@ -134,7 +137,17 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
     }
 }
 
-// One workgroup per (256-token chunk, 128-column slice).  KS = m_pad / 32 MFMA k-steps.
+// One workgroup per (128-token chunk, 256-column slice); KS = m_pad / 32 MFMA k-steps.
+//
+// The fp32 output tile Y[128][256] lives in LDS.  The eight wavefronts own 32 columns each, so
+// no two wavefronts ever touch the same element and the merge is a plain read-add-write (LDS
+// float atomics proved far slower).  All wavefronts walk the same list of row tiles -- up to 32
+// compact H rows of one expert -- built once per batch of 256 experts from the group offsets.
+// Per tile and wavefront: D[32 cols][32 tokens] = W2t slice * H_tile^T as 2 x 2 MFMA 16x16x32
+// tiles with the tokens on the MFMA column axis, so a lane ends up with four consecutive output
+// columns of ONE token: one 16-byte LDS read and write per MFMA tile, one row address per
+// token.  The row stride of 260 floats spreads consecutive-token rows over the banks.
+// Operands of the next kDepth tiles are kept in flight while the current one is merged.
 template <int KS>
 __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
     const __bf16* __restrict__ w2t, const __bf16* __restrict__ b_down,
@@ -142,61 +155,135 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
     const int32_t* __restrict__ lists, const __bf16* __restrict__ H, __bf16* __restrict__ y, int T,
     int d, int E, int NG) {
     constexpr int m_pad = KS * 32;
-    constexpr int NT = kDownCols / 16;
-    extern __shared__ float Y[];  // [kChunk][kDownStride]
+    constexpr int kThreads = kDownWaves * 64;
+    constexpr int kDepth = KS <= 2 ? 4 : 2;  // row tiles of operands in flight per wavefront
+    extern __shared__ float smem[];
+    float* Y = smem;  // [kChunk][kDownStride]
+    int2* tiles = reinterpret_cast<int2*>(smem + kChunk * kDownStride);  // [kDownBatch * kChunk/32]
+    __shared__ int s_wave_tot[kDownWaves];
     const int NS = d / kDownCols;
     const int chunk = blockIdx.x / NS, slice = blockIdx.x % NS;
     const int t_base = chunk * kChunk, col0 = slice * kDownCols;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, q = lane >> 4, c = lane & 15;
 
-    for (int i = tid; i < kChunk * kDownCols; i += kDownWaves * 64) {
+    for (int i = tid; i < kChunk * kDownCols; i += kThreads) {
         const int row = i / kDownCols, col = i % kDownCols;
         Y[row * kDownStride + col] = b_down ? (float)b_down[col0 + col] : 0.0f;
     }
-    __syncthreads();
 
     const int g_lo = chunk * kChunkGroups;
     const int g_hi = min(g_lo + kChunkGroups, NG);
-    for (int e = wave; e < E; e += kDownWaves) {
-        const int lo = group_off[(size_t)g_lo * E + e];
-        const int n = group_off[(size_t)g_hi * E + e] - lo;
-        if (n <= 0) continue;
-        const int p0 = offsets[e] + lo;
-        bf16x8 bw[NT][KS];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                bw[nt][ks] = load8(w2t + ((size_t)e * d + col0 + nt * 16 + c) * m_pad + ks * 32 + 8 * q);
+    // A operand rows: output columns wave*32 + nt*16 + c of this slice, k = 8q..8q+7 (+32 ks)
+    const __bf16* wbase = w2t + (size_t)(col0 + wave * 32 + c) * m_pad + 8 * q;
+    float* ybase = Y + wave * 32 + 4 * q;  // + lrow * kDownStride + nt * 16
 
-        for (int r0 = 0; r0 < n; r0 += 16) {
-            bf16x8 a[KS];
-            const bool va = r0 + c < n;
+    for (int ebase = 0; ebase < E; ebase += kDownBatch) {
+        __syncthreads();  // Y initialised / previous batch's tile list no longer read
+        // ---- tile list of this batch: thread i < kDownBatch describes expert ebase + i
+        int n = 0, p0 = 0;
+        const int e_mine = ebase + tid;
+        if (tid < kDownBatch && e_mine < E) {
+            const int lo = group_off[(size_t)g_lo * E + e_mine];
+            n = group_off[(size_t)g_hi * E + e_mine] - lo;
+            p0 = offsets[e_mine] + lo;
+        }
+        const int nt_mine = (n + 31) >> 5;
+        int incl = nt_mine;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                a[ks] = va ? load8(H + (size_t)(p0 + r0 + c) * m_pad + ks * 32 + 8 * q) : zero8();
-            int lrow[4];
+        for (int off = 1; off < 64; off <<= 1) {
+            const int v = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += v;
+        }
+        if (lane == 63) s_wave_tot[wave] = incl;
+        __syncthreads();
+        int start = incl - nt_mine, ntiles = 0;
+        for (int w2 = 0; w2 < kDownWaves; ++w2) {
+            const int v = s_wave_tot[w2];
+            if (w2 < wave) start += v;
+            ntiles += v;
+        }
+        for (int k = 0; k < nt_mine; ++k)
+            tiles[start + k] = make_int2(p0 + 32 * k, (e_mine << 8) | min(32, n - 32 * k));
+        __syncthreads();
+
+        // ---- walk the tiles with a ring of kDepth tiles of operands in flight
+        bf16x8 a_st[kDepth][2][KS], b_st[kDepth][2][KS];
+        int tok_st[kDepth][2], rows_st[kDepth];
+        // Issues the loads only; nothing here waits on them (token ids stay raw until the tile
+        // is consumed), so kDepth tiles of loads overlap.  Tiles past the end reload the last
+        // one with rows = 0.
+        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2],
+                         int& rows_out) {
+            const int2 ent = tiles[min(ti, ntiles - 1)];
+            const int rows = ent.y & 0xff, e = ent.y >> 8;
+            const __bf16* wp = wbase + (size_t)e * d * m_pad;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int ri = r0 + 4 * q + r;
-                lrow[r] = ri < n ? lists[p0 + ri] - t_base : -1;
+            for (int h = 0; h < 2; ++h) {
+                const int row = ent.x + min(16 * h + c, rows - 1);
+                const __bf16* hp = H + (size_t)row * m_pad + 8 * q;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    a[h][ks] = load8(wp + (size_t)h * 16 * m_pad + 32 * ks);
+                    b[h][ks] = load8(hp + 32 * ks);
+                }
+                tok[h] = lists[row];
             }
+            rows_out = ti < ntiles ? rows : 0;
+        };
+        if (ntiles > 0) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int st = 0; st < kDepth; ++st)
+                fetch(st, a_st[st], b_st[st], tok_st[st], rows_st[st]);
+        }
+        for (int t0 = 0; t0 < ntiles; t0 += kDepth) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc = mfma16(a[ks], bw[nt][ks], acc);
+            for (int st = 0; st < kDepth; ++st) {
+                // keep each stage's work inside the stage: hoisting a later stage's first use of
+                // its loads up here would make this stage wait for them as well
+                __builtin_amdgcn_sched_barrier(0);
+                const int rows = rows_st[st];
+                f32x4 acc[2][2];  // [column tile nt][token tile tt]
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if ((unsigned)lrow[r] < (unsigned)kChunk)
-                        atomicAdd(&Y[lrow[r] * kDownStride + nt * 16 + c], acc[r]);
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt) {
+                        acc[nt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int ks = 0; ks < KS; ++ks)
+                            acc[nt][tt] = mfma16(a_st[st][nt][ks], b_st[st][tt][ks], acc[nt][tt]);
+                    }
+                int lrow0 = tok_st[st][0] - t_base, lrow1 = tok_st[st][1] - t_base;
+                // Pin the MFMAs and the token reads here (an empty asm the optimiser cannot move
+                // values across): otherwise they sink below the refill, the old and the new
+                // operands of the stage overlap and the ring turns into register copies that
+                // wait on loads just issued.  The refill then reuses the stage's registers.
+                asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]),
+                                  "+v"(lrow0), "+v"(lrow1));
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st], rows_st[st]);
+
+                // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of token tt*16 + c
+                const int lrow[2] = {lrow0, lrow1};
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+                    if (16 * tt + c < rows && (unsigned)lrow[tt] < (unsigned)kChunk) {
+                        float4* yp = reinterpret_cast<float4*>(ybase + lrow[tt] * kDownStride);
+                        float4 o0 = yp[0], o1 = yp[4];
+                        o0.x += acc[0][tt][0]; o0.y += acc[0][tt][1];
+                        o0.z += acc[0][tt][2]; o0.w += acc[0][tt][3];
+                        o1.x += acc[1][tt][0]; o1.y += acc[1][tt][1];
+                        o1.z += acc[1][tt][2]; o1.w += acc[1][tt][3];
+                        yp[0] = o0;
+                        yp[4] = o1;
+                    }
+                }
             }
         }
     }
     __syncthreads();
 
-    for (int i = tid; i < kChunk * (kDownCols / 8); i += kDownWaves * 64) {
+    for (int i = tid; i < kChunk * (kDownCols / 8); i += kThreads) {
         const int row = i / (kDownCols / 8), cg = i % (kDownCols / 8);
         const int t = t_base + row;
         if (t < T) {
@@ -223,7 +310,7 @@ template <int KS>
 void launch_down_t(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* group_off,
                    const int32_t* lists, const void* H, void* y, hipStream_t s) {
     const int NG = div_up(T, kGroup), NC = div_up(T, kChunk), NS = L.d_model / kDownCols;
-    const size_t lds = sizeof(float) * (size_t)kChunk * kDownStride;
+    const size_t lds = kDownLds;
     static bool attr_set = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KS>),

@@ -17,9 +17,17 @@ namespace dmoe {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// v_mfma_f32_32x32x16_bf16: D[32][32] += A[32][16] * B[16][32].  With lane = 32*h + c (h = 0..1,
+// c = 0..31): A operand holds A[i = c][k = 8h .. 8h+7], B operand holds B[k = 8h .. 8h+7][j = c],
+// and register r (0..15) of D holds D[i = 8*(r/4) + 4h + (r%4)][j = c].
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
 __device__ __forceinline__ bf16x8 load8(const __bf16* p) {

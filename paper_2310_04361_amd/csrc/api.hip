@@ -78,9 +78,9 @@ int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
             return fail(DMOE_ERR_UNSUPPORTED,
                         "a gated expert with b_up is undefined (Appendix G states it without biases)");
         if (L->dtype == DMOE_BF16) {
-            if (!up_bf16_supported(*L) || !down_bf16_supported(*L))
+            if (!experts_bf16_supported(*L))
                 return fail(DMOE_ERR_UNSUPPORTED,
-                            "bf16 experts need d %% 256 == 0 and expert_size <= 128");
+                            "bf16 experts need d %% 256 == 0 and expert_size <= 128 (<= 64 if gated)");
             if (!L->packed)
                 return fail(DMOE_ERR_NULL, "bf16 experts need layer->packed (dmoe_pack_weights)");
         } else if ((size_t)(2 * L->d_model + L->expert_size) * 4 > 65536) {
@@ -143,10 +143,11 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     w.group_off = o;  o += align_up(sizeof(int32_t) * (size_t)(div_up(T, kGroup) + 1) * E);
     w.counts = o;     o += align_up(sizeof(int32_t) * (size_t)E);
     w.offsets = o;    o += align_up(sizeof(int32_t) * (size_t)(E + 1));
-    w.item_start = o; o += align_up(sizeof(int32_t) * (size_t)(E + 1));
-    w.lists = o;      o += align_up(sizeof(int32_t) * (size_t)T * E);
+    w.item_start = o; o += align_up(sizeof(int32_t) * (size_t)(E + 2));
+    // the expert kernels read whole 32-row tiles: pad the lists and H by one tile
+    w.lists = o;      o += align_up(sizeof(int32_t) * ((size_t)T * E + kTilePad));
     w.H = o;
-    if (L.dtype == DMOE_BF16) o += align_up(2 * (size_t)T * E * m_pad_of(L.expert_size));
+    if (L.dtype == DMOE_BF16) o += align_up(h_fragments(L, T) * (m_pad_of(L.expert_size) / 32) * 1024);
     w.total = o;
     return w;
 }
@@ -158,19 +159,20 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
     int32_t* counts = reinterpret_cast<int32_t*>(ws + w.counts);
     int32_t* offsets = offsets_out ? offsets_out : reinterpret_cast<int32_t*>(ws + w.offsets);
-    int32_t* lists = lists_out ? lists_out : reinterpret_cast<int32_t*>(ws + w.lists);
+    // the kernels always read the workspace copy (padded by one tile); the caller's is a copy
+    int32_t* lists = reinterpret_cast<int32_t*>(ws + w.lists);
     int32_t* item_start = reinterpret_cast<int32_t*>(ws + w.item_start);
     if (L.dtype == DMOE_F32) {
         if (offsets_out)
-            launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, kUpRows,
-                                 lists, s);
+            launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
+                                 lists_out, nullptr, s);
         launch_ffn_f32(L, (const float*)x, T, mask, (float*)y, s);
     } else {
-        launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, item_start, kUpRows,
-                             lists, s);
+        launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, item_start,
+                             up_rows_bf16(L), lists, lists_out, s);
         void* H = ws + w.H;
         launch_up_bf16(L, x, T, offsets, item_start, lists, H, s);
-        launch_down_bf16(L, T, offsets, group_off, lists, H, y, s);
+        launch_down_bf16(L, T, offsets, item_start, group_off, lists, H, y, s);
     }
     return check_launch("expert kernels");
 }
@@ -217,16 +219,18 @@ int32_t dmoe_select_workspace_bytes(int32_t n_tokens, int32_t n_experts, size_t*
 int32_t dmoe_packed_bytes(const dmoe_layer* layer, size_t* out_bytes) {
     if (!out_bytes) return fail(DMOE_ERR_NULL, "out_bytes is NULL");
     if (int rc = check_layer(layer, false, false)) return rc;
-    *out_bytes = layer->dtype == DMOE_BF16
-                     ? align_up(2 * (size_t)layer->n_experts * layer->d_model * m_pad_of(layer->expert_size))
-                     : 0;
+    *out_bytes = packed_layout(*layer).total;
     return DMOE_OK;
 }
 
 int32_t dmoe_pack_weights(const dmoe_layer* layer, void* packed, size_t packed_bytes, void* stream) {
     if (int rc = check_layer(layer, false, false)) return rc;
     if (layer->dtype == DMOE_F32) return DMOE_OK;
-    if (!layer->w_down) return fail(DMOE_ERR_NULL, "w_down is NULL");
+    if (!layer->w_down || !layer->w_up || (layer->gated && !layer->w_gate))
+        return fail(DMOE_ERR_NULL, "expert weights are NULL");
+    if (!experts_bf16_supported(*layer))
+        return fail(DMOE_ERR_UNSUPPORTED,
+                    "bf16 experts need d %% 256 == 0 and expert_size <= 128 (<= 64 if gated)");
     size_t need = 0;
     dmoe_packed_bytes(layer, &need);
     if (!packed) return fail(DMOE_ERR_NULL, "packed is NULL");
@@ -263,8 +267,8 @@ int32_t dmoe_select(const float* scores, int32_t n_tokens, int32_t n_experts, fl
     uint64_t* mask = mask_bits ? mask_bits : reinterpret_cast<uint64_t*>(ws + w.mask);
     if (n_tokens > 0)
         launch_mask_from_scores(scores, n_tokens, n_experts, tau, mask, k_per_token, group_off, s);
-    launch_scan_and_fill(mask, n_tokens, n_experts, group_off, counts, offsets, nullptr, kUpRows,
-                         n_tokens > 0 ? token_lists : nullptr, s);
+    launch_scan_and_fill(mask, n_tokens, n_experts, group_off, counts, offsets, nullptr, 64,
+                         n_tokens > 0 ? token_lists : nullptr, nullptr, s);
     return check_launch("select");
 }
 

@@ -10,13 +10,39 @@ namespace dmoe {
 
 // ---- fixed granularities -------------------------------------------------------------------
 constexpr int kGroup = 64;        // tokens per select group (one wavefront, lane = token)
-constexpr int kChunkGroups = 2;   // groups per down-projection token chunk
-constexpr int kChunk = kGroup * kChunkGroups;   // 128 tokens whose outputs live in LDS together
-constexpr int kUpRows = 64;       // list rows per up-projection work item (4 MFMA column tiles)
+constexpr int kChunkGroups = 1;   // groups per down-projection token chunk
+constexpr int kChunk = kGroup * kChunkGroups;   // 64 tokens whose outputs live in LDS together
+constexpr int kTilePad = 64;      // entries the expert kernels may read past the end of the lists
 
 inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 inline int div_up(int a, int b) { return (a + b - 1) / b; }
 inline int m_pad_of(int m) { return round_up(m, 32); }
+
+// List rows per up-projection work item (a multiple of 16); every expert's region of H starts
+// at a multiple of this many rows.
+inline int up_rows_bf16(const dmoe_layer&) { return 64; }
+
+// H capacity in 16-row fragments for T tokens: every expert may round up to a whole work item,
+// and the down kernel reads one fragment past the last one.
+inline size_t h_fragments(const dmoe_layer& L, int T) {
+    return ((size_t)T * L.n_experts + (size_t)L.n_experts * up_rows_bf16(L)) / 16 + 4;
+}
+
+// Sub-buffers of the packed-weights buffer (bytes from its start).
+struct PackedLayout {
+    size_t w2f, wupf, wgatef, total;
+};
+inline PackedLayout packed_layout(const dmoe_layer& L) {
+    PackedLayout P{};
+    if (L.dtype != DMOE_BF16) return P;
+    const size_t one =
+        (2 * (size_t)L.n_experts * L.d_model * m_pad_of(L.expert_size) + 255) / 256 * 256;
+    P.w2f = 0;
+    P.wupf = one;
+    P.wgatef = 2 * one;
+    P.total = (L.gated ? 3 : 2) * one;
+    return P;
+}
 
 // ---- kernel timing slots --------------------------------------------------------------------
 enum Slot {
@@ -52,7 +78,7 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
                             uint64_t* mask, int32_t* group_off, hipStream_t s);
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
-                          int32_t* token_lists, hipStream_t s);
+                          int32_t* token_lists, int32_t* token_lists_copy, hipStream_t s);
 
 // ---- router (router.hip) ----------------------------------------------------------------------
 void launch_router_f32(const dmoe_layer& L, const float* x, int T, float* scores, hipStream_t s);
@@ -62,15 +88,15 @@ void launch_router_bf16(const dmoe_layer& L, const void* x, int T, float* scores
 void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* mask, float* y,
                     hipStream_t s);
 void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s);
-// H is [capacity][m_pad] bf16, row p belongs to list position p.
+// H holds the hidden activations in 16-row MFMA fragments (layout: see ffn_bf16.hip).
 void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* offsets,
                     const int32_t* item_start, const int32_t* token_lists, void* H,
                     hipStream_t s);
-void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* group_off,
-                      const int32_t* token_lists, const void* H, void* y, hipStream_t s);
+void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* item_start,
+                      const int32_t* group_off, const int32_t* token_lists, const void* H, void* y,
+                      hipStream_t s);
 
-bool up_bf16_supported(const dmoe_layer& L);
-bool down_bf16_supported(const dmoe_layer& L);
+bool experts_bf16_supported(const dmoe_layer& L);
 bool router_bf16_supported(const dmoe_layer& L);
 
 }  // namespace dmoe

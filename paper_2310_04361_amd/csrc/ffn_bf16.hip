@@ -1,17 +1,28 @@
 // bf16 expert execution and merge (Sec. 3.2, Appendix G) on the gfx950 matrix cores.
 //
 // Two kernels, both driven by the sorted per-expert token lists:
-//   up    expert-major grouped GEMM over the compact lists: gathers the listed rows of x (no
-//         copy), multiplies by the expert's up (and gate) rows, applies bias + activation in fp32
-//         and writes the hidden activations, rounded to bf16, to H[list position][m_pad].
-//   down  output-stationary: a workgroup owns 128 consecutive tokens x 256 output columns as an
-//         fp32 tile in LDS, walks all experts, multiplies the chunk's compact H rows of each
-//         expert by that expert's down-projection slice and adds the result into the owning
-//         token rows (plain LDS read-add-write; each wavefront owns its own columns).  Every y
-//         element is written exactly once, in bf16; no global atomics, no second pass.
+//   up    expert-major grouped GEMM over the compact lists.  A wavefront owns UR = 16*TT list
+//         rows of one expert, gathers those rows of x in 128-byte pieces (eight lanes per row, so
+//         the vector memory path sees whole cache lines), stages them in its own LDS buffers and
+//         multiplies them with the expert's up (and gate) rows; bias + activation in fp32; the
+//         hidden activations go out rounded to bf16 in MFMA-fragment order.
+//   down  output-stationary: a workgroup owns 64 consecutive tokens x 256 output columns as an
+//         fp32 tile in LDS, walks all experts, multiplies the chunk's H fragments of each expert
+//         by that expert's down-projection slice and adds the result into the owning token rows
+//         (plain LDS read-add-write; each wavefront owns its own columns).  Every y element is
+//         written exactly once, in bf16; no global atomics, no second pass.
 // Tokens ride on the MFMA column axis in both kernels, so four consecutive neurons (up) or
-// output columns (down) of one token land in one lane: H is written in 8-byte pieces and the LDS
-// merge moves 16 bytes per lane with a single row address.
+// output columns (down) of one token land in one lane.
+//
+// Fragment order.  Every operand that a wavefront reads with one load instruction is stored as
+// the 1 KiB block  [lane 0..63][8 bf16]  in exactly the register layout of the MFMA, because a
+// 16-byte-per-lane access with a 64-byte or larger lane stride costs a cache-line lookup per
+// lane and that, not bandwidth, bounded the first version of these kernels.
+//   H fragment F, k-step ks: lane (q, c) holds, for list row 16*(F - first fragment of the
+//     expert) + c, the neurons 32ks + 16*(s/4) + 4q + (s%4), s = 0..7 -- the order in which the
+//     up kernel's accumulators come out; the packed down-projection uses the same k order.
+//   An expert's H rows start at a multiple of UR rows (its first up-projection work item), so
+//     fragments never mix experts.
 #include "dmoe_internal.h"
 #include "mfma.h"
 
@@ -21,45 +32,110 @@ namespace {
 
 constexpr int kDownWaves = 8;
 constexpr int kDownCols = kDownWaves * 32;     // output columns per down workgroup
-constexpr int kDownBatch = 256;                // experts per tile-list batch
-constexpr int kDownStride = kDownCols + 4;      // LDS row stride in floats
-constexpr size_t kDownLds =
-    sizeof(float) * kChunk * kDownStride + sizeof(int2) * kDownBatch * (kChunk / 32);
+constexpr int kDownBatch = 128;                // experts per tile-list batch
+constexpr int kDownTilesPerExpert = (kChunk / 16 + 2) / 2;   // fragment pairs a chunk can span
+constexpr int kDownStride = kDownCols + 4;     // LDS row stride in floats
+constexpr size_t kDownLds = sizeof(float) * kChunk * kDownStride +
+                            sizeof(int4) * kDownBatch * kDownTilesPerExpert;
+constexpr int kUpRowBytes = 144;               // 64 bf16 of one x row + 16 bytes of bank skew
 
-// w_down[E][m][d] -> w2t[E][d][m_pad], zero-filled for j >= m.
-__global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __restrict__ w2t,
-                                 int E, int m, int d, int m_pad) {
-    const size_t n = (size_t)E * d * m_pad;
+// ---- activations (fp32 in, fp32 out) -------------------------------------------------------------
+// erf by the rational-times-exponential approximation 7.1.26 of Abramowitz & Stegun
+// (absolute error below 1.5e-7, far inside bf16 resolution), tanh through one exponential.
+__device__ __forceinline__ float fast_erf(float v) {
+    const float a = fabsf(v);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, a, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float r = 1.0f - p * t * __expf(-a * a);
+    return copysignf(r, v);
+}
+
+__device__ __forceinline__ float activate_fast(int act, float v) {
+    if (act == DMOE_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == DMOE_ACT_GELU_ERF) return 0.5f * v * (1.0f + fast_erf(v * 0.70710678118654752440f));
+    const float u = 0.79788456080286535588f * (v + 0.044715f * v * v * v);
+    const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * u));  // tanh(u)
+    return 0.5f * v * (1.0f + th);
+}
+
+// ---- one-time weight packing ------------------------------------------------------------------------
+// w_down[E][m][d] -> w2f[E][d/16][KS][64][8]: lane (q, c) of fragment (e, column tile ct, ks)
+// holds W_down[e][32ks + 16*(s/4) + 4q + s%4][16ct + c], zero for neurons >= m.
+__global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __restrict__ w2f,
+                                 int E, int m, int d, int KS) {
+    const size_t n = (size_t)E * d * KS * 32;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) {
-        const int j = (int)(i % m_pad);
-        const size_t ec = i / m_pad;
-        const int col = (int)(ec % d);
-        const int e = (int)(ec / d);
-        w2t[i] = j < m ? w_down[((size_t)e * m + j) * d + col] : (__bf16)0.0f;
+        const int s = (int)(i & 7), lane = (int)((i >> 3) & 63);
+        size_t f = i >> 9;
+        const int ks = (int)(f % KS);
+        f /= KS;
+        const int ct = (int)(f % (d / 16));
+        const int e = (int)(f / (d / 16));
+        const int q = lane >> 4, c = lane & 15;
+        const int neuron = 32 * ks + 16 * (s >> 2) + 4 * q + (s & 3);
+        w2f[i] = neuron < m ? w_down[((size_t)e * m + neuron) * d + 16 * ct + c] : (__bf16)0.0f;
     }
 }
 
-// One wavefront per work item = (expert, 64 consecutive list rows).
-// MT = m_pad / 16 neuron tiles per branch.
-template <int MT, bool GATED>
+// w[E][m][d] -> wf[E][MT][d/32][64][8]: lane (q, c) of fragment (e, neuron tile mt, k-step) holds
+// w[e][16mt + c][32 kstep + 8q + s], zero rows for neurons >= m.
+__global__ void pack_up_kernel(const __bf16* __restrict__ w, __bf16* __restrict__ wf, int E, int m,
+                               int d, int MT) {
+    const size_t n = (size_t)E * MT * 16 * d;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        const int s = (int)(i & 7), lane = (int)((i >> 3) & 63);
+        size_t f = i >> 9;
+        const int kstep = (int)(f % (d / 32));
+        f /= (d / 32);
+        const int mt = (int)(f % MT);
+        const int e = (int)(f / MT);
+        const int q = lane >> 4, c = lane & 15;
+        const int neuron = 16 * mt + c;
+        wf[i] = neuron < m ? w[((size_t)e * m + neuron) * d + 32 * kstep + 8 * q + s] : (__bf16)0.0f;
+    }
+}
+
+// ---- up-projection ---------------------------------------------------------------------------------
+// One wavefront per work item = (expert, UR = 16*TT consecutive list rows); no workgroup-level
+// synchronisation after the work-item table has been staged.  MT = m_pad / 16 neuron tiles per
+// branch.  K advances in blocks of 64: the wavefront loads the next block of its x rows
+// (lane = (row % 8, 16-byte piece of the 128-byte row segment)) and of the weight fragments
+// while the MFMAs run on the current block out of LDS / registers.
+template <int MT, bool GATED, int TT>
 __global__ __launch_bounds__(256) void up_bf16_kernel(
-    const __bf16* __restrict__ x, const __bf16* __restrict__ w_up,
-    const __bf16* __restrict__ w_gate, const __bf16* __restrict__ b_up,
+    const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
+    const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
     const int32_t* __restrict__ offsets, const int32_t* __restrict__ item_start,
-    const int32_t* __restrict__ lists, __bf16* __restrict__ H, int d, int E, int m, int act) {
-    constexpr int TT = kUpRows / 16;
+    const int32_t* __restrict__ lists, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
     constexpr int BR = GATED ? 2 : 1;
-    constexpr int m_pad = MT * 16;
-    extern __shared__ int32_t s_items[];  // item_start[0..E]
-    for (int i = threadIdx.x; i <= E; i += blockDim.x) s_items[i] = item_start[i];
+    constexpr int KS = MT / 2;
+    constexpr int UR = TT * 16;
+    constexpr int NL = TT * 2;  // x load instructions per K block: 8 rows x 128 bytes each
+    extern __shared__ char smem[];
+    int32_t* s_items = reinterpret_cast<int32_t*>(smem);  // item_start[0..E+1]
+    const int items_bytes = ((E + 2) * 4 + 15) & ~15;
+    for (int i = threadIdx.x; i <= E + 1; i += blockDim.x) s_items[i] = item_start[i];
     __syncthreads();
-    const int total = s_items[E];
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15;
+    const int wave_in_block = threadIdx.x >> 6;
+    char* xs = smem + items_bytes + wave_in_block * (2 * UR * kUpRowBytes);
+    const int NK32 = d / 32, NKB = d / 64;
+    const int ld_row = lane >> 3, ld_piece = lane & 7;
+
+    const int total = s_items[E];
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
 
+    // Items are taken in expert-major order.  (Ordering them so that an XCD's wavefronts share a
+    // token window -- for L2 reuse of the x rows -- measured slower: the gathers then collide
+    // on the same L2 channels.)
     for (int item = wave; item < total; item += n_waves) {
         int lo = 0, hi = E;  // last e with s_items[e] <= item
         while (hi - lo > 1) {
@@ -67,23 +143,28 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
             if (s_items[mid] <= item) lo = mid; else hi = mid;
         }
         const int e = lo;
-        const int p0 = offsets[e] + (item - s_items[e]) * kUpRows;
+        const int p0 = offsets[e] + (item - s_items[e]) * UR;
         const int pend = offsets[e + 1];
-        const int rows = min(kUpRows, pend - p0);
 
-        const __bf16* xr[TT];
+        const __bf16* xrow[NL];
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            const int tok = lists[min(p0 + tt * 16 + c, pend - 1)];
-            xr[tt] = x + (size_t)tok * d + 8 * q;
+        for (int i = 0; i < NL; ++i) {
+            const int tok = lists[min(p0 + 8 * i + ld_row, pend - 1)];
+            xrow[i] = x + (size_t)tok * d + 8 * ld_piece;
         }
-        const __bf16* wr[BR][MT];
+        const __bf16* wf[BR];
+        wf[0] = wupf + (size_t)e * MT * NK32 * 512 + lane * 8;
+        if (GATED) wf[BR - 1] = wgatef + (size_t)e * MT * NK32 * 512 + lane * 8;
+
+        // biases of this lane's neurons, fetched now so that their latency hides under the K loop
+        float bias[MT][4];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const size_t row = (size_t)e * m + min(mt * 16 + c, m - 1);
-            wr[0][mt] = w_up + row * d + 8 * q;
-            if (GATED) wr[BR - 1][mt] = w_gate + row * d + 8 * q;
-        }
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int n = 16 * mt + 4 * q + r;
+                bias[mt][r] = (!GATED && b_up) ? (float)b_up[(size_t)e * m + min(n, m - 1)] : 0.0f;
+            }
 
         f32x4 acc[BR][MT][TT];
 #pragma unroll
@@ -93,102 +174,159 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt) acc[br][mt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        for (int k0 = 0; k0 < d; k0 += 32) {
-            bf16x8 b[TT];
+        bf16x8 xr[NL];
+        bf16x8 a0[2][BR][MT], a1[2][BR][MT];
+        auto load_x = [&](int kb) {
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) b[tt] = load8(xr[tt] + k0);
+            for (int i = 0; i < NL; ++i) xr[i] = load8(xrow[i] + 64 * kb);
+        };
+        auto load_a = [&](int kb, bf16x8 (&a)[2][BR][MT]) {
 #pragma unroll
-            for (int br = 0; br < BR; ++br)
+            for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const bf16x8 a = load8(wr[br][mt] + k0);
+                for (int br = 0; br < BR; ++br)
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc[br][mt][tt] = mfma16(a, b[tt], acc[br][mt][tt]);
-                }
+                    for (int mt = 0; mt < MT; ++mt)
+                        a[ks][br][mt] = load8(wf[br] + ((size_t)mt * NK32 + 2 * kb + ks) * 512);
+        };
+        auto store_x = [&](int buf) {
+            char* dst = xs + buf * (UR * kUpRowBytes) + ld_row * kUpRowBytes + ld_piece * 16;
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
+        };
+        auto compute = [&](int buf, const bf16x8 (&a)[2][BR][MT]) {
+            const char* src = xs + buf * (UR * kUpRowBytes) + c * kUpRowBytes + q * 16;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                bf16x8 b[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+                    b[tt] = *reinterpret_cast<const bf16x8*>(src + tt * 16 * kUpRowBytes + ks * 64);
+#pragma unroll
+                for (int br = 0; br < BR; ++br)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt)
+                            acc[br][mt][tt] = mfma16(a[ks][br][mt], b[tt], acc[br][mt][tt]);
+            }
+        };
+
+        load_x(0);
+        load_a(0, a0);
+        store_x(0);
+        // two K blocks per trip so that the two weight-fragment register sets simply alternate
+        for (int kb = 0; kb < NKB; kb += 2) {
+            load_x(kb + 1);
+            load_a(kb + 1, a1);
+            compute(0, a0);
+            store_x(1);
+            const int nb = min(kb + 2, NKB - 1);  // the last trip re-reads a block it will not use
+            load_x(nb);
+            load_a(nb, a0);
+            compute(1, a1);
+            store_x(0);
         }
 
-        // lane (q, c) of tile (mt, tt): neurons mt*16 + 4q + r of list row tt*16 + c
+        // lane (q, c) of tile (mt, tt): neurons 16mt + 4q + r of list row 16tt + c
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int n0 = mt * 16 + 4 * q;
-            float bias[4] = {0.f, 0.f, 0.f, 0.f};
-            if (!GATED && b_up) {
+        for (int tt = 0; tt < TT; ++tt) {
+            __bf16* dst = Hf + (((size_t)item * TT + tt) * KS * 64 + lane) * 8;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (n0 + r < m) bias[r] = (float)b_up[(size_t)e * m + n0 + r];
-            }
+            for (int ks = 0; ks < KS; ++ks) {
+                bf16x8 hv;
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                bf16x4 h;
+                for (int half = 0; half < 2; ++half) {
+                    const int mt = 2 * ks + half;
+                    const int n0 = 16 * mt + 4 * q;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float v;
-                    if (GATED) v = activate(act, acc[BR - 1][mt][tt][r]) * acc[0][mt][tt][r];
-                    else v = activate(act, acc[0][mt][tt][r] + bias[r]);
-                    if (n0 + r >= m) v = 0.0f;
-                    h[r] = (__bf16)v;
+                    for (int r = 0; r < 4; ++r) {
+                        float v;
+                        if (GATED) {
+                            v = activate_fast(act, acc[BR - 1][mt][tt][r]) * acc[0][mt][tt][r];
+                        } else {
+                            v = activate_fast(act, acc[0][mt][tt][r] + bias[mt][r]);
+                        }
+                        if (n0 + r >= m) v = 0.0f;
+                        hv[half * 4 + r] = (__bf16)v;
+                    }
                 }
-                const int ri = tt * 16 + c;
-                if (ri < rows)
-                    *reinterpret_cast<bf16x4*>(H + (size_t)(p0 + ri) * m_pad + n0) = h;
+                *reinterpret_cast<bf16x8*>(dst + (size_t)ks * 512) = hv;
             }
         }
     }
 }
 
-// One workgroup per (128-token chunk, 256-column slice); KS = m_pad / 32 MFMA k-steps.
+// ---- down-projection and merge ------------------------------------------------------------------------
+// One workgroup per (64-token chunk, 256-column slice), two of them per CU; KS = m_pad / 32
+// MFMA k-steps.
 //
-// The fp32 output tile Y[128][256] lives in LDS.  The eight wavefronts own 32 columns each, so
+// The fp32 output tile Y[64][256] lives in LDS.  The eight wavefronts own 32 columns each, so
 // no two wavefronts ever touch the same element and the merge is a plain read-add-write (LDS
-// float atomics proved far slower).  All wavefronts walk the same list of row tiles -- up to 32
-// compact H rows of one expert -- built once per batch of 256 experts from the group offsets.
-// Per tile and wavefront: D[32 cols][32 tokens] = W2t slice * H_tile^T as 2 x 2 MFMA 16x16x32
+// float atomics proved far slower).  All wavefronts walk the same list of tiles -- two
+// consecutive H fragments (32 list rows) of one expert, of which only the rows that belong to
+// this chunk are merged -- built once per batch of experts from the group offsets.
+// Per tile and wavefront: D[32 cols][32 rows] = W2 slice * H_tile^T as 2 x 2 MFMA 16x16x32
 // tiles with the tokens on the MFMA column axis, so a lane ends up with four consecutive output
 // columns of ONE token: one 16-byte LDS read and write per MFMA tile, one row address per
 // token.  The row stride of 260 floats spreads consecutive-token rows over the banks.
 // Operands of the next kDepth tiles are kept in flight while the current one is merged.
 template <int KS>
 __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
-    const __bf16* __restrict__ w2t, const __bf16* __restrict__ b_down,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ group_off,
-    const int32_t* __restrict__ lists, const __bf16* __restrict__ H, __bf16* __restrict__ y, int T,
-    int d, int E, int NG) {
-    constexpr int m_pad = KS * 32;
+    const __bf16* __restrict__ w2f, const __bf16* __restrict__ b_down,
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ item_start,
+    const int32_t* __restrict__ group_off, const int32_t* __restrict__ lists,
+    const __bf16* __restrict__ Hf, __bf16* __restrict__ y, int T, int d, int E, int NG,
+    int frags_per_item) {
     constexpr int kThreads = kDownWaves * 64;
-    constexpr int kDepth = KS <= 2 ? 4 : 2;  // row tiles of operands in flight per wavefront
-    extern __shared__ float smem[];
-    float* Y = smem;  // [kChunk][kDownStride]
-    int2* tiles = reinterpret_cast<int2*>(smem + kChunk * kDownStride);  // [kDownBatch * kChunk/32]
+    constexpr int kDepth = KS <= 2 ? 4 : 2;  // tiles of operands in flight per wavefront
+    extern __shared__ float smem_f[];
+    float* Y = smem_f;  // [kChunk][kDownStride]
+    int4* tiles = reinterpret_cast<int4*>(smem_f + kChunk * kDownStride);
     __shared__ int s_wave_tot[kDownWaves];
+    // The slices of one chunk share its H rows and token lists: keep them on one XCD (workgroups
+    // are dealt round-robin to the 8 XCDs) and next to each other in launch order.
     const int NS = d / kDownCols;
-    const int chunk = blockIdx.x / NS, slice = blockIdx.x % NS;
+    const int k_in_xcd = blockIdx.x >> 3;
+    const int chunk = (k_in_xcd / NS) * 8 + (blockIdx.x & 7), slice = k_in_xcd % NS;
+    if (chunk * kChunk >= T) return;  // the grid is rounded up to whole groups of 8 chunks
     const int t_base = chunk * kChunk, col0 = slice * kDownCols;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, q = lane >> 4, c = lane & 15;
-
-    for (int i = tid; i < kChunk * kDownCols; i += kThreads) {
-        const int row = i / kDownCols, col = i % kDownCols;
-        Y[row * kDownStride + col] = b_down ? (float)b_down[col0 + col] : 0.0f;
+    {   // every row of the tile starts as the output bias of this slice
+        static_assert(kThreads % kDownCols == 0, "one column per thread");
+        const int col = tid % kDownCols;
+        const float bias = b_down ? (float)b_down[col0 + col] : 0.0f;
+        for (int row = tid / kDownCols; row < kChunk; row += kThreads / kDownCols)
+            Y[row * kDownStride + col] = bias;
     }
 
     const int g_lo = chunk * kChunkGroups;
     const int g_hi = min(g_lo + kChunkGroups, NG);
-    // A operand rows: output columns wave*32 + nt*16 + c of this slice, k = 8q..8q+7 (+32 ks)
-    const __bf16* wbase = w2t + (size_t)(col0 + wave * 32 + c) * m_pad + 8 * q;
-    float* ybase = Y + wave * 32 + 4 * q;  // + lrow * kDownStride + nt * 16
+    // weight fragments of this wavefront's two column tiles: + (e * d/16) fragments per expert
+    const __bf16* wbase =
+        w2f + ((size_t)(col0 / 16 + 2 * __builtin_amdgcn_readfirstlane(wave)) * KS * 64 + lane) * 8;
+    const size_t w_expert_stride = (size_t)(d / 16) * KS * 512;
+    const __bf16* hbase = Hf + lane * 8;
+    // element (token t, column wave*32 + nt*16 + 4q) is at ybase + t * kDownStride + nt * 16
+    float* ybase = Y + wave * 32 + 4 * q - (ptrdiff_t)t_base * kDownStride;
 
     for (int ebase = 0; ebase < E; ebase += kDownBatch) {
         __syncthreads();  // Y initialised / previous batch's tile list no longer read
         // ---- tile list of this batch: thread i < kDownBatch describes expert ebase + i
-        int n = 0, p0 = 0;
+        int lo = 0, hi = 0, f0 = 0, nt_mine = 0, list0 = 0, frag0 = 0;
         const int e_mine = ebase + tid;
         if (tid < kDownBatch && e_mine < E) {
-            const int lo = group_off[(size_t)g_lo * E + e_mine];
-            n = group_off[(size_t)g_hi * E + e_mine] - lo;
-            p0 = offsets[e_mine] + lo;
+            lo = group_off[(size_t)g_lo * E + e_mine];
+            hi = group_off[(size_t)g_hi * E + e_mine];
+            if (hi > lo) {
+                f0 = lo >> 4;
+                nt_mine = (((hi - 1) >> 4) - f0 + 2) >> 1;
+                list0 = offsets[e_mine];
+                frag0 = item_start[e_mine] * frags_per_item;
+            }
         }
-        const int nt_mine = (n + 31) >> 5;
         int incl = nt_mine;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -203,38 +341,45 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
             if (w2 < wave) start += v;
             ntiles += v;
         }
-        for (int k = 0; k < nt_mine; ++k)
-            tiles[start + k] = make_int2(p0 + 32 * k, (e_mine << 8) | min(32, n - 32 * k));
+        for (int k = 0; k < nt_mine; ++k) {
+            const int r0 = 16 * (f0 + 2 * k);  // first list row (within the expert) of the tile
+            const int first = max(lo - r0, 0), last = min(hi - r0, 32);
+            tiles[start + k] = make_int4(frag0 + f0 + 2 * k, list0 + r0, e_mine, first | (last << 8));
+        }
         __syncthreads();
-
         // ---- walk the tiles with a ring of kDepth tiles of operands in flight
         bf16x8 a_st[kDepth][2][KS], b_st[kDepth][2][KS];
-        int tok_st[kDepth][2], rows_st[kDepth];
+        int tok_st[kDepth][2], win_st[kDepth];
         // Issues the loads only; nothing here waits on them (token ids stay raw until the tile
-        // is consumed), so kDepth tiles of loads overlap.  Tiles past the end reload the last
-        // one with rows = 0.
-        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2],
-                         int& rows_out) {
-            const int2 ent = tiles[min(ti, ntiles - 1)];
-            const int rows = ent.y & 0xff, e = ent.y >> 8;
-            const __bf16* wp = wbase + (size_t)e * d * m_pad;
+        // is consumed), so kDepth tiles of loads overlap.  The tile entry is uniform: its address
+        // arithmetic stays on the scalar unit and every lane adds only its fixed offset.  Tiles
+        // past the end reload the last one with an empty row window.  Rows outside the window
+        // are read too (the buffers are padded): they only feed MFMA columns of lanes that skip
+        // the merge.
+        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2], int& win) {
+            const int4 ent = tiles[min(ti, ntiles - 1)];
+            const int frag = __builtin_amdgcn_readfirstlane(ent.x);
+            const int lpos = __builtin_amdgcn_readfirstlane(ent.y);
+            const int e = __builtin_amdgcn_readfirstlane(ent.z);
+            const int w = __builtin_amdgcn_readfirstlane(ent.w);
+            const __bf16* wp = wbase + (size_t)e * w_expert_stride;
+            const __bf16* hp = hbase + (size_t)frag * KS * 512;
+            const int32_t* lp = lists + lpos;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int row = ent.x + min(16 * h + c, rows - 1);
-                const __bf16* hp = H + (size_t)row * m_pad + 8 * q;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    a[h][ks] = load8(wp + (size_t)h * 16 * m_pad + 32 * ks);
-                    b[h][ks] = load8(hp + 32 * ks);
+                    a[h][ks] = load8(wp + (h * KS + ks) * 512);
+                    b[h][ks] = load8(hp + (h * KS + ks) * 512);
                 }
-                tok[h] = lists[row];
+                tok[h] = lp[16 * h + c];
             }
-            rows_out = ti < ntiles ? rows : 0;
+            win = ti < ntiles ? w : 0;
         };
         if (ntiles > 0) {
 #pragma unroll
             for (int st = 0; st < kDepth; ++st)
-                fetch(st, a_st[st], b_st[st], tok_st[st], rows_st[st]);
+                fetch(st, a_st[st], b_st[st], tok_st[st], win_st[st]);
         }
         for (int t0 = 0; t0 < ntiles; t0 += kDepth) {
 #pragma unroll
@@ -242,7 +387,7 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
                 // keep each stage's work inside the stage: hoisting a later stage's first use of
                 // its loads up here would make this stage wait for them as well
                 __builtin_amdgcn_sched_barrier(0);
-                const int rows = rows_st[st];
+                const int first = win_st[st] & 0xff, last = win_st[st] >> 8;
                 f32x4 acc[2][2];  // [column tile nt][token tile tt]
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
@@ -253,22 +398,23 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
                         for (int ks = 0; ks < KS; ++ks)
                             acc[nt][tt] = mfma16(a_st[st][nt][ks], b_st[st][tt][ks], acc[nt][tt]);
                     }
-                int lrow0 = tok_st[st][0] - t_base, lrow1 = tok_st[st][1] - t_base;
+                int tok0 = tok_st[st][0], tok1 = tok_st[st][1];
                 // Pin the MFMAs and the token reads here (an empty asm the optimiser cannot move
                 // values across): otherwise they sink below the refill, the old and the new
                 // operands of the stage overlap and the ring turns into register copies that
                 // wait on loads just issued.  The refill then reuses the stage's registers.
                 asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]),
-                                  "+v"(lrow0), "+v"(lrow1));
+                                  "+v"(tok0), "+v"(tok1));
                 __builtin_amdgcn_sched_barrier(0);
-                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st], rows_st[st]);
+                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st], win_st[st]);
 
-                // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of token tt*16 + c
-                const int lrow[2] = {lrow0, lrow1};
+                // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of tile row tt*16 + c
+                const int tok[2] = {tok0, tok1};
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {
-                    if (16 * tt + c < rows && (unsigned)lrow[tt] < (unsigned)kChunk) {
-                        float4* yp = reinterpret_cast<float4*>(ybase + lrow[tt] * kDownStride);
+                    const int row = 16 * tt + c;
+                    if (row >= first && row < last) {
+                        float4* yp = reinterpret_cast<float4*>(ybase + tok[tt] * kDownStride);
                         float4 o0 = yp[0], o1 = yp[4];
                         o0.x += acc[0][tt][0]; o0.y += acc[0][tt][1];
                         o0.z += acc[0][tt][2]; o0.w += acc[0][tt][3];
@@ -296,77 +442,94 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
     }
 }
 
-template <int MT, bool GATED>
-void launch_up_t(const dmoe_layer& L, const void* x, const int32_t* offsets,
+// ---- launchers ---------------------------------------------------------------------------------------
+template <int MT, bool GATED, int TT>
+void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, const int32_t* offsets,
                  const int32_t* item_start, const int32_t* lists, void* H, int grid,
                  hipStream_t s) {
-    const size_t lds = sizeof(int32_t) * (size_t)(L.n_experts + 1);
-    up_bf16_kernel<MT, GATED><<<grid, 256, lds, s>>>(
-        (const __bf16*)x, (const __bf16*)L.w_up, (const __bf16*)L.w_gate, (const __bf16*)L.b_up,
-        offsets, item_start, lists, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
+    const size_t lds = (((size_t)L.n_experts + 2) * 4 + 15) / 16 * 16 +
+                       4 * 2 * (size_t)TT * 16 * kUpRowBytes;
+    static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_bf16_kernel<MT, GATED, TT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    const char* pk = static_cast<const char*>(L.packed);
+    up_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
+        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
+        (const __bf16*)L.b_up, offsets, item_start, lists, (__bf16*)H, L.d_model, L.n_experts,
+        L.expert_size, L.act);
 }
 
 template <int KS>
-void launch_down_t(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* group_off,
-                   const int32_t* lists, const void* H, void* y, hipStream_t s) {
+void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* offsets,
+                   const int32_t* item_start, const int32_t* group_off, const int32_t* lists,
+                   const void* H, void* y, hipStream_t s) {
     const int NG = div_up(T, kGroup), NC = div_up(T, kChunk), NS = L.d_model / kDownCols;
-    const size_t lds = kDownLds;
-    static bool attr_set = false;  // raising the dynamic-LDS limit is a per-function, idempotent setting
+    static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KS>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDownLds);
         attr_set = true;
     }
-    down_bf16_kernel<KS><<<NC * NS, kDownWaves * 64, lds, s>>>(
-        (const __bf16*)L.packed, (const __bf16*)L.b_down, offsets, group_off, lists,
-        (const __bf16*)H, (__bf16*)y, T, L.d_model, L.n_experts, NG);
+    const char* pk = static_cast<const char*>(L.packed);
+    down_bf16_kernel<KS><<<round_up(NC, 8) * NS, kDownWaves * 64, kDownLds, s>>>(
+        (const __bf16*)(pk + P.w2f), (const __bf16*)L.b_down, offsets, item_start, group_off, lists,
+        (const __bf16*)H, (__bf16*)y, T, L.d_model, L.n_experts, NG, up_rows_bf16(L) / 16);
 }
 
 }  // namespace
 
-bool up_bf16_supported(const dmoe_layer& L) {
+bool experts_bf16_supported(const dmoe_layer& L) {
     const int mp = m_pad_of(L.expert_size);
-    return (mp == 32 || mp == 64 || mp == 128) && L.d_model % 32 == 0 && L.n_experts <= 4096;
-}
-
-bool down_bf16_supported(const dmoe_layer& L) {
-    const int mp = m_pad_of(L.expert_size);
-    return (mp == 32 || mp == 64 || mp == 128) && L.d_model % kDownCols == 0;
+    if (!(mp == 32 || mp == 64 || mp == 128)) return false;
+    if (L.gated && mp == 128) return false;  // accumulators of both branches would not fit
+    return L.d_model % kDownCols == 0 && L.n_experts <= 8192;
 }
 
 void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     LaunchTimer tm(kSlotPack, s);
-    pack_down_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_down, (__bf16*)packed, L.n_experts,
-                                          L.expert_size, L.d_model, m_pad_of(L.expert_size));
+    const PackedLayout P = packed_layout(L);
+    const int mp = m_pad_of(L.expert_size);
+    char* pk = static_cast<char*>(packed);
+    pack_down_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_down, (__bf16*)(pk + P.w2f),
+                                          L.n_experts, L.expert_size, L.d_model, mp / 32);
+    pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_up, (__bf16*)(pk + P.wupf), L.n_experts,
+                                        L.expert_size, L.d_model, mp / 16);
+    if (L.gated)
+        pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_gate, (__bf16*)(pk + P.wgatef),
+                                            L.n_experts, L.expert_size, L.d_model, mp / 16);
 }
 
 void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* offsets,
                     const int32_t* item_start, const int32_t* token_lists, void* H,
                     hipStream_t s) {
     LaunchTimer tm(kSlotUp, s);
-    // persistent wavefronts: enough to cover the worst case once, capped at a few per SIMD
-    const long long worst = (long long)T * L.n_experts / kUpRows + L.n_experts;
-    const int grid = (int)std::min<long long>(div_up((int)std::min<long long>(worst, 1 << 30), 4),
-                                              256 * 8);
+    const PackedLayout P = packed_layout(L);
+    // persistent wavefronts: enough to cover the worst case once, capped at two workgroups per CU
+    const long long worst = (long long)T * L.n_experts / up_rows_bf16(L) + L.n_experts;
+    const int grid = (int)std::min<long long>((worst + 3) / 4, 256 * 2);
     const int mt = m_pad_of(L.expert_size) / 16;
     if (L.gated) {
-        if (mt == 2) launch_up_t<2, true>(L, x, offsets, item_start, token_lists, H, grid, s);
-        else if (mt == 4) launch_up_t<4, true>(L, x, offsets, item_start, token_lists, H, grid, s);
-        else launch_up_t<8, true>(L, x, offsets, item_start, token_lists, H, grid, s);
+        if (mt == 2) launch_up_t<2, true, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
+        else launch_up_t<4, true, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
     } else {
-        if (mt == 2) launch_up_t<2, false>(L, x, offsets, item_start, token_lists, H, grid, s);
-        else if (mt == 4) launch_up_t<4, false>(L, x, offsets, item_start, token_lists, H, grid, s);
-        else launch_up_t<8, false>(L, x, offsets, item_start, token_lists, H, grid, s);
+        if (mt == 2) launch_up_t<2, false, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
+        else if (mt == 4) launch_up_t<4, false, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
+        else launch_up_t<8, false, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
     }
 }
 
-void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* group_off,
-                      const int32_t* token_lists, const void* H, void* y, hipStream_t s) {
+void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* item_start,
+                      const int32_t* group_off, const int32_t* token_lists, const void* H, void* y,
+                      hipStream_t s) {
     LaunchTimer tm(kSlotDown, s);
+    const PackedLayout P = packed_layout(L);
     const int ks = m_pad_of(L.expert_size) / 32;
-    if (ks == 1) launch_down_t<1>(L, T, offsets, group_off, token_lists, H, y, s);
-    else if (ks == 2) launch_down_t<2>(L, T, offsets, group_off, token_lists, H, y, s);
-    else launch_down_t<4>(L, T, offsets, group_off, token_lists, H, y, s);
+    if (ks == 1) launch_down_t<1>(L, P, T, offsets, item_start, group_off, token_lists, H, y, s);
+    else if (ks == 2) launch_down_t<2>(L, P, T, offsets, item_start, group_off, token_lists, H, y, s);
+    else launch_down_t<4>(L, P, T, offsets, item_start, group_off, token_lists, H, y, s);
 }
 
 }  // namespace dmoe

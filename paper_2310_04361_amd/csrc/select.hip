@@ -146,18 +146,20 @@ __global__ __launch_bounds__(256) void scan_groups_kernel(int32_t* __restrict__ 
 }
 
 // One wavefront: prefix sums over the experts.  offsets[e] = list start, item_start[e] = first
-// up-projection work item of expert e when every item covers rows_per_item list rows.
+// up-projection work item of expert e when every item covers rows_per_item list rows;
+// item_start[E] = number of items, item_start[E+1] = the largest per-expert item count.
 __global__ __launch_bounds__(64) void scan_experts_kernel(const int32_t* __restrict__ totals, int E,
                                                           int rows_per_item,
                                                           int32_t* __restrict__ counts,
                                                           int32_t* __restrict__ offsets,
                                                           int32_t* __restrict__ item_start) {
     const int lane = lane_id();
-    int carry = 0, icarry = 0;
+    int carry = 0, icarry = 0, imax = 0;
     for (int base = 0; base < E; base += kWave) {
         const int e = base + lane;
         const int c = e < E ? totals[e] : 0;
         const int items = (c + rows_per_item - 1) / rows_per_item;
+        imax = max(imax, items);
         const int incl = wave_inclusive_scan(c);
         const int iincl = wave_inclusive_scan(items);
         if (e < E) {
@@ -168,9 +170,14 @@ __global__ __launch_bounds__(64) void scan_experts_kernel(const int32_t* __restr
         carry += __shfl(incl, kWave - 1, kWave);
         icarry += __shfl(iincl, kWave - 1, kWave);
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) imax = max(imax, __shfl_xor(imax, off, kWave));
     if (lane == 0) {
         offsets[E] = carry;
-        if (item_start) item_start[E] = icarry;
+        if (item_start) {
+            item_start[E] = icarry;
+            item_start[E + 1] = imax;  // the largest number of work items of any expert
+        }
     }
 }
 
@@ -180,7 +187,8 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const uint64_t* __restr
                                                          int E, int W,
                                                          const int32_t* __restrict__ group_off,
                                                          const int32_t* __restrict__ offsets,
-                                                         int32_t* __restrict__ lists) {
+                                                         int32_t* __restrict__ lists,
+                                                         int32_t* __restrict__ lists_copy) {
     const int lane = lane_id();
     const int g = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int NG = (T + kGroup - 1) / kGroup;
@@ -196,7 +204,11 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(const uint64_t* __restr
             if (bal == 0ull) continue;  // uniform
             const int e = 64 * w + b;
             const int base = offsets[e] + group_off[(size_t)g * E + e];
-            if ((word >> b) & 1ull) lists[base + __popcll(bal & below)] = t;
+            if ((word >> b) & 1ull) {
+                const int p = base + __popcll(bal & below);
+                lists[p] = t;
+                if (lists_copy) lists_copy[p] = t;
+            }
         }
     }
 }
@@ -228,7 +240,7 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
 
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
-                          int32_t* token_lists, hipStream_t s) {
+                          int32_t* token_lists, int32_t* token_lists_copy, hipStream_t s) {
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     {
         LaunchTimer tm(kSlotScanGroups, s);
@@ -242,7 +254,7 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
     if (token_lists) {
         LaunchTimer tm(kSlotFill, s);
         fill_lists_kernel<<<div_up(NG, 4), 256, 0, s>>>(mask, T, E, W, group_off, offsets,
-                                                        token_lists);
+                                                        token_lists, token_lists_copy);
     }
 }
 

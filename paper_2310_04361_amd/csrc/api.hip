@@ -24,7 +24,7 @@ int fail(int code, const char* fmt, ...) {
 
 // ---- timing ------------------------------------------------------------------------------------
 const char* const kSlotNames[kSlotCount] = {
-    "router", "mask_count", "lists_to_mask", "scan_groups", "scan_experts", "fill_lists",
+    "router", "mask_count", "lists_to_mask", "scan_groups", "fill_lists",
     "expert_up", "expert_down", "ffn_f32", "small_token", "pack_weights"};
 constexpr int kEventPairs = 8192;
 bool g_timing = false;
@@ -92,6 +92,7 @@ int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
 
 int check_tokens(int32_t T, int32_t E) {
     if (T < 0) return fail(DMOE_ERR_SHAPE, "n_tokens is negative");
+    if (E > kMaxExperts) return fail(DMOE_ERR_UNSUPPORTED, "more than %d experts", kMaxExperts);
     if ((long long)T * E > 0x7fffffffLL - 64)
         return fail(DMOE_ERR_SHAPE, "n_tokens * n_experts does not fit the int32 list indices");
     return DMOE_OK;
@@ -144,8 +145,8 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     w.counts = o;     o += align_up(sizeof(int32_t) * (size_t)E);
     w.offsets = o;    o += align_up(sizeof(int32_t) * (size_t)(E + 1));
     w.item_start = o; o += align_up(sizeof(int32_t) * (size_t)(E + 2));
-    // the expert kernels read whole 32-row tiles: pad the lists and H by one tile
-    w.lists = o;      o += align_up(sizeof(int32_t) * ((size_t)T * E + kTilePad));
+    // token lists aligned to work items: one entry per row of H
+    w.lists = o;      o += align_up(sizeof(int32_t) * h_fragments(L, T) * 16);
     w.H = o;
     if (L.dtype == DMOE_BF16) o += align_up(h_fragments(L, T) * (m_pad_of(L.expert_size) / 32) * 1024);
     w.total = o;
@@ -159,8 +160,8 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
     int32_t* counts = reinterpret_cast<int32_t*>(ws + w.counts);
     int32_t* offsets = offsets_out ? offsets_out : reinterpret_cast<int32_t*>(ws + w.offsets);
-    // the kernels always read the workspace copy (padded by one tile); the caller's is a copy
-    int32_t* lists = reinterpret_cast<int32_t*>(ws + w.lists);
+    // the kernels read the work-item-aligned copy in the workspace; the caller's is compact
+    int32_t* alist = reinterpret_cast<int32_t*>(ws + w.lists);
     int32_t* item_start = reinterpret_cast<int32_t*>(ws + w.item_start);
     if (L.dtype == DMOE_F32) {
         if (offsets_out)
@@ -169,10 +170,10 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
         launch_ffn_f32(L, (const float*)x, T, mask, (float*)y, s);
     } else {
         launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, item_start,
-                             up_rows_bf16(L), lists, lists_out, s);
+                             up_rows_bf16(L), lists_out, alist, s);
         void* H = ws + w.H;
-        launch_up_bf16(L, x, T, offsets, item_start, lists, H, s);
-        launch_down_bf16(L, T, offsets, item_start, group_off, lists, H, y, s);
+        launch_up_bf16(L, x, T, item_start, alist, H, s);
+        launch_down_bf16(L, T, item_start, group_off, alist, H, y, s);
     }
     return check_launch("expert kernels");
 }
@@ -246,8 +247,11 @@ int32_t dmoe_router(const dmoe_layer* layer, const void* x, int32_t n_tokens, fl
     if (int rc = check_tokens(n_tokens, layer->n_experts)) return rc;
     if (n_tokens == 0) return DMOE_OK;
     if (!x || !scores) return fail(DMOE_ERR_NULL, "x or scores is NULL");
-    if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, (hipStream_t)stream);
-    else launch_router_bf16(*layer, x, n_tokens, scores, (hipStream_t)stream);
+    hipStream_t s = (hipStream_t)stream;
+    if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
+    else if (router_fused_supported(*layer))
+        launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, s);
+    else launch_router_bf16(*layer, x, n_tokens, scores, s);
     return check_launch("router");
 }
 
@@ -305,11 +309,15 @@ int32_t dmoe_forward(const dmoe_layer* layer, const void* x, int32_t n_tokens, f
     char* ws = static_cast<char*>(workspace);
     hipStream_t s = (hipStream_t)stream;
     float* scores = scores_out ? scores_out : reinterpret_cast<float*>(ws + w.scores);
-    if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
-    else launch_router_bf16(*layer, x, n_tokens, scores, s);
     uint64_t* mask = mask_out ? mask_out : reinterpret_cast<uint64_t*>(ws + w.mask);
-    launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr,
-                            reinterpret_cast<int32_t*>(ws + w.group_off), s);
+    int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
+    if (layer->dtype == DMOE_BF16 && router_fused_supported(*layer)) {
+        launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, s);
+    } else {
+        if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
+        else launch_router_bf16(*layer, x, n_tokens, scores, s);
+        launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr, group_off, s);
+    }
     return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s);
 }
 

@@ -30,7 +30,7 @@ inline size_t h_fragments(const dmoe_layer& L, int T) {
 
 // Sub-buffers of the packed-weights buffer (bytes from its start).
 struct PackedLayout {
-    size_t w2f, wupf, wgatef, total;
+    size_t w2f, wupf, wgatef, r1f, r2f, total;
 };
 inline PackedLayout packed_layout(const dmoe_layer& L) {
     PackedLayout P{};
@@ -40,7 +40,13 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
     P.w2f = 0;
     P.wupf = one;
     P.wgatef = 2 * one;
-    P.total = (L.gated ? 3 : 2) * one;
+    size_t o = (L.gated ? 3 : 2) * one;
+    // router weights as fragments: r1f[d_h/16][d/32][64][8], r2f[ceil(E/16)][d_h/32][64][8]
+    P.r1f = o;
+    o += (2 * (size_t)round_up(L.router_hidden > 0 ? L.router_hidden : 0, 16) * L.d_model + 255) / 256 * 256;
+    P.r2f = o;
+    o += (2 * (size_t)round_up(L.n_experts, 16) * round_up(L.router_hidden > 0 ? L.router_hidden : 0, 32) + 255) / 256 * 256;
+    P.total = o;
     return P;
 }
 
@@ -50,7 +56,6 @@ enum Slot {
     kSlotMask,
     kSlotListsToMask,
     kSlotScanGroups,
-    kSlotScanExperts,
     kSlotFill,
     kSlotUp,
     kSlotDown,
@@ -78,22 +83,27 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
                             uint64_t* mask, int32_t* group_off, hipStream_t s);
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
-                          int32_t* token_lists, int32_t* token_lists_copy, hipStream_t s);
+                          int32_t* token_lists, int32_t* aligned_lists, hipStream_t s);
+constexpr int kMaxExperts = 4096;  // the list fill keeps 2 ints per expert in LDS
 
 // ---- router (router.hip) ----------------------------------------------------------------------
 void launch_router_f32(const dmoe_layer& L, const float* x, int T, float* scores, hipStream_t s);
 void launch_router_bf16(const dmoe_layer& L, const void* x, int T, float* scores, hipStream_t s);
+// Fused router + gate + group counts (router_fused.hip); mask == nullptr runs the router alone.
+bool router_fused_supported(const dmoe_layer& L);
+void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,
+                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt, hipStream_t s);
 
 // ---- experts ----------------------------------------------------------------------------------
 void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* mask, float* y,
                     hipStream_t s);
 void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s);
 // H holds the hidden activations in 16-row MFMA fragments (layout: see ffn_bf16.hip).
-void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* offsets,
-                    const int32_t* item_start, const int32_t* token_lists, void* H,
-                    hipStream_t s);
-void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* item_start,
-                      const int32_t* group_off, const int32_t* token_lists, const void* H, void* y,
+// alist is the work-item-aligned token list (see select.hip); its index is the row index of H.
+void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* item_start,
+                    const int32_t* alist, void* H, hipStream_t s);
+void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
+                      const int32_t* group_off, const int32_t* alist, const void* H, void* y,
                       hipStream_t s);
 
 bool experts_bf16_supported(const dmoe_layer& L);

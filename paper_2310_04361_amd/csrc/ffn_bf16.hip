@@ -36,7 +36,7 @@ constexpr int kDownBatch = 128;                // experts per tile-list batch
 constexpr int kDownTilesPerExpert = (kChunk / 16 + 2) / 2;   // fragment pairs a chunk can span
 constexpr int kDownStride = kDownCols + 4;     // LDS row stride in floats
 constexpr size_t kDownLds = sizeof(float) * kChunk * kDownStride +
-                            sizeof(int4) * kDownBatch * kDownTilesPerExpert;
+                            sizeof(int2) * kDownBatch * kDownTilesPerExpert;
 constexpr int kUpRowBytes = 144;               // 64 bf16 of one x row + 16 bytes of bank skew
 
 // ---- activations (fp32 in, fp32 out) -------------------------------------------------------------
@@ -112,8 +112,8 @@ template <int MT, bool GATED, int TT>
 __global__ __launch_bounds__(256) void up_bf16_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
     const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ item_start,
-    const int32_t* __restrict__ lists, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
+    const int32_t* __restrict__ item_start, const int32_t* __restrict__ alist,
+    __bf16* __restrict__ Hf, int d, int E, int m, int act) {
     constexpr int BR = GATED ? 2 : 1;
     constexpr int KS = MT / 2;
     constexpr int UR = TT * 16;
@@ -143,13 +143,13 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
             if (s_items[mid] <= item) lo = mid; else hi = mid;
         }
         const int e = lo;
-        const int p0 = offsets[e] + (item - s_items[e]) * UR;
-        const int pend = offsets[e + 1];
-
+        // rows of the aligned list past the expert's last token hold -1: they read token 0 and
+        // produce H rows that nobody merges
+        const int32_t* tl = alist + (size_t)item * UR + ld_row;
         const __bf16* xrow[NL];
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            const int tok = lists[min(p0 + 8 * i + ld_row, pend - 1)];
+            const int tok = max(tl[8 * i], 0);
             xrow[i] = x + (size_t)tok * d + 8 * ld_piece;
         }
         const __bf16* wf[BR];
@@ -275,15 +275,14 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
 template <int KS>
 __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
     const __bf16* __restrict__ w2f, const __bf16* __restrict__ b_down,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ item_start,
-    const int32_t* __restrict__ group_off, const int32_t* __restrict__ lists,
-    const __bf16* __restrict__ Hf, __bf16* __restrict__ y, int T, int d, int E, int NG,
-    int frags_per_item) {
+    const int32_t* __restrict__ item_start, const int32_t* __restrict__ group_off,
+    const int32_t* __restrict__ alist, const __bf16* __restrict__ Hf, __bf16* __restrict__ y, int T,
+    int d, int E, int NG, int frags_per_item) {
     constexpr int kThreads = kDownWaves * 64;
     constexpr int kDepth = KS <= 2 ? 4 : 2;  // tiles of operands in flight per wavefront
     extern __shared__ float smem_f[];
     float* Y = smem_f;  // [kChunk][kDownStride]
-    int4* tiles = reinterpret_cast<int4*>(smem_f + kChunk * kDownStride);
+    int2* tiles = reinterpret_cast<int2*>(smem_f + kChunk * kDownStride);
     __shared__ int s_wave_tot[kDownWaves];
     // The slices of one chunk share its H rows and token lists: keep them on one XCD (workgroups
     // are dealt round-robin to the 8 XCDs) and next to each other in launch order.
@@ -315,15 +314,15 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
     for (int ebase = 0; ebase < E; ebase += kDownBatch) {
         __syncthreads();  // Y initialised / previous batch's tile list no longer read
         // ---- tile list of this batch: thread i < kDownBatch describes expert ebase + i
-        int lo = 0, hi = 0, f0 = 0, nt_mine = 0, list0 = 0, frag0 = 0;
+        int f0 = 0, nt_mine = 0, frag0 = 0;
         const int e_mine = ebase + tid;
         if (tid < kDownBatch && e_mine < E) {
-            lo = group_off[(size_t)g_lo * E + e_mine];
-            hi = group_off[(size_t)g_hi * E + e_mine];
+            // rows lo .. hi-1 of expert e_mine's list belong to this chunk
+            const int lo = group_off[(size_t)g_lo * E + e_mine];
+            const int hi = group_off[(size_t)g_hi * E + e_mine];
             if (hi > lo) {
                 f0 = lo >> 4;
                 nt_mine = (((hi - 1) >> 4) - f0 + 2) >> 1;
-                list0 = offsets[e_mine];
                 frag0 = item_start[e_mine] * frags_per_item;
             }
         }
@@ -341,30 +340,23 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
             if (w2 < wave) start += v;
             ntiles += v;
         }
-        for (int k = 0; k < nt_mine; ++k) {
-            const int r0 = 16 * (f0 + 2 * k);  // first list row (within the expert) of the tile
-            const int first = max(lo - r0, 0), last = min(hi - r0, 32);
-            tiles[start + k] = make_int4(frag0 + f0 + 2 * k, list0 + r0, e_mine, first | (last << 8));
-        }
+        for (int k = 0; k < nt_mine; ++k) tiles[start + k] = make_int2(frag0 + f0 + 2 * k, e_mine);
         __syncthreads();
         // ---- walk the tiles with a ring of kDepth tiles of operands in flight
         bf16x8 a_st[kDepth][2][KS], b_st[kDepth][2][KS];
-        int tok_st[kDepth][2], win_st[kDepth];
-        // Issues the loads only; nothing here waits on them (token ids stay raw until the tile
-        // is consumed), so kDepth tiles of loads overlap.  The tile entry is uniform: its address
-        // arithmetic stays on the scalar unit and every lane adds only its fixed offset.  Tiles
-        // past the end reload the last one with an empty row window.  Rows outside the window
-        // are read too (the buffers are padded): they only feed MFMA columns of lanes that skip
-        // the merge.
-        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2], int& win) {
-            const int4 ent = tiles[min(ti, ntiles - 1)];
+        int tok_st[kDepth][2];
+        // Issues the loads only; nothing here waits on them, so kDepth tiles of loads overlap.
+        // The tile entry is uniform: its address arithmetic stays on the scalar unit and every
+        // lane adds only its fixed offset.  Tiles past the end reload the last one with token
+        // ids of -1.  A tile's rows that belong to other chunks are read too: they only feed MFMA
+        // columns of lanes that skip the merge.
+        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2]) {
+            const int2 ent = tiles[min(ti, ntiles - 1)];
             const int frag = __builtin_amdgcn_readfirstlane(ent.x);
-            const int lpos = __builtin_amdgcn_readfirstlane(ent.y);
-            const int e = __builtin_amdgcn_readfirstlane(ent.z);
-            const int w = __builtin_amdgcn_readfirstlane(ent.w);
+            const int e = __builtin_amdgcn_readfirstlane(ent.y);
             const __bf16* wp = wbase + (size_t)e * w_expert_stride;
             const __bf16* hp = hbase + (size_t)frag * KS * 512;
-            const int32_t* lp = lists + lpos;
+            const int32_t* lp = alist + (size_t)frag * 16;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
 #pragma unroll
@@ -372,14 +364,13 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
                     a[h][ks] = load8(wp + (h * KS + ks) * 512);
                     b[h][ks] = load8(hp + (h * KS + ks) * 512);
                 }
-                tok[h] = lp[16 * h + c];
+                tok[h] = ti < ntiles ? lp[16 * h + c] : -1;
             }
-            win = ti < ntiles ? w : 0;
         };
         if (ntiles > 0) {
 #pragma unroll
             for (int st = 0; st < kDepth; ++st)
-                fetch(st, a_st[st], b_st[st], tok_st[st], win_st[st]);
+                fetch(st, a_st[st], b_st[st], tok_st[st]);
         }
         for (int t0 = 0; t0 < ntiles; t0 += kDepth) {
 #pragma unroll
@@ -387,7 +378,6 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
                 // keep each stage's work inside the stage: hoisting a later stage's first use of
                 // its loads up here would make this stage wait for them as well
                 __builtin_amdgcn_sched_barrier(0);
-                const int first = win_st[st] & 0xff, last = win_st[st] >> 8;
                 f32x4 acc[2][2];  // [column tile nt][token tile tt]
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
@@ -406,14 +396,14 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
                 asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]),
                                   "+v"(tok0), "+v"(tok1));
                 __builtin_amdgcn_sched_barrier(0);
-                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st], win_st[st]);
+                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st]);
 
                 // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of tile row tt*16 + c
                 const int tok[2] = {tok0, tok1};
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {
-                    const int row = 16 * tt + c;
-                    if (row >= first && row < last) {
+                    // rows of other chunks and the -1 slack fail this test
+                    if ((unsigned)(tok[tt] - t_base) < (unsigned)kChunk) {
                         float4* yp = reinterpret_cast<float4*>(ybase + tok[tt] * kDownStride);
                         float4 o0 = yp[0], o1 = yp[4];
                         o0.x += acc[0][tt][0]; o0.y += acc[0][tt][1];
@@ -444,8 +434,8 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
 
 // ---- launchers ---------------------------------------------------------------------------------------
 template <int MT, bool GATED, int TT>
-void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, const int32_t* offsets,
-                 const int32_t* item_start, const int32_t* lists, void* H, int grid,
+void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
+                 const int32_t* item_start, const int32_t* alist, void* H, int grid,
                  hipStream_t s) {
     const size_t lds = (((size_t)L.n_experts + 2) * 4 + 15) / 16 * 16 +
                        4 * 2 * (size_t)TT * 16 * kUpRowBytes;
@@ -458,14 +448,14 @@ void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, cons
     const char* pk = static_cast<const char*>(L.packed);
     up_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
-        (const __bf16*)L.b_up, offsets, item_start, lists, (__bf16*)H, L.d_model, L.n_experts,
+        (const __bf16*)L.b_up, item_start, alist, (__bf16*)H, L.d_model, L.n_experts,
         L.expert_size, L.act);
 }
 
 template <int KS>
-void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* offsets,
-                   const int32_t* item_start, const int32_t* group_off, const int32_t* lists,
-                   const void* H, void* y, hipStream_t s) {
+void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* item_start,
+                   const int32_t* group_off, const int32_t* alist, const void* H, void* y,
+                   hipStream_t s) {
     const int NG = div_up(T, kGroup), NC = div_up(T, kChunk), NS = L.d_model / kDownCols;
     static bool attr_set = false;
     if (!attr_set) {
@@ -475,7 +465,7 @@ void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int3
     }
     const char* pk = static_cast<const char*>(L.packed);
     down_bf16_kernel<KS><<<round_up(NC, 8) * NS, kDownWaves * 64, kDownLds, s>>>(
-        (const __bf16*)(pk + P.w2f), (const __bf16*)L.b_down, offsets, item_start, group_off, lists,
+        (const __bf16*)(pk + P.w2f), (const __bf16*)L.b_down, item_start, group_off, alist,
         (const __bf16*)H, (__bf16*)y, T, L.d_model, L.n_experts, NG, up_rows_bf16(L) / 16);
 }
 
@@ -500,11 +490,19 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     if (L.gated)
         pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_gate, (__bf16*)(pk + P.wgatef),
                                             L.n_experts, L.expert_size, L.d_model, mp / 16);
+    // the router matrices use the same fragment format: "one expert" whose rows are the hidden
+    // units (r_w1) or the experts (r_w2)
+    const int dh = L.router_hidden;
+    if (L.r_w1 && L.r_w2 && dh > 0 && dh % 32 == 0 && L.d_model % 32 == 0) {
+        pack_up_kernel<<<512, 256, 0, s>>>((const __bf16*)L.r_w1, (__bf16*)(pk + P.r1f), 1, dh,
+                                           L.d_model, dh / 16);
+        pack_up_kernel<<<512, 256, 0, s>>>((const __bf16*)L.r_w2, (__bf16*)(pk + P.r2f), 1,
+                                           L.n_experts, dh, div_up(L.n_experts, 16));
+    }
 }
 
-void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* offsets,
-                    const int32_t* item_start, const int32_t* token_lists, void* H,
-                    hipStream_t s) {
+void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* item_start,
+                    const int32_t* alist, void* H, hipStream_t s) {
     LaunchTimer tm(kSlotUp, s);
     const PackedLayout P = packed_layout(L);
     // persistent wavefronts: enough to cover the worst case once, capped at two workgroups per CU
@@ -512,24 +510,24 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* of
     const int grid = (int)std::min<long long>((worst + 3) / 4, 256 * 2);
     const int mt = m_pad_of(L.expert_size) / 16;
     if (L.gated) {
-        if (mt == 2) launch_up_t<2, true, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
-        else launch_up_t<4, true, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
+        if (mt == 2) launch_up_t<2, true, 4>(L, x, P, item_start, alist, H, grid, s);
+        else launch_up_t<4, true, 4>(L, x, P, item_start, alist, H, grid, s);
     } else {
-        if (mt == 2) launch_up_t<2, false, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
-        else if (mt == 4) launch_up_t<4, false, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
-        else launch_up_t<8, false, 4>(L, x, P, offsets, item_start, token_lists, H, grid, s);
+        if (mt == 2) launch_up_t<2, false, 4>(L, x, P, item_start, alist, H, grid, s);
+        else if (mt == 4) launch_up_t<4, false, 4>(L, x, P, item_start, alist, H, grid, s);
+        else launch_up_t<8, false, 4>(L, x, P, item_start, alist, H, grid, s);
     }
 }
 
-void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* offsets, const int32_t* item_start,
-                      const int32_t* group_off, const int32_t* token_lists, const void* H, void* y,
+void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
+                      const int32_t* group_off, const int32_t* alist, const void* H, void* y,
                       hipStream_t s) {
     LaunchTimer tm(kSlotDown, s);
     const PackedLayout P = packed_layout(L);
     const int ks = m_pad_of(L.expert_size) / 32;
-    if (ks == 1) launch_down_t<1>(L, P, T, offsets, item_start, group_off, token_lists, H, y, s);
-    else if (ks == 2) launch_down_t<2>(L, P, T, offsets, item_start, group_off, token_lists, H, y, s);
-    else launch_down_t<4>(L, P, T, offsets, item_start, group_off, token_lists, H, y, s);
+    if (ks == 1) launch_down_t<1>(L, P, T, item_start, group_off, alist, H, y, s);
+    else if (ks == 2) launch_down_t<2>(L, P, T, item_start, group_off, alist, H, y, s);
+    else launch_down_t<4>(L, P, T, item_start, group_off, alist, H, y, s);
 }
 
 }  // namespace dmoe

@@ -1,0 +1,287 @@
+// Router (Sec. 3.3) fused with the dynamic-k gate (Sec. 3.4 Eq. 4) and the per-group expert counts
+// that start the bucketing: one workgroup per group of 64 tokens.
+//
+//   stage 1  hid^T[d_h][64] = R1 * x^T.  The 64 x rows are staged through LDS in K blocks of 64
+//            (eight lanes per 128-byte row piece, double-buffered, one barrier per block); each
+//            of the four wavefronts owns a quarter of the hidden units and reads R1 as packed
+//            MFMA fragments.  bias + relu, round to bf16, park the hidden tile in LDS.
+//   stage 2  s^T[E][64] = R2 * hid^T.  Each wavefront owns every fourth tile of 16 experts, reads
+//            R2 as packed fragments and the hidden tile from LDS; |. + c2| goes to `scores`
+//            (fp32, 16 bytes per lane) and stays in registers for
+//   select   per-token maximum across the four wavefronts (LDS), the exact comparison
+//            (double)s >= (double)tau * (double)max on those very fp32 scores, mask words
+//            assembled per token, then the 64x64 ballot transpose that counts, per expert, the
+//            tokens of the group that keep it.
+// The scores that are written and the mask come from the same registers, so a caller that gates
+// the returned scores again gets the same mask bit for bit.
+#include "dmoe_internal.h"
+#include "mfma.h"
+
+namespace dmoe {
+
+namespace {
+
+constexpr int kXRow = 144;      // bytes per staged x row: 64 bf16 + 16 bytes of bank skew
+constexpr int kMaxTilesPerWave = 8;   // expert tiles per wavefront: E <= 4 * 8 * 16 = 512
+
+// NH = d_h / 16; ETW = expert tiles per wavefront (E <= 64 * ETW).
+template <int NH, int ETW>
+__global__ __launch_bounds__(256) void router_fused_kernel(
+    const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
+    const __bf16* __restrict__ r2f, const __bf16* __restrict__ r_b2, float* __restrict__ scores,
+    int T, int d, int E, float tau, int do_select, uint64_t* __restrict__ mask,
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ group_cnt) {
+    constexpr int dh = NH * 16, HT = NH / 4, KS2 = dh / 32;
+    constexpr int kHRow = dh * 2 + 16;  // bytes per hidden row in LDS
+    extern __shared__ char smem[];
+    char* xs = smem;                                            // [2][64][kXRow]
+    char* hid = smem + 2 * 64 * kXRow;                          // [64][kHRow]
+    float* pmax = reinterpret_cast<float*>(hid + 64 * kHRow);   // [4][64]
+    uint64_t* pw = reinterpret_cast<uint64_t*>(pmax + 256);     // [4][64][W]
+    const int W = (E + 63) >> 6;
+    uint64_t* fin = pw + 4 * 64 * W;                            // [64][W]
+
+    const int g = blockIdx.x, t0 = g * 64;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
+    const int NK32 = d / 32, NKB = d / 64;
+
+    // ---------------------------------------------------------------- stage 1
+    const int ld_row = tid >> 3, ld_piece = tid & 7;
+    const __bf16* xp0 = x + (size_t)min(t0 + ld_row, T - 1) * d + 8 * ld_piece;
+    const __bf16* xp1 = x + (size_t)min(t0 + ld_row + 32, T - 1) * d + 8 * ld_piece;
+    char* xst = xs + ld_row * kXRow + ld_piece * 16;
+    const __bf16* af = r1f + ((size_t)w * HT * NK32 * 64 + lane) * 8;
+
+    f32x4 acc[HT][4];
+#pragma unroll
+    for (int h = 0; h < HT; ++h)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) acc[h][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    bf16x8 xr0, xr1, a0[2][HT], a1[2][HT];
+    auto load_x = [&](int kb) {
+        xr0 = load8(xp0 + 64 * kb);
+        xr1 = load8(xp1 + 64 * kb);
+    };
+    auto load_a = [&](int kb, bf16x8 (&a)[2][HT]) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int h = 0; h < HT; ++h) a[ks][h] = load8(af + ((size_t)h * NK32 + 2 * kb + ks) * 512);
+    };
+    auto store_x = [&](int buf) {
+        *reinterpret_cast<bf16x8*>(xst + buf * 64 * kXRow) = xr0;
+        *reinterpret_cast<bf16x8*>(xst + buf * 64 * kXRow + 32 * kXRow) = xr1;
+    };
+    auto compute = [&](int buf, const bf16x8 (&a)[2][HT]) {
+        const char* src = xs + buf * 64 * kXRow + c * kXRow + q * 16;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 b[4];
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt)
+                b[tt] = *reinterpret_cast<const bf16x8*>(src + tt * 16 * kXRow + ks * 64);
+#pragma unroll
+            for (int h = 0; h < HT; ++h)
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) acc[h][tt] = mfma16(a[ks][h], b[tt], acc[h][tt]);
+        }
+    };
+
+    load_x(0);
+    load_a(0, a0);
+    store_x(0);
+    __syncthreads();
+    for (int kb = 0; kb < NKB; kb += 2) {  // NKB is even
+        load_x(kb + 1);
+        load_a(kb + 1, a1);
+        compute(0, a0);
+        store_x(1);
+        __syncthreads();
+        const int nb = min(kb + 2, NKB - 1);  // the last trip re-reads a block it will not use
+        load_x(nb);
+        load_a(nb, a0);
+        compute(1, a1);
+        store_x(0);
+        __syncthreads();
+    }
+
+    // lane (q, c) of tile (h, tt): hidden units 16*(w*HT + h) + 4q + r of token 16tt + c
+#pragma unroll
+    for (int h = 0; h < HT; ++h) {
+        const int hu0 = 16 * (w * HT + h) + 4 * q;
+        float b1[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r_b1) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) b1[r] = (float)r_b1[hu0 + r];
+        }
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            bf16x4 hv;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) hv[r] = (__bf16)fmaxf(acc[h][tt][r] + b1[r], 0.0f);
+            *reinterpret_cast<bf16x4*>(hid + (16 * tt + c) * kHRow + hu0 * 2) = hv;
+        }
+    }
+    __syncthreads();
+
+    // ---------------------------------------------------------------- stage 2
+    const int NE = (E + 15) >> 4;
+    float sc[ETW][4][4];  // [my tile][token tile][r]
+    float vmax[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < ETW; ++j) {
+        const int et = w + 4 * j;
+        if (et < NE) {  // uniform per wavefront
+            f32x4 a2[4];
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) a2[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS2; ++ks) {
+                const bf16x8 a = load8(r2f + (((size_t)et * KS2 + ks) * 64 + lane) * 8);
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    const bf16x8 b = *reinterpret_cast<const bf16x8*>(
+                        hid + (16 * tt + c) * kHRow + ks * 64 + q * 16);
+                    a2[tt] = mfma16(a, b, a2[tt]);
+                }
+            }
+            const int e0 = 16 * et + 4 * q;  // this lane: experts e0 .. e0+3
+            float b2[4] = {0.f, 0.f, 0.f, 0.f};
+            if (r_b2 && e0 < E) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) b2[r] = (float)r_b2[e0 + r];
+            }
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const int t = t0 + 16 * tt + c;
+                float4 out;
+                out.x = fabsf(a2[tt][0] + b2[0]);
+                out.y = fabsf(a2[tt][1] + b2[1]);
+                out.z = fabsf(a2[tt][2] + b2[2]);
+                out.w = fabsf(a2[tt][3] + b2[3]);
+                if (e0 >= E) out = make_float4(0.f, 0.f, 0.f, 0.f);  // padding experts
+                if (t < T && e0 < E) *reinterpret_cast<float4*>(scores + (size_t)t * E + e0) = out;
+                sc[j][tt][0] = out.x; sc[j][tt][1] = out.y; sc[j][tt][2] = out.z; sc[j][tt][3] = out.w;
+                vmax[tt] = fmaxf(vmax[tt], fmaxf(fmaxf(out.x, out.y), fmaxf(out.z, out.w)));
+            }
+        }
+    }
+    if (!do_select) return;
+
+    // ---------------------------------------------------------------- select
+    // maximum of each token over this wavefront's experts, then over the four wavefronts
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+        float m = vmax[tt];
+        m = fmaxf(m, __shfl_xor(m, 16, 64));
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        if (q == 0) pmax[w * 64 + 16 * tt + c] = m;
+    }
+    __syncthreads();
+    double thr[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+        const int tk = 16 * tt + c;
+        const float m = fmaxf(fmaxf(pmax[tk], pmax[64 + tk]), fmaxf(pmax[128 + tk], pmax[192 + tk]));
+        thr[tt] = (double)tau * (double)m;  // exact: at most 48 significant bits
+    }
+    // this wavefront's bits of each token: tile et fills bits 16*(et%4) .. +15 of word et/4
+    for (int i = tid; i < 4 * 64 * W; i += 256) pw[i] = 0ull;  // (only words we own are rewritten)
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ETW; ++j) {
+        const int et = w + 4 * j;
+        if (et < NE) {
+            const int e0 = 16 * et + 4 * q;
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                uint32_t bits = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const bool keep = (tau == 0.0f) || ((double)sc[j][tt][r] >= thr[tt]);
+                    bits |= (uint32_t)(keep && e0 + r < E) << (4 * q + r);
+                }
+                bits |= __shfl_xor(bits, 16, 64);
+                bits |= __shfl_xor(bits, 32, 64);  // 16 bits: experts 16et .. 16et+15 of token c
+                if (q == (et & 3))                   // one lane group per tile does the write
+                    pw[(w * 64 + 16 * tt + c) * W + (et >> 2)] |= (uint64_t)bits << (16 * (et & 3));
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < 64) {
+        const int t = t0 + tid;
+        int kt = 0;
+        for (int wi = 0; wi < W; ++wi) {
+            const uint64_t word = pw[(0 * 64 + tid) * W + wi] | pw[(1 * 64 + tid) * W + wi] |
+                                  pw[(2 * 64 + tid) * W + wi] | pw[(3 * 64 + tid) * W + wi];
+            fin[tid * W + wi] = t < T ? word : 0ull;
+            if (t < T) mask[(size_t)t * W + wi] = word;
+            kt += __popcll(word);
+        }
+        if (t < T && k_per_token) k_per_token[t] = kt;
+    }
+    __syncthreads();
+    // ballot transpose: lane = token; wavefront w handles words w, w+4, ...
+    for (int wi = w; wi < W; wi += 4) {
+        const uint64_t word = fin[lane * W + wi];
+        int cnt = 0;
+#pragma unroll 8
+        for (int b = 0; b < 64; ++b) {
+            const uint64_t bal = __ballot((word >> b) & 1ull);
+            if (lane == b) cnt = __popcll(bal);
+        }
+        const int e = 64 * wi + lane;
+        if (e < E) group_cnt[(size_t)g * E + e] = cnt;
+    }
+}
+
+template <int NH, int ETW>
+void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
+              int32_t* k_per_token, int32_t* group_cnt, hipStream_t s) {
+    const PackedLayout P = packed_layout(L);
+    const int E = L.n_experts, W = div_up(E, 64);
+    const size_t lds = 2 * 64 * kXRow + 64 * (NH * 32 + 16) + 256 * 4 + (size_t)5 * 64 * W * 8;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_fused_kernel<NH, ETW>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    const char* pk = static_cast<const char*>(L.packed);
+    router_fused_kernel<NH, ETW><<<div_up(T, 64), 256, lds, s>>>(
+        (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1,
+        (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, L.d_model, E, tau,
+        mask != nullptr, mask, k_per_token, group_cnt);
+}
+
+template <int NH>
+void launch_t(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
+              int32_t* k_per_token, int32_t* group_cnt, hipStream_t s) {
+    if (L.n_experts <= 128) launch_t2<NH, 2>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s);
+    else if (L.n_experts <= 256) launch_t2<NH, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s);
+    else launch_t2<NH, 8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s);
+}
+
+}  // namespace
+
+bool router_fused_supported(const dmoe_layer& L) {
+    const int dh = L.router_hidden;
+    return L.packed != nullptr && (dh == 64 || dh == 128 || dh == 256 || dh == 512) &&
+           L.d_model % 128 == 0 && L.n_experts % 4 == 0 && L.n_experts <= 64 * kMaxTilesPerWave;
+}
+
+void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,
+                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt, hipStream_t s) {
+    LaunchTimer tm(kSlotRouter, s);
+    switch (L.router_hidden) {
+    case 64: launch_t<4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
+    case 128: launch_t<8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
+    case 256: launch_t<16>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
+    case 512: launch_t<32>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
+    default: break;  // refused by router_fused_supported
+    }
+}
+
+}  // namespace dmoe

@@ -3,8 +3,8 @@
 //
 // Data flow:  scores -> [mask_count] -> mask bits + per-(group, expert) counts
 //             -> [scan_groups] prefix over token groups per expert
-//             -> [scan_experts] prefix over experts (list offsets, up-projection work items)
-//             -> [fill] ascending per-expert token lists.
+//             -> [fill] prefix over experts (list offsets, up-projection work items) and the
+//                ascending per-expert token lists, compact and work-item aligned.
 // A group is 64 consecutive tokens handled by one wavefront with lane = token; the 64x64 bit
 // transpose between "experts of a token" and "tokens of an expert" is done with ballots.
 #include "dmoe_internal.h"
@@ -145,69 +145,106 @@ __global__ __launch_bounds__(256) void scan_groups_kernel(int32_t* __restrict__ 
     if (lane == 0) group_cnt[(size_t)NG * E + e] = carry;
 }
 
-// One wavefront: prefix sums over the experts.  offsets[e] = list start, item_start[e] = first
-// up-projection work item of expert e when every item covers rows_per_item list rows;
-// item_start[E] = number of items, item_start[E+1] = the largest per-expert item count.
-__global__ __launch_bounds__(64) void scan_experts_kernel(const int32_t* __restrict__ totals, int E,
-                                                          int rows_per_item,
-                                                          int32_t* __restrict__ counts,
-                                                          int32_t* __restrict__ offsets,
-                                                          int32_t* __restrict__ item_start) {
-    const int lane = lane_id();
-    int carry = 0, icarry = 0, imax = 0;
-    for (int base = 0; base < E; base += kWave) {
-        const int e = base + lane;
-        const int c = e < E ? totals[e] : 0;
-        const int items = (c + rows_per_item - 1) / rows_per_item;
-        imax = max(imax, items);
-        const int incl = wave_inclusive_scan(c);
-        const int iincl = wave_inclusive_scan(items);
-        if (e < E) {
-            if (counts) counts[e] = c;
-            offsets[e] = carry + incl - c;
-            if (item_start) item_start[e] = icarry + iincl - items;
-        }
-        carry += __shfl(incl, kWave - 1, kWave);
-        icarry += __shfl(iincl, kWave - 1, kWave);
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) imax = max(imax, __shfl_xor(imax, off, kWave));
-    if (lane == 0) {
-        offsets[E] = carry;
-        if (item_start) {
-            item_start[E] = icarry;
-            item_start[E + 1] = imax;  // the largest number of work items of any expert
-        }
-    }
-}
-
-// One wavefront per group, lane = token: for every expert, the lanes whose token keeps it write
-// their token id at  offsets[e] + group_off[g][e] + (rank among the group's keepers).
-__global__ __launch_bounds__(256) void fill_lists_kernel(const uint64_t* __restrict__ mask, int T,
-                                                         int E, int W,
-                                                         const int32_t* __restrict__ group_off,
-                                                         const int32_t* __restrict__ offsets,
-                                                         int32_t* __restrict__ lists,
-                                                         int32_t* __restrict__ lists_copy) {
-    const int lane = lane_id();
-    const int g = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+// Prefix sums over the experts plus the list fill, one launch.
+//
+// Every workgroup first redoes the (tiny) scan over the per-expert totals in LDS:
+//   s_off[e]  = start of expert e in the compact lists (offsets),
+//   s_item[e] = first up-projection work item of expert e when an item covers rows_per_item list
+//               rows; s_item[E] = number of items.
+// Workgroup 0 also publishes counts / offsets / item_start and pads the aligned list.
+// Then one wavefront per group of 64 tokens (lane = token) turns mask words into list entries:
+// for every expert, the lanes whose token keeps it write their token id at
+//   lists[offsets[e] + group_off[g][e] + rank]                 compact, ascending (caller-visible)
+//   alist[item_start[e] * rows_per_item + group_off[g][e] + rank]   aligned copy for the kernels
+// where rank counts the group's keepers below the lane.  In the aligned copy every expert starts
+// on a work-item boundary -- the same indexing as the rows of H -- and the slack behind its last
+// token holds -1.
+__global__ __launch_bounds__(256) void fill_lists_kernel(
+    const uint64_t* __restrict__ mask, int T, int E, int W, const int32_t* __restrict__ group_off,
+    int rows_per_item, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ item_start, int32_t* __restrict__ lists, int32_t* __restrict__ alist) {
+    extern __shared__ int32_t sm[];
+    int32_t* s_off = sm;                 // [E + 1]
+    int32_t* s_item = sm + (E + 1);      // [E + 1]
+    __shared__ int s_part[2][4];
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int NG = (T + kGroup - 1) / kGroup;
-    if (g >= NG) return;
+    const int32_t* totals = group_off + (size_t)NG * E;
+
+    int carry = 0, icarry = 0;
+    for (int base = 0; base < E; base += 256) {
+        const int e = base + tid;
+        const int cnt = e < E ? totals[e] : 0;
+        const int items = (cnt + rows_per_item - 1) / rows_per_item;
+        const int incl = wave_inclusive_scan(cnt), iincl = wave_inclusive_scan(items);
+        if (lane == kWave - 1) {
+            s_part[0][wave] = incl;
+            s_part[1][wave] = iincl;
+        }
+        __syncthreads();
+        int before = carry, ibefore = icarry, all = 0, iall = 0;
+        for (int w2 = 0; w2 < 4; ++w2) {
+            if (w2 < wave) {
+                before += s_part[0][w2];
+                ibefore += s_part[1][w2];
+            }
+            all += s_part[0][w2];
+            iall += s_part[1][w2];
+        }
+        if (e < E) {
+            s_off[e] = before + incl - cnt;
+            s_item[e] = ibefore + iincl - items;
+        }
+        carry += all;
+        icarry += iall;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        s_off[E] = carry;
+        s_item[E] = icarry;
+    }
+    __syncthreads();
+
+    if (blockIdx.x == 0) {
+        for (int e = tid; e <= E; e += 256) {
+            offsets[e] = s_off[e];
+            if (item_start) item_start[e] = s_item[e];
+            if (e < E && counts) counts[e] = totals[e];
+        }
+        if (alist) {  // -1 behind each expert's last token, up to its next work-item boundary
+            for (int e = wave; e < E; e += 4) {
+                const int first = s_item[e] * rows_per_item + totals[e];
+                const int last = s_item[e + 1] * rows_per_item;
+                for (int p = first + lane; p < last; p += kWave) alist[p] = -1;
+            }
+        }
+    }
+
+    const int g = blockIdx.x * 4 + wave;
+    if (g >= NG || (!lists && !alist)) return;
     const int t = g * kGroup + lane;
     const bool valid = t < T;
     const uint64_t below = (1ull << lane) - 1ull;
     for (int w = 0; w < W; ++w) {
         const uint64_t word = valid ? mask[(size_t)t * W + w] : 0ull;
+        // lane b keeps the three bases of expert 64w + b; the loop below is unrolled, so each
+        // read of them is a constant-lane broadcast on the scalar unit
+        const int e_l = 64 * w + lane;
+        const int goff_l = e_l < E ? group_off[(size_t)g * E + e_l] : 0;
+        const int cbase_l = e_l < E ? s_off[e_l] + goff_l : 0;
+        const int abase_l = e_l < E ? s_item[e_l] * rows_per_item + goff_l : 0;
         const int nb = min(64, E - 64 * w);
-        for (int b = 0; b < nb; ++b) {
-            const uint64_t bal = __ballot((word >> b) & 1ull);
-            if (bal == 0ull) continue;  // uniform
-            const int e = 64 * w + b;
-            const int base = offsets[e] + group_off[(size_t)g * E + e];
-            if ((word >> b) & 1ull) {
-                const int p = base + __popcll(bal & below);
-                lists[p] = t;
-                if (lists_copy) lists_copy[p] = t;
+#pragma unroll
+        for (int b = 0; b < 64; ++b) {
+            const uint64_t bal = __ballot(((word >> b) & 1ull) != 0 && b < nb);
+            if (bal != 0ull) {  // uniform
+                const int cbase = __builtin_amdgcn_readlane(cbase_l, b);
+                const int abase = __builtin_amdgcn_readlane(abase_l, b);
+                if ((word >> b) & 1ull) {
+                    const int rank = __popcll(bal & below);
+                    if (lists) lists[cbase + rank] = t;
+                    if (alist) alist[abase + rank] = t;
+                }
             }
         }
     }
@@ -240,22 +277,23 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
 
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
-                          int32_t* token_lists, int32_t* token_lists_copy, hipStream_t s) {
+                          int32_t* token_lists, int32_t* aligned_lists, hipStream_t s) {
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     {
         LaunchTimer tm(kSlotScanGroups, s);
         scan_groups_kernel<<<div_up(E, 4), 256, 0, s>>>(group_off, NG, E);
     }
-    {
-        LaunchTimer tm(kSlotScanExperts, s);
-        scan_experts_kernel<<<1, 64, 0, s>>>(group_off + (size_t)NG * E, E, rows_per_item, counts,
-                                             offsets, item_start);
+    LaunchTimer tm(kSlotFill, s);
+    const size_t lds = sizeof(int32_t) * 2 * ((size_t)E + 1);
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&fill_lists_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        attr_set = true;
     }
-    if (token_lists) {
-        LaunchTimer tm(kSlotFill, s);
-        fill_lists_kernel<<<div_up(NG, 4), 256, 0, s>>>(mask, T, E, W, group_off, offsets,
-                                                        token_lists, token_lists_copy);
-    }
+    fill_lists_kernel<<<std::max(1, div_up(NG, 4)), 256, lds, s>>>(
+        mask, T, E, W, group_off, rows_per_item, counts, offsets, item_start, token_lists,
+        aligned_lists);
 }
 
 }  // namespace dmoe

@@ -60,7 +60,8 @@ def test_workspace_sizes(lib):
     assert lib.dmoe_select_workspace_bytes(100, 0, ctypes.byref(n)) == B.DMOE_ERR_SHAPE
     Lb = _layer(dtype=B.DMOE_BF16, expert_size=24)
     assert lib.dmoe_packed_bytes(ctypes.byref(Lb), ctypes.byref(n)) == B.DMOE_OK
-    assert n.value == 16 * 128 * 32 * 2
+    # padded down and up projections (m = 24 -> 32) plus the two router matrices
+    assert n.value >= 2 * (16 * 128 * 32 * 2) + 2 * (32 * 128 + 16 * 32) and n.value % 256 == 0
     assert lib.dmoe_packed_bytes(ctypes.byref(L), ctypes.byref(n)) == B.DMOE_OK and n.value == 0
 
 
@@ -117,9 +118,11 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert ffn(L=_layer(w_down=None)) == B.DMOE_ERR_NULL
     assert ffn(L=_layer(gated=1)) == B.DMOE_ERR_NULL                        # no w_gate
     assert ffn(L=_layer(gated=1, w_gate=0x1000, b_up=0x1000)) == B.DMOE_ERR_UNSUPPORTED
-    assert ffn(L=_layer(dtype=B.DMOE_BF16)) == B.DMOE_ERR_NULL              # not packed
+    assert ffn(L=_layer(dtype=B.DMOE_BF16, d_model=256)) == B.DMOE_ERR_NULL            # not packed
     assert ffn(L=_layer(dtype=B.DMOE_BF16, d_model=100, packed=0x1000)) == B.DMOE_ERR_UNSUPPORTED
-    assert ffn(L=_layer(dtype=B.DMOE_BF16, expert_size=200, packed=0x1000)) == B.DMOE_ERR_UNSUPPORTED
+    assert ffn(L=_layer(dtype=B.DMOE_BF16, d_model=256, expert_size=200, packed=0x1000)) == B.DMOE_ERR_UNSUPPORTED
+    assert ffn(L=_layer(dtype=B.DMOE_BF16, d_model=256, expert_size=128, gated=1, w_gate=0x1000,
+                        packed=0x1000)) == B.DMOE_ERR_UNSUPPORTED
     assert ffn(T=0, ws=None, wsb=0) == B.DMOE_OK
     # forward
     fwd = lambda L=L, **k: lib.dmoe_forward(ref(L), *[k.get(a, d) for a, d in (
@@ -133,8 +136,9 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert fwd(T=0, ws=None, wsb=0) == B.DMOE_OK
     assert b"workspace" in lib.dmoe_last_error() or lib.dmoe_last_error() is not None
     # pack
-    Lb = _layer(dtype=B.DMOE_BF16)
+    Lb = _layer(dtype=B.DMOE_BF16, d_model=256)
     assert lib.dmoe_pack_weights(ref(Lb), None, 0, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_pack_weights(ref(_layer(dtype=B.DMOE_BF16)), 0x10000, 1 << 30, None) == B.DMOE_ERR_UNSUPPORTED
     assert lib.dmoe_pack_weights(ref(Lb), 0x10000, 16, None) == B.DMOE_ERR_WORKSPACE
     assert lib.dmoe_pack_weights(ref(L), None, 0, None) == B.DMOE_OK          # fp32: no-op
     # timing slots are readable without enabling

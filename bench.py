@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 N_ROTATE = 8                   # distinct x / y buffers cycled through, so that inputs come from HBM
 
 
-def _event_time_ms(fn, steps):
+def _time_ms(fn, steps):
     import torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -46,6 +46,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override the token count")
     ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the dense-FFN comparisons (keeps a profile to the timed workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (tokens would shard "
@@ -80,7 +82,7 @@ def main() -> int:
 
     for i in range(args.warmup):
         step(i)
-    ms = _event_time_ms(step, args.steps)
+    ms = _time_ms(step, args.steps)
     tokens_per_s = cfg.T / (ms * 1e-3)
 
     # ---- per-kernel durations (HIP events on the launch stream), separate pass
@@ -122,13 +124,14 @@ def main() -> int:
             out = out + L.t["b_down"]
         return out
 
-    for i in range(5):
-        dense(i)
-    dense_ms = _event_time_ms(dense, 30)
-    own_dense_ms = None
-    for i in range(3):
-        step(i, 0.0)
-    own_dense_ms = _event_time_ms(lambda i: step(i, 0.0), 20)
+    dense_ms = own_dense_ms = None
+    if not args.no_dense:
+        for i in range(5):
+            dense(i)
+        dense_ms = _time_ms(dense, 30)
+        for i in range(3):
+            step(i, 0.0)
+        own_dense_ms = _time_ms(lambda i: step(i, 0.0), 20)
 
     sweep = None
     if args.sweep:
@@ -140,22 +143,25 @@ def main() -> int:
             p = int(e2["offsets"][-1].item())
             for i in range(5):
                 step(i, t32)
-            m = _event_time_ms(lambda i: step(i, t32), 50)
+            m = _time_ms(lambda i: step(i, t32), 50)
             sweep.append({"tau": t, "density": round(p / (cfg.T * cfg.E), 4), "ms": round(m, 4),
                           "tokens_per_s": round(cfg.T / (m * 1e-3)),
                           "executed_tflops": round(cost_model.executed_flops(p, cfg.d, cfg.m, cfg.gated) / (m * 1e-3) / 1e12, 2),
-                          "speedup_vs_dense": round(dense_ms / m, 3)})
+                          "speedup_vs_dense": round(dense_ms / m, 3) if dense_ms else None})
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu:
         from oracle import dmoe_oracle as oracle
-        n = min(cfg.T, 1024)
-        t0 = time.perf_counter()
-        oracle.forward(layer_np, x_np[:n], tau)
+        n = min(cfg.T, 16384)
+        runs, t0 = 0, time.perf_counter()
+        while runs < 50 and time.perf_counter() - t0 < 10.0:   # about 10 s of CPU work
+            oracle.forward(layer_np, x_np[:n], tau)
+            runs += 1
         dt = time.perf_counter() - t0
-        cpu = {"value": round(n / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
-               "kind": "oracle", "sample": f"first {n} tokens of {cfg.name}, tau={args.tau}, one run, {dt:.2f} s"}
+        cpu = {"value": round(n * runs / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"first {n} tokens of {cfg.name}, tau={args.tau}, {runs} runs, {dt:.1f} s"}
 
     out = {
         "metric": "tokens/sec of dynamic-k MoE FFN forward (router + gate + experts)",
@@ -166,8 +172,9 @@ def main() -> int:
                                f"{'gated-' if cfg.gated else ''}{cfg.act} tau={args.tau}",
                    "density": round(density, 4), "pairs": pairs},
         "executed_expert_tflops": round(flops / (ms * 1e-3) / 1e12, 2),
-        "dense_ffn_ms": {"vendor_gemm": round(dense_ms, 4), "own_kernels_tau0": round(own_dense_ms, 4)},
-        "speedup_vs_dense": round(dense_ms / ms, 3),
+        "dense_ffn_ms": ({"vendor_gemm": round(dense_ms, 4), "own_kernels_tau0": round(own_dense_ms, 4)}
+                         if dense_ms else None),
+        "speedup_vs_dense": round(dense_ms / ms, 3) if dense_ms else None,
         "kernel_ms": {k: round(v[1], 5) for k, v in kt.items()},
         "roofline": roofline,
         "cpu_baseline": cpu,

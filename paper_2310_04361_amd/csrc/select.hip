@@ -211,12 +211,12 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
             if (item_start) item_start[e] = s_item[e];
             if (e < E && counts) counts[e] = totals[e];
         }
-        if (alist) {  // -1 behind each expert's last token, up to its next work-item boundary
-            for (int e = wave; e < E; e += 4) {
-                const int first = s_item[e] * rows_per_item + totals[e];
-                const int last = s_item[e + 1] * rows_per_item;
-                for (int p = first + lane; p < last; p += kWave) alist[p] = -1;
-            }
+    }
+    if (alist) {  // -1 behind each expert's last token, up to its next work-item boundary
+        for (int i = blockIdx.x * 256 + tid; i < E * rows_per_item; i += gridDim.x * 256) {
+            const int e = i / rows_per_item, j = i % rows_per_item;
+            const int p = s_item[e] * rows_per_item + totals[e] + j;
+            if (p < s_item[e + 1] * rows_per_item) alist[p] = -1;
         }
     }
 

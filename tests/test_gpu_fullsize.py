@@ -1,0 +1,69 @@
+"""Full-size runs (the shapes and launch configuration that bench.py times) checked on sampled
+tokens the oracle can compute one by one, plus properties that hold at any size."""
+import numpy as np
+import pytest
+
+from helpers import TOL, oracle_ffn, tokenwise_rel_err
+from paper_2310_04361_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2310_04361_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("name,tau,n_sample", [("cfg2", 0.5, 256), ("cfg2", 0.9, 256),
+                                               ("cfg3", 0.5, 192), ("cfg4", 0.3, 48),
+                                               ("cfg4", 0.6, 64)])
+def test_full_size_sampled(B, oracle, name, tau, n_sample):
+    import torch
+    cfg = wl.CONFIGS[name]
+    print(f"full size {name} T={cfg.T} tau={tau}", flush=True)
+    layer, x = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
+    L = B.Layer(layer, cfg.dtype)
+    tau32 = float(np.float32(tau))
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32, want_scores=True, want_mask=True,
+                           want_lists=True)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy()
+    mask = B.mask_bits_to_bool(ex["mask_bits"], cfg.E)
+    offsets = ex["offsets"].cpu().numpy()
+    lists = ex["token_lists"].cpu().numpy()[: offsets[-1]]
+    yh = B.from_device(y, cfg.dtype)
+
+    # ---- properties at full size
+    assert (mask.sum(axis=1) >= 1).all()                               # the argmax expert is kept
+    assert mask[np.arange(cfg.T), s.argmax(axis=1)].all()
+    assert offsets[0] == 0 and offsets[-1] == mask.sum()
+    assert np.array_equal(np.diff(offsets), mask.sum(axis=0))
+    expert_of = np.repeat(np.arange(cfg.E), np.diff(offsets))
+    seen = np.zeros_like(mask)
+    seen[lists, expert_of] = 1
+    assert np.array_equal(seen, mask)                                  # lists == mask, as sets
+    starts = np.zeros(len(lists), bool)
+    starts[offsets[:-1][np.diff(offsets) > 0]] = True
+    assert ((np.diff(lists) > 0) | starts[1:]).all()                   # ascending inside a list
+    assert np.isfinite(yh).all()
+
+    # ---- sampled tokens against the oracle
+    rng = np.random.default_rng(5)
+    idx = np.unique(np.concatenate([[0, 63, 64, cfg.T - 1], rng.choice(cfg.T, n_sample, replace=False)]))
+    ref_mask, _ = oracle.select(s[idx].astype(np.float64), tau32)
+    assert np.array_equal(mask[idx], ref_mask)                         # bit-exact on the GPU's scores
+    ref_s = oracle.router(x[idx], layer["r_w1"], layer["r_b1"], layer["r_w2"], layer["r_b2"])
+    assert tokenwise_rel_err(s[idx], ref_s) <= TOL[cfg.dtype]
+    ref_y = oracle_ffn(oracle, layer, x[idx], ref_mask)
+    err = tokenwise_rel_err(yh[idx], ref_y)
+    print(f"  density={mask.mean():.4f} sampled err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]
+
+    # ---- run-to-run reproducibility (the merge order is fixed)
+    y2, _ = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)

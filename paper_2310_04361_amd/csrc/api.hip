@@ -133,7 +133,7 @@ SelectWs select_ws(int T, int E, bool need_mask) {
 }
 
 struct LayerWs {
-    size_t scores, mask, group_off, counts, offsets, item_start, lists, H, total;
+    size_t scores, mask, group_off, counts, offsets, item_start, lists, H, colmask, partial, hid, total;
 };
 LayerWs layer_ws(const dmoe_layer& L, int T) {
     LayerWs w{};
@@ -149,8 +149,21 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     w.lists = o;      o += align_up(sizeof(int32_t) * h_fragments(L, T) * 16);
     w.H = o;
     if (L.dtype == DMOE_BF16) o += align_up(h_fragments(L, T) * (m_pad_of(L.expert_size) / 32) * 1024);
+    // small-token path: which tokens keep each expert, and the per-expert-group partial outputs
+    w.colmask = o;
+    w.partial = o;
+    if (L.dtype == DMOE_BF16 && T <= kSmallTokens) {
+        o += align_up(sizeof(uint64_t) * (size_t)E);
+        w.partial = o;
+        o += align_up(sizeof(float) * (size_t)kSmallMaxGroups * 16 * L.d_model);
+    }
+    w.hid = o;        o += align_up(2 * 16 * (size_t)std::max(L.router_hidden, 16));
     w.total = o;
     return w;
+}
+
+bool use_small_path(const dmoe_layer& L, int T) {
+    return L.dtype == DMOE_BF16 && T <= kSmallTokens && small_bf16_supported(L);
 }
 
 // Experts from mask bits whose group counts are already in group_off (both in the workspace).
@@ -168,6 +181,12 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
             launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
                                  lists_out, nullptr, s);
         launch_ffn_f32(L, (const float*)x, T, mask, (float*)y, s);
+    } else if (use_small_path(L, T)) {
+        if (offsets_out)
+            launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
+                                 lists_out, nullptr, s);
+        launch_small_bf16(L, x, T, reinterpret_cast<const uint64_t*>(ws + w.colmask), ws + w.H,
+                          reinterpret_cast<float*>(ws + w.partial), y, s);
     } else {
         launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, item_start,
                              up_rows_bf16(L), lists_out, alist, s);
@@ -250,7 +269,7 @@ int32_t dmoe_router(const dmoe_layer* layer, const void* x, int32_t n_tokens, fl
     hipStream_t s = (hipStream_t)stream;
     if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
     else if (router_fused_supported(*layer))
-        launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, s);
+        launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, nullptr, s);
     else launch_router_bf16(*layer, x, n_tokens, scores, s);
     return check_launch("router");
 }
@@ -270,7 +289,7 @@ int32_t dmoe_select(const float* scores, int32_t n_tokens, int32_t n_experts, fl
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
     uint64_t* mask = mask_bits ? mask_bits : reinterpret_cast<uint64_t*>(ws + w.mask);
     if (n_tokens > 0)
-        launch_mask_from_scores(scores, n_tokens, n_experts, tau, mask, k_per_token, group_off, s);
+        launch_mask_from_scores(scores, n_tokens, n_experts, tau, mask, k_per_token, group_off, nullptr, s);
     launch_scan_and_fill(mask, n_tokens, n_experts, group_off, counts, offsets, nullptr, 64,
                          n_tokens > 0 ? token_lists : nullptr, nullptr, s);
     return check_launch("select");
@@ -288,8 +307,9 @@ int32_t dmoe_expert_ffn(const dmoe_layer* layer, const void* x, int32_t n_tokens
     char* ws = static_cast<char*>(workspace);
     hipStream_t s = (hipStream_t)stream;
     uint64_t* mask = reinterpret_cast<uint64_t*>(ws + w.mask);
+    uint64_t* colmask = use_small_path(*layer, n_tokens) ? reinterpret_cast<uint64_t*>(ws + w.colmask) : nullptr;
     launch_mask_from_lists(offsets, token_lists, n_tokens, layer->n_experts, mask,
-                           reinterpret_cast<int32_t*>(ws + w.group_off), s);
+                           reinterpret_cast<int32_t*>(ws + w.group_off), colmask, s);
     return run_experts(*layer, x, n_tokens, ws, w, mask, nullptr, nullptr, y, s);
 }
 
@@ -311,12 +331,18 @@ int32_t dmoe_forward(const dmoe_layer* layer, const void* x, int32_t n_tokens, f
     float* scores = scores_out ? scores_out : reinterpret_cast<float*>(ws + w.scores);
     uint64_t* mask = mask_out ? mask_out : reinterpret_cast<uint64_t*>(ws + w.mask);
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
-    if (layer->dtype == DMOE_BF16 && router_fused_supported(*layer)) {
-        launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, s);
+    uint64_t* colmask = use_small_path(*layer, n_tokens) ? reinterpret_cast<uint64_t*>(ws + w.colmask) : nullptr;
+    if (layer->dtype == DMOE_BF16 && router_fused_supported(*layer) && n_tokens <= kSmallTokens) {
+        launch_router_small(*layer, x, n_tokens, ws + w.hid, scores, s);
+        launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr, group_off,
+                                colmask, s);
+    } else if (layer->dtype == DMOE_BF16 && router_fused_supported(*layer)) {
+        launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, colmask, s);
     } else {
         if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
         else launch_router_bf16(*layer, x, n_tokens, scores, s);
-        launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr, group_off, s);
+        launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr, group_off,
+                                colmask, s);
     }
     return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s);
 }

@@ -77,10 +77,12 @@ struct LaunchTimer {
 // ---- select / bucket (select.hip) -----------------------------------------------------------
 // group_off is [(NG+1)][E] int32 with NG = ceil(T/64): after the scans, group_off[g][e] is the
 // number of tokens < 64*g that selected expert e, and row NG holds the per-expert totals.
+// colmask (nullable) is [NG][E] u64: bit j of colmask[g][e] = token 64g + j keeps expert e.
 void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint64_t* mask,
-                             int32_t* k_per_token, int32_t* group_off, hipStream_t s);
+                             int32_t* k_per_token, int32_t* group_off, uint64_t* colmask,
+                             hipStream_t s);
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,
-                            uint64_t* mask, int32_t* group_off, hipStream_t s);
+                            uint64_t* mask, int32_t* group_off, uint64_t* colmask, hipStream_t s);
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
                           int32_t* token_lists, int32_t* aligned_lists, hipStream_t s);
@@ -92,7 +94,21 @@ void launch_router_bf16(const dmoe_layer& L, const void* x, int T, float* scores
 // Fused router + gate + group counts (router_fused.hip); mask == nullptr runs the router alone.
 bool router_fused_supported(const dmoe_layer& L);
 void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,
-                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt, hipStream_t s);
+                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
+                         uint64_t* colmask, hipStream_t s);
+
+// T <= kSmallTokens: router as a weight stream over many workgroups (same support conditions as
+// the fused kernel); hid is a 16 x d_h bf16 scratch buffer.  The gate runs separately.
+void launch_router_small(const dmoe_layer& L, const void* x, int T, void* hid, float* scores,
+                         hipStream_t s);
+
+// ---- small-token experts (ffn_small.hip): T <= kSmallTokens, driven by colmask[0][e] -------------
+constexpr int kSmallTokens = 16;
+constexpr int kSmallMaxGroups = 32;   // expert groups whose partial outputs are summed at the end
+bool small_bf16_supported(const dmoe_layer& L);
+// Hs: E * (m_pad/32) KiB of fragments; partial: kSmallMaxGroups * 16 * d floats.
+void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t* colmask, void* Hs,
+                       float* partial, void* y, hipStream_t s);
 
 // ---- experts ----------------------------------------------------------------------------------
 void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* mask, float* y,

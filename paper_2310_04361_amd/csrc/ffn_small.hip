@@ -1,0 +1,211 @@
+// Small-token (decode) experts: T <= 16 tokens ride in ONE MFMA column tile, so the work is
+// reading every touched expert's weights exactly once -- a weight-bandwidth-bound stream.
+//
+//   up_small    one workgroup per expert; experts nobody selected exit before touching their
+//               weights.  The 16 x rows sit in LDS; wavefront w streams neuron tile w of the up
+//               (and gate) fragments -- 1 KiB contiguous per load, many loads in flight -- and
+//               writes h (zero for tokens that did not select the expert) as an H fragment.
+//   down_small  workgroup = (4 output-column tiles, group of experts): streams the touched
+//               experts' down fragments of its columns, accumulates in registers and writes one
+//               fp32 partial per expert group (no atomics).
+//   finish      y = bf16(b_down + sum of the partials).
+// colmask[e] (bit j = token j keeps expert e) comes from the gate's ballot transpose.
+#include "dmoe_internal.h"
+#include "mfma.h"
+
+namespace dmoe {
+
+namespace {
+
+__device__ __forceinline__ float fast_erf_s(float v) {
+    // Abramowitz & Stegun 7.1.26, |error| < 1.5e-7
+    const float a = fabsf(v);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, a, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    return copysignf(1.0f - p * t * __expf(-a * a), v);
+}
+
+__device__ __forceinline__ float activate_s(int act, float v) {
+    if (act == DMOE_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == DMOE_ACT_GELU_ERF) return 0.5f * v * (1.0f + fast_erf_s(v * 0.70710678118654752440f));
+    const float u = 0.79788456080286535588f * (v + 0.044715f * v * v * v);
+    const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * u));
+    return 0.5f * v * (1.0f + th);
+}
+
+// MT = m_pad / 16 wavefronts per workgroup, one neuron tile each.
+template <int MT, bool GATED>
+__global__ __launch_bounds__(64 * MT) void up_small_kernel(
+    const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
+    const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
+    const uint64_t* __restrict__ colmask, __bf16* __restrict__ Hs, int T, int d, int m, int act) {
+    constexpr int KS = MT / 2, kThreads = 64 * MT;
+    const int e = blockIdx.x;
+    const uint64_t cm = colmask[e];
+    if (cm == 0ull) return;  // uniform: nobody selected this expert
+    extern __shared__ char xs[];  // [16][2d + 16]
+    const int row_bytes = 2 * d + 16;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
+    const int pieces = d / 8;
+    for (int i = tid; i < 16 * pieces; i += kThreads) {
+        const int row = i / pieces, piece = i % pieces;
+        *reinterpret_cast<bf16x8*>(xs + row * row_bytes + piece * 16) =
+            load8(x + (size_t)min(row, T - 1) * d + piece * 8);
+    }
+    __syncthreads();
+
+    const int NK32 = d / 32;
+    const __bf16* au = wupf + (((size_t)e * MT + w) * NK32 * 64 + lane) * 8;
+    const __bf16* ag = wgatef + (((size_t)e * MT + w) * NK32 * 64 + lane) * 8;
+    const char* bsrc = xs + c * row_bytes + q * 16;
+    f32x4 accu = f32x4{0.f, 0.f, 0.f, 0.f}, accg = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int ks = 0; ks < NK32; ++ks) {
+        const bf16x8 b = *reinterpret_cast<const bf16x8*>(bsrc + ks * 64);
+        accu = mfma16(load8(au + (size_t)ks * 512), b, accu);
+        if (GATED) accg = mfma16(load8(ag + (size_t)ks * 512), b, accg);
+    }
+
+    // lane (q, c): neurons 16w + 4q + r of token c
+    const bool keep = c < T && ((cm >> c) & 1ull);
+    bf16x4 hv;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int n = 16 * w + 4 * q + r;
+        float v;
+        if (GATED) {
+            v = activate_s(act, accg[r]) * accu[r];
+        } else {
+            const float bias = b_up ? (float)b_up[(size_t)e * m + min(n, m - 1)] : 0.0f;
+            v = activate_s(act, accu[r] + bias);
+        }
+        if (n >= m || !keep) v = 0.0f;
+        hv[r] = (__bf16)v;
+    }
+    *reinterpret_cast<bf16x4*>(Hs + (((size_t)e * KS + (w >> 1)) * 64 + lane) * 8 + (w & 1) * 4) = hv;
+}
+
+constexpr int kSmallPerGroup = 256;  // experts per group at most
+
+// grid = (column-tile groups of 4, expert groups); KS = m_pad / 32.
+template <int KS>
+__global__ __launch_bounds__(256) void down_small_kernel(
+    const __bf16* __restrict__ w2f, const uint64_t* __restrict__ colmask,
+    const __bf16* __restrict__ Hs, float* __restrict__ partial, int T, int d, int E, int per) {
+    __shared__ int s_list[kSmallPerGroup];
+    __shared__ int s_n;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
+    const int eg = blockIdx.y;
+    const int e0 = eg * per, e1 = min(E, e0 + per);
+    if (w == 0) {  // compact list of this group's touched experts
+        int n = 0;
+        for (int base = e0; base < e1; base += 64) {
+            const int e = base + lane;
+            const bool f = e < e1 && colmask[e] != 0ull;
+            const uint64_t bal = __ballot(f);
+            if (f) s_list[n + __popcll(bal & ((1ull << lane) - 1ull))] = e;
+            n += __popcll(bal);
+        }
+        if (lane == 0) s_n = n;
+    }
+    __syncthreads();
+    const int n = s_n;
+    const int ct = blockIdx.x * 4 + w;
+    if (ct >= d / 16) return;
+    const __bf16* wa = w2f + ((size_t)ct * KS * 64 + lane) * 8;
+    const size_t w_expert_stride = (size_t)(d / 16) * KS * 512;
+    const __bf16* hb = Hs + lane * 8;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int i = 0; i < n; ++i) {
+        const int e = s_list[i];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            acc = mfma16(load8(wa + (size_t)e * w_expert_stride + ks * 512),
+                         load8(hb + ((size_t)e * KS + ks) * 512), acc);
+    }
+    // lane (q, c): columns 16ct + 4q .. +3 of token c
+    if (c < T) {
+        float4 o;
+        o.x = acc[0]; o.y = acc[1]; o.z = acc[2]; o.w = acc[3];
+        *reinterpret_cast<float4*>(partial + ((size_t)eg * 16 + c) * d + 16 * ct + 4 * q) = o;
+    }
+}
+
+__global__ void finish_small_kernel(const float* __restrict__ partial,
+                                    const __bf16* __restrict__ b_down, __bf16* __restrict__ y,
+                                    int T, int d, int EG) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T * d) return;
+    const int t = i / d, col = i % d;
+    float v = b_down ? (float)b_down[col] : 0.0f;
+    for (int eg = 0; eg < EG; ++eg) v += partial[((size_t)eg * 16 + t) * d + col];
+    y[i] = (__bf16)v;
+}
+
+template <int MT, bool GATED>
+void launch_up_small_t(const dmoe_layer& L, const void* x, int T, const PackedLayout& P,
+                       const uint64_t* colmask, void* Hs, hipStream_t s) {
+    const size_t lds = 16 * (2 * (size_t)L.d_model + 16);
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_small_kernel<MT, GATED>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    const char* pk = static_cast<const char*>(L.packed);
+    up_small_kernel<MT, GATED><<<L.n_experts, 64 * MT, lds, s>>>(
+        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
+        (const __bf16*)L.b_up, colmask, (__bf16*)Hs, T, L.d_model, L.expert_size, L.act);
+}
+
+}  // namespace
+
+bool small_bf16_supported(const dmoe_layer& L) {
+    const int mp = m_pad_of(L.expert_size);
+    return L.packed != nullptr && (mp == 32 || mp == 64 || mp == 128) && L.d_model % 32 == 0 &&
+           16 * (2 * (size_t)L.d_model + 16) <= 160 * 1024 - 1024 &&
+           div_up(L.n_experts, kSmallMaxGroups) <= kSmallPerGroup;
+}
+
+void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t* colmask, void* Hs,
+                       float* partial, void* y, hipStream_t s) {
+    LaunchTimer tm(kSlotSmall, s);
+    const PackedLayout P = packed_layout(L);
+    const int mt = m_pad_of(L.expert_size) / 16;
+    if (L.gated) {
+        if (mt == 2) launch_up_small_t<2, true>(L, x, T, P, colmask, Hs, s);
+        else if (mt == 4) launch_up_small_t<4, true>(L, x, T, P, colmask, Hs, s);
+        else launch_up_small_t<8, true>(L, x, T, P, colmask, Hs, s);
+    } else {
+        if (mt == 2) launch_up_small_t<2, false>(L, x, T, P, colmask, Hs, s);
+        else if (mt == 4) launch_up_small_t<4, false>(L, x, T, P, colmask, Hs, s);
+        else launch_up_small_t<8, false>(L, x, T, P, colmask, Hs, s);
+    }
+    // expert groups: enough workgroups to fill the chip, at most kSmallMaxGroups partial sums
+    const int E = L.n_experts, d = L.d_model;
+    const int ncg = div_up(d / 16, 4);
+    int EG = std::max(1, std::min({kSmallMaxGroups, div_up(256, ncg), std::max(1, E / 4)}));
+    EG = std::max(EG, div_up(E, kSmallPerGroup));
+    const int per = div_up(E, EG);
+    EG = div_up(E, per);
+    const char* pk = static_cast<const char*>(L.packed);
+    const dim3 grid(ncg, EG);
+    const int ks = mt / 2;
+    if (ks == 1)
+        down_small_kernel<1><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
+                                                  (const __bf16*)Hs, partial, T, d, E, per);
+    else if (ks == 2)
+        down_small_kernel<2><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
+                                                  (const __bf16*)Hs, partial, T, d, E, per);
+    else
+        down_small_kernel<4><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
+                                                  (const __bf16*)Hs, partial, T, d, E, per);
+    finish_small_kernel<<<div_up(T * d, 256), 256, 0, s>>>(partial, (const __bf16*)L.b_down,
+                                                           (__bf16*)y, T, d, EG);
+}
+
+}  // namespace dmoe

@@ -30,7 +30,8 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
     const __bf16* __restrict__ r2f, const __bf16* __restrict__ r_b2, float* __restrict__ scores,
     int T, int d, int E, float tau, int do_select, uint64_t* __restrict__ mask,
-    int32_t* __restrict__ k_per_token, int32_t* __restrict__ group_cnt) {
+    int32_t* __restrict__ k_per_token, int32_t* __restrict__ group_cnt,
+    uint64_t* __restrict__ colmask) {
     constexpr int dh = NH * 16, HT = NH / 4, KS2 = dh / 32;
     constexpr int kHRow = dh * 2 + 16;  // bytes per hidden row in LDS
     extern __shared__ char smem[];
@@ -226,20 +227,23 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     // ballot transpose: lane = token; wavefront w handles words w, w+4, ...
     for (int wi = w; wi < W; wi += 4) {
         const uint64_t word = fin[lane * W + wi];
-        int cnt = 0;
+        uint64_t col = 0;  // lane b: which tokens of the group keep expert 64wi + b
 #pragma unroll 8
         for (int b = 0; b < 64; ++b) {
             const uint64_t bal = __ballot((word >> b) & 1ull);
-            if (lane == b) cnt = __popcll(bal);
+            if (lane == b) col = bal;
         }
         const int e = 64 * wi + lane;
-        if (e < E) group_cnt[(size_t)g * E + e] = cnt;
+        if (e < E) {
+            group_cnt[(size_t)g * E + e] = __popcll(col);
+            if (colmask) colmask[(size_t)g * E + e] = col;
+        }
     }
 }
 
 template <int NH, int ETW>
 void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
-              int32_t* k_per_token, int32_t* group_cnt, hipStream_t s) {
+               int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
     const PackedLayout P = packed_layout(L);
     const int E = L.n_experts, W = div_up(E, 64);
     const size_t lds = 2 * 64 * kXRow + 64 * (NH * 32 + 16) + 256 * 4 + (size_t)5 * 64 * W * 8;
@@ -253,18 +257,93 @@ void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float t
     router_fused_kernel<NH, ETW><<<div_up(T, 64), 256, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1,
         (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, L.d_model, E, tau,
-        mask != nullptr, mask, k_per_token, group_cnt);
+        mask != nullptr, mask, k_per_token, group_cnt, colmask);
+}
+
+// ---- T <= 16: the same two products spread over many workgroups --------------------------------
+// With so few tokens the router is a weight stream (R1 is 1 MiB at d = 2048, d_h = 256) and one
+// workgroup per 64 tokens would leave it to a single CU.
+//   hidden: workgroup = one tile of 16 hidden units, its four wavefronts split K and reduce
+//           through LDS; hid[16][d_h] (bf16) goes to a small global buffer.
+//   scores: wavefront = one tile of 16 experts.
+// The gate then runs as the stand-alone mask kernel on the stored scores.
+__global__ __launch_bounds__(256) void router_small_hidden_kernel(
+    const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
+    __bf16* __restrict__ hid, int T, int d, int dh) {
+    __shared__ float red[4][64][4];
+    const int h = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
+    const int NK32 = d / 32, per = NK32 / 4;  // d is a multiple of 128
+    const __bf16* xr = x + (size_t)min(c, T - 1) * d + 8 * q;
+    const __bf16* af = r1f + (((size_t)h * NK32) * 64 + lane) * 8;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+    for (int ks = w * per; ks < (w + 1) * per; ++ks)
+        acc = mfma16(load8(af + (size_t)ks * 512), load8(xr + 32 * ks), acc);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[w][lane][r] = acc[r];
+    __syncthreads();
+    if (w == 0) {  // lane (q, c): hidden units 16h + 4q + r of token c
+        bf16x4 hv;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float v = red[0][lane][r] + red[1][lane][r] + red[2][lane][r] + red[3][lane][r];
+            if (r_b1) v += (float)r_b1[16 * h + 4 * q + r];
+            hv[r] = (__bf16)fmaxf(v, 0.0f);
+        }
+        *reinterpret_cast<bf16x4*>(hid + (size_t)c * dh + 16 * h + 4 * q) = hv;
+    }
+}
+
+__global__ __launch_bounds__(256) void router_small_scores_kernel(
+    const __bf16* __restrict__ hid, const __bf16* __restrict__ r2f, const __bf16* __restrict__ r_b2,
+    float* __restrict__ scores, int T, int dh, int E) {
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
+    const int et = blockIdx.x * 4 + w;
+    if (et >= (E + 15) / 16) return;
+    const int KS2 = dh / 32;
+    const __bf16* af = r2f + (((size_t)et * KS2) * 64 + lane) * 8;
+    const __bf16* hb = hid + (size_t)c * dh + 8 * q;
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int ks = 0; ks < KS2; ++ks)
+        acc = mfma16(load8(af + (size_t)ks * 512), load8(hb + 32 * ks), acc);
+    const int e0 = 16 * et + 4 * q;
+    if (c < T && e0 < E) {
+        float4 out;
+        out.x = fabsf(acc[0] + (r_b2 ? (float)r_b2[e0 + 0] : 0.0f));
+        out.y = fabsf(acc[1] + (r_b2 ? (float)r_b2[e0 + 1] : 0.0f));
+        out.z = fabsf(acc[2] + (r_b2 ? (float)r_b2[e0 + 2] : 0.0f));
+        out.w = fabsf(acc[3] + (r_b2 ? (float)r_b2[e0 + 3] : 0.0f));
+        *reinterpret_cast<float4*>(scores + (size_t)c * E + e0) = out;
+    }
 }
 
 template <int NH>
 void launch_t(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
-              int32_t* k_per_token, int32_t* group_cnt, hipStream_t s) {
-    if (L.n_experts <= 128) launch_t2<NH, 2>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s);
-    else if (L.n_experts <= 256) launch_t2<NH, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s);
-    else launch_t2<NH, 8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s);
+              int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
+    if (L.n_experts <= 128)
+        launch_t2<NH, 2>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+    else if (L.n_experts <= 256)
+        launch_t2<NH, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+    else
+        launch_t2<NH, 8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
 }
 
 }  // namespace
+
+void launch_router_small(const dmoe_layer& L, const void* x, int T, void* hid, float* scores,
+                         hipStream_t s) {
+    LaunchTimer tm(kSlotRouter, s);
+    const PackedLayout P = packed_layout(L);
+    const char* pk = static_cast<const char*>(L.packed);
+    const int dh = L.router_hidden, E = L.n_experts;
+    router_small_hidden_kernel<<<dh / 16, 256, 0, s>>>(
+        (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1, (__bf16*)hid, T,
+        L.d_model, dh);
+    router_small_scores_kernel<<<div_up(div_up(E, 16), 4), 256, 0, s>>>(
+        (const __bf16*)hid, (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, dh, E);
+}
 
 bool router_fused_supported(const dmoe_layer& L) {
     const int dh = L.router_hidden;
@@ -273,13 +352,14 @@ bool router_fused_supported(const dmoe_layer& L) {
 }
 
 void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,
-                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt, hipStream_t s) {
+                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
+                         uint64_t* colmask, hipStream_t s) {
     LaunchTimer tm(kSlotRouter, s);
     switch (L.router_hidden) {
-    case 64: launch_t<4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
-    case 128: launch_t<8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
-    case 256: launch_t<16>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
-    case 512: launch_t<32>(L, x, T, scores, tau, mask, k_per_token, group_cnt, s); break;
+    case 64: launch_t<4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
+    case 128: launch_t<8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
+    case 256: launch_t<16>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
+    case 512: launch_t<32>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
     default: break;  // refused by router_fused_supported
     }
 }

@@ -31,12 +31,14 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
 // One wavefront per group of 64 tokens, lane = token.
 // FROM_SCORES: evaluate Eq. 4 on the token's score row and write its mask words;
 // otherwise read the mask words.  Either way, count, for every expert, the tokens of the group
-// that keep it (ballot transpose) into group_cnt[g][e].
+// that keep it (ballot transpose) into group_cnt[g][e]; colmask[g][e], if wanted, receives the
+// 64-bit set of those tokens itself.
 template <bool FROM_SCORES>
 __global__ __launch_bounds__(256) void mask_count_kernel(const float* __restrict__ scores,
                                                          uint64_t* __restrict__ mask,
                                                          int32_t* __restrict__ k_per_token,
-                                                         int32_t* __restrict__ group_cnt, int T,
+                                                         int32_t* __restrict__ group_cnt,
+                                                         uint64_t* __restrict__ colmask, int T,
                                                          int E, int W, float tau) {
     const int lane = lane_id();
     const int g = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
@@ -84,16 +86,59 @@ __global__ __launch_bounds__(256) void mask_count_kernel(const float* __restrict
             if (valid) word = mask[(size_t)t * W + w];
         }
         kt += __popcll(word);
-        int cnt = 0;
+        uint64_t col = 0;  // lane b: which tokens of the group keep expert 64w + b
 #pragma unroll 8
         for (int b = 0; b < 64; ++b) {
             const uint64_t bal = __ballot((word >> b) & 1ull);
-            if (lane == b) cnt = __popcll(bal);
+            if (lane == b) col = bal;
         }
         const int e = 64 * w + lane;
-        if (e < E) group_cnt[(size_t)g * E + e] = cnt;
+        if (e < E) {
+            group_cnt[(size_t)g * E + e] = __popcll(col);
+            if (colmask) colmask[(size_t)g * E + e] = col;
+        }
     }
     if (valid && k_per_token) k_per_token[t] = kt;
+}
+
+// T <= 16: one workgroup, wavefront t = token t with lanes striding the experts, so the score row
+// is read coalesced, the maximum is a wavefront reduction and a ballot IS a mask word.  The
+// transpose to per-expert token sets (colmask) and counts then goes through LDS.
+__global__ __launch_bounds__(1024) void select_small_kernel(const float* __restrict__ scores,
+                                                            uint64_t* __restrict__ mask,
+                                                            int32_t* __restrict__ k_per_token,
+                                                            int32_t* __restrict__ group_cnt,
+                                                            uint64_t* __restrict__ colmask, int T,
+                                                            int E, int W, float tau) {
+    extern __shared__ uint64_t mw[];  // [16][W]
+    const int lane = lane_id(), t = threadIdx.x >> 6;
+    if (t < T) {
+        const float* row = scores + (size_t)t * E;
+        float mx = -INFINITY;
+        for (int e = lane; e < E; e += kWave) mx = fmaxf(mx, row[e]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+        const double thr = (double)tau * (double)mx;  // exact, see mask_count_kernel
+        int kt = 0;
+        for (int w = 0; w < W; ++w) {
+            const int e = 64 * w + lane;
+            const bool keep = e < E && (tau == 0.0f || (double)row[e] >= thr);
+            const uint64_t word = __ballot(keep);
+            kt += __popcll(word);
+            if (lane == 0) {
+                mw[t * W + w] = word;
+                mask[(size_t)t * W + w] = word;
+            }
+        }
+        if (lane == 0 && k_per_token) k_per_token[t] = kt;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += 1024) {
+        uint64_t col = 0;
+        for (int tt = 0; tt < T; ++tt) col |= ((mw[tt * W + (e >> 6)] >> (e & 63)) & 1ull) << tt;
+        group_cnt[e] = __popcll(col);
+        if (colmask) colmask[e] = col;
+    }
 }
 
 __global__ void zero_u64_kernel(uint64_t* p, size_t n) {
@@ -253,15 +298,21 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
 }  // namespace
 
 void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint64_t* mask,
-                             int32_t* k_per_token, int32_t* group_off, hipStream_t s) {
+                             int32_t* k_per_token, int32_t* group_off, uint64_t* colmask,
+                             hipStream_t s) {
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     LaunchTimer tm(kSlotMask, s);
-    mask_count_kernel<true><<<div_up(NG, 4), 256, 0, s>>>(scores, mask, k_per_token, group_off, T,
-                                                          E, W, tau);
+    if (T <= 16) {
+        select_small_kernel<<<1, 1024, sizeof(uint64_t) * 16 * W, s>>>(
+            scores, mask, k_per_token, group_off, colmask, T, E, W, tau);
+        return;
+    }
+    mask_count_kernel<true><<<div_up(NG, 4), 256, 0, s>>>(scores, mask, k_per_token, group_off,
+                                                          colmask, T, E, W, tau);
 }
 
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,
-                            uint64_t* mask, int32_t* group_off, hipStream_t s) {
+                            uint64_t* mask, int32_t* group_off, uint64_t* colmask, hipStream_t s) {
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     {
         LaunchTimer tm(kSlotListsToMask, s);
@@ -271,8 +322,8 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
                                                   reinterpret_cast<unsigned long long*>(mask));
     }
     LaunchTimer tm(kSlotMask, s);
-    mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, nullptr, group_off, T, E,
-                                                           W, 0.0f);
+    mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, nullptr, group_off,
+                                                           colmask, T, E, W, 0.0f);
 }
 
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,

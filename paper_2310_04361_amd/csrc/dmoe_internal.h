@@ -10,7 +10,7 @@ namespace dmoe {
 
 // ---- fixed granularities -------------------------------------------------------------------
 constexpr int kGroup = 64;        // tokens per select group (one wavefront, lane = token)
-constexpr int kChunkGroups = 1;   // groups per down-projection token chunk
+constexpr int kChunkGroups = 2;   // groups per down-projection token chunk
 constexpr int kChunk = kGroup * kChunkGroups;   // 64 tokens whose outputs live in LDS together
 constexpr int kTilePad = 64;      // entries the expert kernels may read past the end of the lists
 

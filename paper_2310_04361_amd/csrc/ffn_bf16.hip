@@ -33,7 +33,7 @@ namespace {
 constexpr int kDownWaves = 8;
 constexpr int kDownCols = kDownWaves * 32;     // output columns per down workgroup
 constexpr int kDownBatch = 128;                // experts per tile-list batch
-constexpr int kDownTilesPerExpert = (kChunk / 16 + 2) / 2;   // fragment pairs a chunk can span
+constexpr int kDownTilesPerExpert = (kChunk + 31) / 32;       // 32-row tiles per (chunk, expert)
 constexpr int kDownStride = kDownCols + 4;     // LDS row stride in floats
 constexpr size_t kDownLds = sizeof(float) * kChunk * kDownStride +
                             sizeof(int2) * kDownBatch * kDownTilesPerExpert;
@@ -264,9 +264,9 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
 //
 // The fp32 output tile Y[64][256] lives in LDS.  The eight wavefronts own 32 columns each, so
 // no two wavefronts ever touch the same element and the merge is a plain read-add-write (LDS
-// float atomics proved far slower).  All wavefronts walk the same list of tiles -- two
-// consecutive H fragments (32 list rows) of one expert, of which only the rows that belong to
-// this chunk are merged -- built once per batch of experts from the group offsets.
+// float atomics proved far slower).  All wavefronts walk the same list of tiles -- up to 32
+// consecutive rows of one expert's part of H, all belonging to this chunk -- built once per
+// batch of experts from the group offsets.
 // Per tile and wavefront: D[32 cols][32 rows] = W2 slice * H_tile^T as 2 x 2 MFMA 16x16x32
 // tiles with the tokens on the MFMA column axis, so a lane ends up with four consecutive output
 // columns of ONE token: one 16-byte LDS read and write per MFMA tile, one row address per
@@ -307,23 +307,21 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
     const __bf16* wbase =
         w2f + ((size_t)(col0 / 16 + 2 * __builtin_amdgcn_readfirstlane(wave)) * KS * 64 + lane) * 8;
     const size_t w_expert_stride = (size_t)(d / 16) * KS * 512;
-    const __bf16* hbase = Hf + lane * 8;
     // element (token t, column wave*32 + nt*16 + 4q) is at ybase + t * kDownStride + nt * 16
     float* ybase = Y + wave * 32 + 4 * q - (ptrdiff_t)t_base * kDownStride;
 
     for (int ebase = 0; ebase < E; ebase += kDownBatch) {
         __syncthreads();  // Y initialised / previous batch's tile list no longer read
         // ---- tile list of this batch: thread i < kDownBatch describes expert ebase + i
-        int f0 = 0, nt_mine = 0, frag0 = 0;
+        int n_mine = 0, nt_mine = 0, row0 = 0;
         const int e_mine = ebase + tid;
         if (tid < kDownBatch && e_mine < E) {
             // rows lo .. hi-1 of expert e_mine's list belong to this chunk
             const int lo = group_off[(size_t)g_lo * E + e_mine];
-            const int hi = group_off[(size_t)g_hi * E + e_mine];
-            if (hi > lo) {
-                f0 = lo >> 4;
-                nt_mine = (((hi - 1) >> 4) - f0 + 2) >> 1;
-                frag0 = item_start[e_mine] * frags_per_item;
+            n_mine = group_off[(size_t)g_hi * E + e_mine] - lo;
+            if (n_mine > 0) {
+                nt_mine = (n_mine + 31) >> 5;
+                row0 = item_start[e_mine] * frags_per_item * 16 + lo;  // row of H / alist
             }
         }
         int incl = nt_mine;
@@ -340,37 +338,41 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
             if (w2 < wave) start += v;
             ntiles += v;
         }
-        for (int k = 0; k < nt_mine; ++k) tiles[start + k] = make_int2(frag0 + f0 + 2 * k, e_mine);
+        for (int k = 0; k < nt_mine; ++k)
+            tiles[start + k] = make_int2(row0 + 32 * k, (e_mine << 8) | min(32, n_mine - 32 * k));
         __syncthreads();
         // ---- walk the tiles with a ring of kDepth tiles of operands in flight
         bf16x8 a_st[kDepth][2][KS], b_st[kDepth][2][KS];
-        int tok_st[kDepth][2];
+        int tok_st[kDepth][2], rows_st[kDepth];
         // Issues the loads only; nothing here waits on them, so kDepth tiles of loads overlap.
-        // The tile entry is uniform: its address arithmetic stays on the scalar unit and every
-        // lane adds only its fixed offset.  Tiles past the end reload the last one with token
-        // ids of -1.  A tile's rows that belong to other chunks are read too: they only feed MFMA
-        // columns of lanes that skip the merge.
-        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2]) {
+        // A tile is up to 32 consecutive rows of H that all belong to this chunk; they start at
+        // any row, so each lane finds its row's fragment and slot itself (the rows of a tile
+        // still sit in at most three adjacent 1 KiB fragments).  Lanes past the tile's last row
+        // read row 0 of the tile again and skip the merge.  Tiles past the end repeat the last
+        // one with no rows.
+        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2], int& rows_out) {
             const int2 ent = tiles[min(ti, ntiles - 1)];
-            const int frag = __builtin_amdgcn_readfirstlane(ent.x);
-            const int e = __builtin_amdgcn_readfirstlane(ent.y);
-            const __bf16* wp = wbase + (size_t)e * w_expert_stride;
-            const __bf16* hp = hbase + (size_t)frag * KS * 512;
-            const int32_t* lp = alist + (size_t)frag * 16;
+            const int row_first = __builtin_amdgcn_readfirstlane(ent.x);
+            const int packed = __builtin_amdgcn_readfirstlane(ent.y);
+            const int rows = ti < ntiles ? (packed & 0xff) : 0;
+            const __bf16* wp = wbase + (size_t)(packed >> 8) * w_expert_stride;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
+                const int row = row_first + (16 * h + c < rows ? 16 * h + c : 0);
+                const __bf16* hp = Hf + ((size_t)(row >> 4) * KS * 64 + 16 * q + (row & 15)) * 8;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     a[h][ks] = load8(wp + (h * KS + ks) * 512);
-                    b[h][ks] = load8(hp + (h * KS + ks) * 512);
+                    b[h][ks] = load8(hp + ks * 512);
                 }
-                tok[h] = ti < ntiles ? lp[16 * h + c] : -1;
+                tok[h] = alist[row];
             }
+            rows_out = rows;
         };
         if (ntiles > 0) {
 #pragma unroll
             for (int st = 0; st < kDepth; ++st)
-                fetch(st, a_st[st], b_st[st], tok_st[st]);
+                fetch(st, a_st[st], b_st[st], tok_st[st], rows_st[st]);
         }
         for (int t0 = 0; t0 < ntiles; t0 += kDepth) {
 #pragma unroll
@@ -396,14 +398,16 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
                 asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]),
                                   "+v"(tok0), "+v"(tok1));
                 __builtin_amdgcn_sched_barrier(0);
-                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st]);
+                const int rows = rows_st[st];
+                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st], rows_st[st]);
 
-                // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of tile row tt*16 + c
+                // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of tile row tt*16 + c.
+                // (Feeding the old values in as the MFMA's C operand instead of adding afterwards
+                // measured slower: the LDS read then sits in front of the MFMAs.)
                 const int tok[2] = {tok0, tok1};
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {
-                    // rows of other chunks and the -1 slack fail this test
-                    if ((unsigned)(tok[tt] - t_base) < (unsigned)kChunk) {
+                    if (16 * tt + c < rows) {
                         float4* yp = reinterpret_cast<float4*>(ybase + tok[tt] * kDownStride);
                         float4 o0 = yp[0], o1 = yp[4];
                         o0.x += acc[0][tt][0]; o0.y += acc[0][tt][1];

@@ -258,6 +258,133 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
     }
 }
 
+// Up-projection for wide experts (8 or more neuron tiles per item, e.g. gated m = 64): there the
+// weights of an expert are as large as its x rows, so streaming them once per wavefront made the
+// kernel a weight stream.  Here a workgroup of four wavefronts owns 4 x 16*TT consecutive list
+// rows of one expert and shares each K block of the weight fragments through LDS (double
+// buffered, one barrier per block); the x rows stay private to their wavefront as above.
+template <int MT, bool GATED, int TT>
+__global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
+    const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
+    const __bf16* __restrict__ wgatef, const int32_t* __restrict__ item_start,
+    const int32_t* __restrict__ alist, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
+    constexpr int BR = GATED ? 2 : 1;
+    constexpr int KS = MT / 2;
+    constexpr int NT = BR * MT;         // neuron tiles per K step
+    constexpr int WR = TT * 16;         // rows per wavefront
+    constexpr int UR = 4 * WR;          // rows per work item
+    constexpr int NL = TT * 2;          // x load instructions per K block
+    constexpr int NWF = 2 * NT;         // weight fragments (1 KiB each) per K block
+    static_assert(NWF % 4 == 0, "weight fragments are copied four at a time");
+    extern __shared__ char smem[];
+    char* wbuf = smem;                                   // [2][NWF][1024]
+    const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15, w = threadIdx.x >> 6;
+    char* xs = smem + 2 * NWF * 1024 + w * (WR * kUpRowBytes);   // [WR][kUpRowBytes], private
+    const int NK32 = d / 32, NKB = d / 64;
+    const int ld_row = lane >> 3, ld_piece = lane & 7;
+    const int total = item_start[E];
+
+    for (int item = blockIdx.x; item < total; item += gridDim.x) {
+        // expert of this item: the last e with item_start[e] <= item (uniform binary search)
+        int lo = 0, hi = E;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (item_start[mid] <= item) lo = mid; else hi = mid;
+        }
+        const int e = lo;
+        const int32_t* tl = alist + (size_t)item * UR + w * WR + ld_row;
+        const bool active = alist[(size_t)item * UR + w * WR] >= 0;  // valid rows are a prefix
+        const __bf16* xrow[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) xrow[i] = x + (size_t)max(tl[8 * i], 0) * d + 8 * ld_piece;
+        // weight fragment f = (br*MT + mt)*2 + ks of K block kb; thread copies piece (f % 4 == w)
+        const __bf16* wsrc[NWF / 4];
+#pragma unroll
+        for (int i = 0; i < NWF / 4; ++i) {
+            const int f = 4 * i + w, ks = f & 1, tile = f >> 1, br = tile / MT, mt = tile % MT;
+            const __bf16* base = (GATED && br == BR - 1) ? wgatef : wupf;
+            wsrc[i] = base + (((size_t)e * MT + mt) * NK32 + ks) * 512 + lane * 8;
+        }
+
+        f32x4 acc[NT][TT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) acc[nt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        bf16x8 xr[NL], wr[NWF / 4];
+        auto load_next = [&](int kb) {
+#pragma unroll
+            for (int i = 0; i < NWF / 4; ++i) wr[i] = load8(wsrc[i] + (size_t)kb * 1024);
+            if (active) {
+#pragma unroll
+                for (int i = 0; i < NL; ++i) xr[i] = load8(xrow[i] + 64 * kb);
+            }
+        };
+        auto store_next = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < NWF / 4; ++i)
+                *reinterpret_cast<bf16x8*>(wbuf + buf * NWF * 1024 + (4 * i + w) * 1024 + lane * 16) = wr[i];
+            if (active) {
+                char* dst = xs + ld_row * kUpRowBytes + ld_piece * 16;
+#pragma unroll
+                for (int i = 0; i < NL; ++i)
+                    *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
+            }
+        };
+        __syncthreads();  // the previous item's last K block has been consumed by every wavefront
+        load_next(0);
+        store_next(0);
+        __syncthreads();
+        for (int kb = 0; kb < NKB; ++kb) {
+            load_next(min(kb + 1, NKB - 1));  // the last trip re-reads a block it will not use
+            if (active) {
+                const char* wsrc_l = wbuf + (kb & 1) * NWF * 1024 + lane * 16;
+                const char* xsrc = xs + c * kUpRowBytes + q * 16;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    bf16x8 b[TT];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        b[tt] = *reinterpret_cast<const bf16x8*>(xsrc + tt * 16 * kUpRowBytes + ks * 64);
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) {
+                        const bf16x8 a = *reinterpret_cast<const bf16x8*>(wsrc_l + (nt * 2 + ks) * 1024);
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) acc[nt][tt] = mfma16(a, b[tt], acc[nt][tt]);
+                    }
+                }
+            }
+            store_next((kb + 1) & 1);
+            __syncthreads();
+        }
+
+        if (active) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                __bf16* dst = Hf + ((((size_t)item * 4 + w) * TT + tt) * KS * 64 + lane) * 8;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    bf16x8 hv;
+#pragma unroll
+                    for (int half = 0; half < 2; ++half) {
+                        const int mt = 2 * ks + half;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            float v;
+                            if (GATED) v = activate_fast(act, acc[MT + mt][tt][r]) * acc[mt][tt][r];
+                            else v = activate_fast(act, acc[mt][tt][r]);
+                            if (16 * mt + 4 * q + r >= m) v = 0.0f;
+                            hv[half * 4 + r] = (__bf16)v;
+                        }
+                    }
+                    *reinterpret_cast<bf16x8*>(dst + (size_t)ks * 512) = hv;
+                }
+            }
+        }
+    }
+}
+
 // ---- down-projection and merge ------------------------------------------------------------------------
 // One workgroup per (64-token chunk, 256-column slice), two of them per CU; KS = m_pad / 32
 // MFMA k-steps.
@@ -456,6 +583,24 @@ void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
         L.expert_size, L.act);
 }
 
+template <int MT, bool GATED, int TT>
+void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
+                      const int32_t* item_start, const int32_t* alist, void* H, int grid,
+                      hipStream_t s) {
+    constexpr int NWF = 2 * (GATED ? 2 : 1) * MT;
+    const size_t lds = 2 * NWF * 1024 + 4 * (size_t)TT * 16 * kUpRowBytes;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_wide_bf16_kernel<MT, GATED, TT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    const char* pk = static_cast<const char*>(L.packed);
+    up_wide_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
+        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef), item_start,
+        alist, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
+}
+
 template <int KS>
 void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* item_start,
                    const int32_t* group_off, const int32_t* alist, const void* H, void* y,
@@ -513,6 +658,12 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* it
     const long long worst = (long long)T * L.n_experts / up_rows_bf16(L) + L.n_experts;
     const int grid = (int)std::min<long long>((worst + 3) / 4, 256 * 2);
     const int mt = m_pad_of(L.expert_size) / 16;
+    if (up_rows_bf16(L) == 256) {  // wide experts without b_up: weights shared through LDS
+        const int wgrid = (int)std::min<long long>((long long)T * L.n_experts / 256 + L.n_experts, 512);
+        if (L.gated) launch_up_wide_t<4, true, 4>(L, x, P, item_start, alist, H, wgrid, s);
+        else launch_up_wide_t<8, false, 4>(L, x, P, item_start, alist, H, wgrid, s);
+        return;
+    }
     if (L.gated) {
         if (mt == 2) launch_up_t<2, true, 4>(L, x, P, item_start, alist, H, grid, s);
         else launch_up_t<4, true, 4>(L, x, P, item_start, alist, H, grid, s);

@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 import numpy as np
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+# HBM bytes per launch of the dominant kernel from separate `rocprofv3 --pmc FETCH_SIZE` /
+# `WRITE_SIZE` runs of this script, scaled by the same counters' readings for a plain 256 MiB copy
+# (profiles/dmoe_forward_cfg2_tau0.5_hbm_traffic.txt).  Only valid for the exact workload named.
+MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 135.5e6 + 25.2e6,
+                    ("cfg2", 0.5, "expert_up"): 458.2e6 + 22.1e6}
 PEAK_HBM_GBS = 8000.0
 N_ROTATE = 8                   # distinct x / y buffers cycled through, so that inputs come from HBM
 
@@ -46,6 +51,8 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override the token count")
     ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense-FFN comparisons (keeps a profile to the timed workload)")
     args = ap.parse_args()
@@ -69,6 +76,14 @@ def main() -> int:
     xs = [x0] + [torch.roll(x0, shifts=17 * (i + 1), dims=0).contiguous() for i in range(N_ROTATE - 1)]
     ys = [torch.empty_like(x0) for _ in range(N_ROTATE)]
     torch.cuda.synchronize()
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # one D2D copy of 256 MiB: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     def step(i, tau=tau):
         B.dmoe_forward(L, xs[i % N_ROTATE], tau, y=ys[i % N_ROTATE])
@@ -100,7 +115,8 @@ def main() -> int:
     experts_ms = sum(kt[k][1] for k in kflops if k in kt)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": None, "avg_kernel_ms": round(dom_ms, 5),
+                "traffic": MEASURED_TRAFFIC.get((cfg.name, args.tau, dom)) if not args.tokens else None,
+                "avg_kernel_ms": round(dom_ms, 5),
                 "experts_tflops": round(flops / (experts_ms * 1e-3) / 1e12, 2)}
 
     # ---- dense FFN of the same shape with the vendor GEMM (context)

@@ -477,10 +477,21 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
         // still sit in at most three adjacent 1 KiB fragments).  Lanes past the tile's last row
         // read row 0 of the tile again and skip the merge.  Tiles past the end repeat the last
         // one with no rows.
+        // lane l of (ent_x, ent_y) holds the entry of tile ent_base + l: one LDS read per 64 tiles,
+        // then constant-cost broadcasts instead of an LDS round trip per tile
+        int ent_base = 0, ent_x = 0, ent_y = 0;
+        auto load_entries = [&](int base) {
+            const int2 ent = tiles[min(base + lane, max(ntiles - 1, 0))];
+            ent_base = base;
+            ent_x = ent.x;
+            ent_y = ent.y;
+        };
+        load_entries(0);
         auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2], int& rows_out) {
-            const int2 ent = tiles[min(ti, ntiles - 1)];
-            const int row_first = __builtin_amdgcn_readfirstlane(ent.x);
-            const int packed = __builtin_amdgcn_readfirstlane(ent.y);
+            const int tc = min(ti, ntiles - 1);
+            if (tc >= ent_base + 64) load_entries(tc);  // uniform
+            const int row_first = __builtin_amdgcn_readlane(ent_x, tc - ent_base);
+            const int packed = __builtin_amdgcn_readlane(ent_y, tc - ent_base);
             const int rows = ti < ntiles ? (packed & 0xff) : 0;
             const __bf16* wp = wbase + (size_t)(packed >> 8) * w_expert_stride;
 #pragma unroll
@@ -529,8 +540,8 @@ __global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
                 fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st], rows_st[st]);
 
                 // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of tile row tt*16 + c.
-                // (Feeding the old values in as the MFMA's C operand instead of adding afterwards
-                // measured slower: the LDS read then sits in front of the MFMAs.)
+                // (Two variants measured slower: feeding the old values in as the MFMA's C operand,
+                // and requesting them before the MFMAs.)
                 const int tok[2] = {tok0, tok1};
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {

@@ -3,9 +3,13 @@
 
 One step = one dmoe_forward (router, gate, bucketing, experts) over one batch of synthetic
 tokens that already sit in HBM.  The headline workload is the BERT-base-shaped bf16 layer
-(d=768, 128 experts of 24 neurons, GELU, 128x128 tokens) at tau = 0.5.  Prints ONE JSON line.
+(d=768, 128 experts of 24 neurons, GELU, 128x128 tokens) at tau = 0.5.  Prints ONE JSON line;
+its "other_workloads" list carries the remaining shapes (ViT-shaped ragged batch, the gated
+Gemma-shaped layer at prefill and at 16-token decode, the attention-projection module), each
+with its own roofline object.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--tau 0.5] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--tau 0.5]
+                    [--sweep] [--no-others] [--no-cpu] [--no-dense]
 """
 from __future__ import annotations
 
@@ -22,13 +26,16 @@ if ROOT not in sys.path:
 import numpy as np
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from separate `rocprofv3 --pmc FETCH_SIZE` /
 # `WRITE_SIZE` runs of this script, scaled by the same counters' readings for a plain 256 MiB copy
 # (profiles/dmoe_forward_cfg2_tau0.5_hbm_traffic.txt).  Only valid for the exact workload named.
 MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 135.5e6 + 25.2e6,
                     ("cfg2", 0.5, "expert_up"): 458.2e6 + 22.1e6}
-PEAK_HBM_GBS = 8000.0
 N_ROTATE = 8                   # distinct x / y buffers cycled through, so that inputs come from HBM
+N_LAYER_COPIES_DECODE = 4      # distinct weight copies cycled through at decode sizes: together
+                               # they exceed the 256 MB last-level cache, so weights come from HBM
+OTHERS = (("cfg3", 0.5), ("cfg4", 0.3), ("cfg4", 0.6), ("cfg5a", 0.5), ("cfg5b", 0.5))
 
 
 def _time_ms(fn, steps):
@@ -41,6 +48,119 @@ def _time_ms(fn, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+class Workload:
+    """One layer + its rotated inputs on the device."""
+
+    def __init__(self, name, tokens=0):
+        import torch
+        from paper_2310_04361_amd import binding as B, workloads as wl
+        cfg = wl.CONFIGS[name]
+        if tokens:
+            cfg = wl.with_tokens(cfg, tokens)
+        self.cfg = cfg
+        self.layer_np, self.x_np = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
+        self.decode = cfg.T <= 16
+        n_layers = N_LAYER_COPIES_DECODE if self.decode else 1
+        self.layers = [B.Layer(self.layer_np, cfg.dtype) for _ in range(n_layers)]
+        x0 = B.to_device(self.x_np, cfg.dtype)
+        self.xs = [x0] + [torch.roll(x0, shifts=17 * (i + 1), dims=0).contiguous()
+                          for i in range(N_ROTATE - 1)]
+        self.ys = [torch.empty_like(x0) for _ in range(N_ROTATE)]
+        torch.cuda.synchronize()
+
+    def step(self, i, tau, hot=False):
+        from paper_2310_04361_amd import binding as B
+        L = self.layers[0 if hot else i % len(self.layers)]
+        B.dmoe_forward(L, self.xs[i % N_ROTATE], tau, y=self.ys[i % N_ROTATE])
+
+    def measure(self, tau_arg, steps, warmup, traffic_ok=True):
+        """Whole-forward time, per-kernel times (HIP events on the launch stream) and the
+        roofline object of the dominant expert kernel."""
+        import torch
+        from paper_2310_04361_amd import binding as B, cost_model
+        cfg = self.cfg
+        tau = float(np.float32(tau_arg))
+        # executed pairs (the same for every rotated copy: the rows are only permuted)
+        _, ex = B.dmoe_forward(self.layers[0], self.xs[0], tau, want_lists=True)
+        torch.cuda.synchronize()
+        offsets = ex["offsets"].cpu().numpy()
+        pairs = int(offsets[-1])
+        touched = int(np.count_nonzero(np.diff(offsets)))
+        flops = cost_model.executed_flops(pairs, cfg.d, cfg.m, cfg.gated)
+
+        for i in range(warmup):
+            self.step(i, tau)
+        ms = _time_ms(lambda i: self.step(i, tau), steps)
+
+        B.timing(True)
+        for i in range(min(steps, 200)):
+            self.step(i, tau)
+        torch.cuda.synchronize()
+        kt = {k: t / n for k, (n, t) in B.timing_read().items() if n}
+        B.timing(False)
+
+        g = 3 if cfg.gated else 2
+        if self.decode:
+            # weight-streaming kernels: algorithmic bytes = the touched experts' weights, once
+            per_expert = 2.0 * cfg.d * cfg.m
+            kbytes = {"small_up": touched * per_expert * (g - 1), "small_down": touched * per_expert}
+            dom = max(kbytes, key=lambda k: kt.get(k, 0.0))
+            achieved = kbytes[dom] / (kt[dom] * 1e-3) / 1e9
+            both_ms = kt["small_up"] + kt["small_down"]
+            roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
+                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
+                        "traffic": None, "avg_kernel_ms": round(kt[dom], 5),
+                        "touched_experts": touched,
+                        "experts_gbs": round(sum(kbytes.values()) / (both_ms * 1e-3) / 1e9, 1),
+                        "weight_copies_rotated": len(self.layers)}
+        else:
+            kflops = {"expert_up": flops * (g - 1) / g, "expert_down": flops / g}
+            dom = max(kflops, key=lambda k: kt.get(k, 0.0))
+            achieved = kflops[dom] / (kt[dom] * 1e-3) / 1e12
+            experts_ms = sum(kt[k] for k in kflops if k in kt)
+            roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
+                        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                        "traffic": MEASURED_TRAFFIC.get((cfg.name, tau_arg, dom)) if traffic_ok else None,
+                        "avg_kernel_ms": round(kt[dom], 5),
+                        "experts_tflops": round(flops / (experts_ms * 1e-3) / 1e12, 2)}
+        return {"ms": ms, "pairs": pairs, "density": pairs / (cfg.T * cfg.E), "flops": flops,
+                "kernel_ms": {k: round(v, 5) for k, v in kt.items()}, "roofline": roofline}
+
+    def dense_ms(self):
+        """Dense FFN of the same shape with the vendor GEMM (context)."""
+        import torch
+        cfg, L = self.cfg, self.layers[0]
+        W_up = L.t["w_up"].reshape(cfg.H, cfg.d)
+        W_dn = L.t["w_down"].reshape(cfg.H, cfg.d)
+        W_g = L.t["w_gate"].reshape(cfg.H, cfg.d) if cfg.gated else None
+        act = {"relu": torch.relu, "gelu_erf": torch.nn.functional.gelu,
+               "gelu_tanh": lambda v: torch.nn.functional.gelu(v, approximate="tanh")}[cfg.act]
+
+        def dense(i):
+            x = self.xs[i % N_ROTATE]
+            if cfg.gated:
+                h = act(x @ W_g.T) * (x @ W_up.T)
+            else:
+                h = x @ W_up.T
+                if L.t["b_up"] is not None:
+                    h = h + L.t["b_up"].reshape(-1)
+                h = act(h)
+            out = h @ W_dn
+            if L.t["b_down"] is not None:
+                out = out + L.t["b_down"]
+            return out
+
+        for i in range(5):
+            dense(i)
+        return _time_ms(dense, 30)
+
+    def describe(self, tau):
+        cfg = self.cfg
+        return (f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} m={cfg.m} d_h={cfg.d_h} "
+                f"{'gated-' if cfg.gated else ''}{cfg.act} tau={tau}")
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,6 +171,7 @@ def main() -> int:
     ap.add_argument("--tokens", type=int, default=0, help="override the token count")
     ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-others", action="store_true", help="skip the other workloads")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-dense", action="store_true",
@@ -62,20 +183,13 @@ def main() -> int:
         return 2
 
     import torch
-    from paper_2310_04361_amd import binding as B, cost_model, workloads as wl
+    from paper_2310_04361_amd import binding as B, cost_model
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    cfg = wl.CONFIGS[args.workload]
-    if args.tokens:
-        cfg = wl.with_tokens(cfg, args.tokens)
+    w = Workload(args.workload, args.tokens)
+    cfg = w.cfg
     tau = float(np.float32(args.tau))
-    layer_np, x_np = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
-    L = B.Layer(layer_np, cfg.dtype)
-    x0 = B.to_device(x_np, cfg.dtype)
-    xs = [x0] + [torch.roll(x0, shifts=17 * (i + 1), dims=0).contiguous() for i in range(N_ROTATE - 1)]
-    ys = [torch.empty_like(x0) for _ in range(N_ROTATE)]
-    torch.cuda.synchronize()
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -85,81 +199,27 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    def step(i, tau=tau):
-        B.dmoe_forward(L, xs[i % N_ROTATE], tau, y=ys[i % N_ROTATE])
-
-    # executed pairs (the same for every rotated copy: the rows are only permuted)
-    _, ex = B.dmoe_forward(L, x0, tau, want_lists=True)
-    torch.cuda.synchronize()
-    pairs = int(ex["offsets"][-1].item())
-    density = pairs / (cfg.T * cfg.E)
-    flops = cost_model.executed_flops(pairs, cfg.d, cfg.m, cfg.gated)
-
-    for i in range(args.warmup):
-        step(i)
-    ms = _time_ms(step, args.steps)
-    tokens_per_s = cfg.T / (ms * 1e-3)
-
-    # ---- per-kernel durations (HIP events on the launch stream), separate pass
-    B.timing(True)
-    for i in range(min(args.steps, 200)):
-        step(i)
-    torch.cuda.synchronize()
-    kt = {k: (n, t / n) for k, (n, t) in B.timing_read().items() if n}
-    B.timing(False)
-    g = 3 if cfg.gated else 2
-    kflops = {"expert_up": flops * (g - 1) / g, "expert_down": flops / g}
-    dom = max(kflops, key=lambda k: kt[k][1] if k in kt else 0.0)
-    dom_ms = kt[dom][1]
-    achieved = kflops[dom] / (dom_ms * 1e-3) / 1e12
-    experts_ms = sum(kt[k][1] for k in kflops if k in kt)
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": MEASURED_TRAFFIC.get((cfg.name, args.tau, dom)) if not args.tokens else None,
-                "avg_kernel_ms": round(dom_ms, 5),
-                "experts_tflops": round(flops / (experts_ms * 1e-3) / 1e12, 2)}
-
-    # ---- dense FFN of the same shape with the vendor GEMM (context)
-    W_up = L.t["w_up"].reshape(cfg.H, cfg.d)
-    W_dn = L.t["w_down"].reshape(cfg.H, cfg.d)
-    W_g = L.t["w_gate"].reshape(cfg.H, cfg.d) if cfg.gated else None
-    act = {"relu": torch.relu, "gelu_erf": torch.nn.functional.gelu,
-           "gelu_tanh": lambda v: torch.nn.functional.gelu(v, approximate="tanh")}[cfg.act]
-
-    def dense(i):
-        x = xs[i % N_ROTATE]
-        if cfg.gated:
-            h = act(x @ W_g.T) * (x @ W_up.T)
-        else:
-            h = x @ W_up.T
-            if L.t["b_up"] is not None:
-                h = h + L.t["b_up"].reshape(-1)
-            h = act(h)
-        out = h @ W_dn
-        if L.t["b_down"] is not None:
-            out = out + L.t["b_down"]
-        return out
+    r = w.measure(args.tau, args.steps, args.warmup, traffic_ok=not args.tokens)
+    ms = r["ms"]
 
     dense_ms = own_dense_ms = None
     if not args.no_dense:
-        for i in range(5):
-            dense(i)
-        dense_ms = _time_ms(dense, 30)
+        dense_ms = w.dense_ms()
         for i in range(3):
-            step(i, 0.0)
-        own_dense_ms = _time_ms(lambda i: step(i, 0.0), 20)
+            w.step(i, 0.0)
+        own_dense_ms = _time_ms(lambda i: w.step(i, 0.0), 20)
 
     sweep = None
     if args.sweep:
         sweep = []
         for t in cfg.taus:
             t32 = float(np.float32(t))
-            _, e2 = B.dmoe_forward(L, x0, t32, want_lists=True)
+            _, e2 = B.dmoe_forward(w.layers[0], w.xs[0], t32, want_lists=True)
             torch.cuda.synchronize()
             p = int(e2["offsets"][-1].item())
             for i in range(5):
-                step(i, t32)
-            m = _time_ms(lambda i: step(i, t32), 50)
+                w.step(i, t32)
+            m = _time_ms(lambda i: w.step(i, t32), 50)
             sweep.append({"tau": t, "density": round(p / (cfg.T * cfg.E), 4), "ms": round(m, 4),
                           "tokens_per_s": round(cfg.T / (m * 1e-3)),
                           "executed_tflops": round(cost_model.executed_flops(p, cfg.d, cfg.m, cfg.gated) / (m * 1e-3) / 1e12, 2),
@@ -172,7 +232,7 @@ def main() -> int:
         n = min(cfg.T, 16384)
         runs, t0 = 0, time.perf_counter()
         while runs < 50 and time.perf_counter() - t0 < 10.0:   # about 10 s of CPU work
-            oracle.forward(layer_np, x_np[:n], tau)
+            oracle.forward(w.layer_np, w.x_np[:n], tau)
             runs += 1
         dt = time.perf_counter() - t0
         cpu = {"value": round(n * runs / dt, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
@@ -181,22 +241,49 @@ def main() -> int:
 
     out = {
         "metric": "tokens/sec of dynamic-k MoE FFN forward (router + gate + experts)",
-        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "value": round(cfg.T / (ms * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} m={cfg.m} d_h={cfg.d_h} "
-                               f"{'gated-' if cfg.gated else ''}{cfg.act} tau={args.tau}",
-                   "density": round(density, 4), "pairs": pairs},
-        "executed_expert_tflops": round(flops / (ms * 1e-3) / 1e12, 2),
+        "config": {"workload": w.describe(args.tau), "density": round(r["density"], 4),
+                   "pairs": r["pairs"]},
+        "executed_expert_tflops": round(r["flops"] / (ms * 1e-3) / 1e12, 2),
         "dense_ffn_ms": ({"vendor_gemm": round(dense_ms, 4), "own_kernels_tau0": round(own_dense_ms, 4)}
                          if dense_ms else None),
         "speedup_vs_dense": round(dense_ms / ms, 3) if dense_ms else None,
-        "kernel_ms": {k: round(v[1], 5) for k, v in kt.items()},
-        "roofline": roofline,
+        "kernel_ms": r["kernel_ms"],
+        "roofline": r["roofline"],
         "cpu_baseline": cpu,
     }
     if sweep:
         out["tau_sweep"] = sweep
+
+    if not args.no_others:
+        del w
+        torch.cuda.empty_cache()
+        others, cache = [], {}
+        for name, t in OTHERS:
+            if (name, t) == (args.workload, args.tau) and not args.tokens:
+                continue
+            if name not in cache:
+                cache.clear()
+                torch.cuda.empty_cache()
+                cache[name] = Workload(name)
+                cache[name + "/dense"] = None if args.no_dense else cache[name].dense_ms()
+            wo, dms = cache[name], cache[name + "/dense"]
+            steps = 100 if wo.cfg.T > 16 else 400
+            ro = wo.measure(t, steps, 10, traffic_ok=False)
+            entry = {"workload": wo.describe(t), "ms_per_step": round(ro["ms"], 5),
+                     "tokens_per_s": round(wo.cfg.T / (ro["ms"] * 1e-3), 1),
+                     "density": round(ro["density"], 4), "pairs": ro["pairs"],
+                     "executed_expert_tflops": round(ro["flops"] / (ro["ms"] * 1e-3) / 1e12, 2),
+                     "dense_vendor_gemm_ms": round(dms, 4) if dms else None,
+                     "speedup_vs_dense": round(dms / ro["ms"], 3) if dms else None,
+                     "kernel_ms": ro["kernel_ms"], "roofline": ro["roofline"]}
+            if wo.decode:
+                hot = _time_ms(lambda i: wo.step(i, float(np.float32(t)), hot=True), steps)
+                entry["ms_per_step_weights_cached"] = round(hot, 5)
+            others.append(entry)
+        out["other_workloads"] = others
     print(json.dumps(out))
     return 0
 

@@ -35,17 +35,18 @@ inline size_t h_fragments(const dmoe_layer& L, int T) {
 
 // Sub-buffers of the packed-weights buffer (bytes from its start).
 struct PackedLayout {
-    size_t w2f, wupf, wgatef, r1f, r2f, total;
+    size_t w2f, w2g, wupf, wgatef, r1f, r2f, total;
 };
 inline PackedLayout packed_layout(const dmoe_layer& L) {
     PackedLayout P{};
     if (L.dtype != DMOE_BF16) return P;
     const size_t one =
         (2 * (size_t)L.n_experts * L.d_model * m_pad_of(L.expert_size) + 255) / 256 * 256;
-    P.w2f = 0;
-    P.wupf = one;
-    P.wgatef = 2 * one;
-    size_t o = (L.gated ? 3 : 2) * one;
+    P.w2f = 0;          // down-projection, 16x16x32 fragments (small-token path)
+    P.w2g = one;        // down-projection, 32x32x16 fragments (down_bf16.hip)
+    P.wupf = 2 * one;
+    P.wgatef = 3 * one;
+    size_t o = (L.gated ? 4 : 3) * one;
     // router weights as fragments: r1f[d_h/16][d/32][64][8], r2f[ceil(E/16)][d_h/32][64][8]
     P.r1f = o;
     o += (2 * (size_t)round_up(L.router_hidden > 0 ? L.router_hidden : 0, 16) * L.d_model + 255) / 256 * 256;
@@ -65,7 +66,9 @@ enum Slot {
     kSlotUp,
     kSlotDown,
     kSlotFfnF32,
-    kSlotSmall,
+    kSlotSmallUp,
+    kSlotSmallDown,
+    kSlotSmallFinish,
     kSlotPack,
     kSlotCount
 };
@@ -119,12 +122,16 @@ void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t
 void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* mask, float* y,
                     hipStream_t s);
 void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s);
-// H holds the hidden activations in 16-row MFMA fragments (layout: see ffn_bf16.hip).
+// H holds one row of m_pad hidden activations per list row (layout: see ffn_bf16.hip).
 // alist is the work-item-aligned token list (see select.hip); its index is the row index of H.
 void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* item_start,
                     const int32_t* alist, void* H, hipStream_t s);
+// Down-projection and merge (down_bf16.hip): mask is the token-major selection bitmask that the
+// lists were built from; group_off[g][e] = rows of expert e that belong to tokens before group g.
+bool down_bf16_supported(const dmoe_layer& L);
+void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s);
 void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
-                      const int32_t* group_off, const int32_t* alist, const void* H, void* y,
+                      const int32_t* group_off, const uint64_t* mask, const void* H, void* y,
                       hipStream_t s);
 
 bool experts_bf16_supported(const dmoe_layer& L);

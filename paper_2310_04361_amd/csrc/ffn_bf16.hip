@@ -1,28 +1,21 @@
-// bf16 expert execution and merge (Sec. 3.2, Appendix G) on the gfx950 matrix cores.
+// bf16 expert up-projection (+ gate) and activation (Sec. 3.2, Appendix G) on the gfx950 matrix
+// cores, and the one-time packing of the expert and router weights.
 //
-// Two kernels, both driven by the sorted per-expert token lists:
 //   up    expert-major grouped GEMM over the compact lists.  A wavefront owns UR = 16*TT list
 //         rows of one expert, gathers those rows of x in 128-byte pieces (eight lanes per row, so
 //         the vector memory path sees whole cache lines), stages them in its own LDS buffers and
 //         multiplies them with the expert's up (and gate) rows; bias + activation in fp32; the
-//         hidden activations go out rounded to bf16 in MFMA-fragment order.
-//   down  output-stationary: a workgroup owns 64 consecutive tokens x 256 output columns as an
-//         fp32 tile in LDS, walks all experts, multiplies the chunk's H fragments of each expert
-//         by that expert's down-projection slice and adds the result into the owning token rows
-//         (plain LDS read-add-write; each wavefront owns its own columns).  Every y element is
-//         written exactly once, in bf16; no global atomics, no second pass.
-// Tokens ride on the MFMA column axis in both kernels, so four consecutive neurons (up) or
-// output columns (down) of one token land in one lane.
+//         hidden activations go out rounded to bf16, one row of m_pad values per list row.
+// Tokens ride on the MFMA column axis, so four consecutive neurons of one token land in one lane.
 //
-// Fragment order.  Every operand that a wavefront reads with one load instruction is stored as
-// the 1 KiB block  [lane 0..63][8 bf16]  in exactly the register layout of the MFMA, because a
-// 16-byte-per-lane access with a 64-byte or larger lane stride costs a cache-line lookup per
-// lane and that, not bandwidth, bounded the first version of these kernels.
-//   H fragment F, k-step ks: lane (q, c) holds, for list row 16*(F - first fragment of the
-//     expert) + c, the neurons 32ks + 16*(s/4) + 4q + (s%4), s = 0..7 -- the order in which the
-//     up kernel's accumulators come out; the packed down-projection uses the same k order.
-//   An expert's H rows start at a multiple of UR rows (its first up-projection work item), so
-//     fragments never mix experts.
+// Fragment order.  Every weight operand that a wavefront reads with one load instruction is
+// stored as the 1 KiB block  [lane 0..63][8 bf16]  in exactly the register layout of the MFMA,
+// because a 16-byte-per-lane access with a 64-byte or larger lane stride costs a cache-line
+// lookup per lane and that, not bandwidth, bounded the first version of these kernels.
+//   H row (m_pad bf16): 16-byte piece 4ks + q holds the neurons 32ks + 4q + {0..3} and
+//     32ks + 16 + 4q + {0..3} -- the order in which the accumulators of lane (q, .) come out;
+//     the packed down-projection uses the same order.
+//   An expert's H rows start at a multiple of UR rows (its first up-projection work item).
 #include "dmoe_internal.h"
 #include "mfma.h"
 
@@ -30,13 +23,6 @@ namespace dmoe {
 
 namespace {
 
-constexpr int kDownWaves = 8;
-constexpr int kDownCols = kDownWaves * 32;     // output columns per down workgroup
-constexpr int kDownBatch = 128;                // experts per tile-list batch
-constexpr int kDownTilesPerExpert = (kChunk + 31) / 32;       // 32-row tiles per (chunk, expert)
-constexpr int kDownStride = kDownCols + 4;     // LDS row stride in floats
-constexpr size_t kDownLds = sizeof(float) * kChunk * kDownStride +
-                            sizeof(int2) * kDownBatch * kDownTilesPerExpert;
 constexpr int kUpRowBytes = 144;               // 64 bf16 of one x row + 16 bytes of bank skew
 
 // ---- activations (fp32 in, fp32 out) -------------------------------------------------------------
@@ -62,7 +48,7 @@ __device__ __forceinline__ float activate_fast(int act, float v) {
 }
 
 // ---- one-time weight packing ------------------------------------------------------------------------
-// w_down[E][m][d] -> w2f[E][d/16][KS][64][8]: lane (q, c) of fragment (e, column tile ct, ks)
+// (small-token path) w_down[E][m][d] -> w2f[E][d/16][KS][64][8]: lane (q, c) of fragment (e, column tile ct, ks)
 // holds W_down[e][32ks + 16*(s/4) + 4q + s%4][16ct + c], zero for neurons >= m.
 __global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __restrict__ w2f,
                                  int E, int m, int d, int KS) {
@@ -232,7 +218,7 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
         // lane (q, c) of tile (mt, tt): neurons 16mt + 4q + r of list row 16tt + c
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
-            __bf16* dst = Hf + (((size_t)item * TT + tt) * KS * 64 + lane) * 8;
+            __bf16* dst = Hf + ((size_t)item * UR + 16 * tt + c) * (KS * 32) + 8 * q;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 bf16x8 hv;
@@ -252,7 +238,7 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
                         hv[half * 4 + r] = (__bf16)v;
                     }
                 }
-                *reinterpret_cast<bf16x8*>(dst + (size_t)ks * 512) = hv;
+                *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
             }
         }
     }
@@ -362,7 +348,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
         if (active) {
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                __bf16* dst = Hf + ((((size_t)item * 4 + w) * TT + tt) * KS * 64 + lane) * 8;
+                __bf16* dst = Hf + ((size_t)item * UR + w * WR + 16 * tt + c) * (KS * 32) + 8 * q;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     bf16x8 hv;
@@ -378,198 +364,9 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
                             hv[half * 4 + r] = (__bf16)v;
                         }
                     }
-                    *reinterpret_cast<bf16x8*>(dst + (size_t)ks * 512) = hv;
+                    *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
                 }
             }
-        }
-    }
-}
-
-// ---- down-projection and merge ------------------------------------------------------------------------
-// One workgroup per (64-token chunk, 256-column slice), two of them per CU; KS = m_pad / 32
-// MFMA k-steps.
-//
-// The fp32 output tile Y[64][256] lives in LDS.  The eight wavefronts own 32 columns each, so
-// no two wavefronts ever touch the same element and the merge is a plain read-add-write (LDS
-// float atomics proved far slower).  All wavefronts walk the same list of tiles -- up to 32
-// consecutive rows of one expert's part of H, all belonging to this chunk -- built once per
-// batch of experts from the group offsets.
-// Per tile and wavefront: D[32 cols][32 rows] = W2 slice * H_tile^T as 2 x 2 MFMA 16x16x32
-// tiles with the tokens on the MFMA column axis, so a lane ends up with four consecutive output
-// columns of ONE token: one 16-byte LDS read and write per MFMA tile, one row address per
-// token.  The row stride of 260 floats spreads consecutive-token rows over the banks.
-// Operands of the next kDepth tiles are kept in flight while the current one is merged.
-template <int KS>
-__global__ __launch_bounds__(kDownWaves * 64) void down_bf16_kernel(
-    const __bf16* __restrict__ w2f, const __bf16* __restrict__ b_down,
-    const int32_t* __restrict__ item_start, const int32_t* __restrict__ group_off,
-    const int32_t* __restrict__ alist, const __bf16* __restrict__ Hf, __bf16* __restrict__ y, int T,
-    int d, int E, int NG, int frags_per_item) {
-    constexpr int kThreads = kDownWaves * 64;
-    constexpr int kDepth = KS <= 2 ? 4 : 2;  // tiles of operands in flight per wavefront
-    extern __shared__ float smem_f[];
-    float* Y = smem_f;  // [kChunk][kDownStride]
-    int2* tiles = reinterpret_cast<int2*>(smem_f + kChunk * kDownStride);
-    __shared__ int s_wave_tot[kDownWaves];
-    // The slices of one chunk share its H rows and token lists: keep them on one XCD (workgroups
-    // are dealt round-robin to the 8 XCDs) and next to each other in launch order.
-    const int NS = d / kDownCols;
-    const int k_in_xcd = blockIdx.x >> 3;
-    const int chunk = (k_in_xcd / NS) * 8 + (blockIdx.x & 7), slice = k_in_xcd % NS;
-    if (chunk * kChunk >= T) return;  // the grid is rounded up to whole groups of 8 chunks
-    const int t_base = chunk * kChunk, col0 = slice * kDownCols;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6, q = lane >> 4, c = lane & 15;
-    {   // every row of the tile starts as the output bias of this slice
-        static_assert(kThreads % kDownCols == 0, "one column per thread");
-        const int col = tid % kDownCols;
-        const float bias = b_down ? (float)b_down[col0 + col] : 0.0f;
-        for (int row = tid / kDownCols; row < kChunk; row += kThreads / kDownCols)
-            Y[row * kDownStride + col] = bias;
-    }
-
-    const int g_lo = chunk * kChunkGroups;
-    const int g_hi = min(g_lo + kChunkGroups, NG);
-    // weight fragments of this wavefront's two column tiles: + (e * d/16) fragments per expert
-    const __bf16* wbase =
-        w2f + ((size_t)(col0 / 16 + 2 * __builtin_amdgcn_readfirstlane(wave)) * KS * 64 + lane) * 8;
-    const size_t w_expert_stride = (size_t)(d / 16) * KS * 512;
-    // element (token t, column wave*32 + nt*16 + 4q) is at ybase + t * kDownStride + nt * 16
-    float* ybase = Y + wave * 32 + 4 * q - (ptrdiff_t)t_base * kDownStride;
-
-    for (int ebase = 0; ebase < E; ebase += kDownBatch) {
-        __syncthreads();  // Y initialised / previous batch's tile list no longer read
-        // ---- tile list of this batch: thread i < kDownBatch describes expert ebase + i
-        int n_mine = 0, nt_mine = 0, row0 = 0;
-        const int e_mine = ebase + tid;
-        if (tid < kDownBatch && e_mine < E) {
-            // rows lo .. hi-1 of expert e_mine's list belong to this chunk
-            const int lo = group_off[(size_t)g_lo * E + e_mine];
-            n_mine = group_off[(size_t)g_hi * E + e_mine] - lo;
-            if (n_mine > 0) {
-                nt_mine = (n_mine + 31) >> 5;
-                row0 = item_start[e_mine] * frags_per_item * 16 + lo;  // row of H / alist
-            }
-        }
-        int incl = nt_mine;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int v = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += v;
-        }
-        if (lane == 63) s_wave_tot[wave] = incl;
-        __syncthreads();
-        int start = incl - nt_mine, ntiles = 0;
-        for (int w2 = 0; w2 < kDownWaves; ++w2) {
-            const int v = s_wave_tot[w2];
-            if (w2 < wave) start += v;
-            ntiles += v;
-        }
-        for (int k = 0; k < nt_mine; ++k)
-            tiles[start + k] = make_int2(row0 + 32 * k, (e_mine << 8) | min(32, n_mine - 32 * k));
-        __syncthreads();
-        // ---- walk the tiles with a ring of kDepth tiles of operands in flight
-        bf16x8 a_st[kDepth][2][KS], b_st[kDepth][2][KS];
-        int tok_st[kDepth][2], rows_st[kDepth];
-        // Issues the loads only; nothing here waits on them, so kDepth tiles of loads overlap.
-        // A tile is up to 32 consecutive rows of H that all belong to this chunk; they start at
-        // any row, so each lane finds its row's fragment and slot itself (the rows of a tile
-        // still sit in at most three adjacent 1 KiB fragments).  Lanes past the tile's last row
-        // read row 0 of the tile again and skip the merge.  Tiles past the end repeat the last
-        // one with no rows.
-        // lane l of (ent_x, ent_y) holds the entry of tile ent_base + l: one LDS read per 64 tiles,
-        // then constant-cost broadcasts instead of an LDS round trip per tile
-        int ent_base = 0, ent_x = 0, ent_y = 0;
-        auto load_entries = [&](int base) {
-            const int2 ent = tiles[min(base + lane, max(ntiles - 1, 0))];
-            ent_base = base;
-            ent_x = ent.x;
-            ent_y = ent.y;
-        };
-        load_entries(0);
-        auto fetch = [&](int ti, bf16x8 (&a)[2][KS], bf16x8 (&b)[2][KS], int (&tok)[2], int& rows_out) {
-            const int tc = min(ti, ntiles - 1);
-            if (tc >= ent_base + 64) load_entries(tc);  // uniform
-            const int row_first = __builtin_amdgcn_readlane(ent_x, tc - ent_base);
-            const int packed = __builtin_amdgcn_readlane(ent_y, tc - ent_base);
-            const int rows = ti < ntiles ? (packed & 0xff) : 0;
-            const __bf16* wp = wbase + (size_t)(packed >> 8) * w_expert_stride;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int row = row_first + (16 * h + c < rows ? 16 * h + c : 0);
-                const __bf16* hp = Hf + ((size_t)(row >> 4) * KS * 64 + 16 * q + (row & 15)) * 8;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    a[h][ks] = load8(wp + (h * KS + ks) * 512);
-                    b[h][ks] = load8(hp + ks * 512);
-                }
-                tok[h] = alist[row];
-            }
-            rows_out = rows;
-        };
-        if (ntiles > 0) {
-#pragma unroll
-            for (int st = 0; st < kDepth; ++st)
-                fetch(st, a_st[st], b_st[st], tok_st[st], rows_st[st]);
-        }
-        for (int t0 = 0; t0 < ntiles; t0 += kDepth) {
-#pragma unroll
-            for (int st = 0; st < kDepth; ++st) {
-                // keep each stage's work inside the stage: hoisting a later stage's first use of
-                // its loads up here would make this stage wait for them as well
-                __builtin_amdgcn_sched_barrier(0);
-                f32x4 acc[2][2];  // [column tile nt][token tile tt]
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int tt = 0; tt < 2; ++tt) {
-                        acc[nt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int ks = 0; ks < KS; ++ks)
-                            acc[nt][tt] = mfma16(a_st[st][nt][ks], b_st[st][tt][ks], acc[nt][tt]);
-                    }
-                int tok0 = tok_st[st][0], tok1 = tok_st[st][1];
-                // Pin the MFMAs and the token reads here (an empty asm the optimiser cannot move
-                // values across): otherwise they sink below the refill, the old and the new
-                // operands of the stage overlap and the ring turns into register copies that
-                // wait on loads just issued.  The refill then reuses the stage's registers.
-                asm volatile("" : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]),
-                                  "+v"(tok0), "+v"(tok1));
-                __builtin_amdgcn_sched_barrier(0);
-                const int rows = rows_st[st];
-                fetch(t0 + st + kDepth, a_st[st], b_st[st], tok_st[st], rows_st[st]);
-
-                // lane (q, c) of tile (nt, tt): columns nt*16 + 4q .. +3 of tile row tt*16 + c.
-                // (Two variants measured slower: feeding the old values in as the MFMA's C operand,
-                // and requesting them before the MFMAs.)
-                const int tok[2] = {tok0, tok1};
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt) {
-                    if (16 * tt + c < rows) {
-                        float4* yp = reinterpret_cast<float4*>(ybase + tok[tt] * kDownStride);
-                        float4 o0 = yp[0], o1 = yp[4];
-                        o0.x += acc[0][tt][0]; o0.y += acc[0][tt][1];
-                        o0.z += acc[0][tt][2]; o0.w += acc[0][tt][3];
-                        o1.x += acc[1][tt][0]; o1.y += acc[1][tt][1];
-                        o1.z += acc[1][tt][2]; o1.w += acc[1][tt][3];
-                        yp[0] = o0;
-                        yp[4] = o1;
-                    }
-                }
-            }
-        }
-    }
-    __syncthreads();
-
-    for (int i = tid; i < kChunk * (kDownCols / 8); i += kThreads) {
-        const int row = i / (kDownCols / 8), cg = i % (kDownCols / 8);
-        const int t = t_base + row;
-        if (t < T) {
-            const float* src = Y + row * kDownStride + cg * 8;
-            bf16x8 o;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) o[k] = (__bf16)src[k];
-            *reinterpret_cast<bf16x8*>(y + (size_t)t * d + col0 + cg * 8) = o;
         }
     }
 }
@@ -612,30 +409,13 @@ void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
         alist, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
 }
 
-template <int KS>
-void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* item_start,
-                   const int32_t* group_off, const int32_t* alist, const void* H, void* y,
-                   hipStream_t s) {
-    const int NG = div_up(T, kGroup), NC = div_up(T, kChunk), NS = L.d_model / kDownCols;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KS>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDownLds);
-        attr_set = true;
-    }
-    const char* pk = static_cast<const char*>(L.packed);
-    down_bf16_kernel<KS><<<round_up(NC, 8) * NS, kDownWaves * 64, kDownLds, s>>>(
-        (const __bf16*)(pk + P.w2f), (const __bf16*)L.b_down, item_start, group_off, alist,
-        (const __bf16*)H, (__bf16*)y, T, L.d_model, L.n_experts, NG, up_rows_bf16(L) / 16);
-}
-
 }  // namespace
 
 bool experts_bf16_supported(const dmoe_layer& L) {
     const int mp = m_pad_of(L.expert_size);
     if (!(mp == 32 || mp == 64 || mp == 128)) return false;
     if (L.gated && mp == 128) return false;  // accumulators of both branches would not fit
-    return L.d_model % kDownCols == 0 && L.n_experts <= 8192;
+    return down_bf16_supported(L) && L.n_experts <= 8192;
 }
 
 void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
@@ -645,6 +425,7 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     char* pk = static_cast<char*>(packed);
     pack_down_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_down, (__bf16*)(pk + P.w2f),
                                           L.n_experts, L.expert_size, L.d_model, mp / 32);
+    launch_pack_down_bf16(L, pk + P.w2g, s);
     pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_up, (__bf16*)(pk + P.wupf), L.n_experts,
                                         L.expert_size, L.d_model, mp / 16);
     if (L.gated)
@@ -683,17 +464,6 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* it
         else if (mt == 4) launch_up_t<4, false, 4>(L, x, P, item_start, alist, H, grid, s);
         else launch_up_t<8, false, 4>(L, x, P, item_start, alist, H, grid, s);
     }
-}
-
-void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
-                      const int32_t* group_off, const int32_t* alist, const void* H, void* y,
-                      hipStream_t s) {
-    LaunchTimer tm(kSlotDown, s);
-    const PackedLayout P = packed_layout(L);
-    const int ks = m_pad_of(L.expert_size) / 32;
-    if (ks == 1) launch_down_t<1>(L, P, T, item_start, group_off, alist, H, y, s);
-    else if (ks == 2) launch_down_t<2>(L, P, T, item_start, group_off, alist, H, y, s);
-    else launch_down_t<4>(L, P, T, item_start, group_off, alist, H, y, s);
 }
 
 }  // namespace dmoe

@@ -173,17 +173,19 @@ bool small_bf16_supported(const dmoe_layer& L) {
 
 void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t* colmask, void* Hs,
                        float* partial, void* y, hipStream_t s) {
-    LaunchTimer tm(kSlotSmall, s);
     const PackedLayout P = packed_layout(L);
     const int mt = m_pad_of(L.expert_size) / 16;
-    if (L.gated) {
-        if (mt == 2) launch_up_small_t<2, true>(L, x, T, P, colmask, Hs, s);
-        else if (mt == 4) launch_up_small_t<4, true>(L, x, T, P, colmask, Hs, s);
-        else launch_up_small_t<8, true>(L, x, T, P, colmask, Hs, s);
-    } else {
-        if (mt == 2) launch_up_small_t<2, false>(L, x, T, P, colmask, Hs, s);
-        else if (mt == 4) launch_up_small_t<4, false>(L, x, T, P, colmask, Hs, s);
-        else launch_up_small_t<8, false>(L, x, T, P, colmask, Hs, s);
+    {
+        LaunchTimer tm(kSlotSmallUp, s);
+        if (L.gated) {
+            if (mt == 2) launch_up_small_t<2, true>(L, x, T, P, colmask, Hs, s);
+            else if (mt == 4) launch_up_small_t<4, true>(L, x, T, P, colmask, Hs, s);
+            else launch_up_small_t<8, true>(L, x, T, P, colmask, Hs, s);
+        } else {
+            if (mt == 2) launch_up_small_t<2, false>(L, x, T, P, colmask, Hs, s);
+            else if (mt == 4) launch_up_small_t<4, false>(L, x, T, P, colmask, Hs, s);
+            else launch_up_small_t<8, false>(L, x, T, P, colmask, Hs, s);
+        }
     }
     // expert groups: enough workgroups to fill the chip, at most kSmallMaxGroups partial sums
     const int E = L.n_experts, d = L.d_model;
@@ -195,15 +197,19 @@ void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t
     const char* pk = static_cast<const char*>(L.packed);
     const dim3 grid(ncg, EG);
     const int ks = mt / 2;
-    if (ks == 1)
-        down_small_kernel<1><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
-                                                  (const __bf16*)Hs, partial, T, d, E, per);
-    else if (ks == 2)
-        down_small_kernel<2><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
-                                                  (const __bf16*)Hs, partial, T, d, E, per);
-    else
-        down_small_kernel<4><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
-                                                  (const __bf16*)Hs, partial, T, d, E, per);
+    {
+        LaunchTimer tm(kSlotSmallDown, s);
+        if (ks == 1)
+            down_small_kernel<1><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
+                                                      (const __bf16*)Hs, partial, T, d, E, per);
+        else if (ks == 2)
+            down_small_kernel<2><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
+                                                      (const __bf16*)Hs, partial, T, d, E, per);
+        else
+            down_small_kernel<4><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
+                                                      (const __bf16*)Hs, partial, T, d, E, per);
+    }
+    LaunchTimer tm(kSlotSmallFinish, s);
     finish_small_kernel<<<div_up(T * d, 256), 256, 0, s>>>(partial, (const __bf16*)L.b_down,
                                                            (__bf16*)y, T, d, EG);
 }

@@ -19,10 +19,14 @@
 // tokens -- the hardware returns zeros for those and moves no data.  The pieces go to LDS in
 // MFMA operand order; after one barrier every wavefront reads the four finished tiles.
 //
-// Pipeline per expert e (one barrier): write the tiles of e+1 (fetched during the previous
-// step) to LDS buffer (e+1) % 3, issue the fetch for e+2 and the weight loads for e+1, barrier,
-// then multiply expert e out of buffer e % 3.  Three buffers keep a wavefront that runs ahead
-// from overwriting tiles that a slower one still reads.
+// Pipeline.  Work advances in phases of 8 MFMAs (one k-step of one expert for the wavefront's
+// 4 token tiles x 2 column tiles).  The first phase of expert e writes the tiles of e+1 (fetched
+// one expert earlier) to LDS buffer (e+1) % 3 and issues the fetch for e+2; every phase requests
+// the weight blocks of the phase R-1 ahead and reads from LDS the B operands of the next phase;
+// the one barrier per expert sits in the middle of its MFMAs.  Three buffers keep a wavefront
+// that runs ahead from overwriting tiles that a slower one still reads.  What is left over the
+// pure MFMA time is mostly the wait for the H fetch, whose latency exceeds one expert's MFMA
+// time while loads complete in issue order.
 //
 // Operand layouts (v_mfma_f32_32x32x16_bf16, lane = 32h + c):
 //   H row: 2*KS2 pieces of 16 bytes; piece p = 4*ks + q holds neurons 32ks + 4q + {0..3} and
@@ -111,8 +115,10 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
         go_out = grow[ec];
     };
     u32x4 breg[KS2];
-    auto build_issue = [&](int e) {  // called with e = 0, 1, 2, ... in this order
-        if ((e & 31) == 0) {         // the values fetched 32 experts ago become current
+    __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)H, 0, 0, 0x00020000);
+    uint32_t b_voff = 0x80000000u;
+    auto build_prepare = [&](int e) {  // called with e = 0, 1, 2, ... in this order
+        if ((e & 31) == 0) {           // the values fetched 32 experts ago become current
             if (e > 0) {
                 mw = mw_next;
                 rowv = is_next * rows_per_item + go_next;
@@ -126,12 +132,18 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
         const int row0 = __builtin_amdgcn_readlane(rowv, e & 31);
         // at most 64 rows of this expert belong to the group; unselected tokens get an offset
         // beyond the descriptor's range, for which the load returns zeros
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void*)(H + (size_t)row0 * (kRowBytes / 2)), 0, kGroup * kRowBytes, 0x00020000);
-        const uint32_t voff = sel ? (uint32_t)(rank * kRowBytes + bh * (kRowBytes / 2)) : 0x80000000u;
+        b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(H + (size_t)row0 * (kRowBytes / 2)), 0,
+                                                   kGroup * kRowBytes, 0x00020000);
+        b_voff = sel ? (uint32_t)(rank * kRowBytes + bh * (kRowBytes / 2)) : 0x80000000u;
+    };
+    auto build_fetch = [&]() {
 #pragma unroll
         for (int s = 0; s < KS2; ++s)
-            breg[s] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff + 16 * s, 0, 0);
+            breg[s] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff + 16 * s, 0, 0);
+    };
+    auto build_issue = [&](int e) {
+        build_prepare(e);
+        build_fetch();
     };
     // lane = token 32h + c of the group: tile 2bg + h of the chunk, operand lane (bh, c)
     char* const wdst = img + (((2 * bg + h) * KS2) * 64 + 32 * bh + c) * 16;
@@ -144,12 +156,16 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
     // ---- multiplying role: 128 tokens x columns col_w .. col_w + 63
     const __bf16* const wsrc = w2g + ((size_t)(col_w / 32) * KS2 * 64 + lane) * 8;
     const size_t w_expert_stride = (size_t)(d / 32) * KS2 * 512;
-    auto load_a = [&](int e, bf16x8 (&a)[2][KS2]) {
-        const __bf16* p = wsrc + (size_t)e * w_expert_stride;
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-            for (int s = 0; s < KS2; ++s) a[ct][s] = load8(p + (ct * KS2 + s) * 512);
+    // Work advances in phases: phase p = expert p / KS2, k-step p % KS2 = 8 MFMAs (4 token tiles x
+    // 2 column tiles) that need two 1 KiB weight blocks.  R weight sets are in flight, so a block
+    // is requested R - 1 phases before its use whatever the expert size.
+    constexpr int R = KS2 < 4 ? 4 : KS2;   // phases per loop trip = weight sets
+    constexpr int EPT = R / KS2;           // experts per loop trip
+    auto load_phase = [&](int p, bf16x8 (&a)[2]) {
+        const int e = min(p / KS2, E - 1), ks = p % KS2;
+        const __bf16* src = wsrc + (size_t)e * w_expert_stride + ks * 512;
+        a[0] = load8(src);
+        a[1] = load8(src + KS2 * 512);
     };
     f32x16 acc[kDnTiles][2];
 #pragma unroll
@@ -162,49 +178,77 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
         }
     }
     const char* const rsrc_l = img + lane * 16;
-    auto consume = [&](int buf, const bf16x8 (&a)[2][KS2]) {
-#pragma unroll
-        for (int j = 0; j < kDnTiles; ++j) {
-            bf16x8 b[KS2];
-#pragma unroll
-            for (int s = 0; s < KS2; ++s)
-                b[s] = *reinterpret_cast<const bf16x8*>(rsrc_l + buf * kImage + (j * KS2 + s) * 1024);
-#pragma unroll
-            for (int s = 0; s < KS2; ++s)
-#pragma unroll
-                for (int ct = 0; ct < 2; ++ct) acc[j][ct] = mfma32(a[ct][s], b[s], acc[j][ct]);
-        }
+    // k-step ks of the four token tiles of the expert in buffer buf
+    auto read_piece = [&](int buf, int ks, int j) {
+        return *reinterpret_cast<const bf16x8*>(rsrc_l + buf * kImage + (j * KS2 + ks) * 1024);
     };
-
-    bf16x8 a0[2][KS2], a1[2][KS2];
+    auto read_pieces = [&](int buf, int ks, bf16x8 (&b)[kDnTiles]) {
+#pragma unroll
+        for (int j = 0; j < kDnTiles; ++j) b[j] = read_piece(buf, ks, j);
+    };
     auto next_buf = [](int buf) { return buf == kDnBuffers - 1 ? 0 : buf + 1; };
-    auto stage = [&](int e, int buf, const bf16x8 (&a_use)[2][KS2], bf16x8 (&a_load)[2][KS2]) {
-        // keep the stages apart: hoisting the next stage's LDS writes into this stage's MFMAs
-        // would make them wait for the loads issued a few instructions earlier
-        __builtin_amdgcn_sched_barrier(0);
-        write_tiles(next_buf(buf));          // expert e + 1 (all zero past the last expert)
-        build_issue(e + 2);
-        load_a(min(e + 1, E - 1), a_load);
-        lds_barrier();
-        consume(buf, a_use);
-    };
+
+    bf16x8 aw[R][2];
+    bf16x8 bb[2][kDnTiles];  // B operands of the current phase and of the next one
     {
         int is0, go0;
         load_batch(0, mw, is0, go0);
         rowv = is0 * rows_per_item + go0;
     }
+    // Same issue order as in the loop (H fetch first, then the weight loads): the wait before an
+    // LDS write is computed for the worse of the two ways into the loop, and with the fetch
+    // issued last here it would wait for every load in flight on every trip.
     build_issue(0);
     write_tiles(0);
     build_issue(1);
-    load_a(0, a0);
+#pragma unroll
+    for (int q = 0; q < R - 1; ++q) load_phase(q, aw[q]);
+    lds_barrier();
+    read_pieces(0, 0, bb[0]);
     int buf = 0;
-    // two experts per trip so that the two weight register sets simply alternate; an odd E runs
-    // one extra expert whose tiles are all zero
-    for (int e = 0; e < E; e += 2) {
-        stage(e, buf, a0, a1);
-        buf = next_buf(buf);
-        stage(e + 1, buf, a1, a0);
-        buf = next_buf(buf);
+    // Per expert: its first phase writes the tiles of the NEXT expert to LDS and issues the fetch
+    // for the one after; the barrier sits in the middle of the expert's MFMAs.  Every phase first
+    // issues its weight loads and the LDS reads of the NEXT phase's B operands (k-step 0 of the
+    // next expert in the last phase: the barrier has passed by then), then runs its 8 MFMAs on
+    // operands requested a phase ago.  So the LDS write, the barrier and all LDS reads overlap
+    // with matrix work of the same wavefront.  A trip past the last expert multiplies zero tiles.
+    for (int e0 = 0; e0 < E; e0 += EPT) {
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            const int e = e0 + q / KS2;
+            const int ks = q % KS2;
+            const int nb = next_buf(buf);
+            const int rbuf = ks < KS2 - 1 ? buf : nb, rks = ks < KS2 - 1 ? ks + 1 : 0;
+            // A wavefront issues in order, and an MFMA keeps the matrix pipe busy for 32 cycles
+            // only: everything else the phase has to do is cut into pieces that sit BETWEEN its
+            // MFMAs, each pinned by a scheduling barrier.  Left alone the scheduler groups the
+            // pieces (the pipe idles meanwhile), sinks the H fetch to the end of the expert
+            // (loads complete in issue order, so the next LDS write would wait for everything)
+            // and issues each LDS read just before its use.
+            auto mf = [&](int j, int ct) {
+                acc[j][ct] = mfma32(aw[q][ct], bb[q & 1][j], acc[j][ct]);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks == 0) write_tiles(nb);
+            mf(0, 0);
+            if (ks == 0) build_prepare(e + 2);
+            mf(0, 1);
+            if (ks == 0) build_fetch();
+            mf(1, 0);
+            load_phase(e0 * KS2 + q + R - 1, aw[(q + R - 1) % R]);
+            mf(1, 1);
+            bb[(q + 1) & 1][0] = read_piece(rbuf, rks, 0);
+            bb[(q + 1) & 1][1] = read_piece(rbuf, rks, 1);
+            mf(2, 0);
+            bb[(q + 1) & 1][2] = read_piece(rbuf, rks, 2);
+            bb[(q + 1) & 1][3] = read_piece(rbuf, rks, 3);
+            mf(2, 1);
+            mf(3, 0);
+            mf(3, 1);
+            if (ks == KS2 / 2 - 1) lds_barrier();  // every wavefront has written its part of e + 1
+            if (ks == KS2 - 1) buf = nb;
+        }
     }
 
     // lane (h, c) of tile (j, ct): columns col_w + 32ct + 16h .. +15 of token t_base + 32j + c

@@ -25,7 +25,7 @@ int fail(int code, const char* fmt, ...) {
 // ---- timing ------------------------------------------------------------------------------------
 const char* const kSlotNames[kSlotCount] = {
     "router", "mask_count", "lists_to_mask", "scan_groups", "fill_lists",
-    "expert_up", "expert_down", "ffn_f32", "small_up", "small_down", "small_finish", "pack_weights"};
+    "expert_up", "expert_down", "expert_down_sparse", "ffn_f32", "small_up", "small_down", "small_finish", "pack_weights"};
 constexpr int kEventPairs = 8192;
 bool g_timing = false;
 std::vector<hipEvent_t> g_ev;      // 2 * kEventPairs once enabled
@@ -192,7 +192,9 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
                              up_rows_bf16(L), lists_out, alist, s);
         void* H = ws + w.H;
         launch_up_bf16(L, x, T, item_start, alist, H, s);
-        launch_down_bf16(L, T, item_start, group_off, mask, H, y, s);
+        const long long max_sparse = down_max_pairs_sparse(L, T);
+        launch_down_rmw_bf16(L, T, item_start, group_off, alist, offsets, H, y, max_sparse, s);
+        launch_down_bf16(L, T, item_start, group_off, mask, offsets, H, y, max_sparse, s);
     }
     return check_launch("expert kernels");
 }

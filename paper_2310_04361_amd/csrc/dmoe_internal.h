@@ -65,6 +65,7 @@ enum Slot {
     kSlotFill,
     kSlotUp,
     kSlotDown,
+    kSlotDownRmw,
     kSlotFfnF32,
     kSlotSmallUp,
     kSlotSmallDown,
@@ -130,9 +131,16 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* it
 // lists were built from; group_off[g][e] = rows of expert e that belong to tokens before group g.
 bool down_bf16_supported(const dmoe_layer& L);
 void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s);
+// Two kernels, both launched: offsets[E] (the executed pairs) decides on the device which one
+// works -- at most max_pairs_sparse pairs: the pair-proportional kernel (down_rmw_bf16.hip),
+// more: the one that sums over experts inside the matrix cores (down_bf16.hip).
 void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
-                      const int32_t* group_off, const uint64_t* mask, const void* H, void* y,
-                      hipStream_t s);
+                      const int32_t* group_off, const uint64_t* mask, const int32_t* offsets,
+                      const void* H, void* y, long long max_pairs_sparse, hipStream_t s);
+void launch_down_rmw_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
+                          const int32_t* group_off, const int32_t* alist, const int32_t* offsets,
+                          const void* H, void* y, long long max_pairs_sparse, hipStream_t s);
+long long down_max_pairs_sparse(const dmoe_layer& L, int T);
 
 bool experts_bf16_supported(const dmoe_layer& L);
 bool router_bf16_supported(const dmoe_layer& L);

@@ -75,8 +75,10 @@ template <int KS2>
 __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
     const __bf16* __restrict__ w2g, const __bf16* __restrict__ b_down,
     const int32_t* __restrict__ item_start, const int32_t* __restrict__ group_off,
-    const uint32_t* __restrict__ mask32, const __bf16* __restrict__ H, __bf16* __restrict__ y,
-    int T, int d, int E, int NG, int W32, int rows_per_item) {
+    const uint32_t* __restrict__ mask32, const int32_t* __restrict__ offsets,
+    const __bf16* __restrict__ H, __bf16* __restrict__ y, int T, int d, int E, int NG, int W32,
+    int rows_per_item, long long max_pairs_sparse) {
+    if (offsets[E] <= max_pairs_sparse) return;  // sparse enough for the pair-proportional kernel
     constexpr int kRowBytes = KS2 * 32;              // one H row: m_pad bf16
     constexpr int kImage = kDnTiles * KS2 * 1024;    // the B tiles of one expert
     extern __shared__ __attribute__((aligned(16))) char img[];  // [kDnBuffers][kImage]
@@ -274,8 +276,8 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
 
 template <int KS2>
 void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* item_start,
-                   const int32_t* group_off, const uint64_t* mask, const void* H, void* y,
-                   hipStream_t s) {
+                   const int32_t* group_off, const uint64_t* mask, const int32_t* offsets,
+                   const void* H, void* y, long long max_pairs_sparse, hipStream_t s) {
     const int NG = div_up(T, kGroup), NC = div_up(T, kDnTokens), NS = L.d_model / kDnCols;
     constexpr size_t lds = (size_t)kDnBuffers * kDnTiles * KS2 * 1024;
     static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
@@ -287,8 +289,8 @@ void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int3
     const char* pk = static_cast<const char*>(L.packed);
     down_bf16_kernel<KS2><<<round_up(NC, 8) * NS, 256, lds, s>>>(
         (const __bf16*)(pk + P.w2g), (const __bf16*)L.b_down, item_start, group_off,
-        reinterpret_cast<const uint32_t*>(mask), (const __bf16*)H, (__bf16*)y, T, L.d_model,
-        L.n_experts, NG, 2 * div_up(L.n_experts, 64), up_rows_bf16(L));
+        reinterpret_cast<const uint32_t*>(mask), offsets, (const __bf16*)H, (__bf16*)y, T,
+        L.d_model, L.n_experts, NG, 2 * div_up(L.n_experts, 64), up_rows_bf16(L), max_pairs_sparse);
 }
 
 }  // namespace
@@ -304,14 +306,14 @@ void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s) {
 }
 
 void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
-                      const int32_t* group_off, const uint64_t* mask, const void* H, void* y,
-                      hipStream_t s) {
+                      const int32_t* group_off, const uint64_t* mask, const int32_t* offsets,
+                      const void* H, void* y, long long max_pairs_sparse, hipStream_t s) {
     LaunchTimer tm(kSlotDown, s);
     const PackedLayout P = packed_layout(L);
     const int ks2 = m_pad_of(L.expert_size) / 16;
-    if (ks2 == 2) launch_down_t<2>(L, P, T, item_start, group_off, mask, H, y, s);
-    else if (ks2 == 4) launch_down_t<4>(L, P, T, item_start, group_off, mask, H, y, s);
-    else launch_down_t<8>(L, P, T, item_start, group_off, mask, H, y, s);
+    if (ks2 == 2) launch_down_t<2>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
+    else if (ks2 == 4) launch_down_t<4>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
+    else launch_down_t<8>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
 }
 
 }  // namespace dmoe

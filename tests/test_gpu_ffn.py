@@ -44,6 +44,13 @@ CASES = [
     ("cfg4", 64, None, 0.1),        # all 256 experts
     ("cfg5b", 16, None, 0.25),
     ("paper", 200, None, 0.4),      # 24 experts of 128 neurons
+    # densities on both sides of the switch between the two down-projection kernels
+    # (pair-proportional below about 0.05 / 0.08, matrix-core merge above)
+    ("cfg2", 700, None, 0.04),
+    ("cfg2", 700, None, 0.06),
+    ("cfg4", 300, None, 0.05),
+    ("cfg4", 300, None, 0.12),
+    ("paper", 200, None, 0.05),
 ]
 
 

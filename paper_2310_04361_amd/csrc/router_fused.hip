@@ -1,10 +1,10 @@
 // Router (Sec. 3.3) fused with the dynamic-k gate (Sec. 3.4 Eq. 4) and the per-group expert counts
 // that start the bucketing: one workgroup per group of 64 tokens.
 //
-//   stage 1  hid^T[d_h][64] = R1 * x^T.  The 64 x rows are staged through LDS in K blocks of 64
-//            (eight lanes per 128-byte row piece, double-buffered, one barrier per block); each
-//            of the four wavefronts owns a quarter of the hidden units and reads R1 as packed
-//            MFMA fragments.  bias + relu, round to bf16, park the hidden tile in LDS.
+//   stage 1  hid^T[d_h][64] = R1 * x^T.  The 64 x rows are staged in LDS (eight lanes per 128-byte
+//            row piece), up to 768 columns at a time with all loads of the chunk in flight
+//            together; each of the four wavefronts owns a quarter of the hidden units and reads
+//            R1 as packed MFMA fragments.  bias + relu, round to bf16, park the hidden tile in LDS.
 //   stage 2  s^T[E][64] = R2 * hid^T.  Each wavefront owns every fourth tile of 16 experts, reads
 //            R2 as packed fragments and the hidden tile from LDS; |. + c2| goes to `scores`
 //            (fp32, 16 bytes per lane) and stays in registers for
@@ -21,11 +21,12 @@ namespace dmoe {
 
 namespace {
 
-constexpr int kXRow = 144;      // bytes per staged x row: 64 bf16 + 16 bytes of bank skew
 constexpr int kMaxTilesPerWave = 8;   // expert tiles per wavefront: E <= 4 * 8 * 16 = 512
 
-// NH = d_h / 16; ETW = expert tiles per wavefront (E <= 64 * ETW).
-template <int NH, int ETW>
+// NH = d_h / 16; ETW = expert tiles per wavefront (E <= 64 * ETW); KBC = K blocks (64 wide) of x
+// that sit in LDS at a time: 12 (all of d = 768) when there is at most about one workgroup per
+// CU and its own latency is what counts, 4 when several workgroups share a CU and hide it.
+template <int NH, int ETW, int KBC>
 __global__ __launch_bounds__(256) void router_fused_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
     const __bf16* __restrict__ r2f, const __bf16* __restrict__ r_b2, float* __restrict__ scores,
@@ -34,9 +35,10 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     uint64_t* __restrict__ colmask) {
     constexpr int dh = NH * 16, HT = NH / 4, KS2 = dh / 32;
     constexpr int kHRow = dh * 2 + 16;  // bytes per hidden row in LDS
+    constexpr int kXRowC = KBC * 128 + 16;  // bytes per staged x row: KBC blocks + bank skew
     extern __shared__ char smem[];
-    char* xs = smem;                                            // [2][64][kXRow]
-    char* hid = smem + 2 * 64 * kXRow;                          // [64][kHRow]
+    char* xs = smem;                                            // [64][kXRowC]
+    char* hid = smem + 64 * kXRowC;                             // [64][kHRow]
     float* pmax = reinterpret_cast<float*>(hid + 64 * kHRow);   // [4][64]
     uint64_t* pw = reinterpret_cast<uint64_t*>(pmax + 256);     // [4][64][W]
     const int W = (E + 63) >> 6;
@@ -47,10 +49,14 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     const int NK32 = d / 32, NKB = d / 64;
 
     // ---------------------------------------------------------------- stage 1
+    // x comes from HBM: all loads of a chunk are issued together so that their latency is paid
+    // once per chunk, not once per K block (loads complete in issue order, so a prefetch of x
+    // inside the K loop would hold up the R1 fragments behind it).  The K loop itself has no
+    // barrier and only L2-resident loads.
     const int ld_row = tid >> 3, ld_piece = tid & 7;
     const __bf16* xp0 = x + (size_t)min(t0 + ld_row, T - 1) * d + 8 * ld_piece;
     const __bf16* xp1 = x + (size_t)min(t0 + ld_row + 32, T - 1) * d + 8 * ld_piece;
-    char* xst = xs + ld_row * kXRow + ld_piece * 16;
+    char* xst = xs + ld_row * kXRowC + ld_piece * 16;
     const __bf16* af = r1f + ((size_t)w * HT * NK32 * 64 + lane) * 8;
 
     f32x4 acc[HT][4];
@@ -59,29 +65,24 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) acc[h][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    bf16x8 xr0, xr1, a0[2][HT], a1[2][HT];
-    auto load_x = [&](int kb) {
-        xr0 = load8(xp0 + 64 * kb);
-        xr1 = load8(xp1 + 64 * kb);
-    };
+    // R1 fragments: a ring of four K blocks, requested three blocks before their use (an L2
+    // round trip takes longer than the 16 to 32 MFMAs of one block)
+    bf16x8 ar[4][2][HT];
     auto load_a = [&](int kb, bf16x8 (&a)[2][HT]) {
+        kb = min(kb, NKB - 1);  // the last trips re-read a block they will not use
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int h = 0; h < HT; ++h) a[ks][h] = load8(af + ((size_t)h * NK32 + 2 * kb + ks) * 512);
     };
-    auto store_x = [&](int buf) {
-        *reinterpret_cast<bf16x8*>(xst + buf * 64 * kXRow) = xr0;
-        *reinterpret_cast<bf16x8*>(xst + buf * 64 * kXRow + 32 * kXRow) = xr1;
-    };
-    auto compute = [&](int buf, const bf16x8 (&a)[2][HT]) {
-        const char* src = xs + buf * 64 * kXRow + c * kXRow + q * 16;
+    auto compute = [&](int kbl, const bf16x8 (&a)[2][HT]) {
+        const char* src = xs + c * kXRowC + kbl * 128 + q * 16;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             bf16x8 b[4];
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt)
-                b[tt] = *reinterpret_cast<const bf16x8*>(src + tt * 16 * kXRow + ks * 64);
+                b[tt] = *reinterpret_cast<const bf16x8*>(src + tt * 16 * kXRowC + ks * 64);
 #pragma unroll
             for (int h = 0; h < HT; ++h)
 #pragma unroll
@@ -89,22 +90,36 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
     };
 
-    load_x(0);
-    load_a(0, a0);
-    store_x(0);
-    __syncthreads();
-    for (int kb = 0; kb < NKB; kb += 2) {  // NKB is even
-        load_x(kb + 1);
-        load_a(kb + 1, a1);
-        compute(0, a0);
-        store_x(1);
-        __syncthreads();
-        const int nb = min(kb + 2, NKB - 1);  // the last trip re-reads a block it will not use
-        load_x(nb);
-        load_a(nb, a0);
-        compute(1, a1);
-        store_x(0);
-        __syncthreads();
+    for (int kb0 = 0; kb0 < NKB; kb0 += KBC) {
+        const int nkb = min(KBC, NKB - kb0);  // a multiple of 4: d is a multiple of 256
+        {
+            bf16x8 xr[2 * KBC];
+#pragma unroll
+            for (int i = 0; i < KBC; ++i)
+                if (i < nkb) {
+                    xr[2 * i] = load8(xp0 + 64 * (kb0 + i));
+                    xr[2 * i + 1] = load8(xp1 + 64 * (kb0 + i));
+                }
+            if (kb0 > 0) lds_barrier();  // the previous chunk has been consumed
+#pragma unroll
+            for (int i = 0; i < KBC; ++i)
+                if (i < nkb) {
+                    *reinterpret_cast<bf16x8*>(xst + i * 128) = xr[2 * i];
+                    *reinterpret_cast<bf16x8*>(xst + 32 * kXRowC + i * 128) = xr[2 * i + 1];
+                }
+        }
+        if (kb0 == 0) {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) load_a(i, ar[i]);
+        }
+        lds_barrier();
+        for (int kbl = 0; kbl < nkb; kbl += 4) {  // nkb is a multiple of 4
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                load_a(kb0 + kbl + i + 3, ar[(i + 3) & 3]);
+                compute(kbl + i, ar[i]);
+            }
+        }
     }
 
     // lane (q, c) of tile (h, tt): hidden units 16*(w*HT + h) + 4q + r of token 16tt + c
@@ -130,16 +145,25 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     const int NE = (E + 15) >> 4;
     float sc[ETW][4][4];  // [my tile][token tile][r]
     float vmax[4] = {0.f, 0.f, 0.f, 0.f};
+    // R2 fragments of the next tile are requested before the current one is multiplied
+    bf16x8 r2a[2][KS2];
+    auto load_r2 = [&](int et, bf16x8 (&a)[KS2]) {
+        et = min(et, NE - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS2; ++ks) a[ks] = load8(r2f + (((size_t)et * KS2 + ks) * 64 + lane) * 8);
+    };
+    load_r2(w, r2a[0]);
 #pragma unroll
     for (int j = 0; j < ETW; ++j) {
         const int et = w + 4 * j;
+        if (j + 1 < ETW) load_r2(et + 4, r2a[(j + 1) & 1]);
         if (et < NE) {  // uniform per wavefront
             f32x4 a2[4];
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) a2[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS2; ++ks) {
-                const bf16x8 a = load8(r2f + (((size_t)et * KS2 + ks) * 64 + lane) * 8);
+                const bf16x8 a = r2a[j & 1][ks];
 #pragma unroll
                 for (int tt = 0; tt < 4; ++tt) {
                     const bf16x8 b = *reinterpret_cast<const bf16x8*>(
@@ -241,23 +265,33 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     }
 }
 
-template <int NH, int ETW>
-void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
+template <int NH, int ETW, int KBC>
+void launch_t3(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
                int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
     const PackedLayout P = packed_layout(L);
     const int E = L.n_experts, W = div_up(E, 64);
-    const size_t lds = 2 * 64 * kXRow + 64 * (NH * 32 + 16) + 256 * 4 + (size_t)5 * 64 * W * 8;
+    const size_t lds = 64 * (KBC * 128 + 16) + 64 * (NH * 32 + 16) + 256 * 4 + (size_t)5 * 64 * W * 8;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_fused_kernel<NH, ETW>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_fused_kernel<NH, ETW, KBC>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    router_fused_kernel<NH, ETW><<<div_up(T, 64), 256, lds, s>>>(
+    router_fused_kernel<NH, ETW, KBC><<<div_up(T, 64), 256, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1,
         (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, L.d_model, E, tau,
         mask != nullptr, mask, k_per_token, group_cnt, colmask);
+}
+
+template <int NH, int ETW>
+void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
+               int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
+    constexpr int kBig = NH <= 8 ? 12 : (NH == 16 ? 8 : 4);
+    if (kBig > 4 && div_up(T, 64) <= 512)
+        launch_t3<NH, ETW, kBig>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+    else
+        launch_t3<NH, ETW, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
 }
 
 // ---- T <= 16: the same two products spread over many workgroups --------------------------------
@@ -348,7 +382,7 @@ void launch_router_small(const dmoe_layer& L, const void* x, int T, void* hid, f
 bool router_fused_supported(const dmoe_layer& L) {
     const int dh = L.router_hidden;
     return L.packed != nullptr && (dh == 64 || dh == 128 || dh == 256 || dh == 512) &&
-           L.d_model % 128 == 0 && L.n_experts % 4 == 0 && L.n_experts <= 64 * kMaxTilesPerWave;
+           L.d_model % 256 == 0 && L.n_experts % 4 == 0 && L.n_experts <= 64 * kMaxTilesPerWave;
 }
 
 void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,

@@ -265,22 +265,25 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
         }
     }
 
-    const int g = blockIdx.x * 4 + wave;
+    // one workgroup per group of 64 tokens (lane = token); wavefront w takes the experts
+    // 64*word + 16w .. +15 of every mask word
+    const int g = blockIdx.x;
     if (g >= NG || (!lists && !alist)) return;
     const int t = g * kGroup + lane;
     const bool valid = t < T;
     const uint64_t below = (1ull << lane) - 1ull;
     for (int w = 0; w < W; ++w) {
         const uint64_t word = valid ? mask[(size_t)t * W + w] : 0ull;
-        // lane b keeps the three bases of expert 64w + b; the loop below is unrolled, so each
-        // read of them is a constant-lane broadcast on the scalar unit
+        // lane b keeps the three bases of expert 64w + b; b is uniform in the loop below, so each
+        // read of them is a broadcast through the scalar unit
         const int e_l = 64 * w + lane;
         const int goff_l = e_l < E ? group_off[(size_t)g * E + e_l] : 0;
         const int cbase_l = e_l < E ? s_off[e_l] + goff_l : 0;
         const int abase_l = e_l < E ? s_item[e_l] * rows_per_item + goff_l : 0;
         const int nb = min(64, E - 64 * w);
 #pragma unroll
-        for (int b = 0; b < 64; ++b) {
+        for (int bi = 0; bi < 16; ++bi) {
+            const int b = 16 * wave + bi;
             const uint64_t bal = __ballot(((word >> b) & 1ull) != 0 && b < nb);
             if (bal != 0ull) {  // uniform
                 const int cbase = __builtin_amdgcn_readlane(cbase_l, b);
@@ -342,7 +345,7 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         attr_set = true;
     }
-    fill_lists_kernel<<<std::max(1, div_up(NG, 4)), 256, lds, s>>>(
+    fill_lists_kernel<<<std::max(1, NG), 256, lds, s>>>(
         mask, T, E, W, group_off, rows_per_item, counts, offsets, item_start, token_lists,
         aligned_lists);
 }

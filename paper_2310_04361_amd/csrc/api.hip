@@ -133,7 +133,7 @@ SelectWs select_ws(int T, int E, bool need_mask) {
 }
 
 struct LayerWs {
-    size_t scores, mask, group_off, counts, offsets, item_start, lists, H, colmask, partial, hid, total;
+    size_t scores, mask, group_off, counts, offsets, item_start, witem, wfirst, lists, H, colmask, partial, hid, total;
 };
 LayerWs layer_ws(const dmoe_layer& L, int T) {
     LayerWs w{};
@@ -145,6 +145,10 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     w.counts = o;     o += align_up(sizeof(int32_t) * (size_t)E);
     w.offsets = o;    o += align_up(sizeof(int32_t) * (size_t)(E + 1));
     w.item_start = o; o += align_up(sizeof(int32_t) * (size_t)(E + 2));
+    // window tables of the up-projection
+    const int n_windows = L.dtype == DMOE_BF16 ? div_up(div_up(T, kGroup), up_window_groups(L, T)) : 0;
+    w.witem = o;      o += align_up(sizeof(int32_t) * (size_t)n_windows * (E + 1));
+    w.wfirst = o;     o += align_up(sizeof(int32_t) * (size_t)n_windows * E);
     // token lists aligned to work items: one entry per row of H
     w.lists = o;      o += align_up(sizeof(int32_t) * h_fragments(L, T) * 16);
     w.H = o;
@@ -179,19 +183,22 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
     if (L.dtype == DMOE_F32) {
         if (offsets_out)
             launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
-                                 lists_out, nullptr, s);
+                                 lists_out, nullptr, 1, nullptr, nullptr, s);
         launch_ffn_f32(L, (const float*)x, T, mask, (float*)y, s);
     } else if (use_small_path(L, T)) {
         if (offsets_out)
             launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
-                                 lists_out, nullptr, s);
+                                 lists_out, nullptr, 1, nullptr, nullptr, s);
         launch_small_bf16(L, x, T, reinterpret_cast<const uint64_t*>(ws + w.colmask), ws + w.H,
                           reinterpret_cast<float*>(ws + w.partial), y, s);
     } else {
+        int32_t* witem = reinterpret_cast<int32_t*>(ws + w.witem);
+        int32_t* wfirst = reinterpret_cast<int32_t*>(ws + w.wfirst);
         launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, item_start,
-                             up_rows_bf16(L), lists_out, alist, s);
+                             up_rows_bf16(L), lists_out, alist, up_window_groups(L, T), witem,
+                             wfirst, s);
         void* H = ws + w.H;
-        launch_up_bf16(L, x, T, item_start, alist, H, s);
+        launch_up_bf16(L, x, T, witem, wfirst, alist, H, s);
         const long long max_sparse = down_max_pairs_sparse(L, T);
         launch_down_rmw_bf16(L, T, item_start, group_off, alist, offsets, H, y, max_sparse, s);
         launch_down_bf16(L, T, item_start, group_off, mask, offsets, H, y, max_sparse, s);
@@ -293,7 +300,7 @@ int32_t dmoe_select(const float* scores, int32_t n_tokens, int32_t n_experts, fl
     if (n_tokens > 0)
         launch_mask_from_scores(scores, n_tokens, n_experts, tau, mask, k_per_token, group_off, nullptr, s);
     launch_scan_and_fill(mask, n_tokens, n_experts, group_off, counts, offsets, nullptr, 64,
-                         n_tokens > 0 ? token_lists : nullptr, nullptr, s);
+                         n_tokens > 0 ? token_lists : nullptr, nullptr, 1, nullptr, nullptr, s);
     return check_launch("select");
 }
 

@@ -94,7 +94,13 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
                             uint64_t* mask, int32_t* group_off, uint64_t* colmask, hipStream_t s);
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
-                          int32_t* token_lists, int32_t* aligned_lists, hipStream_t s);
+                          int32_t* token_lists, int32_t* aligned_lists, int window_groups,
+                          int32_t* witem, int32_t* wfirst, hipStream_t s);
+// The up-projection walks its work items window by window (window = window_groups consecutive
+// 64-token groups, window w on XCD w % 8) so that the x rows an XCD gathers stay in its L2:
+// witem[NW][E+1], wfirst[NW][E] are built with the lists (nullable: no tables).  A single window
+// (wide experts, whose weight stream would flush the rows anyway) is shared by all XCDs.
+int up_window_groups(const dmoe_layer& L, int T);
 constexpr int kMaxExperts = 4096;  // the list fill keeps 2 ints per expert in LDS
 
 // ---- router (router.hip) ----------------------------------------------------------------------
@@ -125,8 +131,8 @@ void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* 
 void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s);
 // H holds one row of m_pad hidden activations per list row (layout: see ffn_bf16.hip).
 // alist is the work-item-aligned token list (see select.hip); its index is the row index of H.
-void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* item_start,
-                    const int32_t* alist, void* H, hipStream_t s);
+void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* witem,
+                    const int32_t* wfirst, const int32_t* alist, void* H, hipStream_t s);
 // Down-projection and merge (down_bf16.hip): mask is the token-major selection bitmask that the
 // lists were built from; group_off[g][e] = rows of expert e that belong to tokens before group g.
 bool down_bf16_supported(const dmoe_layer& L);

@@ -16,6 +16,8 @@
 //     32ks + 16 + 4q + {0..3} -- the order in which the accumulators of lane (q, .) come out;
 //     the packed down-projection uses the same order.
 //   An expert's H rows start at a multiple of UR rows (its first up-projection work item).
+#include <cmath>
+
 #include "dmoe_internal.h"
 #include "mfma.h"
 
@@ -98,37 +100,46 @@ template <int MT, bool GATED, int TT>
 __global__ __launch_bounds__(256) void up_bf16_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
     const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
-    const int32_t* __restrict__ item_start, const int32_t* __restrict__ alist,
-    __bf16* __restrict__ Hf, int d, int E, int m, int act) {
+    const int32_t* __restrict__ witem, const int32_t* __restrict__ wfirst, int NW,
+    const int32_t* __restrict__ alist, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
     constexpr int BR = GATED ? 2 : 1;
     constexpr int KS = MT / 2;
     constexpr int UR = TT * 16;
     constexpr int NL = TT * 2;  // x load instructions per K block: 8 rows x 128 bytes each
     extern __shared__ char smem[];
-    int32_t* s_items = reinterpret_cast<int32_t*>(smem);  // item_start[0..E+1]
-    const int items_bytes = ((E + 2) * 4 + 15) & ~15;
-    for (int i = threadIdx.x; i <= E + 1; i += blockDim.x) s_items[i] = item_start[i];
-    __syncthreads();
+    int32_t* s_wit = reinterpret_cast<int32_t*>(smem);  // witem[w][0..E], then wfirst[w][0..E-1]
+    int32_t* s_wf = s_wit + (E + 1);
+    const int items_bytes = ((2 * E + 1) * 4 + 15) & ~15;
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15;
     const int wave_in_block = threadIdx.x >> 6;
     char* xs = smem + items_bytes + wave_in_block * (2 * UR * kUpRowBytes);
     const int NK32 = d / 32, NKB = d / 64;
     const int ld_row = lane >> 3, ld_piece = lane & 7;
 
-    const int total = s_items[E];
-    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int n_waves = (gridDim.x * blockDim.x) >> 6;
-
-    // Items are taken in expert-major order.  (Ordering them so that an XCD's wavefronts share a
-    // token window -- for L2 reuse of the x rows -- measured slower: the gathers then collide
-    // on the same L2 channels.)
-    for (int item = wave; item < total; item += n_waves) {
-        int lo = 0, hi = E;  // last e with s_items[e] <= item
+    // Work items are walked window by window: the wavefronts of XCD k (workgroups are dealt
+    // round-robin to the 8 XCDs) take the windows k, k+8, ... so that the x rows they gather --
+    // each row is used by every expert its token selected -- stay in that XCD's L2; gathered out
+    // of the last-level cache the same rows come in at about a third of the rate.
+    // A single window is shared by all workgroups.
+    const bool windowed = NW > 1;
+    const int wg = windowed ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int n_wg = windowed ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    const int wave = wg * (blockDim.x >> 6) + wave_in_block;
+    const int n_waves = n_wg * (blockDim.x >> 6);
+    for (int wdx = windowed ? (int)(blockIdx.x & 7) : 0; wdx < NW; wdx += 8) {
+    __syncthreads();  // the previous window's table is no longer read
+    for (int i = threadIdx.x; i <= 2 * E; i += blockDim.x)
+        s_wit[i] = i <= E ? witem[(size_t)wdx * (E + 1) + i] : wfirst[(size_t)wdx * E + (i - E - 1)];
+    __syncthreads();
+    const int total = s_wit[E];
+    for (int j = wave; j < total; j += n_waves) {
+        int lo = 0, hi = E;  // last e with s_wit[e] <= j
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (s_items[mid] <= item) lo = mid; else hi = mid;
+            if (s_wit[mid] <= j) lo = mid; else hi = mid;
         }
         const int e = lo;
+        const int item = s_wf[e] + (j - s_wit[e]);
         // rows of the aligned list past the expert's last token hold -1: they read token 0 and
         // produce H rows that nobody merges
         const int32_t* tl = alist + (size_t)item * UR + ld_row;
@@ -242,6 +253,7 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
             }
         }
     }
+    }  // windows
 }
 
 // Up-projection for wide experts (8 or more neuron tiles per item, e.g. gated m = 64): there the
@@ -252,8 +264,9 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
 template <int MT, bool GATED, int TT>
 __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
-    const __bf16* __restrict__ wgatef, const int32_t* __restrict__ item_start,
-    const int32_t* __restrict__ alist, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
+    const __bf16* __restrict__ wgatef, const int32_t* __restrict__ witem,
+    const int32_t* __restrict__ wfirst, int NW, const int32_t* __restrict__ alist,
+    __bf16* __restrict__ Hf, int d, int E, int m, int act) {
     constexpr int BR = GATED ? 2 : 1;
     constexpr int KS = MT / 2;
     constexpr int NT = BR * MT;         // neuron tiles per K step
@@ -268,16 +281,23 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
     char* xs = smem + 2 * NWF * 1024 + w * (WR * kUpRowBytes);   // [WR][kUpRowBytes], private
     const int NK32 = d / 32, NKB = d / 64;
     const int ld_row = lane >> 3, ld_piece = lane & 7;
-    const int total = item_start[E];
-
-    for (int item = blockIdx.x; item < total; item += gridDim.x) {
-        // expert of this item: the last e with item_start[e] <= item (uniform binary search)
+    // windows as in the kernel above: XCD k takes the windows k, k+8, ...; a single window is
+    // shared by all workgroups
+    const bool windowed = NW > 1;
+    const int wg = windowed ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int n_wg = windowed ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    for (int wdx = windowed ? (int)(blockIdx.x & 7) : 0; wdx < NW; wdx += 8) {
+    const int32_t* wit = witem + (size_t)wdx * (E + 1);
+    const int total = wit[E];
+    for (int j = wg; j < total; j += n_wg) {
+        // expert of this item: the last e with wit[e] <= j (uniform binary search)
         int lo = 0, hi = E;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (item_start[mid] <= item) lo = mid; else hi = mid;
+            if (wit[mid] <= j) lo = mid; else hi = mid;
         }
         const int e = lo;
+        const int item = wfirst[(size_t)wdx * E + e] + (j - wit[e]);
         const int32_t* tl = alist + (size_t)item * UR + w * WR + ld_row;
         const bool active = alist[(size_t)item * UR + w * WR] >= 0;  // valid rows are a prefix
         const __bf16* xrow[NL];
@@ -369,14 +389,15 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
             }
         }
     }
+    }  // windows
 }
 
 // ---- launchers ---------------------------------------------------------------------------------------
 template <int MT, bool GATED, int TT>
-void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
-                 const int32_t* item_start, const int32_t* alist, void* H, int grid,
+void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, const int32_t* witem,
+                 const int32_t* wfirst, int NW, const int32_t* alist, void* H, int grid,
                  hipStream_t s) {
-    const size_t lds = (((size_t)L.n_experts + 2) * 4 + 15) / 16 * 16 +
+    const size_t lds = ((2 * (size_t)L.n_experts + 1) * 4 + 15) / 16 * 16 +
                        4 * 2 * (size_t)TT * 16 * kUpRowBytes;
     static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
     if (!attr_set) {
@@ -387,14 +408,14 @@ void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
     const char* pk = static_cast<const char*>(L.packed);
     up_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
-        (const __bf16*)L.b_up, item_start, alist, (__bf16*)H, L.d_model, L.n_experts,
+        (const __bf16*)L.b_up, witem, wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts,
         L.expert_size, L.act);
 }
 
 template <int MT, bool GATED, int TT>
 void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
-                      const int32_t* item_start, const int32_t* alist, void* H, int grid,
-                      hipStream_t s) {
+                      const int32_t* witem, const int32_t* wfirst, int NW, const int32_t* alist,
+                      void* H, int grid, hipStream_t s) {
     constexpr int NWF = 2 * (GATED ? 2 : 1) * MT;
     const size_t lds = 2 * NWF * 1024 + 4 * (size_t)TT * 16 * kUpRowBytes;
     static bool attr_set = false;
@@ -405,8 +426,8 @@ void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
     }
     const char* pk = static_cast<const char*>(L.packed);
     up_wide_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
-        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef), item_start,
-        alist, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
+        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef), witem,
+        wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
 }
 
 }  // namespace
@@ -442,27 +463,44 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     }
 }
 
-void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* item_start,
-                    const int32_t* alist, void* H, hipStream_t s) {
+// Groups of 64 tokens per up-projection window: the x rows of a window (about 3 MB) should stay
+// in the 4 MB L2 of the XCD that works on it, and the number of windows is a multiple of 8 so
+// that every XCD gets the same number.
+int up_window_groups(const dmoe_layer& L, int T) {
+    const int NG = div_up(T, kGroup);
+    // wide experts: per window the XCD would stream every expert's weights (far more than its
+    // L2) through the same cache, and the 256-row items span more than a window; measured slower
+    if (up_rows_bf16(L) != 64) return NG;
+    const double x_bytes = 2.0 * (double)NG * kGroup * L.d_model;
+    const double window_bytes = 3.2 * 1048576.0;
+    const int n_windows = 8 * std::max(1, (int)ceil(x_bytes / (8.0 * window_bytes)));
+    return std::max(1, div_up(NG, n_windows));
+}
+
+void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* witem,
+                    const int32_t* wfirst, const int32_t* alist, void* H, hipStream_t s) {
     LaunchTimer tm(kSlotUp, s);
     const PackedLayout P = packed_layout(L);
-    // persistent wavefronts: enough to cover the worst case once, capped at two workgroups per CU
+    const int NW = div_up(div_up(T, kGroup), up_window_groups(L, T));
+    // persistent wavefronts: enough to cover the worst case once, capped at two workgroups per
+    // CU; a multiple of 8 so that every XCD runs the same number
     const long long worst = (long long)T * L.n_experts / up_rows_bf16(L) + L.n_experts;
-    const int grid = (int)std::min<long long>((worst + 3) / 4, 256 * 2);
+    const int grid = round_up((int)std::min<long long>((worst + 3) / 4, 256 * 2), 8);
     const int mt = m_pad_of(L.expert_size) / 16;
     if (up_rows_bf16(L) == 256) {  // wide experts without b_up: weights shared through LDS
-        const int wgrid = (int)std::min<long long>((long long)T * L.n_experts / 256 + L.n_experts, 512);
-        if (L.gated) launch_up_wide_t<4, true, 4>(L, x, P, item_start, alist, H, wgrid, s);
-        else launch_up_wide_t<8, false, 4>(L, x, P, item_start, alist, H, wgrid, s);
+        const int wgrid = round_up(
+            (int)std::min<long long>((long long)T * L.n_experts / 256 + L.n_experts, 512), 8);
+        if (L.gated) launch_up_wide_t<4, true, 4>(L, x, P, witem, wfirst, NW, alist, H, wgrid, s);
+        else launch_up_wide_t<8, false, 4>(L, x, P, witem, wfirst, NW, alist, H, wgrid, s);
         return;
     }
     if (L.gated) {
-        if (mt == 2) launch_up_t<2, true, 4>(L, x, P, item_start, alist, H, grid, s);
-        else launch_up_t<4, true, 4>(L, x, P, item_start, alist, H, grid, s);
+        if (mt == 2) launch_up_t<2, true, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
+        else launch_up_t<4, true, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
     } else {
-        if (mt == 2) launch_up_t<2, false, 4>(L, x, P, item_start, alist, H, grid, s);
-        else if (mt == 4) launch_up_t<4, false, 4>(L, x, P, item_start, alist, H, grid, s);
-        else launch_up_t<8, false, 4>(L, x, P, item_start, alist, H, grid, s);
+        if (mt == 2) launch_up_t<2, false, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
+        else if (mt == 4) launch_up_t<4, false, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
+        else launch_up_t<8, false, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
     }
 }
 

@@ -207,7 +207,8 @@ __global__ __launch_bounds__(256) void scan_groups_kernel(int32_t* __restrict__ 
 __global__ __launch_bounds__(256) void fill_lists_kernel(
     const uint64_t* __restrict__ mask, int T, int E, int W, const int32_t* __restrict__ group_off,
     int rows_per_item, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
-    int32_t* __restrict__ item_start, int32_t* __restrict__ lists, int32_t* __restrict__ alist) {
+    int32_t* __restrict__ item_start, int32_t* __restrict__ lists, int32_t* __restrict__ alist,
+    int GW, int NW, int32_t* __restrict__ witem, int32_t* __restrict__ wfirst) {
     extern __shared__ int32_t sm[];
     int32_t* s_off = sm;                 // [E + 1]
     int32_t* s_item = sm + (E + 1);      // [E + 1]
@@ -256,6 +257,46 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
             if (item_start) item_start[e] = s_item[e];
             if (e < E && counts) counts[e] = totals[e];
         }
+    }
+    // Window table for the up-projection (block w lays out window w = GW consecutive groups):
+    // the work items of expert e that window w works on are wfirst[w][e] .. + n (those whose
+    // rows mostly belong to tokens of the window); witem[w][e] is the exclusive prefix of n over
+    // the experts.
+    if (witem && (int)blockIdx.x < NW) {
+        const int wdx = blockIdx.x;
+        const int32_t* r_lo = group_off + (size_t)(wdx * GW) * E;
+        const int32_t* r_hi = group_off + (size_t)min(wdx * GW + GW, NG) * E;
+        int wcarry = 0;
+        for (int base = 0; base < E; base += 256) {
+            const int e = base + tid;
+            int n = 0, first = 0;
+            if (e < E) {
+                // the expert's items are dealt to the windows in proportion to its rows there
+                // (cutting at ceil(row / rows_per_item) would hand every expert's first,
+                // rounded-up item to window 0 and overload its XCD)
+                const long long cnt = totals[e];
+                const long long items = (cnt + rows_per_item - 1) / rows_per_item;
+                const int k0 = cnt ? (int)((r_lo[e] * items + cnt / 2) / cnt) : 0;
+                const int k1 = cnt ? (int)((r_hi[e] * items + cnt / 2) / cnt) : 0;
+                n = k1 - k0;
+                first = s_item[e] + k0;
+            }
+            const int incl = wave_inclusive_scan(n);
+            __syncthreads();  // s_part from the previous pass has been read
+            if (lane == kWave - 1) s_part[0][wave] = incl;
+            __syncthreads();
+            int before = wcarry, all = 0;
+            for (int w2 = 0; w2 < 4; ++w2) {
+                if (w2 < wave) before += s_part[0][w2];
+                all += s_part[0][w2];
+            }
+            if (e < E) {
+                witem[(size_t)wdx * (E + 1) + e] = before + incl - n;
+                wfirst[(size_t)wdx * E + e] = first;
+            }
+            wcarry += all;
+        }
+        if (tid == 0) witem[(size_t)wdx * (E + 1) + E] = wcarry;
     }
     if (alist) {  // -1 behind each expert's last token, up to its next work-item boundary
         for (int i = blockIdx.x * 256 + tid; i < E * rows_per_item; i += gridDim.x * 256) {
@@ -331,8 +372,10 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
 
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
-                          int32_t* token_lists, int32_t* aligned_lists, hipStream_t s) {
+                          int32_t* token_lists, int32_t* aligned_lists, int window_groups,
+                          int32_t* witem, int32_t* wfirst, hipStream_t s) {
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
+    const int NW = witem ? div_up(NG, window_groups) : 0;
     {
         LaunchTimer tm(kSlotScanGroups, s);
         scan_groups_kernel<<<div_up(E, 4), 256, 0, s>>>(group_off, NG, E);
@@ -347,7 +390,7 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
     }
     fill_lists_kernel<<<std::max(1, NG), 256, lds, s>>>(
         mask, T, E, W, group_off, rows_per_item, counts, offsets, item_start, token_lists,
-        aligned_lists);
+        aligned_lists, window_groups, NW, witem, wfirst);
 }
 
 }  // namespace dmoe

@@ -30,8 +30,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from separate `rocprofv3 --pmc FETCH_SIZE` /
 # `WRITE_SIZE` runs of this script, scaled by the same counters' readings for a plain 256 MiB copy
 # (profiles/dmoe_forward_cfg2_tau0.5_hbm_traffic.txt).  Only valid for the exact workload named.
-MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 135.5e6 + 25.2e6,
-                    ("cfg2", 0.5, "expert_up"): 458.2e6 + 22.1e6}
+MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 91.5e6 + 25.2e6,
+                    ("cfg2", 0.5, "expert_up"): 155.9e6 + 22.1e6}
 N_ROTATE = 8                   # distinct x / y buffers cycled through, so that inputs come from HBM
 N_LAYER_COPIES_DECODE = 4      # distinct weight copies cycled through at decode sizes: together
                                # they exceed the 256 MB last-level cache, so weights come from HBM
@@ -114,10 +114,12 @@ class Workload:
                         "experts_gbs": round(sum(kbytes.values()) / (both_ms * 1e-3) / 1e9, 1),
                         "weight_copies_rotated": len(self.layers)}
         else:
-            kflops = {"expert_up": flops * (g - 1) / g, "expert_down": flops / g}
+            # two down kernels are launched; the one the density selects does the work
+            down = max(("expert_down", "expert_down_sparse"), key=lambda k: kt.get(k, 0.0))
+            kflops = {"expert_up": flops * (g - 1) / g, down: flops / g}
             dom = max(kflops, key=lambda k: kt.get(k, 0.0))
             achieved = kflops[dom] / (kt[dom] * 1e-3) / 1e12
-            experts_ms = sum(kt[k] for k in kflops if k in kt)
+            experts_ms = sum(kt.get(k, 0.0) for k in ("expert_up", "expert_down", "expert_down_sparse"))
             roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(achieved / PEAK_BF16_TFLOPS, 4),

@@ -86,10 +86,14 @@ int32_t dmoe_select_workspace_bytes(int32_t n_tokens, int32_t n_experts, size_t 
 int32_t dmoe_packed_bytes(const dmoe_layer *layer, size_t *out_bytes);
 
 /*
- * One-time re-layout of the down-projection for the MFMA kernels (bf16 layers): writes, into
- * `packed` (device, 256-byte aligned, dmoe_packed_bytes() large), w_down transposed per expert
- * to [E][d][m_pad] with m_pad = m rounded up to 32 and zero fill.  Put the pointer into
- * layer->packed afterwards.  For fp32 layers this is a no-op that accepts packed == NULL.
+ * One-time re-layout of the weights for the MFMA kernels (bf16 layers): writes, into `packed`
+ * (device, 256-byte aligned, dmoe_packed_bytes() large), the expert matrices (w_up, w_gate, w_down
+ * -- the latter in two orders) and the router matrices (r_w1, r_w2) as 1 KiB blocks in the
+ * register order of the matrix-core operands, the expert size rounded up to a multiple of 32
+ * with zero neurons.  The layout is private to the library.  Reads the layer's weight pointers;
+ * asynchronous on `stream`.  Put the pointer into layer->packed afterwards and keep the buffer
+ * (and the original weights) alive as long as the layer is used.  For fp32 layers this is a
+ * no-op that accepts packed == NULL.
  */
 int32_t dmoe_pack_weights(const dmoe_layer *layer, void *packed, size_t packed_bytes,
                           void *stream);

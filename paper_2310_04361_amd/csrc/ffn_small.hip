@@ -1,10 +1,12 @@
 // Small-token (decode) experts: T <= 16 tokens ride in ONE MFMA column tile, so the work is
 // reading every touched expert's weights exactly once -- a weight-bandwidth-bound stream.
 //
-//   up_small    one workgroup per expert; experts nobody selected exit before touching their
-//               weights.  The 16 x rows sit in LDS; wavefront w streams neuron tile w of the up
-//               (and gate) fragments -- 1 KiB contiguous per load, many loads in flight -- and
-//               writes h (zero for tokens that did not select the expert) as an H fragment.
+//   up_small    one workgroup of sixteen wavefronts per expert; experts nobody selected exit
+//               before touching their weights.  The 16 x rows sit in LDS; wavefront (tile, slice)
+//               streams a K slice of one neuron tile of the up (and gate) fragments -- 1 KiB
+//               contiguous per load, 8 to 16 loads in flight per wavefront -- the slices are added
+//               through LDS and h (zero for tokens that did not select the expert) goes out as an
+//               H fragment.
 //   down_small  workgroup = (4 output-column tiles, group of experts): streams the touched
 //               experts' down fragments of its columns, accumulates in registers and writes one
 //               fp32 partial per expert group (no atomics).
@@ -36,19 +38,29 @@ __device__ __forceinline__ float activate_s(int act, float v) {
     return 0.5f * v * (1.0f + th);
 }
 
-// MT = m_pad / 16 wavefronts per workgroup, one neuron tile each.
+// Sixteen wavefronts per workgroup = MT neuron tiles (m_pad / 16) x KQ slices of the K range: an
+// expert's weights are a pure stream, so what counts is how many bytes a CU keeps in flight.
+// Wavefront (mt, kq) streams its slice of tile mt (up and gate fragments, eight k-steps of loads
+// issued together), the KQ partial products are added through LDS.
+constexpr int kUpSmallWaves = 16;
+
 template <int MT, bool GATED>
-__global__ __launch_bounds__(64 * MT) void up_small_kernel(
+__global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
     const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
-    const uint64_t* __restrict__ colmask, __bf16* __restrict__ Hs, int T, int d, int m, int act) {
-    constexpr int KS = MT / 2, kThreads = 64 * MT;
+    const uint64_t* __restrict__ colmask, __bf16* __restrict__ Hs, int T, int d, int m, int act,
+    int KQ) {
+    constexpr int KS = MT / 2, kThreads = 64 * kUpSmallWaves, BR = GATED ? 2 : 1;
     const int e = blockIdx.x;
     const uint64_t cm = colmask[e];
     if (cm == 0ull) return;  // uniform: nobody selected this expert
-    extern __shared__ char xs[];  // [16][2d + 16]
+    extern __shared__ char smem[];
     const int row_bytes = 2 * d + 16;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
+    char* xs = smem;                                                    // [16][2d + 16]
+    float* red = reinterpret_cast<float*>(smem + 16 * row_bytes);       // [16 waves][BR][64][4]
+    const int tid = threadIdx.x, lane = tid & 63, q = lane >> 4, c = lane & 15;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int mt = w % MT, kq = w / MT;
     const int pieces = d / 8;
     for (int i = tid; i < 16 * pieces; i += kThreads) {
         const int row = i / pieces, piece = i % pieces;
@@ -57,35 +69,64 @@ __global__ __launch_bounds__(64 * MT) void up_small_kernel(
     }
     __syncthreads();
 
-    const int NK32 = d / 32;
-    const __bf16* au = wupf + (((size_t)e * MT + w) * NK32 * 64 + lane) * 8;
-    const __bf16* ag = wgatef + (((size_t)e * MT + w) * NK32 * 64 + lane) * 8;
-    const char* bsrc = xs + c * row_bytes + q * 16;
-    f32x4 accu = f32x4{0.f, 0.f, 0.f, 0.f}, accg = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-    for (int ks = 0; ks < NK32; ++ks) {
-        const bf16x8 b = *reinterpret_cast<const bf16x8*>(bsrc + ks * 64);
-        accu = mfma16(load8(au + (size_t)ks * 512), b, accu);
-        if (GATED) accg = mfma16(load8(ag + (size_t)ks * 512), b, accg);
+    const int NK32 = d / 32, per = NK32 / KQ;  // k-steps per slice (KQ divides NK32)
+    f32x4 acc[BR];
+#pragma unroll
+    for (int br = 0; br < BR; ++br) acc[br] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (kq < KQ) {
+        const __bf16* au = wupf + (((size_t)e * MT + mt) * NK32 * 64 + lane) * 8;
+        const __bf16* ag = wgatef + (((size_t)e * MT + mt) * NK32 * 64 + lane) * 8;
+        const char* bsrc = xs + c * row_bytes + q * 16;
+        const int k0 = kq * per;
+        for (int kb = 0; kb < per; kb += 8) {
+            bf16x8 a[8][BR];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int ks = k0 + min(kb + i, per - 1);  // past the slice: a block already read
+                a[i][0] = load8(au + (size_t)ks * 512);
+                if (GATED) a[i][BR - 1] = load8(ag + (size_t)ks * 512);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (kb + i < per) {
+                    const bf16x8 b = *reinterpret_cast<const bf16x8*>(bsrc + (k0 + kb + i) * 64);
+#pragma unroll
+                    for (int br = 0; br < BR; ++br) acc[br] = mfma16(a[i][br], b, acc[br]);
+                }
+            }
+        }
     }
-
-    // lane (q, c): neurons 16w + 4q + r of token c
+#pragma unroll
+    for (int br = 0; br < BR; ++br)
+        *reinterpret_cast<f32x4*>(red + ((w * BR + br) * 64 + lane) * 4) = acc[br];
+    __syncthreads();
+    if (kq != 0) return;
+    // wavefront (mt, 0): sum the KQ slices; lane (q, c): neurons 16mt + 4q + r of token c
+#pragma unroll
+    for (int br = 0; br < BR; ++br) {
+        f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < KQ; ++k) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(red + (((k * MT + mt) * BR + br) * 64 + lane) * 4);
+            sum += v;
+        }
+        acc[br] = sum;
+    }
     const bool keep = c < T && ((cm >> c) & 1ull);
     bf16x4 hv;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const int n = 16 * w + 4 * q + r;
+        const int n = 16 * mt + 4 * q + r;
         float v;
         if (GATED) {
-            v = activate_s(act, accg[r]) * accu[r];
+            v = activate_s(act, acc[BR - 1][r]) * acc[0][r];
         } else {
             const float bias = b_up ? (float)b_up[(size_t)e * m + min(n, m - 1)] : 0.0f;
-            v = activate_s(act, accu[r] + bias);
+            v = activate_s(act, acc[0][r] + bias);
         }
         if (n >= m || !keep) v = 0.0f;
         hv[r] = (__bf16)v;
     }
-    *reinterpret_cast<bf16x4*>(Hs + (((size_t)e * KS + (w >> 1)) * 64 + lane) * 8 + (w & 1) * 4) = hv;
+    *reinterpret_cast<bf16x4*>(Hs + (((size_t)e * KS + (mt >> 1)) * 64 + lane) * 8 + (mt & 1) * 4) = hv;
 }
 
 constexpr int kSmallPerGroup = 256;  // experts per group at most
@@ -142,24 +183,38 @@ __global__ void finish_small_kernel(const float* __restrict__ partial,
     if (i >= T * d) return;
     const int t = i / d, col = i % d;
     float v = b_down ? (float)b_down[col] : 0.0f;
-    for (int eg = 0; eg < EG; ++eg) v += partial[((size_t)eg * 16 + t) * d + col];
+    const float* p = partial + (size_t)t * d + col;
+    const size_t stride = (size_t)16 * d;
+    int eg = 0;
+    for (; eg + 8 <= EG; eg += 8) {  // eight independent loads in flight
+        float u[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) u[k] = p[(size_t)(eg + k) * stride];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v += u[k];
+    }
+    for (; eg < EG; ++eg) v += p[(size_t)eg * stride];
     y[i] = (__bf16)v;
 }
 
 template <int MT, bool GATED>
 void launch_up_small_t(const dmoe_layer& L, const void* x, int T, const PackedLayout& P,
                        const uint64_t* colmask, void* Hs, hipStream_t s) {
-    const size_t lds = 16 * (2 * (size_t)L.d_model + 16);
+    const size_t lds = 16 * (2 * (size_t)L.d_model + 16) +
+                       sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4;
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_small_kernel<MT, GATED>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
+    // K slices: as many as the sixteen wavefronts allow and the k-steps divide into
+    int KQ = kUpSmallWaves / MT;
+    while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
     const char* pk = static_cast<const char*>(L.packed);
-    up_small_kernel<MT, GATED><<<L.n_experts, 64 * MT, lds, s>>>(
+    up_small_kernel<MT, GATED><<<L.n_experts, 64 * kUpSmallWaves, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
-        (const __bf16*)L.b_up, colmask, (__bf16*)Hs, T, L.d_model, L.expert_size, L.act);
+        (const __bf16*)L.b_up, colmask, (__bf16*)Hs, T, L.d_model, L.expert_size, L.act, KQ);
 }
 
 }  // namespace
@@ -167,7 +222,7 @@ void launch_up_small_t(const dmoe_layer& L, const void* x, int T, const PackedLa
 bool small_bf16_supported(const dmoe_layer& L) {
     const int mp = m_pad_of(L.expert_size);
     return L.packed != nullptr && (mp == 32 || mp == 64 || mp == 128) && L.d_model % 32 == 0 &&
-           16 * (2 * (size_t)L.d_model + 16) <= 160 * 1024 - 1024 &&
+           16 * (2 * (size_t)L.d_model + 16) <= 160 * 1024 - 16 * 1024 &&
            div_up(L.n_experts, kSmallMaxGroups) <= kSmallPerGroup;
 }
 
@@ -190,7 +245,7 @@ void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t
     // expert groups: enough workgroups to fill the chip, at most kSmallMaxGroups partial sums
     const int E = L.n_experts, d = L.d_model;
     const int ncg = div_up(d / 16, 4);
-    int EG = std::max(1, std::min({kSmallMaxGroups, div_up(256, ncg), std::max(1, E / 4)}));
+    int EG = std::max(1, std::min({kSmallMaxGroups, div_up(1024, ncg), std::max(1, E / 4)}));
     EG = std::max(EG, div_up(E, kSmallPerGroup));
     const int per = div_up(E, EG);
     EG = div_up(E, per);

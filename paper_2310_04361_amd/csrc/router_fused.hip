@@ -297,23 +297,25 @@ void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float t
 // ---- T <= 16: the same two products spread over many workgroups --------------------------------
 // With so few tokens the router is a weight stream (R1 is 1 MiB at d = 2048, d_h = 256) and one
 // workgroup per 64 tokens would leave it to a single CU.
-//   hidden: workgroup = one tile of 16 hidden units, its four wavefronts split K and reduce
-//           through LDS; hid[16][d_h] (bf16) goes to a small global buffer.
+//   hidden: workgroup = one tile of 16 hidden units, its (up to) sixteen wavefronts split K and
+//           reduce through LDS; hid[16][d_h] (bf16) goes to a small global buffer.
 //   scores: wavefront = one tile of 16 experts.
 // The gate then runs as the stand-alone mask kernel on the stored scores.
-__global__ __launch_bounds__(256) void router_small_hidden_kernel(
+__global__ __launch_bounds__(1024) void router_small_hidden_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
-    __bf16* __restrict__ hid, int T, int d, int dh) {
-    __shared__ float red[4][64][4];
+    __bf16* __restrict__ hid, int T, int d, int dh, int KQ) {
+    __shared__ float red[16][64][4];
     const int h = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
-    const int NK32 = d / 32, per = NK32 / 4;  // d is a multiple of 128
+    const int NK32 = d / 32, per = NK32 / KQ;  // KQ <= 16 wavefronts split K; KQ divides NK32
     const __bf16* xr = x + (size_t)min(c, T - 1) * d + 8 * q;
     const __bf16* af = r1f + (((size_t)h * NK32) * 64 + lane) * 8;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (w < KQ) {
 #pragma unroll 8
-    for (int ks = w * per; ks < (w + 1) * per; ++ks)
-        acc = mfma16(load8(af + (size_t)ks * 512), load8(xr + 32 * ks), acc);
+        for (int ks = w * per; ks < (w + 1) * per; ++ks)
+            acc = mfma16(load8(af + (size_t)ks * 512), load8(xr + 32 * ks), acc);
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r) red[w][lane][r] = acc[r];
     __syncthreads();
@@ -321,7 +323,8 @@ __global__ __launch_bounds__(256) void router_small_hidden_kernel(
         bf16x4 hv;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float v = red[0][lane][r] + red[1][lane][r] + red[2][lane][r] + red[3][lane][r];
+            float v = 0.0f;
+            for (int k = 0; k < KQ; ++k) v += red[k][lane][r];
             if (r_b1) v += (float)r_b1[16 * h + 4 * q + r];
             hv[r] = (__bf16)fmaxf(v, 0.0f);
         }
@@ -372,9 +375,11 @@ void launch_router_small(const dmoe_layer& L, const void* x, int T, void* hid, f
     const PackedLayout P = packed_layout(L);
     const char* pk = static_cast<const char*>(L.packed);
     const int dh = L.router_hidden, E = L.n_experts;
-    router_small_hidden_kernel<<<dh / 16, 256, 0, s>>>(
+    int KQ = 16;  // wavefronts that split K: as many as divide the k-steps
+    while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
+    router_small_hidden_kernel<<<dh / 16, 1024, 0, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1, (__bf16*)hid, T,
-        L.d_model, dh);
+        L.d_model, dh, KQ);
     router_small_scores_kernel<<<div_up(div_up(E, 16), 4), 256, 0, s>>>(
         (const __bf16*)hid, (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, dh, E);
 }

@@ -176,6 +176,11 @@ def main() -> int:
     ap.add_argument("--no-others", action="store_true", help="skip the other workloads")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--top-k", type=int, default=0,
+                    help="also time the headline workload with the top-k gate (k experts per token)")
+    ap.add_argument("--paper-sweep", action="store_true",
+                    help="also time dmoe_expert_ffn on the paper's benchmark shape (24 experts x 128, "
+                         "d=768, 256x197 tokens) under Bernoulli(p) decisions, p = 0 .. 1 (Sec. 4.4)")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense-FFN comparisons (keeps a profile to the timed workload)")
     args = ap.parse_args()
@@ -258,6 +263,38 @@ def main() -> int:
     }
     if sweep:
         out["tau_sweep"] = sweep
+
+    if args.top_k:
+        k = args.top_k
+        for i in range(5):
+            B.dmoe_forward_topk(w.layers[0], w.xs[i % N_ROTATE], k, y=w.ys[i % N_ROTATE])
+        m = _time_ms(lambda i: B.dmoe_forward_topk(w.layers[0], w.xs[i % N_ROTATE], k,
+                                                   y=w.ys[i % N_ROTATE]), 100)
+        out["top_k_gate"] = {"k": k, "ms_per_step": round(m, 5),
+                             "tokens_per_s": round(cfg.T / (m * 1e-3), 1),
+                             "speedup_vs_dense": round(dense_ms / m, 3) if dense_ms else None}
+
+    if args.paper_sweep:
+        from paper_2310_04361_amd import workloads as wl
+        pw = Workload("paper")
+        pc, pL = pw.cfg, pw.layers[0]
+        pd = None if args.no_dense else pw.dense_ms()
+        rows = []
+        for p in (0.0, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0):
+            mask = wl.bernoulli_mask(pc.T, pc.E, p, seed=7)
+            offs = np.concatenate([[0], np.cumsum(mask.sum(axis=0))]).astype(np.int32)
+            lists = np.concatenate([np.flatnonzero(mask[:, e]) for e in range(pc.E)] + [np.zeros(1)]).astype(np.int32)
+            offs_d, lists_d = torch.from_numpy(offs).cuda(), torch.from_numpy(lists).cuda()
+            for i in range(3):
+                B.dmoe_expert_ffn(pL, pw.xs[i % N_ROTATE], offs_d, lists_d)
+            m = _time_ms(lambda i: B.dmoe_expert_ffn(pL, pw.xs[i % N_ROTATE], offs_d, lists_d), 20)
+            rows.append({"p": p, "ms": round(m, 4),
+                         "vs_dense": round(pd / m, 3) if pd else None})
+        out["paper_shape_bernoulli_sweep"] = {"workload": pw.describe("-"), "note": "dmoe_expert_ffn "
+                                              "only (decisions given, no router), as in Sec. 4.4",
+                                              "dense_vendor_gemm_ms": round(pd, 4) if pd else None,
+                                              "rows": rows}
+        del pw
 
     if not args.no_others:
         del w

@@ -151,6 +151,23 @@ int32_t dmoe_forward(const dmoe_layer *layer, const void *x, int32_t n_tokens, f
                      int32_t *token_lists_out, void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* ---- the conventional top-k gate (the rule Sec. 3.3 / 3.4 compare dynamic-k against) --------- */
+
+/*
+ * As dmoe_select / dmoe_forward, but every token keeps exactly k experts: those with the k
+ * largest scores, ties at the k-th score going to the lower expert index.  0 <= k <= E
+ * (DMOE_ERR_SHAPE otherwise); k == 0 keeps nothing (y = b_down), k == E is the dense layer.
+ * Same buffers, workspace sizes, ownership and asynchrony as the dynamic-k calls.
+ */
+int32_t dmoe_select_topk(const float *scores, int32_t n_tokens, int32_t n_experts, int32_t k,
+                         uint64_t *mask_bits, int32_t *k_per_token, int32_t *counts,
+                         int32_t *offsets, int32_t *token_lists, void *workspace,
+                         size_t workspace_bytes, void *stream);
+int32_t dmoe_forward_topk(const dmoe_layer *layer, const void *x, int32_t n_tokens, int32_t k,
+                          void *y, float *scores_out, uint64_t *mask_out, int32_t *offsets_out,
+                          int32_t *token_lists_out, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
 /* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
 
 /*

@@ -24,7 +24,7 @@ DTYPE_CODES = {"f32": DMOE_F32, "bf16": DMOE_BF16}
 EXPORTS = (
     "dmoe_version", "dmoe_last_error", "dmoe_workspace_bytes", "dmoe_select_workspace_bytes",
     "dmoe_packed_bytes", "dmoe_pack_weights", "dmoe_router", "dmoe_select", "dmoe_expert_ffn",
-    "dmoe_forward", "dmoe_timing_enable", "dmoe_timing_reset", "dmoe_timing_slots",
+    "dmoe_forward", "dmoe_select_topk", "dmoe_forward_topk", "dmoe_timing_enable", "dmoe_timing_reset", "dmoe_timing_slots",
     "dmoe_timing_read",
 )
 
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.dmoe_select.argtypes = [V, I, I, F, V, V, V, V, V, V, SZ, V]
         L.dmoe_expert_ffn.argtypes = [LP, V, I, V, V, V, V, SZ, V]
         L.dmoe_forward.argtypes = [LP, V, I, F, V, V, V, V, V, V, SZ, V]
+        L.dmoe_select_topk.argtypes = [V, I, I, I, V, V, V, V, V, V, SZ, V]
+        L.dmoe_forward_topk.argtypes = [LP, V, I, I, V, V, V, V, V, V, SZ, V]
         L.dmoe_timing_enable.argtypes = [I]
         L.dmoe_timing_read.argtypes = [I, P(ctypes.c_char_p), P(ctypes.c_int64), P(ctypes.c_double)]
         for name in EXPORTS:
@@ -169,10 +171,10 @@ def dmoe_router(layer: Layer, x):
     return scores
 
 
-def dmoe_select(scores, tau: float, want_mask=True, want_k=True):
-    """Dynamic-k gate + bucketing (Eq. 4).  Returns a dict of device tensors:
-    mask_bits [T, ceil(E/64)] int64, k_per_token [T], counts [E], offsets [E+1],
-    token_lists [T*E] (only the first offsets[E] entries are meaningful)."""
+def dmoe_select(scores, tau: float, want_mask=True, want_k=True, top_k=None):
+    """Dynamic-k gate + bucketing (Eq. 4), or the top-k gate when top_k is given.  Returns a dict
+    of device tensors: mask_bits [T, ceil(E/64)] int64, k_per_token [T], counts [E],
+    offsets [E+1], token_lists [T*E] (only the first offsets[E] entries are meaningful)."""
     import torch
     T, E = scores.shape
     dev = scores.device
@@ -187,11 +189,19 @@ def dmoe_select(scores, tau: float, want_mask=True, want_k=True):
     n = ctypes.c_size_t(0)
     check(lib().dmoe_select_workspace_bytes(T, E, ctypes.byref(n)))
     ws = torch.empty(max(n.value, 256), dtype=torch.uint8, device=dev)
-    check(lib().dmoe_select(scores.data_ptr(), T, E, float(tau), _ptr(out["mask_bits"]),
-                            _ptr(out["k_per_token"]), out["counts"].data_ptr(),
-                            out["offsets"].data_ptr(), out["token_lists"].data_ptr(),
-                            ws.data_ptr(), ws.numel(), _stream()))
+    tail = (_ptr(out["mask_bits"]), _ptr(out["k_per_token"]), out["counts"].data_ptr(),
+            out["offsets"].data_ptr(), out["token_lists"].data_ptr(), ws.data_ptr(), ws.numel(),
+            _stream())
+    if top_k is None:
+        check(lib().dmoe_select(scores.data_ptr(), T, E, float(tau), *tail))
+    else:
+        check(lib().dmoe_select_topk(scores.data_ptr(), T, E, int(top_k), *tail))
     return out
+
+
+def dmoe_select_topk(scores, k: int, want_mask=True, want_k=True):
+    """Top-k gate + bucketing: exactly k experts per token (ties to the lower index)."""
+    return dmoe_select(scores, 0.0, want_mask, want_k, top_k=k)
 
 
 def dmoe_expert_ffn(layer: Layer, x, offsets, token_lists):
@@ -207,8 +217,9 @@ def dmoe_expert_ffn(layer: Layer, x, offsets, token_lists):
 
 
 def dmoe_forward(layer: Layer, x, tau: float, want_scores=False, want_mask=False,
-                 want_lists=False, y=None):
-    """Whole layer.  Returns (y, extras) with extras holding the requested optional outputs."""
+                 want_lists=False, y=None, top_k=None):
+    """Whole layer (top-k gate instead of the dynamic-k one when top_k is given).  Returns
+    (y, extras) with extras holding the requested optional outputs."""
     import torch
     T = x.shape[0]
     dev = x.device
@@ -223,11 +234,19 @@ def dmoe_forward(layer: Layer, x, tau: float, want_scores=False, want_mask=False
         ex["offsets"] = torch.empty((layer.E + 1,), dtype=torch.int32, device=dev)
         ex["token_lists"] = torch.empty((max(T * layer.E, 1),), dtype=torch.int32, device=dev)
     ws = layer.workspace(T)
-    check(lib().dmoe_forward(layer.ref(), x.data_ptr(), T, float(tau), y.data_ptr(),
-                             _ptr(ex.get("scores")), _ptr(ex.get("mask_bits")),
-                             _ptr(ex.get("offsets")), _ptr(ex.get("token_lists")),
-                             ws.data_ptr(), ws.numel(), _stream()))
+    tail = (y.data_ptr(), _ptr(ex.get("scores")), _ptr(ex.get("mask_bits")),
+            _ptr(ex.get("offsets")), _ptr(ex.get("token_lists")), ws.data_ptr(), ws.numel(),
+            _stream())
+    if top_k is None:
+        check(lib().dmoe_forward(layer.ref(), x.data_ptr(), T, float(tau), *tail))
+    else:
+        check(lib().dmoe_forward_topk(layer.ref(), x.data_ptr(), T, int(top_k), *tail))
     return y, ex
+
+
+def dmoe_forward_topk(layer: Layer, x, k: int, **kw):
+    """Whole layer with the top-k gate."""
+    return dmoe_forward(layer, x, 0.0, top_k=k, **kw)
 
 
 def mask_bits_to_bool(mask_bits, E: int) -> np.ndarray:

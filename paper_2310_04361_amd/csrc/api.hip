@@ -283,12 +283,27 @@ int32_t dmoe_router(const dmoe_layer* layer, const void* x, int32_t n_tokens, fl
     return check_launch("router");
 }
 
-int32_t dmoe_select(const float* scores, int32_t n_tokens, int32_t n_experts, float tau,
-                    uint64_t* mask_bits, int32_t* k_per_token, int32_t* counts, int32_t* offsets,
-                    int32_t* token_lists, void* workspace, size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// The gate of a call: the dynamic-k threshold (top_k < 0) or a fixed number of experts.
+struct Gate {
+    float tau;
+    int top_k;
+};
+int check_gate(const Gate& g, int E) {
+    if (g.top_k < 0) return check_tau(g.tau);
+    if (g.top_k > E) return fail(DMOE_ERR_SHAPE, "k = %d exceeds the %d experts", g.top_k, E);
+    return DMOE_OK;
+}
+
+int select_impl(const float* scores, int32_t n_tokens, int32_t n_experts, Gate gate,
+                uint64_t* mask_bits, int32_t* k_per_token, int32_t* counts, int32_t* offsets,
+                int32_t* token_lists, void* workspace, size_t workspace_bytes, void* stream) {
     if (n_experts <= 0) return fail(DMOE_ERR_SHAPE, "n_experts must be positive");
     if (int rc = check_tokens(n_tokens, n_experts)) return rc;
-    if (int rc = check_tau(tau)) return rc;
+    if (int rc = check_gate(gate, n_experts)) return rc;
     if (!offsets) return fail(DMOE_ERR_NULL, "offsets is NULL");
     if (n_tokens > 0 && (!scores || !token_lists)) return fail(DMOE_ERR_NULL, "scores or token_lists is NULL");
     const SelectWs w = select_ws(n_tokens, n_experts, mask_bits == nullptr);
@@ -297,11 +312,35 @@ int32_t dmoe_select(const float* scores, int32_t n_tokens, int32_t n_experts, fl
     hipStream_t s = (hipStream_t)stream;
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
     uint64_t* mask = mask_bits ? mask_bits : reinterpret_cast<uint64_t*>(ws + w.mask);
-    if (n_tokens > 0)
-        launch_mask_from_scores(scores, n_tokens, n_experts, tau, mask, k_per_token, group_off, nullptr, s);
+    if (n_tokens > 0) {
+        if (gate.top_k < 0)
+            launch_mask_from_scores(scores, n_tokens, n_experts, gate.tau, mask, k_per_token, group_off, nullptr, s);
+        else
+            launch_mask_topk(scores, n_tokens, n_experts, gate.top_k, mask, k_per_token, group_off, nullptr, s);
+    }
     launch_scan_and_fill(mask, n_tokens, n_experts, group_off, counts, offsets, nullptr, 64,
                          n_tokens > 0 ? token_lists : nullptr, nullptr, 1, nullptr, nullptr, s);
     return check_launch("select");
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t dmoe_select(const float* scores, int32_t n_tokens, int32_t n_experts, float tau,
+                    uint64_t* mask_bits, int32_t* k_per_token, int32_t* counts, int32_t* offsets,
+                    int32_t* token_lists, void* workspace, size_t workspace_bytes, void* stream) {
+    return select_impl(scores, n_tokens, n_experts, Gate{tau, -1}, mask_bits, k_per_token, counts,
+                       offsets, token_lists, workspace, workspace_bytes, stream);
+}
+
+int32_t dmoe_select_topk(const float* scores, int32_t n_tokens, int32_t n_experts, int32_t k,
+                         uint64_t* mask_bits, int32_t* k_per_token, int32_t* counts,
+                         int32_t* offsets, int32_t* token_lists, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    if (k < 0) return fail(DMOE_ERR_SHAPE, "k must not be negative");
+    return select_impl(scores, n_tokens, n_experts, Gate{0.0f, k}, mask_bits, k_per_token, counts,
+                       offsets, token_lists, workspace, workspace_bytes, stream);
 }
 
 int32_t dmoe_expert_ffn(const dmoe_layer* layer, const void* x, int32_t n_tokens,
@@ -322,13 +361,17 @@ int32_t dmoe_expert_ffn(const dmoe_layer* layer, const void* x, int32_t n_tokens
     return run_experts(*layer, x, n_tokens, ws, w, mask, nullptr, nullptr, y, s);
 }
 
-int32_t dmoe_forward(const dmoe_layer* layer, const void* x, int32_t n_tokens, float tau, void* y,
-                     float* scores_out, uint64_t* mask_out, int32_t* offsets_out,
-                     int32_t* token_lists_out, void* workspace, size_t workspace_bytes,
-                     void* stream) {
+}  // extern "C"
+
+namespace {
+
+int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate gate, void* y,
+                 float* scores_out, uint64_t* mask_out, int32_t* offsets_out,
+                 int32_t* token_lists_out, void* workspace, size_t workspace_bytes, void* stream) {
     if (int rc = check_layer(layer, true, true)) return rc;
     if (int rc = check_tokens(n_tokens, layer->n_experts)) return rc;
-    if (int rc = check_tau(tau)) return rc;
+    if (int rc = check_gate(gate, layer->n_experts)) return rc;
+    const float tau = gate.tau;
     if ((offsets_out == nullptr) != (token_lists_out == nullptr))
         return fail(DMOE_ERR_NULL, "offsets_out and token_lists_out go together");
     if (n_tokens == 0) return DMOE_OK;
@@ -341,19 +384,48 @@ int32_t dmoe_forward(const dmoe_layer* layer, const void* x, int32_t n_tokens, f
     uint64_t* mask = mask_out ? mask_out : reinterpret_cast<uint64_t*>(ws + w.mask);
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
     uint64_t* colmask = use_small_path(*layer, n_tokens) ? reinterpret_cast<uint64_t*>(ws + w.colmask) : nullptr;
-    if (layer->dtype == DMOE_BF16 && router_fused_supported(*layer) && n_tokens <= kSmallTokens) {
-        launch_router_small(*layer, x, n_tokens, ws + w.hid, scores, s);
-        launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr, group_off,
-                                colmask, s);
-    } else if (layer->dtype == DMOE_BF16 && router_fused_supported(*layer)) {
+    const bool fused_router = layer->dtype == DMOE_BF16 && router_fused_supported(*layer);
+    if (fused_router && n_tokens > kSmallTokens && gate.top_k < 0) {
+        // router, dynamic-k gate and group counts in one kernel
         launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, colmask, s);
     } else {
-        if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
-        else launch_router_bf16(*layer, x, n_tokens, scores, s);
-        launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr, group_off,
-                                colmask, s);
+        if (fused_router && n_tokens <= kSmallTokens)
+            launch_router_small(*layer, x, n_tokens, ws + w.hid, scores, s);
+        else if (fused_router)
+            launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, nullptr, s);
+        else if (layer->dtype == DMOE_F32)
+            launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
+        else
+            launch_router_bf16(*layer, x, n_tokens, scores, s);
+        if (gate.top_k < 0)
+            launch_mask_from_scores(scores, n_tokens, layer->n_experts, tau, mask, nullptr,
+                                    group_off, colmask, s);
+        else
+            launch_mask_topk(scores, n_tokens, layer->n_experts, gate.top_k, mask, nullptr,
+                             group_off, colmask, s);
     }
     return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t dmoe_forward(const dmoe_layer* layer, const void* x, int32_t n_tokens, float tau, void* y,
+                     float* scores_out, uint64_t* mask_out, int32_t* offsets_out,
+                     int32_t* token_lists_out, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+    return forward_impl(layer, x, n_tokens, Gate{tau, -1}, y, scores_out, mask_out, offsets_out,
+                        token_lists_out, workspace, workspace_bytes, stream);
+}
+
+int32_t dmoe_forward_topk(const dmoe_layer* layer, const void* x, int32_t n_tokens, int32_t k,
+                          void* y, float* scores_out, uint64_t* mask_out, int32_t* offsets_out,
+                          int32_t* token_lists_out, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    if (k < 0) return fail(DMOE_ERR_SHAPE, "k must not be negative");
+    return forward_impl(layer, x, n_tokens, Gate{0.0f, k}, y, scores_out, mask_out, offsets_out,
+                        token_lists_out, workspace, workspace_bytes, stream);
 }
 
 int32_t dmoe_timing_enable(int32_t on) {

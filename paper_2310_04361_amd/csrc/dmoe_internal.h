@@ -90,6 +90,9 @@ struct LaunchTimer {
 void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint64_t* mask,
                              int32_t* k_per_token, int32_t* group_off, uint64_t* colmask,
                              hipStream_t s);
+// Top-k gate: exactly k experts per token, ties at the k-th score to the lower expert index.
+void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
+                      int32_t* k_per_token, int32_t* group_off, uint64_t* colmask, hipStream_t s);
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,
                             uint64_t* mask, int32_t* group_off, uint64_t* colmask, hipStream_t s);
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,

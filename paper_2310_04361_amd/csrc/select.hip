@@ -101,6 +101,57 @@ __global__ __launch_bounds__(256) void mask_count_kernel(const float* __restrict
     if (valid && k_per_token) k_per_token[t] = kt;
 }
 
+// Top-k gate (the conventional rule that Sec. 3.3 / 3.4 compare against): keep the k largest
+// scores of each token, ties at the k-th value going to the lower expert index, so that exactly
+// k are kept.  One wavefront per token with the lanes striding the experts (coalesced row read).
+// The k-th largest value is found by a radix descent over the 32 bits of an order-preserving
+// integer image of the scores (one ballot per 64 experts and bit); the experts equal to it are
+// then admitted in index order until k are reached.  CH = ceil(E / 64) values per lane.
+template <int CH>
+__global__ __launch_bounds__(256) void topk_mask_kernel(const float* __restrict__ scores,
+                                                        uint64_t* __restrict__ mask, int T, int E,
+                                                        int W, int k) {
+    const int lane = lane_id();
+    const int t = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    if (t >= T) return;  // uniform per wavefront
+    const float* row = scores + (size_t)t * E;
+    uint32_t key[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int e = 64 * c + lane;
+        // -0 and +0 compare equal, as they do as numbers; then flip so that unsigned order =
+        // numeric order (sign bit set: all bits flipped, else only the sign bit)
+        const uint32_t b = e < E ? __float_as_uint(row[e] + 0.0f) : 0x80000000u;  // padding: -0 -> below
+        key[c] = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+        if (e >= E) key[c] = 0u;  // below every real score
+    }
+    // largest x with #{key >= x} >= k
+    uint32_t x = 0u;
+    if (k > 0) {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t cand = x | (1u << bit);
+            int cnt = 0;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) cnt += __popcll(__ballot(key[c] >= cand));
+            if (cnt >= k) x = cand;  // uniform
+        }
+    }
+    int above = 0;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) above += __popcll(__ballot(key[c] > x));
+    int need = k - above;  // how many of the experts equal to x are admitted, lowest index first
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int e = 64 * c + lane;
+        const bool eq = key[c] == x && e < E;
+        const uint64_t eqb = __ballot(eq);
+        const bool take = eq && __popcll(eqb & ((1ull << lane) - 1ull)) < need;
+        const uint64_t word = __ballot(k > 0 && ((key[c] > x && e < E) || take));
+        need -= min(need, __popcll(eqb));
+        if (lane == 0 && c < W) mask[(size_t)t * W + c] = word;
+    }
+}
+
 // T <= 16: one workgroup, wavefront t = token t with lanes striding the experts, so the score row
 // is read coalesced, the maximum is a wavefront reduction and a ballot IS a mask word.  The
 // transpose to per-expert token sets (colmask) and counts then goes through LDS.
@@ -367,6 +418,23 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
     }
     LaunchTimer tm(kSlotMask, s);
     mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, nullptr, group_off,
+                                                           colmask, T, E, W, 0.0f);
+}
+
+void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
+                      int32_t* k_per_token, int32_t* group_off, uint64_t* colmask, hipStream_t s) {
+    const int W = div_up(E, 64), NG = div_up(T, kGroup);
+    LaunchTimer tm(kSlotMask, s);
+    const int grid = div_up(T, 4);
+    if (W <= 1) topk_mask_kernel<1><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
+    else if (W <= 2) topk_mask_kernel<2><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
+    else if (W <= 4) topk_mask_kernel<4><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
+    else if (W <= 8) topk_mask_kernel<8><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
+    else if (W <= 16) topk_mask_kernel<16><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
+    else if (W <= 32) topk_mask_kernel<32><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
+    else topk_mask_kernel<64><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
+    // counts per (group, expert), the per-token counts and, if wanted, the per-expert token sets
+    mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, k_per_token, group_off,
                                                            colmask, T, E, W, 0.0f);
 }
 

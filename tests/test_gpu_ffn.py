@@ -162,3 +162,32 @@ def test_forward_bf16_score_handoff(B, oracle, name, T, E, tau):
     y2, _ = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32)
     torch.cuda.synchronize()
     assert tokenwise_rel_err(B.from_device(y2, cfg.dtype), ref_y) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("name,T,E,k", [("cfg2", 600, None, 20), ("cfg2", 300, None, 2),
+                                        ("cfg4", 200, 64, 9), ("cfg5b", 16, None, 8),
+                                        ("cfg1", 128, None, 4)])
+def test_forward_topk_score_handoff(B, oracle, name, T, E, k):
+    """Whole layer with the top-k gate: the oracle's top-k gate on the GPU's fp32 scores must give
+    the same mask bit for bit, and its experts the same output."""
+    import torch
+    cfg = small_cfg(name, T, E)
+    print(f"forward_topk {name} T={T} k={k}", flush=True)
+    layer, x = wl.make_layer(cfg, 4), wl.make_input(cfg, 4)
+    L = B.Layer(layer, cfg.dtype)
+    y, ex = B.dmoe_forward_topk(L, B.to_device(x, cfg.dtype), k, want_scores=True, want_mask=True,
+                                want_lists=True)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy()
+    ref_mask = oracle.select_topk(s.astype(np.float64), k)
+    got_mask = B.mask_bits_to_bool(ex["mask_bits"], cfg.E)
+    assert np.array_equal(got_mask, ref_mask)
+    offsets = ex["offsets"].cpu().numpy()
+    assert offsets[-1] == T * k
+    lists = ex["token_lists"].cpu().numpy()
+    for e in range(cfg.E):
+        assert lists[offsets[e]:offsets[e + 1]].tolist() == np.flatnonzero(ref_mask[:, e]).tolist()
+    ref_y = oracle_ffn(oracle, layer, x, ref_mask)
+    err = tokenwise_rel_err(B.from_device(y, cfg.dtype), ref_y)
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]

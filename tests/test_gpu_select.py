@@ -86,3 +86,55 @@ def test_select_empty(B):
     torch.cuda.synchronize()
     assert out["offsets"].cpu().numpy().tolist() == [0] * 17
     assert out["counts"].cpu().numpy().tolist() == [0] * 16
+
+
+# ---- the top-k gate ------------------------------------------------------------------------------
+def _check_topk(B, oracle, scores, k):
+    import torch
+    T, E = scores.shape
+    out = B.dmoe_select_topk(torch.from_numpy(scores).cuda(), k)
+    torch.cuda.synchronize()
+    ref_mask = oracle.select_topk(scores.astype(np.float64), k)
+    ref_counts, ref_offsets, ref_lists = oracle.bucket(ref_mask)
+    got_mask = B.mask_bits_to_bool(out["mask_bits"], E)
+    assert np.array_equal(got_mask, ref_mask)          # bit-exact, ties included
+    words = out["mask_bits"].cpu().numpy().view(np.uint64)
+    if E % 64:
+        assert not (words[:, -1] >> np.uint64(E % 64)).any()
+    assert (out["k_per_token"].cpu().numpy() == k).all()
+    assert np.array_equal(out["counts"].cpu().numpy(), ref_counts)
+    offsets = out["offsets"].cpu().numpy()
+    assert np.array_equal(offsets, ref_offsets) and offsets[-1] == T * k
+    lists = out["token_lists"].cpu().numpy()[: offsets[-1]]
+    for e in range(E):
+        got = lists[offsets[e]:offsets[e + 1]]
+        assert got.tolist() == ref_lists[ref_offsets[e]:ref_offsets[e + 1]].tolist()
+
+
+@pytest.mark.parametrize("T,E", [(1, 16), (65, 32), (257, 24), (1000, 128), (300, 256), (130, 70),
+                                 (40, 700), (4099, 128)])
+@pytest.mark.parametrize("kind", ["halfnormal", "grid", "zipf"])
+def test_select_topk_matches_oracle(B, oracle, T, E, kind):
+    scores = wl.random_scores(T, E, seed=T + E + 1, kind=kind)   # "grid" is full of ties
+    for k in sorted({0, 1, 2, E // 3, E - 1, E}):
+        print(f"select_topk T={T} E={E} kind={kind} k={k}", flush=True)
+        _check_topk(B, oracle, scores, k)
+
+
+def test_select_topk_degenerate_rows(B, oracle):
+    scores = wl.random_scores(100, 64, seed=11)
+    scores[3] = 0.0                     # all equal: the k lowest indices
+    scores[5] = -scores[5]              # negative scores are ordered as numbers
+    scores[7, ::2] = np.float32(-0.0)   # -0 and +0 tie
+    scores[7, 1::2] = 0.0
+    for k in (1, 5, 64):
+        _check_topk(B, oracle, scores, k)
+
+
+def test_select_topk_rejects_bad_k(B):
+    import torch
+    s = torch.zeros((4, 16), dtype=torch.float32, device="cuda")
+    for k in (-1, 17):
+        with pytest.raises(B.DmoeError) as ei:
+            B.dmoe_select_topk(s, k)
+        assert ei.value.code == B.DMOE_ERR_SHAPE

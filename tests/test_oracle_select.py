@@ -109,3 +109,19 @@ def test_topk_gate(oracle):
     m = oracle.select_topk(s, 4)
     for t in range(20):
         assert set(np.flatnonzero(m[t])) == set(np.argsort(-s[t])[:4])
+
+
+def test_topk_gate_ties_go_to_the_lower_index(oracle):
+    """The rule as stated: rank by (score descending, index ascending), keep the first k."""
+    s = np.array([[1.0, 3.0, 3.0, 3.0, 0.0],
+                  [2.0, 2.0, 2.0, 2.0, 2.0],
+                  [0.0, -0.0, 5.0, -1.0, 0.0]])
+    assert oracle.select_topk(s, 2).tolist() == [[0, 1, 1, 0, 0], [1, 1, 0, 0, 0], [1, 0, 1, 0, 0]]
+    assert oracle.select_topk(s, 4).tolist() == [[1, 1, 1, 1, 0], [1, 1, 1, 1, 0], [1, 1, 1, 0, 1]]
+    # brute force: a stable sort of the negated scores is that ranking
+    rng = np.random.default_rng(3)
+    s = rng.integers(0, 4, size=(30, 12)).astype(np.float64)
+    for k in (1, 5, 11):
+        m = oracle.select_topk(s, k)
+        for t in range(30):
+            assert set(np.flatnonzero(m[t])) == set(np.argsort(-s[t], kind="stable")[:k])

@@ -70,9 +70,10 @@ __global__ void pack_down32_kernel(const __bf16* __restrict__ w_down, __bf16* __
     }
 }
 
-// KS2 = m_pad / 16 MFMA k-steps per expert.
-template <int KS2>
-__global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
+// KS2 = m_pad / 16 MFMA k-steps per expert; R = weight sets in flight (see below); WPS = wavefronts
+// per SIMD the register budget is cut for.
+template <int KS2, int R, int WPS>
+__global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     const __bf16* __restrict__ w2g, const __bf16* __restrict__ b_down,
     const int32_t* __restrict__ item_start, const int32_t* __restrict__ group_off,
     const uint32_t* __restrict__ mask32, const int32_t* __restrict__ offsets,
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
         is_out = item_start[ec];
         go_out = grow[ec];
     };
-    u32x4 breg[KS2];
+    u32x4 breg[2][KS2];  // H pieces of two experts in flight (fetched two experts ahead)
     __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)H, 0, 0, 0x00020000);
     uint32_t b_voff = 0x80000000u;
     auto build_prepare = [&](int e) {  // called with e = 0, 1, 2, ... in this order
@@ -138,21 +139,17 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
                                                    kGroup * kRowBytes, 0x00020000);
         b_voff = sel ? (uint32_t)(rank * kRowBytes + bh * (kRowBytes / 2)) : 0x80000000u;
     };
-    auto build_fetch = [&]() {
+    auto build_fetch = [&](u32x4 (&br)[KS2]) {
 #pragma unroll
         for (int s = 0; s < KS2; ++s)
-            breg[s] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff + 16 * s, 0, 0);
-    };
-    auto build_issue = [&](int e) {
-        build_prepare(e);
-        build_fetch();
+            br[s] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff + 16 * s, 0, 0);
     };
     // lane = token 32h + c of the group: tile 2bg + h of the chunk, operand lane (bh, c)
     char* const wdst = img + (((2 * bg + h) * KS2) * 64 + 32 * bh + c) * 16;
-    auto write_tiles = [&](int buf) {
+    auto write_tiles = [&](int buf, const u32x4 (&br)[KS2]) {
 #pragma unroll
         for (int s = 0; s < KS2; ++s)
-            *reinterpret_cast<u32x4*>(wdst + buf * kImage + s * 1024) = breg[s];
+            *reinterpret_cast<u32x4*>(wdst + buf * kImage + s * 1024) = br[s];
     };
 
     // ---- multiplying role: 128 tokens x columns col_w .. col_w + 63
@@ -160,9 +157,11 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
     const size_t w_expert_stride = (size_t)(d / 32) * KS2 * 512;
     // Work advances in phases: phase p = expert p / KS2, k-step p % KS2 = 8 MFMAs (4 token tiles x
     // 2 column tiles) that need two 1 KiB weight blocks.  R weight sets are in flight, so a block
-    // is requested R - 1 phases before its use whatever the expert size.
-    constexpr int R = KS2 < 4 ? 4 : KS2;   // phases per loop trip = weight sets
-    constexpr int EPT = R / KS2;           // experts per loop trip
+    // is requested R - 1 phases before its use whatever the expert size.  A loop trip is two
+    // experts, so that the two register sets of the H fetch simply alternate.
+    // The weights of an expert reach all workgroups of an XCD at about the same time, so nearly
+    // every request is answered from beyond L2: R has to cover that latency.
+    constexpr int PH = R > 2 * KS2 ? R : 2 * KS2;  // phases per loop trip (an even number of experts)
     auto load_phase = [&](int p, bf16x8 (&a)[2]) {
         const int e = min(p / KS2, E - 1), ks = p % KS2;
         const __bf16* src = wsrc + (size_t)e * w_expert_stride + ks * 512;
@@ -200,24 +199,31 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
     // Same issue order as in the loop (H fetch first, then the weight loads): the wait before an
     // LDS write is computed for the worse of the two ways into the loop, and with the fetch
     // issued last here it would wait for every load in flight on every trip.
-    build_issue(0);
-    write_tiles(0);
-    build_issue(1);
+    build_prepare(0);
+    build_fetch(breg[0]);
+    write_tiles(0, breg[0]);
+    build_prepare(1);
+    build_fetch(breg[1]);
+    build_prepare(2);
+    build_fetch(breg[0]);
 #pragma unroll
     for (int q = 0; q < R - 1; ++q) load_phase(q, aw[q]);
     lds_barrier();
     read_pieces(0, 0, bb[0]);
     int buf = 0;
     // Per expert: its first phase writes the tiles of the NEXT expert to LDS and issues the fetch
-    // for the one after; the barrier sits in the middle of the expert's MFMAs.  Every phase first
+    // for the one three ahead (the H rows come from beyond L2: fetched only one expert's MFMA
+    // time ahead they were waited for on every expert); the barrier sits in the middle of the
+    // expert's MFMAs.  Every phase first
     // issues its weight loads and the LDS reads of the NEXT phase's B operands (k-step 0 of the
     // next expert in the last phase: the barrier has passed by then), then runs its 8 MFMAs on
     // operands requested a phase ago.  So the LDS write, the barrier and all LDS reads overlap
     // with matrix work of the same wavefront.  A trip past the last expert multiplies zero tiles.
-    for (int e0 = 0; e0 < E; e0 += EPT) {
+    for (int e0 = 0; e0 < E; e0 += PH / KS2) {
 #pragma unroll
-        for (int q = 0; q < R; ++q) {
+        for (int q = 0; q < PH; ++q) {
             const int e = e0 + q / KS2;
+            u32x4 (&br)[KS2] = breg[(q / KS2 + 1) & 1];  // tiles of e + 1 now, then of e + 3
             const int ks = q % KS2;
             const int nb = next_buf(buf);
             const int rbuf = ks < KS2 - 1 ? buf : nb, rks = ks < KS2 - 1 ? ks + 1 : 0;
@@ -228,15 +234,15 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
             // (loads complete in issue order, so the next LDS write would wait for everything)
             // and issues each LDS read just before its use.
             auto mf = [&](int j, int ct) {
-                acc[j][ct] = mfma32(aw[q][ct], bb[q & 1][j], acc[j][ct]);
+                acc[j][ct] = mfma32(aw[q % R][ct], bb[q & 1][j], acc[j][ct]);
                 __builtin_amdgcn_sched_barrier(0);
             };
             __builtin_amdgcn_sched_barrier(0);
-            if (ks == 0) write_tiles(nb);
+            if (ks == 0) write_tiles(nb, br);
             mf(0, 0);
-            if (ks == 0) build_prepare(e + 2);
+            if (ks == 0) build_prepare(e + 3);
             mf(0, 1);
-            if (ks == 0) build_fetch();
+            if (ks == 0) build_fetch(br);
             mf(1, 0);
             load_phase(e0 * KS2 + q + R - 1, aw[(q + R - 1) % R]);
             mf(1, 1);
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(256, KS2 <= 4 ? 2 : 1) void down_bf16_kernel(
     }
 }
 
-template <int KS2>
+template <int KS2, int R, int WPS>
 void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* item_start,
                    const int32_t* group_off, const uint64_t* mask, const int32_t* offsets,
                    const void* H, void* y, long long max_pairs_sparse, hipStream_t s) {
@@ -282,12 +288,12 @@ void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int3
     constexpr size_t lds = (size_t)kDnBuffers * kDnTiles * KS2 * 1024;
     static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KS2>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KS2, R, WPS>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    down_bf16_kernel<KS2><<<round_up(NC, 8) * NS, 256, lds, s>>>(
+    down_bf16_kernel<KS2, R, WPS><<<round_up(NC, 8) * NS, 256, lds, s>>>(
         (const __bf16*)(pk + P.w2g), (const __bf16*)L.b_down, item_start, group_off,
         reinterpret_cast<const uint32_t*>(mask), offsets, (const __bf16*)H, (__bf16*)y, T,
         L.d_model, L.n_experts, NG, 2 * div_up(L.n_experts, 64), up_rows_bf16(L), max_pairs_sparse);
@@ -311,9 +317,17 @@ void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
     LaunchTimer tm(kSlotDown, s);
     const PackedLayout P = packed_layout(L);
     const int ks2 = m_pad_of(L.expert_size) / 16;
-    if (ks2 == 2) launch_down_t<2>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
-    else if (ks2 == 4) launch_down_t<4>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
-    else launch_down_t<8>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
+    // at most one workgroup per CU: a wavefront may use the whole register file of its SIMD, which
+    // buys a deeper ring of weight sets
+    const bool one_per_cu = div_up(T, kDnTokens) * (L.d_model / kDnCols) <= 256;
+#define DMOE_DOWN(KS2_, R_, WPS_) \
+    launch_down_t<KS2_, R_, WPS_>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s)
+    if (ks2 == 2 && one_per_cu) DMOE_DOWN(2, 16, 1);
+    else if (ks2 == 2) DMOE_DOWN(2, 8, 2);
+    else if (ks2 == 4 && one_per_cu) DMOE_DOWN(4, 16, 1);
+    else if (ks2 == 4) DMOE_DOWN(4, 4, 2);
+    else DMOE_DOWN(8, 8, 1);
+#undef DMOE_DOWN
 }
 
 }  // namespace dmoe

@@ -319,8 +319,22 @@ def main() -> int:
                      "speedup_vs_dense": round(dms / ro["ms"], 3) if dms else None,
                      "kernel_ms": ro["kernel_ms"], "roofline": ro["roofline"]}
             if wo.decode:
-                hot = _time_ms(lambda i: wo.step(i, float(np.float32(t)), hot=True), steps)
+                t32 = float(np.float32(t))
+                hot = _time_ms(lambda i: wo.step(i, t32, hot=True), steps)
                 entry["ms_per_step_weights_cached"] = round(hot, 5)
+                # the same forward recorded once per weight copy as a HIP graph and replayed: the
+                # launch gaps between its six kernels go away
+                graphs = []
+                for li, Lc in enumerate(wo.layers):
+                    gph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gph):
+                        B.dmoe_forward(Lc, wo.xs[li], t32, y=wo.ys[li])
+                    graphs.append(gph)
+                for gph in graphs:
+                    gph.replay()
+                entry["ms_per_step_graph_replay"] = round(
+                    _time_ms(lambda i: graphs[i % len(graphs)].replay(), steps), 5)
+                del graphs
             others.append(entry)
         out["other_workloads"] = others
     print(json.dumps(out))

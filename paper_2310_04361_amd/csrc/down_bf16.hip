@@ -29,8 +29,7 @@
 // time while loads complete in issue order.
 //
 // Operand layouts (v_mfma_f32_32x32x16_bf16, lane = 32h + c):
-//   H row: 2*KS2 pieces of 16 bytes; piece p = 4*ks + q holds neurons 32ks + 4q + {0..3} and
-//     32ks + 16 + 4q + {0..3} -- the order in which the up kernel's accumulators come out.
+//   H row: 2*KS2 pieces of 16 bytes, piece p = neurons 8p .. 8p+7.
 //   B tile (32 tokens, k-step s): lane (h, c) holds piece h*KS2 + s of token c's row.
 //   w2g[E][d/32][KS2][64][8]: lane (h, r) of block (e, column tile, s) holds the same neurons
 //     for output column 32*tile + 16*((r>>2)&1) + 4*(r>>3) + (r&3).  With that column order the
@@ -64,8 +63,7 @@ __global__ void pack_down32_kernel(const __bf16* __restrict__ w_down, __bf16* __
         const int e = (int)(f / (d / 32));
         const int h = lane >> 5, r = lane & 31;
         const int col = 32 * ct + 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
-        const int p = h * KS2 + s, ks = p >> 2, q = p & 3;
-        const int neuron = 32 * ks + (s8 < 4 ? 4 * q + s8 : 16 + 4 * q + (s8 - 4));
+        const int neuron = 8 * (h * KS2 + s) + s8;  // piece h*KS2 + s of the H row
         w2g[i] = neuron < m ? w_down[((size_t)e * m + neuron) * d + col] : (__bf16)0.0f;
     }
 }

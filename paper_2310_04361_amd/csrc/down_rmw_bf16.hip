@@ -19,7 +19,8 @@
 // token.  The row stride of 260 floats spreads consecutive-token rows over the banks.
 // Operands of the next kDepth tiles are kept in flight while the current one is merged.
 // Weights: the 16x16x32 fragments w2f (also used by the small-token path); H rows as written by
-// the up kernel (16-byte piece 4ks + q of a row = the eight neurons of lane group q, k-step ks).
+// the up kernel (16-byte piece 4ks + q of a row = neurons 8(4ks + q) .. +7 = the k values of lane
+// group q in k-step ks).
 #include "dmoe_internal.h"
 #include "mfma.h"
 

@@ -12,9 +12,9 @@
 // stored as the 1 KiB block  [lane 0..63][8 bf16]  in exactly the register layout of the MFMA,
 // because a 16-byte-per-lane access with a 64-byte or larger lane stride costs a cache-line
 // lookup per lane and that, not bandwidth, bounded the first version of these kernels.
-//   H row (m_pad bf16): 16-byte piece 4ks + q holds the neurons 32ks + 4q + {0..3} and
-//     32ks + 16 + 4q + {0..3} -- the order in which the accumulators of lane (q, .) come out;
-//     the packed down-projection uses the same order.
+//   H row (m_pad bf16): natural neuron order -- the packed up weights place the neurons on the
+//     MFMA rows (neuron_of_slot in mfma.h) so that the accumulators of lane (q, .) for the tile
+//     pair (2ks, 2ks+1) are the eight consecutive neurons of the 16-byte piece 4ks + q.
 //   An expert's H rows start at a multiple of UR rows (its first up-projection work item).
 #include <cmath>
 
@@ -51,7 +51,7 @@ __device__ __forceinline__ float activate_fast(int act, float v) {
 
 // ---- one-time weight packing ------------------------------------------------------------------------
 // (small-token path) w_down[E][m][d] -> w2f[E][d/16][KS][64][8]: lane (q, c) of fragment (e, column tile ct, ks)
-// holds W_down[e][32ks + 16*(s/4) + 4q + s%4][16ct + c], zero for neurons >= m.
+// holds W_down[e][8*(4ks + q) + s][16ct + c] (piece 4ks + q of an H row), zero for neurons >= m.
 __global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __restrict__ w2f,
                                  int E, int m, int d, int KS) {
     const size_t n = (size_t)E * d * KS * 32;
@@ -65,15 +65,16 @@ __global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __re
         const int ct = (int)(f % (d / 16));
         const int e = (int)(f / (d / 16));
         const int q = lane >> 4, c = lane & 15;
-        const int neuron = 32 * ks + 16 * (s >> 2) + 4 * q + (s & 3);
+        const int neuron = 8 * (4 * ks + q) + s;  // piece 4ks + q of the H row
         w2f[i] = neuron < m ? w_down[((size_t)e * m + neuron) * d + 16 * ct + c] : (__bf16)0.0f;
     }
 }
 
 // w[E][m][d] -> wf[E][MT][d/32][64][8]: lane (q, c) of fragment (e, neuron tile mt, k-step) holds
-// w[e][16mt + c][32 kstep + 8q + s], zero rows for neurons >= m.
+// w[e][n(mt, c)][32 kstep + 8q + s], zero rows for neurons >= m; n(mt, c) = neuron_of_slot for the
+// expert matrices, 16mt + c for the router matrices.
 __global__ void pack_up_kernel(const __bf16* __restrict__ w, __bf16* __restrict__ wf, int E, int m,
-                               int d, int MT) {
+                               int d, int MT, int piece_order) {
     const size_t n = (size_t)E * MT * 16 * d;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -85,7 +86,8 @@ __global__ void pack_up_kernel(const __bf16* __restrict__ w, __bf16* __restrict_
         const int mt = (int)(f % MT);
         const int e = (int)(f / MT);
         const int q = lane >> 4, c = lane & 15;
-        const int neuron = 16 * mt + c;
+        // experts: the neuron order that makes H pieces consecutive; router matrices: natural
+        const int neuron = piece_order ? neuron_of_slot(mt, c) : 16 * mt + c;
         wf[i] = neuron < m ? w[((size_t)e * m + neuron) * d + 32 * kstep + 8 * q + s] : (__bf16)0.0f;
     }
 }
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int n = 16 * mt + 4 * q + r;
+                const int n = neuron_of_slot(mt, 4 * q + r);
                 bias[mt][r] = (!GATED && b_up) ? (float)b_up[(size_t)e * m + min(n, m - 1)] : 0.0f;
             }
 
@@ -236,7 +238,7 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     const int mt = 2 * ks + half;
-                    const int n0 = 16 * mt + 4 * q;
+                    const int n0 = neuron_of_slot(mt, 4 * q);  // + r: consecutive
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         float v;
@@ -380,7 +382,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
                             float v;
                             if (GATED) v = activate_fast(act, acc[MT + mt][tt][r]) * acc[mt][tt][r];
                             else v = activate_fast(act, acc[mt][tt][r]);
-                            if (16 * mt + 4 * q + r >= m) v = 0.0f;
+                            if (neuron_of_slot(mt, 4 * q + r) >= m) v = 0.0f;
                             hv[half * 4 + r] = (__bf16)v;
                         }
                     }
@@ -448,18 +450,18 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
                                           L.n_experts, L.expert_size, L.d_model, mp / 32);
     launch_pack_down_bf16(L, pk + P.w2g, s);
     pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_up, (__bf16*)(pk + P.wupf), L.n_experts,
-                                        L.expert_size, L.d_model, mp / 16);
+                                        L.expert_size, L.d_model, mp / 16, 1);
     if (L.gated)
         pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_gate, (__bf16*)(pk + P.wgatef),
-                                            L.n_experts, L.expert_size, L.d_model, mp / 16);
+                                            L.n_experts, L.expert_size, L.d_model, mp / 16, 1);
     // the router matrices use the same fragment format: "one expert" whose rows are the hidden
     // units (r_w1) or the experts (r_w2)
     const int dh = L.router_hidden;
     if (L.r_w1 && L.r_w2 && dh > 0 && dh % 32 == 0 && L.d_model % 32 == 0) {
         pack_up_kernel<<<512, 256, 0, s>>>((const __bf16*)L.r_w1, (__bf16*)(pk + P.r1f), 1, dh,
-                                           L.d_model, dh / 16);
+                                           L.d_model, dh / 16, 0);
         pack_up_kernel<<<512, 256, 0, s>>>((const __bf16*)L.r_w2, (__bf16*)(pk + P.r2f), 1,
-                                           L.n_experts, dh, div_up(L.n_experts, 16));
+                                           L.n_experts, dh, div_up(L.n_experts, 16), 0);
     }
 }
 

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
         *reinterpret_cast<f32x4*>(red + ((w * BR + br) * 64 + lane) * 4) = acc[br];
     __syncthreads();
     if (kq != 0) return;
-    // wavefront (mt, 0): sum the KQ slices; lane (q, c): neurons 16mt + 4q + r of token c
+    // wavefront (mt, 0): sum the KQ slices; lane (q, c): neurons neuron_of_slot(mt, 4q + r) of token c
 #pragma unroll
     for (int br = 0; br < BR; ++br) {
         f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
     bf16x4 hv;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const int n = 16 * mt + 4 * q + r;
+        const int n = neuron_of_slot(mt, 4 * q + r);
         float v;
         if (GATED) {
             v = activate_s(act, acc[BR - 1][r]) * acc[0][r];

@@ -39,6 +39,16 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Neuron order of the hidden activations.  Lane (q, .) of the up-projection's 16-neuron tile mt
+// holds the accumulator rows 4q + r; the packed up weights put the neurons there so that the
+// 16-byte piece p = 4*(mt/2) + q of an H row (rows 4q + r of the tile pair 2*(mt/2), +1) is the
+// eight CONSECUTIVE neurons 8p .. 8p+7: an expert of m neurons fills exactly its first
+// ceil(m / 8) pieces, which lets the down-projection pack the real pieces of consecutive experts
+// densely into its k-steps.
+__host__ __device__ __forceinline__ int neuron_of_slot(int mt, int row) {
+    return 8 * (4 * (mt >> 1) + (row >> 2)) + 4 * (mt & 1) + (row & 3);
+}
+
 __device__ __forceinline__ bf16x8 load8(const __bf16* p) {
     return *reinterpret_cast<const bf16x8*>(p);
 }

@@ -139,6 +139,7 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
 // Down-projection and merge (down_bf16.hip): mask is the token-major selection bitmask that the
 // lists were built from; group_off[g][e] = rows of expert e that belong to tokens before group g.
 bool down_bf16_supported(const dmoe_layer& L);
+bool down_bf16_addressable(const dmoe_layer& L, int T);
 void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s);
 // Two kernels, both launched: offsets[E] (the executed pairs) decides on the device which one
 // works -- at most max_pairs_sparse pairs: the pair-proportional kernel (down_rmw_bf16.hip),

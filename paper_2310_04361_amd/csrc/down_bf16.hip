@@ -53,8 +53,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kDnTokens = 128;  // tokens per workgroup: 4 tiles of 32 = 2 select groups of 64
 constexpr int kDnTiles = 4;
-constexpr int kDnCols = 256;    // columns per workgroup: 4 wavefronts x 64
-constexpr int kDnBuffers = 3;
+constexpr int kDnColStep = 128;  // a workgroup covers CT * 128 columns: 4 wavefronts x CT tiles of 32
 
 // Pieces per expert (padded up to a supported count), experts per stage, k-steps per stage.
 struct DownPacking {
@@ -95,21 +94,44 @@ __global__ void pack_down32_kernel(const __bf16* __restrict__ w_down, __bf16* __
 
 constexpr int const_gcd(int a, int b) { return b == 0 ? a : const_gcd(b, a % b); }
 
-// KSP k-steps per stage of G experts (PG = 2*KSP/G pieces each); R = weight sets in flight;
-// WPS = wavefronts per SIMD the register budget is cut for.
-template <int KSP, int G, int R, int WPS>
+// Buffer descriptor flags of a raw (unstructured) buffer: offsets at or beyond num_records read
+// as zero and move no data.
+constexpr int kRawBuffer = 0x00020000;
+
+constexpr int kDnTrip = 4;  // stages per loop trip = LDS buffers = H register sets
+
+// KSP k-steps per stage of G experts (PG = 2*KSP/G pieces each); R = weight sets in flight
+// (divides 4 KSP); WPS = wavefronts per SIMD the register budget is cut for; CT = column tiles
+// per wavefront (2: the workgroup covers 256 columns; 3: 384 columns, 192 accumulator registers,
+// one workgroup per CU only).
+//
+// Instruction count matters as much as latency here: with one wavefront per SIMD every
+// instruction that is not an MFMA delays the next MFMA by about 4 cycles, and a wait inside a
+// conditional block is computed for the worst path into it.  So the loop has no condition and
+// few instructions: all global loads are buffer loads whose per-lane offsets are loop invariant
+// (the moving part is one scalar offset); a loop trip is 4 stages, so every LDS address and
+// register set is a compile-time constant; a token's mask word is shifted down by one bit per
+// expert and replaced once per 32 experts BETWEEN two runs of the loop, by the word requested a
+// run earlier; the MFMAs of a phase start with the operands that were requested last, so that
+// one wait covers the phase.
+template <int KSP, int G, int R, int WPS, int CT>
 __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     const __bf16* __restrict__ w2g, const __bf16* __restrict__ b_down,
     const int32_t* __restrict__ item_start, const int32_t* __restrict__ group_off,
     const uint32_t* __restrict__ mask32, const int32_t* __restrict__ offsets,
     const __bf16* __restrict__ H, __bf16* __restrict__ y, int T, int d, int E, int NG, int W32,
-    int rows_per_item, int row_bytes, long long max_pairs_sparse) {
+    int rows_per_item, int row_shift, uint32_t w_bytes, uint32_t h_bytes,
+    long long max_pairs_sparse) {
+    static_assert((kDnTrip * KSP) % R == 0 && 32 % (kDnTrip * G) == 0, "loop trip");
     if (offsets[E] <= max_pairs_sparse) return;  // sparse enough for the pair-proportional kernel
     constexpr int PG = 2 * KSP / G;                  // pieces per expert
     constexpr int kImage = kDnTiles * KSP * 1024;    // the B tiles of one stage
-    extern __shared__ __attribute__((aligned(16))) char img[];  // [kDnBuffers][kImage]
+    constexpr int PH = kDnTrip * KSP;                // phases per loop trip
+    constexpr int kTripsPerBatch = 32 / (kDnTrip * G);
+    extern __shared__ __attribute__((aligned(16))) char img[];  // [kDnTrip][kImage]
     // The column slices of one chunk share its H rows: keep them on one XCD (workgroups are dealt
     // round-robin to the 8 XCDs) and next to each other in launch order.
+    constexpr int kDnCols = CT * kDnColStep;
     const int NS = d / kDnCols;
     const int k_in_xcd = blockIdx.x >> 3;
     const int chunk = (k_in_xcd / NS) * 8 + (blockIdx.x & 7), slice = k_in_xcd % NS;
@@ -118,8 +140,8 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane >> 5, c = lane & 31;
-    const int col_w = slice * kDnCols + wave * 64;
-    const int n_stages = (E + G - 1) / G;
+    const int col_w = slice * kDnCols + wave * (32 * CT);
+    const int n_trips = (E + kDnTrip * G - 1) / (kDnTrip * G);
 
     // ---- tile-building role: select group bg of the chunk (lane = token), lane half bh
     const int bg = wave & 1, bh = wave >> 1;
@@ -128,55 +150,46 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     const bool tok_ok = tok_b < T;
     const uint32_t* mrow = mask32 + (size_t)min(tok_b, T - 1) * W32;
     const int32_t* grow = group_off + (size_t)min(g, NG) * E;  // group_off has NG + 1 rows
-    // per batch of 32 experts: this token's mask word, and in lane i the first H row of
-    // (expert 32b + i, group g)
-    // Nothing below sits under a condition that depends on the expert: a load inside a
-    // conditional region makes the compiler's wait-count bookkeeping assume the worst at the
-    // join, and the stage would wait for the loads it has just issued.  Past the last expert the
-    // same code runs on clamped addresses with every token unselected.
+    // Per batch of 32 experts: this token's mask word (shifted down as the experts go by; zero
+    // for a token beyond T and past the last expert: the words hold no bits from E up), and in
+    // lane i the first H row of (expert 32b + i, group g).
     const int n_batches = (E + 31) >> 5;
-    uint32_t mw = 0u, mw_next = 0u;
-    int rowv = 0, is_next = 0, go_next = 0;
+    uint32_t mw, mw_next;
+    int rowv, is_next, go_next;
     auto load_batch = [&](int b, uint32_t& m_out, int& is_out, int& go_out) {
-        m_out = tok_ok ? mrow[b] : 0u;
-        const int ec = min(32 * b + c, E - 1);
+        const int bc = min(b, n_batches - 1);
+        m_out = mrow[bc];  // of a clamped token and batch: masked when it becomes current
+        const int ec = min(32 * bc + c, E - 1);
         is_out = item_start[ec];
         go_out = grow[ec];
     };
-    u32x4 breg[2][KSP];  // H pieces of two stages in flight
-    __amdgpu_buffer_rsrc_t b_rsrc[G];
+    const __amdgpu_buffer_rsrc_t h_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)H, 0, (int)h_bytes, kRawBuffer);
+    u32x4 breg[kDnTrip][KSP];  // H pieces of the stages in flight
     uint32_t b_voff[G];
-#pragma unroll
-    for (int eo = 0; eo < G; ++eo) {
-        b_rsrc[eo] = __builtin_amdgcn_make_buffer_rsrc((void*)H, 0, 0, 0x00020000);
-        b_voff[eo] = 0x80000000u;
-    }
-    auto build_prepare = [&](int e, int eo) {  // called with e = 0, 1, 2, ... in this order
-        if ((e & 31) == 0) {                   // the values fetched 32 experts ago become current
-            if (e > 0) {
-                mw = mw_next;
-                rowv = is_next * rows_per_item + go_next;
-            }
-            load_batch(min((e >> 5) + 1, n_batches - 1), mw_next, is_next, go_next);
-        }
-        const bool sel = ((mw >> (e & 31)) & 1u) != 0u && e < E;
+    int sh_base = 0;  // position in the current batch of the first expert of the next trip
+    // Byte offset of the token's H row of expert `sh` of the batch, or an offset beyond the buffer
+    // (h_bytes is below 2^31) for an unselected token: the load returns zeros for those.
+    auto build_prepare = [&](int sh, int eo) {
+        const bool sel = (mw & 1u) != 0u;
+        mw >>= 1;
         const uint64_t bal = __ballot(sel);
-        const int rank = __builtin_amdgcn_mbcnt_hi(
+        const uint32_t rank = __builtin_amdgcn_mbcnt_hi(
             (uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
-        const int row0 = __builtin_amdgcn_readlane(rowv, e & 31);
-        // at most 64 rows of this expert belong to the group; unselected tokens get an offset
-        // beyond the descriptor's range, for which the load returns zeros
-        b_rsrc[eo] = __builtin_amdgcn_make_buffer_rsrc(
-            (void*)((const char*)H + (size_t)row0 * row_bytes), 0, kGroup * row_bytes, 0x00020000);
-        b_voff[eo] = sel ? (uint32_t)(rank * row_bytes) : 0x80000000u;
+        const uint32_t row0 = (uint32_t)__builtin_amdgcn_readlane(rowv, sh);
+        b_voff[eo] = ((row0 + rank) << row_shift) | (sel ? 0u : 0x80000000u);
     };
+    // piece 2s + bh of the stage: expert (2s + bh) / PG of the stage, piece (2s + bh) % PG of its
+    // row; the piece offset is a per-wavefront scalar
+    uint32_t p_soff[KSP];
+#pragma unroll
+    for (int s = 0; s < KSP; ++s) p_soff[s] = 16u * (uint32_t)((2 * s + bh) % PG);
     auto build_fetch = [&](u32x4 (&br)[KSP]) {
 #pragma unroll
         for (int s = 0; s < KSP; ++s) {
-            const int pi = 2 * s + bh;  // piece of the stage (uniform per wavefront)
-            const int eo = G == 1 ? 0 : pi / PG, p = pi - eo * PG;
-            br[s] = __builtin_amdgcn_raw_buffer_load_b128(
-                eo ? b_rsrc[G - 1] : b_rsrc[0], (eo ? b_voff[G - 1] : b_voff[0]) + 16 * p, 0, 0);
+            const int eo0 = G == 1 ? 0 : (2 * s) / PG, eo1 = G == 1 ? 0 : (2 * s + 1) / PG;
+            const uint32_t v = eo0 == eo1 ? b_voff[eo0] : (bh ? b_voff[eo1] : b_voff[eo0]);
+            br[s] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, v, p_soff[s], 0);
         }
     };
     // lane = token 32h + c of the group: tile 2bg + h of the chunk, operand lane (bh, c)
@@ -187,113 +200,137 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
             *reinterpret_cast<u32x4*>(wdst + buf * kImage + s * 1024) = br[s];
     };
 
-    // ---- multiplying role: 128 tokens x columns col_w .. col_w + 63
-    const __bf16* const wsrc = w2g + ((size_t)(col_w / 32) * KSP * 64 + lane) * 8;
-    const size_t w_stage_stride = (size_t)(d / 32) * KSP * 512;
-    // Work advances in phases: phase p = stage p / KSP, k-step p % KSP = 8 MFMAs (4 token tiles x
-    // 2 column tiles) that need two 1 KiB weight blocks.  R weight sets are in flight, so a block
-    // is requested R - 1 phases before its use whatever the expert size (the weights of a stage
-    // reach all workgroups of an XCD at about the same time, so nearly every request is answered
-    // from beyond L2).  A loop trip is an even number of stages, so that the two register sets
-    // of the H fetch simply alternate.
-    constexpr int PH = R * (2 * KSP) / const_gcd(R, 2 * KSP);  // phases per loop trip
-    auto load_phase = [&](int p, bf16x8 (&a)[2]) {
-        const int st = min(p / KSP, n_stages - 1), ks = p % KSP;
-        const __bf16* src = wsrc + (size_t)st * w_stage_stride + ks * 512;
-        a[0] = load8(src);
-        a[1] = load8(src + KSP * 512);
+    // ---- multiplying role: 128 tokens x columns col_w .. col_w + 32 CT - 1
+    // Work advances in phases: phase p = stage p / KSP, k-step p % KSP = 4 * CT MFMAs (4 token
+    // tiles x CT column tiles) that need CT 1 KiB weight blocks.  R weight sets are in flight, so
+    // a block is requested R - 1 phases before its use whatever the expert size (the weights of a
+    // stage reach all workgroups of an XCD at about the same time, so nearly every request is
+    // answered from beyond L2).  Past the last stage the offsets leave the buffer and the blocks
+    // read as zero.
+    const __amdgpu_buffer_rsrc_t w_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)w2g, 0, (int)w_bytes, kRawBuffer);
+    uint32_t a_voff[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+        a_voff[ct] = (uint32_t)(((col_w / 32 + ct) * KSP * 64 + lane) * 16);
+    const uint32_t w_stage_bytes = (uint32_t)(d / 32) * KSP * 1024;
+    uint32_t a_stage = 0;  // byte offset of the stage the next weight request belongs to
+    // requests the weights of the next phase in order; ks = its k-step (compile-time)
+    auto load_phase = [&](int ks, bf16x8 (&a)[CT]) {
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+            a[ct] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                        w_rsrc, a_voff[ct] + (uint32_t)(ks & 3) * 1024u,
+                        a_stage + (uint32_t)(ks >> 2) * 4096u, 0));
+        if (ks == KSP - 1) a_stage += w_stage_bytes;
     };
-    f32x16 acc[kDnTiles][2];
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float bias = b_down ? (float)b_down[col_w + 32 * ct + 16 * h + i] : 0.0f;
-#pragma unroll
-            for (int j = 0; j < kDnTiles; ++j) acc[j][ct][i] = bias;
-        }
+
+    bf16x8 aw[R][CT];
+    bf16x8 bb[2][kDnTiles];  // B operands of the current phase and of the next one
+    // Start-up: the offsets and fetches of stages 0 .. 3, then the first weight requests (every H
+    // fetch before the first weight request, as in the loop: the wait before an LDS write is
+    // computed for the worse of the two ways into the loop).
+    {
+        int is0, go0;
+        load_batch(0, mw, is0, go0);
+        load_batch(1, mw_next, is_next, go_next);
+        rowv = is0 * rows_per_item + go0;
+        mw = tok_ok ? mw : 0u;
     }
+#pragma unroll
+    for (int i = 0; i < kDnTrip; ++i) {
+#pragma unroll
+        for (int eo = 0; eo < G; ++eo) build_prepare(i * G + eo, eo);
+        build_fetch(breg[i]);
+    }
+    sh_base = (kDnTrip * G) & 31;
+#pragma unroll
+    for (int q = 0; q < R - 1; ++q) load_phase(q % KSP, aw[q]);
+    // every accumulator starts at the output bias: lane (h, c) holds columns 16h .. 16h + 15 of
+    // each column tile (two 16-byte loads per tile, none under a per-element condition)
+    f32x16 acc[kDnTiles][CT];
+    {
+        bf16x8 bias[CT][2];
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) bias[ct][0] = bias[ct][1] = zero8();
+        if (b_down) {
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                bias[ct][0] = load8(b_down + col_w + 32 * ct + 16 * h);
+                bias[ct][1] = load8(b_down + col_w + 32 * ct + 16 * h + 8);
+            }
+        }
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+#pragma unroll
+                for (int j = 0; j < kDnTiles; ++j) acc[j][ct][i] = (float)bias[ct][i >> 3][i & 7];
+    }
+    write_tiles(0, breg[0]);
+    lds_barrier();
     const char* const rsrc_l = img + lane * 16;
     // k-step ks of token tile j of the stage in buffer buf
     auto read_piece = [&](int buf, int ks, int j) {
         return *reinterpret_cast<const bf16x8*>(rsrc_l + buf * kImage + (j * KSP + ks) * 1024);
     };
-    auto next_buf = [](int buf) { return buf == kDnBuffers - 1 ? 0 : buf + 1; };
-    auto prepare_stage = [&](int st) {
-#pragma unroll
-        for (int eo = 0; eo < G; ++eo) build_prepare(st * G + eo, eo);
-    };
-
-    bf16x8 aw[R][2];
-    bf16x8 bb[2][kDnTiles];  // B operands of the current phase and of the next one
-    {
-        int is0, go0;
-        load_batch(0, mw, is0, go0);
-        rowv = is0 * rows_per_item + go0;
-    }
-    // Same issue order as in the loop (H fetch first, then the weight loads): the wait before an
-    // LDS write is computed for the worse of the two ways into the loop, and with the fetch
-    // issued last here it would wait for every load in flight on every trip.
-    prepare_stage(0);
-    build_fetch(breg[0]);
-    write_tiles(0, breg[0]);
-    prepare_stage(1);
-    build_fetch(breg[1]);
-    prepare_stage(2);
-    build_fetch(breg[0]);
-#pragma unroll
-    for (int q = 0; q < R - 1; ++q) load_phase(q, aw[q]);
-    lds_barrier();
 #pragma unroll
     for (int j = 0; j < kDnTiles; ++j) bb[0][j] = read_piece(0, 0, j);
-    int buf = 0;
-    // Per stage: its first phase writes the tiles of the NEXT stage to LDS and issues the fetch
-    // for the one three ahead (the H rows come from beyond L2: fetched only one stage's MFMA
-    // time ahead they were waited for on every stage); the barrier sits in the middle of the
-    // stage's MFMAs.  Every phase first issues its weight loads and the LDS reads of the NEXT
-    // phase's B operands (k-step 0 of the next stage in the last phase: the barrier has passed
-    // by then), then runs its 8 MFMAs on operands requested a phase ago.  So the LDS write, the
-    // barrier and all LDS reads overlap with matrix work of the same wavefront.  A trip past
-    // the last stage multiplies zero tiles.
-    for (int s0 = 0; s0 < n_stages; s0 += PH / KSP) {
+    // Stage i of a trip (buffer i, MFMAs on the tiles of stage st): its first phase writes the
+    // tiles of stage st + 1 to buffer i + 1 (fetched three stages earlier into register set
+    // i + 1) and computes the offsets and issues the fetch of stage st + 4 into set i (written
+    // out one stage ago); the barrier sits in the middle of the stage's MFMAs.  Every phase
+    // requests the weights of the phase R - 1 ahead and reads from LDS the B operands of the NEXT
+    // phase (k-step 0 of the next stage in the last phase: the barrier has passed by then), then
+    // runs its MFMAs on operands requested earlier.  So the LDS write, the barrier and all LDS
+    // reads overlap with matrix work of the same wavefront; the pieces sit between single MFMAs,
+    // pinned by scheduling barriers (left alone the scheduler groups them and the matrix pipe
+    // idles meanwhile).  Four buffers keep a wavefront that runs ahead from overwriting tiles
+    // that a slower one still reads.  A trip past the last stage multiplies zero tiles.
+    int trip = 0, trip_end = min(kTripsPerBatch - 1, n_trips), batch = 1;
+    for (;;) {
+        do {
 #pragma unroll
-        for (int q = 0; q < PH; ++q) {
-            const int st = s0 + q / KSP;
-            const int ks = q % KSP;
-            const int nb = next_buf(buf);
-            const int rbuf = ks < KSP - 1 ? buf : nb, rks = ks < KSP - 1 ? ks + 1 : 0;
-            u32x4 (&br)[KSP] = breg[(q / KSP + 1) & 1];  // tiles of stage st + 1 now, then of st + 3
-            // A wavefront issues in order, and an MFMA keeps the matrix pipe busy for 32 cycles
-            // only: everything else the phase has to do is cut into pieces that sit BETWEEN its
-            // MFMAs, each pinned by a scheduling barrier.  Left alone the scheduler groups the
-            // pieces (the pipe idles meanwhile), sinks the H fetch to the end of the stage
-            // (loads complete in issue order, so the next LDS write would wait for everything)
-            // and issues each LDS read just before its use.
-            auto mf = [&](int j, int ct) {
-                acc[j][ct] = mfma32(aw[q % R][ct], bb[q & 1][j], acc[j][ct]);
+            for (int q = 0; q < PH; ++q) {
+                constexpr int kLast = kDnTiles * CT - 1;
+                const int i = q / KSP, ks = q % KSP, ni = (i + 1) % kDnTrip;
+                const int rbuf = ks < KSP - 1 ? i : ni, rks = ks < KSP - 1 ? ks + 1 : 0;
                 __builtin_amdgcn_sched_barrier(0);
-            };
-            __builtin_amdgcn_sched_barrier(0);
-            if (ks == 0) write_tiles(nb, br);
-            mf(0, 0);
-            if (ks == 0) build_prepare((st + 3) * G, 0);
-            mf(0, 1);
-            if (ks == 0 && G == 2) build_prepare((st + 3) * G + 1, G - 1);
-            mf(1, 0);
-            if (ks == 0) build_fetch(br);
-            load_phase(s0 * KSP + q + R - 1, aw[(q + R - 1) % R]);
-            mf(1, 1);
-            bb[(q + 1) & 1][0] = read_piece(rbuf, rks, 0);
-            bb[(q + 1) & 1][1] = read_piece(rbuf, rks, 1);
-            mf(2, 0);
-            bb[(q + 1) & 1][2] = read_piece(rbuf, rks, 2);
-            bb[(q + 1) & 1][3] = read_piece(rbuf, rks, 3);
-            mf(2, 1);
-            mf(3, 0);
-            mf(3, 1);
-            if (ks == (KSP >> 1) - 1) lds_barrier();  // every wavefront has written its part of st + 1
-            if (ks == KSP - 1) buf = nb;
-        }
+                if (ks == 0) write_tiles(ni, breg[ni]);
+#pragma unroll
+                for (int n = 0; n <= kLast; ++n) {
+                    // the operands requested last come first: their wait covers the whole phase
+                    const int j = kDnTiles - 1 - n / CT, ct = CT - 1 - n % CT;
+                    acc[j][ct] = mfma32(aw[q % R][ct], bb[q & 1][j], acc[j][ct]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (n == 0 && ks == 0) build_prepare(sh_base + i * G, 0);
+                    if (n == 1 && ks == 0 && G == 2) build_prepare(sh_base + i * G + 1, G - 1);
+                    if (n == 2) {
+                        if (ks == 0) build_fetch(breg[i]);
+                        load_phase((q + R - 1) % KSP, aw[(q + R - 1) % R]);
+                    }
+                    if (n == 3) {
+                        bb[(q + 1) & 1][0] = read_piece(rbuf, rks, 0);
+                        bb[(q + 1) & 1][1] = read_piece(rbuf, rks, 1);
+                    }
+                    if (n == 4) {
+                        bb[(q + 1) & 1][2] = read_piece(rbuf, rks, 2);
+                        bb[(q + 1) & 1][3] = read_piece(rbuf, rks, 3);
+                    }
+                }
+                if (ks == (KSP >> 1) - 1) lds_barrier();  // every wavefront has written its part of st + 1
+            }
+            sh_base += kDnTrip * G;
+        } while (++trip < trip_end);
+        if (trip >= n_trips) break;
+        // the next trip computes the offsets of the first experts of the next batch: its mask
+        // word and first rows were requested a whole run of the loop ago
+        mw = (tok_ok && batch < n_batches) ? mw_next : 0u;
+        rowv = is_next * rows_per_item + go_next;
+        ++batch;
+        load_batch(batch, mw_next, is_next, go_next);
+        sh_base = 0;
+        trip_end = min(trip + kTripsPerBatch, n_trips);
     }
 
     // lane (h, c) of tile (j, ct): columns col_w + 32ct + 16h .. +15 of token t_base + 32j + c
@@ -302,7 +339,7 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
         const int t = t_base + 32 * j + c;
         if (t < T) {
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
+            for (int ct = 0; ct < CT; ++ct) {
                 bf16x8 o0, o1;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -317,31 +354,50 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     }
 }
 
-template <int KSP, int G, int R, int WPS>
+// Bytes of the packed down weights and of the H rows the kernel may address: both are reached
+// through 32-bit buffer offsets.
+size_t down_w_bytes(const dmoe_layer& L) {
+    const DownPacking dp = down_packing(L.expert_size);
+    return (size_t)div_up(L.n_experts, dp.G) * (L.d_model / 32) * dp.KSP * 1024;
+}
+size_t down_h_bytes(const dmoe_layer& L, int T) {
+    return (size_t)h_fragments(L, T) * 16 * 2 * m_pad_of(L.expert_size);
+}
+
+template <int KSP, int G, int R, int WPS, int CT>
 void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* item_start,
                    const int32_t* group_off, const uint64_t* mask, const int32_t* offsets,
                    const void* H, void* y, long long max_pairs_sparse, hipStream_t s) {
-    const int NG = div_up(T, kGroup), NC = div_up(T, kDnTokens), NS = L.d_model / kDnCols;
-    constexpr size_t lds = (size_t)kDnBuffers * kDnTiles * KSP * 1024;
+    const int NG = div_up(T, kGroup), NC = div_up(T, kDnTokens), NS = L.d_model / (CT * kDnColStep);
+    constexpr size_t lds = (size_t)kDnTrip * kDnTiles * KSP * 1024;
     static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KSP, G, R, WPS>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KSP, G, R, WPS, CT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    down_bf16_kernel<KSP, G, R, WPS><<<round_up(NC, 8) * NS, 256, lds, s>>>(
+    const int row_bytes = 2 * m_pad_of(L.expert_size);
+    int row_shift = 0;
+    while ((1 << row_shift) < row_bytes) ++row_shift;
+    down_bf16_kernel<KSP, G, R, WPS, CT><<<round_up(NC, 8) * NS, 256, lds, s>>>(
         (const __bf16*)(pk + P.w2g), (const __bf16*)L.b_down, item_start, group_off,
         reinterpret_cast<const uint32_t*>(mask), offsets, (const __bf16*)H, (__bf16*)y, T,
-        L.d_model, L.n_experts, NG, 2 * div_up(L.n_experts, 64), up_rows_bf16(L),
-        2 * m_pad_of(L.expert_size), max_pairs_sparse);
+        L.d_model, L.n_experts, NG, 2 * div_up(L.n_experts, 64), up_rows_bf16(L), row_shift,
+        (uint32_t)down_w_bytes(L), (uint32_t)down_h_bytes(L, T), max_pairs_sparse);
 }
 
 }  // namespace
 
 bool down_bf16_supported(const dmoe_layer& L) {
     const int mp = m_pad_of(L.expert_size);
-    return (mp == 32 || mp == 64 || mp == 128) && L.d_model % kDnCols == 0;
+    return (mp == 32 || mp == 64 || mp == 128) && L.d_model % (2 * kDnColStep) == 0;
+}
+
+// The matrix-core kernel reaches the packed weights and H through 32-bit buffer offsets, and
+// marks unselected tokens with offsets from 2^31 up.
+bool down_bf16_addressable(const dmoe_layer& L, int T) {
+    return down_w_bytes(L) < (1ull << 32) && down_h_bytes(L, T) < (1ull << 31);
 }
 
 void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s) {
@@ -356,23 +412,42 @@ void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
     LaunchTimer tm(kSlotDown, s);
     const PackedLayout P = packed_layout(L);
     const DownPacking dp = down_packing(L.expert_size);
+    // Shape of a workgroup: 128 tokens x 256 columns (one or two workgroups per CU), or 128 tokens
+    // x 384 columns where that divides d (one per CU).  The wide shape is taken where it lets every
+    // CU run exactly one workgroup while the narrow one would give some CUs two (16384 tokens,
+    // d = 768: 256 workgroups of 12 tiles against 384 of 8 on 256 CUs).
+    const int NC = div_up(T, kDnTokens);
+    const int wg2 = NC * (L.d_model / (2 * kDnColStep));
+    const bool can3 = L.d_model % (3 * kDnColStep) == 0;
+    const int wg3 = can3 ? NC * (L.d_model / (3 * kDnColStep)) : 0;
+    const bool wide = can3 && wg3 <= 256 && wg2 > 256;
     // at most one workgroup per CU: a wavefront may use the whole register file of its SIMD, which
     // buys a deeper ring of weight sets
-    const bool one_per_cu = div_up(T, kDnTokens) * (L.d_model / kDnCols) <= 256;
-#define DMOE_DOWN(KSP_, G_, R_, WPS_) \
-    launch_down_t<KSP_, G_, R_, WPS_>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s)
-#define DMOE_DOWN_BY_GRID(KSP_, G_, R2_)            \
-    do {                                            \
-        if (one_per_cu) DMOE_DOWN(KSP_, G_, 16, 1); \
-        else DMOE_DOWN(KSP_, G_, R2_, 2);           \
+    const bool one_per_cu = wg2 <= 256;
+#define DMOE_DOWN(KSP_, G_, R_, WPS_, CT_) \
+    launch_down_t<KSP_, G_, R_, WPS_, CT_>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s)
+    // Weight sets in flight per shape: wide / one narrow workgroup per CU / two per CU (R divides
+    // 4 KSP).  From 6 k-steps per stage up the four LDS buffers leave room for one workgroup per
+    // CU only.
+#define DMOE_DOWN_BY_GRID(KSP_, G_, RW_, R1_, R2_)              \
+    do {                                                        \
+        if (wide) DMOE_DOWN(KSP_, G_, RW_, 1, 3);               \
+        else if (one_per_cu) DMOE_DOWN(KSP_, G_, R1_, 1, 2);     \
+        else DMOE_DOWN(KSP_, G_, R2_, 2, 2);                    \
     } while (0)
-    if (dp.KSP == 2 && dp.G == 2) DMOE_DOWN_BY_GRID(2, 2, 8);
-    else if (dp.KSP == 2) DMOE_DOWN_BY_GRID(2, 1, 8);
-    else if (dp.KSP == 3 && dp.G == 2) DMOE_DOWN_BY_GRID(3, 2, 4);
-    else if (dp.KSP == 3) DMOE_DOWN_BY_GRID(3, 1, 4);
-    else if (dp.KSP == 4) DMOE_DOWN_BY_GRID(4, 1, 4);
-    else if (dp.KSP == 6) DMOE_DOWN_BY_GRID(6, 1, 4);
-    else DMOE_DOWN(8, 1, 8, 1);
+#define DMOE_DOWN_ONE_PER_CU(KSP_, G_, RW_, R1_)  \
+    do {                                          \
+        if (wide) DMOE_DOWN(KSP_, G_, RW_, 1, 3); \
+        else DMOE_DOWN(KSP_, G_, R1_, 1, 2);      \
+    } while (0)
+    if (dp.KSP == 2 && dp.G == 2) DMOE_DOWN_BY_GRID(2, 2, 8, 8, 4);
+    else if (dp.KSP == 2) DMOE_DOWN_BY_GRID(2, 1, 8, 8, 4);
+    else if (dp.KSP == 3 && dp.G == 2) DMOE_DOWN_BY_GRID(3, 2, 12, 12, 4);
+    else if (dp.KSP == 3) DMOE_DOWN_BY_GRID(3, 1, 12, 12, 4);
+    else if (dp.KSP == 4) DMOE_DOWN_BY_GRID(4, 1, 8, 16, 4);
+    else if (dp.KSP == 6) DMOE_DOWN_ONE_PER_CU(6, 1, 8, 12);
+    else DMOE_DOWN_ONE_PER_CU(8, 1, 4, 8);
+#undef DMOE_DOWN_ONE_PER_CU
 #undef DMOE_DOWN_BY_GRID
 #undef DMOE_DOWN
 }

@@ -232,8 +232,10 @@ void launch_down_rmw_t(const dmoe_layer& L, const PackedLayout& P, int T, const 
 }  // namespace
 
 // Density (executed pairs / (T * E)) up to which the pair-proportional kernel is the faster one:
-// measured crossovers, about 0.05 for 32-neuron rows of H and 0.08 for wider ones.
+// measured crossovers, about 0.05 for 32-neuron rows of H and 0.08 for wider ones.  Sizes that
+// the matrix-core kernel cannot address all go to this one.
 long long down_max_pairs_sparse(const dmoe_layer& L, int T) {
+    if (!down_bf16_addressable(L, T)) return 0x7fffffffffffffffLL;
     const double dens = m_pad_of(L.expert_size) <= 32 ? 0.05 : 0.08;
     return (long long)(dens * (double)T * (double)L.n_experts);
 }

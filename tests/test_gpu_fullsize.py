@@ -20,10 +20,15 @@ def B():
 
 @pytest.mark.parametrize("name,tau,n_sample", [("cfg2", 0.5, 256), ("cfg2", 0.9, 256),
                                                ("cfg3", 0.5, 192), ("cfg4", 0.3, 48),
-                                               ("cfg4", 0.6, 64)])
+                                               ("cfg4", 0.6, 64),
+                                               # ragged last chunk in the token range where the
+                                               # down-projection takes its 384-column shape
+                                               ("cfg2:11000", 0.3, 128)])
 def test_full_size_sampled(B, oracle, name, tau, n_sample):
     import torch
-    cfg = wl.CONFIGS[name]
+    cfg = wl.CONFIGS[name.split(":")[0]]
+    if ":" in name:
+        cfg = wl.with_tokens(cfg, int(name.split(":")[1]))
     print(f"full size {name} T={cfg.T} tau={tau}", flush=True)
     layer, x = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
     L = B.Layer(layer, cfg.dtype)

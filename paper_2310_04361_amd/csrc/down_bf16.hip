@@ -184,20 +184,23 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     uint32_t p_soff[KSP];
 #pragma unroll
     for (int s = 0; s < KSP; ++s) p_soff[s] = 16u * (uint32_t)((2 * s + bh) % PG);
+    auto fetch_piece = [&](int s, u32x4 (&br)[KSP]) {
+        const int eo0 = G == 1 ? 0 : (2 * s) / PG, eo1 = G == 1 ? 0 : (2 * s + 1) / PG;
+        const uint32_t v = eo0 == eo1 ? b_voff[eo0] : (bh ? b_voff[eo1] : b_voff[eo0]);
+        br[s] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, v, p_soff[s], 0);
+    };
     auto build_fetch = [&](u32x4 (&br)[KSP]) {
 #pragma unroll
-        for (int s = 0; s < KSP; ++s) {
-            const int eo0 = G == 1 ? 0 : (2 * s) / PG, eo1 = G == 1 ? 0 : (2 * s + 1) / PG;
-            const uint32_t v = eo0 == eo1 ? b_voff[eo0] : (bh ? b_voff[eo1] : b_voff[eo0]);
-            br[s] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, v, p_soff[s], 0);
-        }
+        for (int s = 0; s < KSP; ++s) fetch_piece(s, br);
     };
     // lane = token 32h + c of the group: tile 2bg + h of the chunk, operand lane (bh, c)
     char* const wdst = img + (((2 * bg + h) * KSP) * 64 + 32 * bh + c) * 16;
+    auto write_piece = [&](int buf, int s, const u32x4 (&br)[KSP]) {
+        *reinterpret_cast<u32x4*>(wdst + buf * kImage + s * 1024) = br[s];
+    };
     auto write_tiles = [&](int buf, const u32x4 (&br)[KSP]) {
 #pragma unroll
-        for (int s = 0; s < KSP; ++s)
-            *reinterpret_cast<u32x4*>(wdst + buf * kImage + s * 1024) = br[s];
+        for (int s = 0; s < KSP; ++s) write_piece(buf, s, br);
     };
 
     // ---- multiplying role: 128 tokens x columns col_w .. col_w + 32 CT - 1
@@ -215,14 +218,17 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
         a_voff[ct] = (uint32_t)(((col_w / 32 + ct) * KSP * 64 + lane) * 16);
     const uint32_t w_stage_bytes = (uint32_t)(d / 32) * KSP * 1024;
     uint32_t a_stage = 0;  // byte offset of the stage the next weight request belongs to
-    // requests the weights of the next phase in order; ks = its k-step (compile-time)
+    // requests the weights of the next phase in order, column tile by column tile; ks = its
+    // k-step (compile-time)
+    auto load_block = [&](int ks, int ct, bf16x8 (&a)[CT]) {
+        a[ct] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                    w_rsrc, a_voff[ct] + (uint32_t)(ks & 3) * 1024u,
+                    a_stage + (uint32_t)(ks >> 2) * 4096u, 0));
+        if (ct == CT - 1 && ks == KSP - 1) a_stage += w_stage_bytes;
+    };
     auto load_phase = [&](int ks, bf16x8 (&a)[CT]) {
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct)
-            a[ct] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
-                        w_rsrc, a_voff[ct] + (uint32_t)(ks & 3) * 1024u,
-                        a_stage + (uint32_t)(ks >> 2) * 4096u, 0));
-        if (ks == KSP - 1) a_stage += w_stage_bytes;
+        for (int ct = 0; ct < CT; ++ct) load_block(ks, ct, a);
     };
 
     bf16x8 aw[R][CT];
@@ -295,25 +301,33 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
                 constexpr int kLast = kDnTiles * CT - 1;
                 const int i = q / KSP, ks = q % KSP, ni = (i + 1) % kDnTrip;
                 const int rbuf = ks < KSP - 1 ? i : ni, rks = ks < KSP - 1 ? ks + 1 : 0;
+                // A memory instruction takes the wavefront several cycles to issue: at most one
+                // global load (and two LDS operations) sits between two MFMAs, so that the
+                // matrix pipe hides it.
                 __builtin_amdgcn_sched_barrier(0);
-                if (ks == 0) write_tiles(ni, breg[ni]);
+                if (ks == 0) write_piece(ni, 0, breg[ni]);
 #pragma unroll
                 for (int n = 0; n <= kLast; ++n) {
                     // the operands requested last come first: their wait covers the whole phase
                     const int j = kDnTiles - 1 - n / CT, ct = CT - 1 - n % CT;
                     acc[j][ct] = mfma32(aw[q % R][ct], bb[q & 1][j], acc[j][ct]);
                     __builtin_amdgcn_sched_barrier(0);
-                    if (n == 0 && ks == 0) build_prepare(sh_base + i * G, 0);
-                    if (n == 1 && ks == 0 && G == 2) build_prepare(sh_base + i * G + 1, G - 1);
-                    if (n == 2) {
-                        if (ks == 0) build_fetch(breg[i]);
-                        load_phase((q + R - 1) % KSP, aw[(q + R - 1) % R]);
+                    if (ks == 0) {
+                        if (n == 0) build_prepare(sh_base + i * G, 0);
+                        if (n == 1 && G == 2) build_prepare(sh_base + i * G + 1, G - 1);
+#pragma unroll
+                        for (int s = 1; s < KSP; ++s)
+                            if (n == (s - 1) % 2) write_piece(ni, s, breg[ni]);
+#pragma unroll
+                        for (int s = 0; s < KSP; ++s)
+                            if (n == (2 + CT + s < kLast ? 2 + CT + s : kLast)) fetch_piece(s, breg[i]);
                     }
-                    if (n == 3) {
+                    if (n >= 2 && n < 2 + CT) load_block((q + R - 1) % KSP, n - 2, aw[(q + R - 1) % R]);
+                    if (n == 2) {
                         bb[(q + 1) & 1][0] = read_piece(rbuf, rks, 0);
                         bb[(q + 1) & 1][1] = read_piece(rbuf, rks, 1);
                     }
-                    if (n == 4) {
+                    if (n == 3) {
                         bb[(q + 1) & 1][2] = read_piece(rbuf, rks, 2);
                         bb[(q + 1) & 1][3] = read_piece(rbuf, rks, 3);
                     }

@@ -60,7 +60,7 @@ struct DownPacking {
     int PG, G, KSP;
 };
 DownPacking down_packing(int m) {
-    static const int kCounts[] = {2, 3, 4, 6, 8, 12, 16};
+    static const int kCounts[] = {2, 3, 4, 6, 8, 16};  // H rows are 32, 64 or 128 neurons wide
     int pg = div_up(m, 8);
     for (int v : kCounts)
         if (pg <= v) {
@@ -441,8 +441,8 @@ void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
 #define DMOE_DOWN(KSP_, G_, R_, WPS_, CT_) \
     launch_down_t<KSP_, G_, R_, WPS_, CT_>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s)
     // Weight sets in flight per shape: wide / one narrow workgroup per CU / two per CU (R divides
-    // 4 KSP).  From 6 k-steps per stage up the four LDS buffers leave room for one workgroup per
-    // CU only.
+    // 4 KSP).  With 8 k-steps per stage the four LDS buffers (128 KiB) leave room for one
+    // workgroup per CU only.
 #define DMOE_DOWN_BY_GRID(KSP_, G_, RW_, R1_, R2_)              \
     do {                                                        \
         if (wide) DMOE_DOWN(KSP_, G_, RW_, 1, 3);               \
@@ -459,7 +459,6 @@ void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
     else if (dp.KSP == 3 && dp.G == 2) DMOE_DOWN_BY_GRID(3, 2, 12, 12, 4);
     else if (dp.KSP == 3) DMOE_DOWN_BY_GRID(3, 1, 12, 12, 4);
     else if (dp.KSP == 4) DMOE_DOWN_BY_GRID(4, 1, 8, 16, 4);
-    else if (dp.KSP == 6) DMOE_DOWN_ONE_PER_CU(6, 1, 8, 12);
     else DMOE_DOWN_ONE_PER_CU(8, 1, 4, 8);
 #undef DMOE_DOWN_ONE_PER_CU
 #undef DMOE_DOWN_BY_GRID

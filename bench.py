@@ -163,6 +163,67 @@ class Workload:
                 f"{'gated-' if cfg.gated else ''}{cfg.act} tau={tau}")
 
 
+def encoder_block_timing(tau_arg=0.5, heads=12):
+    """ViT-B-shaped pre-norm encoder block on the 256x197-token tensor of the paper's latency
+    experiment: x + Attn(LN(x)), then + FFN(LN(.)).  Everything but the FFN is vendor code (torch
+    LayerNorm, GEMMs, scaled-dot-product attention) and only serves as the fixed part of the
+    block; the FFN is either the dense vendor-GEMM FFN or dmoe_forward on the ViT-shaped layer
+    (cfg3).  The FFN input is the cfg3 tensor itself, so that the density is the one reported for
+    cfg3; the two parts are timed in sequence on one stream but their data are not chained."""
+    import torch
+    import torch.nn.functional as F
+    from paper_2310_04361_amd import binding as B
+    w = Workload("cfg3")
+    cfg, L = w.cfg, w.layers[0]
+    tau = float(np.float32(tau_arg))
+    Bt, S, d = 256, 197, cfg.d
+    g = torch.Generator(device="cuda").manual_seed(0)
+    wqkv = (torch.randn(3 * d, d, device="cuda", generator=g) / d ** 0.5).to(torch.bfloat16)
+    wo = (torch.randn(d, d, device="cuda", generator=g) / d ** 0.5).to(torch.bfloat16)
+    ln_w = torch.ones(d, device="cuda", dtype=torch.bfloat16)
+    ln_b = torch.zeros(d, device="cuda", dtype=torch.bfloat16)
+    W_up, W_dn = L.t["w_up"].reshape(cfg.H, d), L.t["w_down"].reshape(cfg.H, d)
+
+    def attention_part(i):
+        x = w.xs[i % N_ROTATE]
+        hdn = F.layer_norm(x, (d,), ln_w, ln_b)
+        qkv = (hdn @ wqkv.T).view(Bt, S, 3, heads, d // heads).permute(2, 0, 3, 1, 4)
+        a = F.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2])
+        a = a.transpose(1, 2).reshape(Bt * S, d) @ wo.T
+        y1 = x + a
+        return y1, F.layer_norm(y1, (d,), ln_w, ln_b)
+
+    def dense_ffn(i):
+        x = w.xs[i % N_ROTATE]
+        hdn = F.gelu(x @ W_up.T + L.t["b_up"].reshape(-1))
+        return hdn @ W_dn + L.t["b_down"]
+
+    def block_dense(i):
+        y1, _ = attention_part(i)
+        return y1 + dense_ffn(i)
+
+    def block_dmoe(i):
+        y1, _ = attention_part(i)
+        B.dmoe_forward(L, w.xs[i % N_ROTATE], tau, y=w.ys[i % N_ROTATE])
+        return y1 + w.ys[i % N_ROTATE]
+
+    res = {}
+    for name, fn in (("attention_part_ms", attention_part), ("dense_ffn_ms", dense_ffn),
+                     ("dmoe_ffn_ms", lambda i: w.step(i, tau)),
+                     ("block_dense_ms", block_dense), ("block_dmoe_ms", block_dmoe)):
+        for i in range(3):
+            fn(i)
+        res[name] = round(_time_ms(fn, 20), 4)
+    res["ffn_speedup"] = round(res["dense_ffn_ms"] / res["dmoe_ffn_ms"], 3)
+    res["block_speedup"] = round(res["block_dense_ms"] / res["block_dmoe_ms"], 3)
+    res["workload"] = f"ViT-B-shaped block, {Bt}x{S} tokens, d={d}, {heads} heads; FFN = {w.describe(tau_arg)}"
+    res["note"] = ("LayerNorm, projections and attention are vendor (torch) kernels; only the FFN "
+                   "differs between the two block timings")
+    del w
+    torch.cuda.empty_cache()
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -181,6 +242,10 @@ def main() -> int:
     ap.add_argument("--paper-sweep", action="store_true",
                     help="also time dmoe_expert_ffn on the paper's benchmark shape (24 experts x 128, "
                          "d=768, 256x197 tokens) under Bernoulli(p) decisions, p = 0 .. 1 (Sec. 4.4)")
+    ap.add_argument("--block", action="store_true",
+                    help="also time a ViT-B-shaped encoder block (LayerNorm, 12-head attention, "
+                         "residuals, FFN) on 256x197 tokens with the dense FFN and with the "
+                         "dynamic-k layer in its place (Sec. 4.4: what survives end to end)")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense-FFN comparisons (keeps a profile to the timed workload)")
     args = ap.parse_args()
@@ -295,6 +360,9 @@ def main() -> int:
                                               "dense_vendor_gemm_ms": round(pd, 4) if pd else None,
                                               "rows": rows}
         del pw
+
+    if args.block:
+        out["encoder_block"] = encoder_block_timing()
 
     if not args.no_others:
         del w

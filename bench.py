@@ -403,6 +403,29 @@ def main() -> int:
                 entry["ms_per_step_graph_replay"] = round(
                     _time_ms(lambda i: graphs[i % len(graphs)].replay(), steps), 5)
                 del graphs
+                if name == "cfg5b":
+                    # the query / key / value modules of one attention layer (Sec. 3.5): three
+                    # layers of this shape on one input, one launch per stage for the group
+                    qkv = wo.layers[:3]
+                    ys3 = [torch.empty_like(wo.ys[0]) for _ in range(3)]
+                    taus3 = [t32] * 3
+                    for i in range(5):
+                        B.dmoe_forward_group(qkv, wo.xs[i % N_ROTATE], taus3, ys=ys3)
+                    grp = _time_ms(lambda i: B.dmoe_forward_group(qkv, wo.xs[i % N_ROTATE], taus3, ys=ys3), steps)
+
+                    def three(i):
+                        for li in range(3):
+                            B.dmoe_forward(qkv[li], wo.xs[i % N_ROTATE], t32, y=ys3[li])
+                    sep = _time_ms(three, steps)
+                    gph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(gph):
+                        B.dmoe_forward_group(qkv, wo.xs[0], taus3, ys=ys3)
+                    gph.replay()
+                    rep = _time_ms(lambda i: gph.replay(), steps)
+                    entry["qkv_group"] = {"layers": 3, "ms_group_call": round(grp, 5),
+                                          "ms_three_single_calls": round(sep, 5),
+                                          "ms_group_graph_replay": round(rep, 5)}
+                    del gph
             others.append(entry)
         out["other_workloads"] = others
     print(json.dumps(out))

@@ -168,6 +168,32 @@ int32_t dmoe_forward_topk(const dmoe_layer *layer, const void *x, int32_t n_toke
                           int32_t *token_lists_out, void *workspace, size_t workspace_bytes,
                           void *stream);
 
+/* ---- several converted layers with one input (the attention projections, Sec. 3.5) ------------- */
+
+/*
+ * Sec. 3.5 replaces the query, key, value and output projections of an attention layer by small
+ * MLPs that are then converted like an FFN, so a Transformer block holds four more dynamic-k
+ * layers; Q, K and V read the same input.  dmoe_forward_group runs 1 to 4 layers of ONE shape
+ * (d_model, n_experts, expert_size, router_hidden, gated, act, dtype all equal; weights, biases and
+ * tau per layer) on the same x and writes layer i's output to host_ys[i].  Up to 16 tokens (bf16
+ * layers) every stage -- router, gate, up-projection, down-projection, merge -- is ONE launch for
+ * the whole group, which is what counts at that size; for more tokens the layers run one after
+ * the other exactly as dmoe_forward would run them.  Results are those of dmoe_forward, bit for
+ * bit.
+ *   layers     host array of n_layers pointers to host dmoe_layer structs
+ *   host_taus  host array of n_layers thresholds, each in [0, 1]
+ *   host_ys    host array of n_layers DEVICE pointers, y_i[T][d] each, distinct
+ *   workspace  dmoe_group_workspace_bytes() large (the sum of the layers' dmoe_workspace_bytes),
+ *              256-byte aligned
+ * DMOE_ERR_SHAPE for n_layers outside 1..4, DMOE_ERR_UNSUPPORTED for layers of different shape;
+ * otherwise the errors, ownership and asynchrony of dmoe_forward.
+ */
+int32_t dmoe_group_workspace_bytes(const dmoe_layer *const *layers, int32_t n_layers,
+                                   int32_t n_tokens, size_t *out_bytes);
+int32_t dmoe_forward_group(const dmoe_layer *const *layers, int32_t n_layers, const void *x,
+                           int32_t n_tokens, const float *host_taus, void *const *host_ys,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
 
 /*

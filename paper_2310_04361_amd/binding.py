@@ -24,7 +24,8 @@ DTYPE_CODES = {"f32": DMOE_F32, "bf16": DMOE_BF16}
 EXPORTS = (
     "dmoe_version", "dmoe_last_error", "dmoe_workspace_bytes", "dmoe_select_workspace_bytes",
     "dmoe_packed_bytes", "dmoe_pack_weights", "dmoe_router", "dmoe_select", "dmoe_expert_ffn",
-    "dmoe_forward", "dmoe_select_topk", "dmoe_forward_topk", "dmoe_timing_enable", "dmoe_timing_reset", "dmoe_timing_slots",
+    "dmoe_forward", "dmoe_select_topk", "dmoe_forward_topk", "dmoe_group_workspace_bytes",
+    "dmoe_forward_group", "dmoe_timing_enable", "dmoe_timing_reset", "dmoe_timing_slots",
     "dmoe_timing_read",
 )
 
@@ -75,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.dmoe_forward.argtypes = [LP, V, I, F, V, V, V, V, V, V, SZ, V]
         L.dmoe_select_topk.argtypes = [V, I, I, I, V, V, V, V, V, V, SZ, V]
         L.dmoe_forward_topk.argtypes = [LP, V, I, I, V, V, V, V, V, V, SZ, V]
+        L.dmoe_group_workspace_bytes.argtypes = [P(LP), I, I, P(SZ)]
+        L.dmoe_forward_group.argtypes = [P(LP), I, V, I, P(F), P(V), V, SZ, V]
         L.dmoe_timing_enable.argtypes = [I]
         L.dmoe_timing_read.argtypes = [I, P(ctypes.c_char_p), P(ctypes.c_int64), P(ctypes.c_double)]
         for name in EXPORTS:
@@ -242,6 +245,32 @@ def dmoe_forward(layer: Layer, x, tau: float, want_scores=False, want_mask=False
     else:
         check(lib().dmoe_forward_topk(layer.ref(), x.data_ptr(), T, int(top_k), *tail))
     return y, ex
+
+
+_group_ws = {}
+
+
+def dmoe_forward_group(layers, x, taus, ys=None):
+    """1 to 4 layers of one shape on the same input (the attention projections of Sec. 3.5).
+    Returns the list of outputs."""
+    import torch
+    n, T = len(layers), x.shape[0]
+    if ys is None:
+        ys = [torch.empty((T, L.d), dtype=_torch_dtype(L.dtype), device=x.device) for L in layers]
+    LP = ctypes.POINTER(DmoeLayerStruct)
+    refs = (LP * n)(*[ctypes.pointer(L.c) for L in layers])
+    need = ctypes.c_size_t(0)
+    check(lib().dmoe_group_workspace_bytes(refs, n, T, ctypes.byref(need)))
+    key = (x.device, max(need.value, 256))
+    ws = _group_ws.get(key)
+    if ws is None:
+        _group_ws.clear()
+        ws = _group_ws[key] = torch.empty(key[1], dtype=torch.uint8, device=x.device)
+    tau_arr = (ctypes.c_float * n)(*[float(t) for t in taus])
+    y_arr = (ctypes.c_void_p * n)(*[y.data_ptr() for y in ys])
+    check(lib().dmoe_forward_group(refs, n, x.data_ptr(), T, tau_arr, y_arr, ws.data_ptr(),
+                                   ws.numel(), _stream()))
+    return ys
 
 
 def dmoe_forward_topk(layer: Layer, x, k: int, **kw):

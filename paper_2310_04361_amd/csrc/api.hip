@@ -170,6 +170,33 @@ bool use_small_path(const dmoe_layer& L, int T) {
     return L.dtype == DMOE_BF16 && T <= kSmallTokens && small_bf16_supported(L);
 }
 
+// Pointers of one layer for the small-token kernels (its workspace carved as in layer_ws).
+SmallMod small_mod(const dmoe_layer& L, char* ws, const LayerWs& w, float* scores, uint64_t* mask,
+                   void* y, float tau) {
+    const PackedLayout P = packed_layout(L);
+    const char* pk = static_cast<const char*>(L.packed);
+    SmallMod M{};
+    M.r1f = (const __bf16*)(pk + P.r1f);
+    M.r_b1 = (const __bf16*)L.r_b1;
+    M.r2f = (const __bf16*)(pk + P.r2f);
+    M.r_b2 = (const __bf16*)L.r_b2;
+    M.wupf = (const __bf16*)(pk + P.wupf);
+    M.wgatef = (const __bf16*)(pk + P.wgatef);
+    M.b_up = (const __bf16*)L.b_up;
+    M.w2f = (const __bf16*)(pk + P.w2f);
+    M.b_down = (const __bf16*)L.b_down;
+    M.hid = (__bf16*)(ws + w.hid);
+    M.Hs = (__bf16*)(ws + w.H);
+    M.y = (__bf16*)y;
+    M.scores = scores;
+    M.partial = reinterpret_cast<float*>(ws + w.partial);
+    M.mask = mask;
+    M.colmask = reinterpret_cast<uint64_t*>(ws + w.colmask);
+    M.group_cnt = reinterpret_cast<int32_t*>(ws + w.group_off);
+    M.tau = tau;
+    return M;
+}
+
 // Experts from mask bits whose group counts are already in group_off (both in the workspace).
 int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const LayerWs& w,
                 const uint64_t* mask, int32_t* offsets_out, int32_t* lists_out, void* y,
@@ -189,8 +216,9 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
         if (offsets_out)
             launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
                                  lists_out, nullptr, 1, nullptr, nullptr, s);
-        launch_small_bf16(L, x, T, reinterpret_cast<const uint64_t*>(ws + w.colmask), ws + w.H,
-                          reinterpret_cast<float*>(ws + w.partial), y, s);
+        SmallGroup G{};
+        G.m[0] = small_mod(L, ws, w, nullptr, nullptr, y, 0.0f);
+        launch_small_bf16(L, G, 1, x, T, s);
     } else {
         int32_t* witem = reinterpret_cast<int32_t*>(ws + w.witem);
         int32_t* wfirst = reinterpret_cast<int32_t*>(ws + w.wfirst);
@@ -389,8 +417,11 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
         // router, dynamic-k gate and group counts in one kernel
         launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, colmask, s);
     } else {
-        if (fused_router && n_tokens <= kSmallTokens)
-            launch_router_small(*layer, x, n_tokens, ws + w.hid, scores, s);
+        if (fused_router && n_tokens <= kSmallTokens) {
+            SmallGroup G{};
+            G.m[0] = small_mod(*layer, ws, w, scores, mask, y, tau);
+            launch_router_small(*layer, G, 1, x, n_tokens, s);
+        }
         else if (fused_router)
             launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, nullptr, s);
         else if (layer->dtype == DMOE_F32)
@@ -426,6 +457,72 @@ int32_t dmoe_forward_topk(const dmoe_layer* layer, const void* x, int32_t n_toke
     if (k < 0) return fail(DMOE_ERR_SHAPE, "k must not be negative");
     return forward_impl(layer, x, n_tokens, Gate{0.0f, k}, y, scores_out, mask_out, offsets_out,
                         token_lists_out, workspace, workspace_bytes, stream);
+}
+
+int32_t dmoe_group_workspace_bytes(const dmoe_layer* const* layers, int32_t n_layers,
+                                   int32_t n_tokens, size_t* out_bytes) {
+    if (!layers || !out_bytes) return fail(DMOE_ERR_NULL, "layers or out_bytes is NULL");
+    if (n_layers < 1 || n_layers > kGroupMax)
+        return fail(DMOE_ERR_SHAPE, "a group holds 1 to %d layers", kGroupMax);
+    size_t total = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        if (int rc = check_layer(layers[i], true, true)) return rc;
+        if (int rc = check_tokens(n_tokens, layers[i]->n_experts)) return rc;
+        total += align_up(layer_ws(*layers[i], n_tokens).total);
+    }
+    *out_bytes = total;
+    return DMOE_OK;
+}
+
+int32_t dmoe_forward_group(const dmoe_layer* const* layers, int32_t n_layers, const void* x,
+                           int32_t n_tokens, const float* host_taus, void* const* host_ys,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+    if (!layers || !host_taus || !host_ys) return fail(DMOE_ERR_NULL, "layers, host_taus or host_ys is NULL");
+    if (n_layers < 1 || n_layers > kGroupMax)
+        return fail(DMOE_ERR_SHAPE, "a group holds 1 to %d layers", kGroupMax);
+    size_t need = 0, off[kGroupMax];
+    for (int i = 0; i < n_layers; ++i) {
+        if (int rc = check_layer(layers[i], true, true)) return rc;
+        if (int rc = check_tokens(n_tokens, layers[i]->n_experts)) return rc;
+        if (int rc = check_tau(host_taus[i])) return rc;
+        const dmoe_layer &A = *layers[0], &B = *layers[i];
+        if (A.d_model != B.d_model || A.n_experts != B.n_experts || A.expert_size != B.expert_size ||
+            A.router_hidden != B.router_hidden || A.gated != B.gated || A.act != B.act ||
+            A.dtype != B.dtype)
+            return fail(DMOE_ERR_UNSUPPORTED, "the layers of a group must have one shape, activation and dtype");
+        off[i] = need;
+        need += align_up(layer_ws(B, n_tokens).total);
+    }
+    if (n_tokens == 0) return DMOE_OK;
+    if (!x) return fail(DMOE_ERR_NULL, "x is NULL");
+    for (int i = 0; i < n_layers; ++i)
+        if (!host_ys[i]) return fail(DMOE_ERR_NULL, "host_ys[%d] is NULL", i);
+    if (int rc = check_ws(workspace, workspace_bytes, need)) return rc;
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t s = (hipStream_t)stream;
+    const dmoe_layer& L0 = *layers[0];
+    bool fused = use_small_path(L0, n_tokens);
+    for (int i = 0; i < n_layers; ++i) fused = fused && router_fused_supported(*layers[i]);
+    if (!fused) {  // larger batches: one layer after the other, each in its share of the workspace
+        for (int i = 0; i < n_layers; ++i) {
+            const size_t share = align_up(layer_ws(*layers[i], n_tokens).total);
+            if (int rc = forward_impl(layers[i], x, n_tokens, Gate{host_taus[i], -1}, host_ys[i], nullptr,
+                                      nullptr, nullptr, nullptr, ws + off[i], share, stream))
+                return rc;
+        }
+        return DMOE_OK;
+    }
+    SmallGroup G{};
+    for (int i = 0; i < n_layers; ++i) {
+        const LayerWs w = layer_ws(*layers[i], n_tokens);
+        char* wsi = ws + off[i];
+        G.m[i] = small_mod(*layers[i], wsi, w, reinterpret_cast<float*>(wsi + w.scores),
+                           reinterpret_cast<uint64_t*>(wsi + w.mask), host_ys[i], host_taus[i]);
+    }
+    launch_router_small(L0, G, n_layers, x, n_tokens, s);
+    launch_select_small_group(L0, G, n_layers, n_tokens, s);
+    launch_small_bf16(L0, G, n_layers, x, n_tokens, s);
+    return DMOE_OK;
 }
 
 int32_t dmoe_timing_enable(int32_t on) {

@@ -115,18 +115,39 @@ void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* score
                          uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
                          uint64_t* colmask, hipStream_t s);
 
-// T <= kSmallTokens: router as a weight stream over many workgroups (same support conditions as
-// the fused kernel); hid is a 16 x d_h bf16 scratch buffer.  The gate runs separately.
-void launch_router_small(const dmoe_layer& L, const void* x, int T, void* hid, float* scores,
-                         hipStream_t s);
+// ---- small-token path (T <= kSmallTokens): up to kGroupMax layers of one shape per launch ----
+// The attention projections Q, K and V are three converted layers with the same input (Sec. 3.5),
+// and at 16 tokens a forward is a handful of launches that each last a few microseconds: every
+// small-token kernel therefore takes the per-layer pointers of a whole group and works on layer
+// blockIdx.z.  A single layer is a group of one.
+constexpr int kGroupMax = 4;
+struct SmallMod {
+    const __bf16 *r1f, *r_b1, *r2f, *r_b2;                 // packed router matrices, biases
+    const __bf16 *wupf, *wgatef, *b_up, *w2f, *b_down;     // packed expert matrices, biases
+    __bf16 *hid, *Hs, *y;                                  // router hidden tile, H fragments, output
+    float *scores, *partial;                               // scores [T][E]; per-expert-group partial outputs
+    uint64_t *mask, *colmask;                              // mask [T][W]; colmask [E]
+    int32_t* group_cnt;                                    // [E] tokens per expert
+    float tau;
+};
+struct SmallGroup {
+    SmallMod m[kGroupMax];
+};
+// Router as a weight stream over many workgroups (same support conditions as the fused kernel);
+// hid is a 16 x d_h bf16 scratch buffer per layer.  The gate runs separately.
+void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x,
+                         int T, hipStream_t s);
+// Dynamic-k gate of every layer of the group on its stored scores (mask, colmask, group_cnt).
+void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_layers, int T,
+                               hipStream_t s);
 
 // ---- small-token experts (ffn_small.hip): T <= kSmallTokens, driven by colmask[0][e] -------------
 constexpr int kSmallTokens = 16;
 constexpr int kSmallMaxGroups = 32;   // expert groups whose partial outputs are summed at the end
 bool small_bf16_supported(const dmoe_layer& L);
 // Hs: E * (m_pad/32) KiB of fragments; partial: kSmallMaxGroups * 16 * d floats.
-void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t* colmask, void* Hs,
-                       float* partial, void* y, hipStream_t s);
+void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
+                       hipStream_t s);
 
 // ---- experts ----------------------------------------------------------------------------------
 void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* mask, float* y,

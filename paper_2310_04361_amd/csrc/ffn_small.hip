@@ -46,10 +46,13 @@ constexpr int kUpSmallWaves = 16;
 
 template <int MT, bool GATED>
 __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
-    const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
-    const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
-    const uint64_t* __restrict__ colmask, __bf16* __restrict__ Hs, int T, int d, int m, int act,
-    int KQ) {
+    const SmallGroup G, const __bf16* __restrict__ x, int T, int d, int m, int act, int KQ) {
+    const SmallMod& M = G.m[blockIdx.z];
+    const __bf16* __restrict__ wupf = M.wupf;
+    const __bf16* __restrict__ wgatef = M.wgatef;
+    const __bf16* __restrict__ b_up = M.b_up;
+    const uint64_t* __restrict__ colmask = M.colmask;
+    __bf16* __restrict__ Hs = M.Hs;
     constexpr int KS = MT / 2, kThreads = 64 * kUpSmallWaves, BR = GATED ? 2 : 1;
     const int e = blockIdx.x;
     const uint64_t cm = colmask[e];
@@ -133,9 +136,13 @@ constexpr int kSmallPerGroup = 256;  // experts per group at most
 
 // grid = (column-tile groups of 4, expert groups); KS = m_pad / 32.
 template <int KS>
-__global__ __launch_bounds__(256) void down_small_kernel(
-    const __bf16* __restrict__ w2f, const uint64_t* __restrict__ colmask,
-    const __bf16* __restrict__ Hs, float* __restrict__ partial, int T, int d, int E, int per) {
+__global__ __launch_bounds__(256) void down_small_kernel(const SmallGroup G, int T, int d, int E,
+                                                         int per) {
+    const SmallMod& M = G.m[blockIdx.z];
+    const __bf16* __restrict__ w2f = M.w2f;
+    const uint64_t* __restrict__ colmask = M.colmask;
+    const __bf16* __restrict__ Hs = M.Hs;
+    float* __restrict__ partial = M.partial;
     __shared__ int s_list[kSmallPerGroup];
     __shared__ int s_n;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
@@ -176,9 +183,11 @@ __global__ __launch_bounds__(256) void down_small_kernel(
     }
 }
 
-__global__ void finish_small_kernel(const float* __restrict__ partial,
-                                    const __bf16* __restrict__ b_down, __bf16* __restrict__ y,
-                                    int T, int d, int EG) {
+__global__ void finish_small_kernel(const SmallGroup G, int T, int d, int EG) {
+    const SmallMod& M = G.m[blockIdx.z];
+    const float* __restrict__ partial = M.partial;
+    const __bf16* __restrict__ b_down = M.b_down;
+    __bf16* __restrict__ y = M.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= T * d) return;
     const int t = i / d, col = i % d;
@@ -198,8 +207,8 @@ __global__ void finish_small_kernel(const float* __restrict__ partial,
 }
 
 template <int MT, bool GATED>
-void launch_up_small_t(const dmoe_layer& L, const void* x, int T, const PackedLayout& P,
-                       const uint64_t* colmask, void* Hs, hipStream_t s) {
+void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
+                       hipStream_t s) {
     const size_t lds = 16 * (2 * (size_t)L.d_model + 16) +
                        sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4;
     static bool attr_set = false;
@@ -211,10 +220,8 @@ void launch_up_small_t(const dmoe_layer& L, const void* x, int T, const PackedLa
     // K slices: as many as the sixteen wavefronts allow and the k-steps divide into
     int KQ = kUpSmallWaves / MT;
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
-    const char* pk = static_cast<const char*>(L.packed);
-    up_small_kernel<MT, GATED><<<L.n_experts, 64 * kUpSmallWaves, lds, s>>>(
-        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
-        (const __bf16*)L.b_up, colmask, (__bf16*)Hs, T, L.d_model, L.expert_size, L.act, KQ);
+    up_small_kernel<MT, GATED><<<dim3(L.n_experts, 1, n_layers), 64 * kUpSmallWaves, lds, s>>>(
+        G, (const __bf16*)x, T, L.d_model, L.expert_size, L.act, KQ);
 }
 
 }  // namespace
@@ -226,20 +233,19 @@ bool small_bf16_supported(const dmoe_layer& L) {
            div_up(L.n_experts, kSmallMaxGroups) <= kSmallPerGroup;
 }
 
-void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t* colmask, void* Hs,
-                       float* partial, void* y, hipStream_t s) {
-    const PackedLayout P = packed_layout(L);
+void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
+                       hipStream_t s) {
     const int mt = m_pad_of(L.expert_size) / 16;
     {
         LaunchTimer tm(kSlotSmallUp, s);
         if (L.gated) {
-            if (mt == 2) launch_up_small_t<2, true>(L, x, T, P, colmask, Hs, s);
-            else if (mt == 4) launch_up_small_t<4, true>(L, x, T, P, colmask, Hs, s);
-            else launch_up_small_t<8, true>(L, x, T, P, colmask, Hs, s);
+            if (mt == 2) launch_up_small_t<2, true>(L, G, n_layers, x, T, s);
+            else if (mt == 4) launch_up_small_t<4, true>(L, G, n_layers, x, T, s);
+            else launch_up_small_t<8, true>(L, G, n_layers, x, T, s);
         } else {
-            if (mt == 2) launch_up_small_t<2, false>(L, x, T, P, colmask, Hs, s);
-            else if (mt == 4) launch_up_small_t<4, false>(L, x, T, P, colmask, Hs, s);
-            else launch_up_small_t<8, false>(L, x, T, P, colmask, Hs, s);
+            if (mt == 2) launch_up_small_t<2, false>(L, G, n_layers, x, T, s);
+            else if (mt == 4) launch_up_small_t<4, false>(L, G, n_layers, x, T, s);
+            else launch_up_small_t<8, false>(L, G, n_layers, x, T, s);
         }
     }
     // expert groups: enough workgroups to fill the chip, at most kSmallMaxGroups partial sums
@@ -249,24 +255,16 @@ void launch_small_bf16(const dmoe_layer& L, const void* x, int T, const uint64_t
     EG = std::max(EG, div_up(E, kSmallPerGroup));
     const int per = div_up(E, EG);
     EG = div_up(E, per);
-    const char* pk = static_cast<const char*>(L.packed);
-    const dim3 grid(ncg, EG);
+    const dim3 grid(ncg, EG, n_layers);
     const int ks = mt / 2;
     {
         LaunchTimer tm(kSlotSmallDown, s);
-        if (ks == 1)
-            down_small_kernel<1><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
-                                                      (const __bf16*)Hs, partial, T, d, E, per);
-        else if (ks == 2)
-            down_small_kernel<2><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
-                                                      (const __bf16*)Hs, partial, T, d, E, per);
-        else
-            down_small_kernel<4><<<grid, 256, 0, s>>>((const __bf16*)(pk + P.w2f), colmask,
-                                                      (const __bf16*)Hs, partial, T, d, E, per);
+        if (ks == 1) down_small_kernel<1><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        else if (ks == 2) down_small_kernel<2><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        else down_small_kernel<4><<<grid, 256, 0, s>>>(G, T, d, E, per);
     }
     LaunchTimer tm(kSlotSmallFinish, s);
-    finish_small_kernel<<<div_up(T * d, 256), 256, 0, s>>>(partial, (const __bf16*)L.b_down,
-                                                           (__bf16*)y, T, d, EG);
+    finish_small_kernel<<<dim3(div_up(T * d, 256), 1, n_layers), 256, 0, s>>>(G, T, d, EG);
 }
 
 }  // namespace dmoe

@@ -302,8 +302,11 @@ void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float t
 //   scores: wavefront = one tile of 16 experts.
 // The gate then runs as the stand-alone mask kernel on the stored scores.
 __global__ __launch_bounds__(1024) void router_small_hidden_kernel(
-    const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
-    __bf16* __restrict__ hid, int T, int d, int dh, int KQ) {
+    const SmallGroup G, const __bf16* __restrict__ x, int T, int d, int dh, int KQ) {
+    const SmallMod& M = G.m[blockIdx.z];
+    const __bf16* __restrict__ r1f = M.r1f;
+    const __bf16* __restrict__ r_b1 = M.r_b1;
+    __bf16* __restrict__ hid = M.hid;
     __shared__ float red[16][64][4];
     const int h = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
@@ -332,9 +335,13 @@ __global__ __launch_bounds__(1024) void router_small_hidden_kernel(
     }
 }
 
-__global__ __launch_bounds__(256) void router_small_scores_kernel(
-    const __bf16* __restrict__ hid, const __bf16* __restrict__ r2f, const __bf16* __restrict__ r_b2,
-    float* __restrict__ scores, int T, int dh, int E) {
+__global__ __launch_bounds__(256) void router_small_scores_kernel(const SmallGroup G, int T,
+                                                                  int dh, int E) {
+    const SmallMod& M = G.m[blockIdx.z];
+    const __bf16* __restrict__ hid = M.hid;
+    const __bf16* __restrict__ r2f = M.r2f;
+    const __bf16* __restrict__ r_b2 = M.r_b2;
+    float* __restrict__ scores = M.scores;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
     const int et = blockIdx.x * 4 + w;
     if (et >= (E + 15) / 16) return;
@@ -369,19 +376,15 @@ void launch_t(const dmoe_layer& L, const void* x, int T, float* scores, float ta
 
 }  // namespace
 
-void launch_router_small(const dmoe_layer& L, const void* x, int T, void* hid, float* scores,
-                         hipStream_t s) {
+void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x,
+                         int T, hipStream_t s) {
     LaunchTimer tm(kSlotRouter, s);
-    const PackedLayout P = packed_layout(L);
-    const char* pk = static_cast<const char*>(L.packed);
     const int dh = L.router_hidden, E = L.n_experts;
     int KQ = 16;  // wavefronts that split K: as many as divide the k-steps
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
-    router_small_hidden_kernel<<<dh / 16, 1024, 0, s>>>(
-        (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1, (__bf16*)hid, T,
-        L.d_model, dh, KQ);
-    router_small_scores_kernel<<<div_up(div_up(E, 16), 4), 256, 0, s>>>(
-        (const __bf16*)hid, (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, dh, E);
+    router_small_hidden_kernel<<<dim3(dh / 16, 1, n_layers), 1024, 0, s>>>(G, (const __bf16*)x, T,
+                                                                          L.d_model, dh, KQ);
+    router_small_scores_kernel<<<dim3(div_up(div_up(E, 16), 4), 1, n_layers), 256, 0, s>>>(G, T, dh, E);
 }
 
 bool router_fused_supported(const dmoe_layer& L) {

@@ -155,12 +155,12 @@ __global__ __launch_bounds__(256) void topk_mask_kernel(const float* __restrict_
 // T <= 16: one workgroup, wavefront t = token t with lanes striding the experts, so the score row
 // is read coalesced, the maximum is a wavefront reduction and a ballot IS a mask word.  The
 // transpose to per-expert token sets (colmask) and counts then goes through LDS.
-__global__ __launch_bounds__(1024) void select_small_kernel(const float* __restrict__ scores,
-                                                            uint64_t* __restrict__ mask,
-                                                            int32_t* __restrict__ k_per_token,
-                                                            int32_t* __restrict__ group_cnt,
-                                                            uint64_t* __restrict__ colmask, int T,
-                                                            int E, int W, float tau) {
+__device__ __forceinline__ void select_small_body(const float* __restrict__ scores,
+                                                  uint64_t* __restrict__ mask,
+                                                  int32_t* __restrict__ k_per_token,
+                                                  int32_t* __restrict__ group_cnt,
+                                                  uint64_t* __restrict__ colmask, int T, int E,
+                                                  int W, float tau) {
     extern __shared__ uint64_t mw[];  // [16][W]
     const int lane = lane_id(), t = threadIdx.x >> 6;
     if (t < T) {
@@ -190,6 +190,22 @@ __global__ __launch_bounds__(1024) void select_small_kernel(const float* __restr
         group_cnt[e] = __popcll(col);
         if (colmask) colmask[e] = col;
     }
+}
+
+__global__ __launch_bounds__(1024) void select_small_kernel(const float* __restrict__ scores,
+                                                            uint64_t* __restrict__ mask,
+                                                            int32_t* __restrict__ k_per_token,
+                                                            int32_t* __restrict__ group_cnt,
+                                                            uint64_t* __restrict__ colmask, int T,
+                                                            int E, int W, float tau) {
+    select_small_body(scores, mask, k_per_token, group_cnt, colmask, T, E, W, tau);
+}
+
+// the same gate for every layer of a group (blockIdx.z = layer), each with its own tau
+__global__ __launch_bounds__(1024) void select_small_group_kernel(const SmallGroup G, int T, int E,
+                                                                  int W) {
+    const SmallMod& M = G.m[blockIdx.z];
+    select_small_body(M.scores, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
 }
 
 __global__ void zero_u64_kernel(uint64_t* p, size_t n) {
@@ -404,6 +420,13 @@ void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint6
     }
     mask_count_kernel<true><<<div_up(NG, 4), 256, 0, s>>>(scores, mask, k_per_token, group_off,
                                                           colmask, T, E, W, tau);
+}
+
+void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_layers, int T,
+                               hipStream_t s) {
+    const int E = L.n_experts, W = div_up(E, 64);
+    LaunchTimer tm(kSlotMask, s);
+    select_small_group_kernel<<<dim3(1, 1, n_layers), 1024, sizeof(uint64_t) * 16 * W, s>>>(G, T, E, W);
 }
 
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,

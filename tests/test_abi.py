@@ -144,3 +144,33 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     # timing slots are readable without enabling
     assert lib.dmoe_timing_slots() >= 8
     assert lib.dmoe_timing_read(999, None, None, None) == B.DMOE_ERR_SHAPE
+
+
+def test_group_calls_reject_bad_arguments_before_launch(lib):
+    LP = ctypes.POINTER(B.DmoeLayerStruct)
+    a, b = _layer(), _layer()
+    other = _layer(n_experts=32)
+    n = ctypes.c_size_t(0)
+    one = ctypes.c_size_t(0)
+    assert lib.dmoe_workspace_bytes(ctypes.byref(a), 128, ctypes.byref(one)) == B.DMOE_OK
+    refs = (LP * 2)(ctypes.pointer(a), ctypes.pointer(b))
+    assert lib.dmoe_group_workspace_bytes(refs, 2, 128, ctypes.byref(n)) == B.DMOE_OK
+    assert n.value == 2 * one.value                  # the sum of the layers' workspaces
+    assert lib.dmoe_group_workspace_bytes(refs, 0, 128, ctypes.byref(n)) == B.DMOE_ERR_SHAPE
+    assert lib.dmoe_group_workspace_bytes(refs, 5, 128, ctypes.byref(n)) == B.DMOE_ERR_SHAPE
+    assert lib.dmoe_group_workspace_bytes(None, 2, 128, ctypes.byref(n)) == B.DMOE_ERR_NULL
+    taus = (ctypes.c_float * 2)(0.5, 0.5)
+    ys = (ctypes.c_void_p * 2)(0x2000, 0x3000)
+    ws = 0x100000
+    args = (0x4000, 128, taus, ys, ws, n.value, None)
+    mixed = (LP * 2)(ctypes.pointer(a), ctypes.pointer(other))
+    assert lib.dmoe_forward_group(mixed, 2, *args) == B.DMOE_ERR_UNSUPPORTED   # two shapes
+    assert b"one shape" in lib.dmoe_last_error()
+    assert lib.dmoe_forward_group(refs, 0, *args) == B.DMOE_ERR_SHAPE
+    assert lib.dmoe_forward_group(refs, 2, 0x4000, 128, None, ys, ws, n.value, None) == B.DMOE_ERR_NULL
+    bad_tau = (ctypes.c_float * 2)(0.5, 1.5)
+    assert lib.dmoe_forward_group(refs, 2, 0x4000, 128, bad_tau, ys, ws, n.value, None) == B.DMOE_ERR_TAU
+    no_y = (ctypes.c_void_p * 2)(0x2000, None)
+    assert lib.dmoe_forward_group(refs, 2, 0x4000, 128, taus, no_y, ws, n.value, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_forward_group(refs, 2, 0x4000, 128, taus, ys, ws, n.value - 256, None) == B.DMOE_ERR_WORKSPACE
+    assert lib.dmoe_forward_group(refs, 2, None, 0, taus, ys, None, 0, None) == B.DMOE_OK  # no tokens: no-op

@@ -416,6 +416,12 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
     if (fused_router && n_tokens > kSmallTokens && gate.top_k < 0) {
         // router, dynamic-k gate and group counts in one kernel
         launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, colmask, s);
+    } else if (fused_router && colmask && gate.top_k < 0 &&
+               layer->n_experts <= kSmallFusedSelectMaxE) {
+        // small-token path: hidden product, then scores + gate in one workgroup
+        SmallGroup G{};
+        G.m[0] = small_mod(*layer, ws, w, scores, mask, y, tau);
+        launch_router_select_small(*layer, G, 1, x, n_tokens, s);
     } else {
         if (fused_router && n_tokens <= kSmallTokens) {
             SmallGroup G{};
@@ -519,8 +525,12 @@ int32_t dmoe_forward_group(const dmoe_layer* const* layers, int32_t n_layers, co
         G.m[i] = small_mod(*layers[i], wsi, w, reinterpret_cast<float*>(wsi + w.scores),
                            reinterpret_cast<uint64_t*>(wsi + w.mask), host_ys[i], host_taus[i]);
     }
-    launch_router_small(L0, G, n_layers, x, n_tokens, s);
-    launch_select_small_group(L0, G, n_layers, n_tokens, s);
+    if (L0.n_experts <= kSmallFusedSelectMaxE) {
+        launch_router_select_small(L0, G, n_layers, x, n_tokens, s);
+    } else {
+        launch_router_small(L0, G, n_layers, x, n_tokens, s);
+        launch_select_small_group(L0, G, n_layers, n_tokens, s);
+    }
     launch_small_bf16(L0, G, n_layers, x, n_tokens, s);
     return DMOE_OK;
 }

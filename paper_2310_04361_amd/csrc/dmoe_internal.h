@@ -137,6 +137,13 @@ struct SmallGroup {
 // hid is a 16 x d_h bf16 scratch buffer per layer.  The gate runs separately.
 void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x,
                          int T, hipStream_t s);
+void launch_router_small_hidden(const dmoe_layer& L, const SmallGroup& G, int n_layers,
+                                const void* x, int T, hipStream_t s);
+// The same with the dynamic-k gate of every layer (M.tau) folded into the second kernel, which
+// then also writes mask, colmask and group_cnt; for E <= kSmallFusedSelectMaxE.
+constexpr int kSmallFusedSelectMaxE = 1024;
+void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
+                                const void* x, int T, hipStream_t s);
 // Dynamic-k gate of every layer of the group on its stored scores (mask, colmask, group_cnt).
 void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_layers, int T,
                                hipStream_t s);

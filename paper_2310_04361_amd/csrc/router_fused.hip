@@ -376,14 +376,21 @@ void launch_t(const dmoe_layer& L, const void* x, int T, float* scores, float ta
 
 }  // namespace
 
-void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x,
-                         int T, hipStream_t s) {
+void launch_router_small_hidden(const dmoe_layer& L, const SmallGroup& G, int n_layers,
+                                const void* x, int T, hipStream_t s) {
     LaunchTimer tm(kSlotRouter, s);
-    const int dh = L.router_hidden, E = L.n_experts;
+    const int dh = L.router_hidden;
     int KQ = 16;  // wavefronts that split K: as many as divide the k-steps
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
     router_small_hidden_kernel<<<dim3(dh / 16, 1, n_layers), 1024, 0, s>>>(G, (const __bf16*)x, T,
                                                                           L.d_model, dh, KQ);
+}
+
+void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x,
+                         int T, hipStream_t s) {
+    launch_router_small_hidden(L, G, n_layers, x, T, s);
+    LaunchTimer tm(kSlotRouter, s);
+    const int dh = L.router_hidden, E = L.n_experts;
     router_small_scores_kernel<<<dim3(div_up(div_up(E, 16), 4), 1, n_layers), 256, 0, s>>>(G, T, dh, E);
 }
 

@@ -8,6 +8,7 @@
 // A group is 64 consecutive tokens handled by one wavefront with lane = token; the 64x64 bit
 // transpose between "experts of a token" and "tokens of an expert" is done with ballots.
 #include "dmoe_internal.h"
+#include "mfma.h"
 
 namespace dmoe {
 
@@ -199,6 +200,39 @@ __global__ __launch_bounds__(1024) void select_small_kernel(const float* __restr
                                                             uint64_t* __restrict__ colmask, int T,
                                                             int E, int W, float tau) {
     select_small_body(scores, mask, k_per_token, group_cnt, colmask, T, E, W, tau);
+}
+
+// Second router product and the gate in one workgroup per layer (T <= 16, E <= 1024): wavefront
+// w multiplies the expert tiles w, w + 16, ... (s = |R2 hid + c2|, Sec. 3.3), the scores go to
+// global memory and to LDS, and after one barrier the gate above runs on the LDS copy.  One
+// launch less than scores + gate, which is what counts at this size.
+__global__ __launch_bounds__(1024) void router_scores_select_small_kernel(const SmallGroup G, int T,
+                                                                          int dh, int E, int W) {
+    extern __shared__ uint64_t mw[];  // [16][W] mask words, then [16][E] fp32 scores
+    const SmallMod& M = G.m[blockIdx.z];
+    float* sc = reinterpret_cast<float*>(mw + 16 * W);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
+    const int KS2 = dh / 32, NE = (E + 15) >> 4;
+    const __bf16* hb = M.hid + (size_t)c * dh + 8 * q;
+    for (int et = w; et < NE; et += 16) {
+        const __bf16* af = M.r2f + (((size_t)et * KS2) * 64 + lane) * 8;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+        for (int ks = 0; ks < KS2; ++ks)
+            acc = mfma16(load8(af + (size_t)ks * 512), load8(hb + 32 * ks), acc);
+        const int e0 = 16 * et + 4 * q;  // lane (q, c): experts e0 .. e0+3 of token c
+        if (c < T && e0 < E) {
+            float4 out;
+            out.x = fabsf(acc[0] + (M.r_b2 ? (float)M.r_b2[e0 + 0] : 0.0f));
+            out.y = fabsf(acc[1] + (M.r_b2 ? (float)M.r_b2[e0 + 1] : 0.0f));
+            out.z = fabsf(acc[2] + (M.r_b2 ? (float)M.r_b2[e0 + 2] : 0.0f));
+            out.w = fabsf(acc[3] + (M.r_b2 ? (float)M.r_b2[e0 + 3] : 0.0f));
+            *reinterpret_cast<float4*>(M.scores + (size_t)c * E + e0) = out;
+            *reinterpret_cast<float4*>(sc + (size_t)c * E + e0) = out;
+        }
+    }
+    __syncthreads();
+    select_small_body(sc, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
 }
 
 // the same gate for every layer of a group (blockIdx.z = layer), each with its own tau
@@ -427,6 +461,23 @@ void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_l
     const int E = L.n_experts, W = div_up(E, 64);
     LaunchTimer tm(kSlotMask, s);
     select_small_group_kernel<<<dim3(1, 1, n_layers), 1024, sizeof(uint64_t) * 16 * W, s>>>(G, T, E, W);
+}
+
+void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
+                                const void* x, int T, hipStream_t s) {
+    // first product: the many-workgroup hidden kernel of the plain small router (the scores
+    // kernel it launches as well is replaced by the fused one below)
+    const int E = L.n_experts, W = div_up(E, 64);
+    launch_router_small_hidden(L, G, n_layers, x, T, s);
+    LaunchTimer tm(kSlotMask, s);
+    const size_t lds = sizeof(uint64_t) * 16 * W + sizeof(float) * 16 * (size_t)E;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_scores_select_small_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        attr_set = true;
+    }
+    router_scores_select_small_kernel<<<dim3(1, 1, n_layers), 1024, lds, s>>>(G, T, L.router_hidden, E, W);
 }
 
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,

@@ -51,14 +51,17 @@ def _time_ms(fn, steps):
 class Workload:
     """One layer + its rotated inputs on the device."""
 
-    def __init__(self, name, tokens=0):
+    def __init__(self, name, tokens=0, e4m3=False):
         import torch
         from paper_2310_04361_amd import binding as B, workloads as wl
         cfg = wl.CONFIGS[name]
         if tokens:
             cfg = wl.with_tokens(cfg, tokens)
         self.cfg = cfg
+        self.e4m3 = e4m3   # expert matrices stored in 8-bit E4M3 (one byte per weight)
         self.layer_np, self.x_np = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
+        if e4m3:
+            self.layer_np = wl.quantize_experts_e4m3(self.layer_np)
         self.decode = cfg.T <= 16
         n_layers = N_LAYER_COPIES_DECODE if self.decode else 1
         self.layers = [B.Layer(self.layer_np, cfg.dtype) for _ in range(n_layers)]
@@ -102,7 +105,7 @@ class Workload:
         g = 3 if cfg.gated else 2
         if self.decode:
             # weight-streaming kernels: algorithmic bytes = the touched experts' weights, once
-            per_expert = 2.0 * cfg.d * cfg.m
+            per_expert = (1.0 if self.e4m3 else 2.0) * cfg.d * cfg.m
             kbytes = {"small_up": touched * per_expert * (g - 1), "small_down": touched * per_expert}
             dom = max(kbytes, key=lambda k: kt.get(k, 0.0))
             achieved = kbytes[dom] / (kt[dom] * 1e-3) / 1e9
@@ -403,6 +406,18 @@ def main() -> int:
                 entry["ms_per_step_graph_replay"] = round(
                     _time_ms(lambda i: graphs[i % len(graphs)].replay(), steps), 5)
                 del graphs
+                if name == "cfg5a":
+                    # the same layer with its expert matrices stored in 8-bit E4M3: half the
+                    # weight bytes per touched expert
+                    del wo
+                    cache.clear()
+                    torch.cuda.empty_cache()
+                    w8 = Workload(name, e4m3=True)
+                    r8 = w8.measure(t, steps, 10, traffic_ok=False)
+                    entry["e4m3_weights"] = {"ms_per_step": round(r8["ms"], 5),
+                                             "kernel_ms": r8["kernel_ms"], "roofline": r8["roofline"]}
+                    del w8
+                    wo = None
                 if name == "cfg5b":
                     # the query / key / value modules of one attention layer (Sec. 3.5): three
                     # layers of this shape on one input, one launch per stage for the group

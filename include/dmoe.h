@@ -48,6 +48,8 @@ typedef enum {
 } dmoe_status;
 
 enum { DMOE_F32 = 0, DMOE_BF16 = 1 };
+/* storage of the expert matrices w_up, w_gate, w_down (dmoe_layer.weight_format) */
+enum { DMOE_W_NATIVE = 0, DMOE_W_FP8_E4M3 = 1 };
 enum { DMOE_ACT_RELU = 0, DMOE_ACT_GELU_ERF = 1, DMOE_ACT_GELU_TANH = 2 };
 
 /*
@@ -64,11 +66,28 @@ typedef struct {
     int32_t gated;         /* 0 plain two-layer FFN, 1 gated (GLU) FFN */
     int32_t act;           /* DMOE_ACT_* */
     int32_t dtype;         /* DMOE_F32 | DMOE_BF16: x, y and every parameter */
-    int32_t reserved;      /* must be 0 */
+    int32_t weight_format; /* DMOE_W_NATIVE: expert matrices in `dtype`; DMOE_W_FP8_E4M3: see below */
     const void *w_up, *w_gate, *b_up, *w_down, *b_down;
     const void *r_w1, *r_b1, *r_w2, *r_b2;
     const void *packed;
+    const float *w_scales; /* DMOE_W_FP8_E4M3 only: [E][3] fp32, see below; else ignored */
 } dmoe_layer;
+
+/*
+ * Lower-precision experts (Appendix C times the experts in float16 and int8 as well; here weight-only 8-bit
+ * floating point, the format the gfx950 matrix units and converters handle natively).
+ * With weight_format == DMOE_W_FP8_E4M3 (bf16 layers only) w_up, w_gate and w_down hold one byte
+ * per weight in the OCP 8-bit format E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits;
+ * no infinities, largest value 448; the two NaN codes 0x7f / 0xff must not occur), in the same
+ * [E][m][d] order, and
+ *   W_up,e = w_scales[3e+0] * e4m3(w_up[e]),  W_gate,e = w_scales[3e+1] * e4m3(w_gate[e]),
+ *   W_down,e = w_scales[3e+2] * e4m3(w_down[e]).
+ * Every scale must be a power of two: then each weight is exactly a bf16 number, and the layer
+ * computes what a DMOE_W_NATIVE bf16 layer with those weights computes -- the prefill kernels
+ * run on bf16 copies made by dmoe_pack_weights, the small-token kernels (up to 16 tokens, where
+ * the weights are the traffic) stream the bytes and convert in registers.  x, y, biases and the
+ * router stay bf16.
+ */
 
 /* Library version (major*10000 + minor*100 + patch) and the text of the last error of the
  * calling thread ("" if none).  The returned string is owned by the library. */

@@ -20,6 +20,7 @@ DMOE_ERR_TAU, DMOE_ERR_WORKSPACE, DMOE_ERR_HIP = 4, 5, 6
 DMOE_F32, DMOE_BF16 = 0, 1
 ACT_CODES = {"relu": 0, "gelu_erf": 1, "gelu_tanh": 2}
 DTYPE_CODES = {"f32": DMOE_F32, "bf16": DMOE_BF16}
+DMOE_W_NATIVE, DMOE_W_FP8_E4M3 = 0, 1
 
 EXPORTS = (
     "dmoe_version", "dmoe_last_error", "dmoe_workspace_bytes", "dmoe_select_workspace_bytes",
@@ -35,11 +36,11 @@ class DmoeLayerStruct(ctypes.Structure):
         ("d_model", ctypes.c_int32), ("n_experts", ctypes.c_int32),
         ("expert_size", ctypes.c_int32), ("router_hidden", ctypes.c_int32),
         ("gated", ctypes.c_int32), ("act", ctypes.c_int32), ("dtype", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("weight_format", ctypes.c_int32),
         ("w_up", ctypes.c_void_p), ("w_gate", ctypes.c_void_p), ("b_up", ctypes.c_void_p),
         ("w_down", ctypes.c_void_p), ("b_down", ctypes.c_void_p),
         ("r_w1", ctypes.c_void_p), ("r_b1", ctypes.c_void_p), ("r_w2", ctypes.c_void_p),
-        ("r_b2", ctypes.c_void_p), ("packed", ctypes.c_void_p),
+        ("r_b2", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("w_scales", ctypes.c_void_p),
     ]
 
 
@@ -138,10 +139,21 @@ class Layer:
         self.act = params["act"]
         self.t = {k: to_device(params.get(k), dtype, device)
                   for k in ("w_up", "w_gate", "b_up", "w_down", "b_down", "r_w1", "r_b1", "r_w2", "r_b2")}
+        # 8-bit expert weights (params["w8"]: E4M3 codes and power-of-two scales): the library gets
+        # the codes; self.t keeps the bf16 values of the same weights for dense comparisons
+        w8 = params.get("w8")
+        self.w8 = None
+        ptrs = {k: _ptr(v) for k, v in self.t.items()}
+        if w8 is not None:
+            self.w8 = {k: torch.from_numpy(np.ascontiguousarray(w8[k])).to(device)
+                       for k in ("w_up", "w_gate", "w_down", "scales") if w8.get(k) is not None}
+            for k in ("w_up", "w_gate", "w_down"):
+                ptrs[k] = _ptr(self.w8.get(k))
         self.c = DmoeLayerStruct(
             d_model=d, n_experts=E, expert_size=m, router_hidden=self.d_h,
-            gated=int(self.gated), act=ACT_CODES[self.act], dtype=DTYPE_CODES[dtype], reserved=0,
-            **{k: _ptr(v) for k, v in self.t.items()}, packed=None)
+            gated=int(self.gated), act=ACT_CODES[self.act], dtype=DTYPE_CODES[dtype],
+            weight_format=DMOE_W_FP8_E4M3 if w8 is not None else DMOE_W_NATIVE,
+            **ptrs, packed=None, w_scales=_ptr(self.w8["scales"]) if w8 is not None else None)
         nbytes = ctypes.c_size_t(0)
         check(lib().dmoe_packed_bytes(ctypes.byref(self.c), ctypes.byref(nbytes)))
         self.packed = None

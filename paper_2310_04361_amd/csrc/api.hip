@@ -58,7 +58,12 @@ int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
         return fail(DMOE_ERR_SHAPE, "d_model, n_experts and expert_size must be positive");
     if (L->dtype != DMOE_F32 && L->dtype != DMOE_BF16)
         return fail(DMOE_ERR_UNSUPPORTED, "dtype %d is not DMOE_F32 or DMOE_BF16", L->dtype);
-    if (L->reserved != 0) return fail(DMOE_ERR_UNSUPPORTED, "reserved field must be 0");
+    if (L->weight_format != DMOE_W_NATIVE && L->weight_format != DMOE_W_FP8_E4M3)
+        return fail(DMOE_ERR_UNSUPPORTED, "weight_format %d is not DMOE_W_NATIVE or DMOE_W_FP8_E4M3", L->weight_format);
+    if (L->weight_format == DMOE_W_FP8_E4M3) {
+        if (L->dtype != DMOE_BF16) return fail(DMOE_ERR_UNSUPPORTED, "8-bit expert weights need a bf16 layer");
+        if (!L->w_scales) return fail(DMOE_ERR_NULL, "8-bit expert weights need w_scales");
+    }
     if (L->gated != 0 && L->gated != 1) return fail(DMOE_ERR_UNSUPPORTED, "gated must be 0 or 1");
     if (need_router) {
         if (L->router_hidden <= 0) return fail(DMOE_ERR_SHAPE, "router_hidden must be positive");
@@ -184,6 +189,10 @@ SmallMod small_mod(const dmoe_layer& L, char* ws, const LayerWs& w, float* score
     M.wgatef = (const __bf16*)(pk + P.wgatef);
     M.b_up = (const __bf16*)L.b_up;
     M.w2f = (const __bf16*)(pk + P.w2f);
+    M.wupf8 = (const uint8_t*)(pk + P.wupf8);
+    M.wgatef8 = (const uint8_t*)(pk + P.wgatef8);
+    M.w2f8 = (const uint8_t*)(pk + P.w2f8);
+    M.w_scales = L.weight_format == DMOE_W_FP8_E4M3 ? L.w_scales : nullptr;
     M.b_down = (const __bf16*)L.b_down;
     M.hid = (__bf16*)(ws + w.hid);
     M.Hs = (__bf16*)(ws + w.H);
@@ -494,7 +503,7 @@ int32_t dmoe_forward_group(const dmoe_layer* const* layers, int32_t n_layers, co
         const dmoe_layer &A = *layers[0], &B = *layers[i];
         if (A.d_model != B.d_model || A.n_experts != B.n_experts || A.expert_size != B.expert_size ||
             A.router_hidden != B.router_hidden || A.gated != B.gated || A.act != B.act ||
-            A.dtype != B.dtype)
+            A.dtype != B.dtype || A.weight_format != B.weight_format)
             return fail(DMOE_ERR_UNSUPPORTED, "the layers of a group must have one shape, activation and dtype");
         off[i] = need;
         need += align_up(layer_ws(B, n_tokens).total);

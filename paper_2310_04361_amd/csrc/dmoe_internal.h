@@ -35,7 +35,7 @@ inline size_t h_fragments(const dmoe_layer& L, int T) {
 
 // Sub-buffers of the packed-weights buffer (bytes from its start).
 struct PackedLayout {
-    size_t w2f, w2g, wupf, wgatef, r1f, r2f, total;
+    size_t w2f, w2g, wupf, wgatef, r1f, r2f, w2f8, wupf8, wgatef8, total;
 };
 inline PackedLayout packed_layout(const dmoe_layer& L) {
     PackedLayout P{};
@@ -52,6 +52,16 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
     o += (2 * (size_t)round_up(L.router_hidden > 0 ? L.router_hidden : 0, 16) * L.d_model + 255) / 256 * 256;
     P.r2f = o;
     o += (2 * (size_t)round_up(L.n_experts, 16) * round_up(L.router_hidden > 0 ? L.router_hidden : 0, 32) + 255) / 256 * 256;
+    // 8-bit expert weights: the same fragments with one byte per weight for the small-token
+    // kernels (w2f8, wupf8, wgatef8: half of `one` each)
+    P.w2f8 = P.wupf8 = P.wgatef8 = o;
+    if (L.weight_format == DMOE_W_FP8_E4M3) {
+        const size_t half = (one / 2 + 255) / 256 * 256;
+        P.w2f8 = o;
+        P.wupf8 = o + half;
+        P.wgatef8 = o + 2 * half;
+        o += (L.gated ? 3 : 2) * half;
+    }
     P.total = o;
     return P;
 }
@@ -124,6 +134,8 @@ constexpr int kGroupMax = 4;
 struct SmallMod {
     const __bf16 *r1f, *r_b1, *r2f, *r_b2;                 // packed router matrices, biases
     const __bf16 *wupf, *wgatef, *b_up, *w2f, *b_down;     // packed expert matrices, biases
+    const uint8_t *wupf8, *wgatef8, *w2f8;                 // the same fragments, one E4M3 byte per weight
+    const float* w_scales;                                 // [E][3] (up, gate, down); null: bf16 weights
     __bf16 *hid, *Hs, *y;                                  // router hidden tile, H fragments, output
     float *scores, *partial;                               // scores [T][E]; per-expert-group partial outputs
     uint64_t *mask, *colmask;                              // mask [T][W]; colmask [E]

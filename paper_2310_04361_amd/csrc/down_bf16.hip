@@ -71,8 +71,9 @@ DownPacking down_packing(int m) {
     return DownPacking{pg, g, g * pg / 2};
 }
 
-__global__ void pack_down32_kernel(const __bf16* __restrict__ w_down, __bf16* __restrict__ w2g,
-                                   int E, int m, int d, int PG, int G, int KSP) {
+__global__ void pack_down32_kernel(const void* __restrict__ w_down, const float* __restrict__ scales,
+                                   int fp8, __bf16* __restrict__ w2g, int E, int m, int d, int PG,
+                                   int G, int KSP) {
     const int n_stages = (E + G - 1) / G;
     const size_t n = (size_t)n_stages * (d / 32) * KSP * 512;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -88,7 +89,9 @@ __global__ void pack_down32_kernel(const __bf16* __restrict__ w_down, __bf16* __
         const int col = 32 * ct + 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
         const int pi = 2 * s + h;                   // piece of the stage
         const int e = st * G + pi / PG, neuron = 8 * (pi % PG) + s8;
-        w2g[i] = (e < E && neuron < m) ? w_down[((size_t)e * m + neuron) * d + col] : (__bf16)0.0f;
+        w2g[i] = (e < E && neuron < m)
+                     ? expert_weight(w_down, scales, fp8, 2, e, ((size_t)e * m + neuron) * d + col)
+                     : (__bf16)0.0f;
     }
 }
 
@@ -416,8 +419,9 @@ bool down_bf16_addressable(const dmoe_layer& L, int T) {
 
 void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s) {
     const DownPacking dp = down_packing(L.expert_size);
-    pack_down32_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_down, (__bf16*)w2g, L.n_experts,
-                                            L.expert_size, L.d_model, dp.PG, dp.G, dp.KSP);
+    pack_down32_kernel<<<2048, 256, 0, s>>>(L.w_down, L.w_scales,
+                                            L.weight_format == DMOE_W_FP8_E4M3, (__bf16*)w2g,
+                                            L.n_experts, L.expert_size, L.d_model, dp.PG, dp.G, dp.KSP);
 }
 
 void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,

@@ -52,8 +52,21 @@ __device__ __forceinline__ float activate_fast(int act, float v) {
 // ---- one-time weight packing ------------------------------------------------------------------------
 // (small-token path) w_down[E][m][d] -> w2f[E][d/16][KS][64][8]: lane (q, c) of fragment (e, column tile ct, ks)
 // holds W_down[e][8*(4ks + q) + s][16ct + c] (piece 4ks + q of an H row), zero for neurons >= m.
-__global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __restrict__ w2f,
-                                 int E, int m, int d, int KS) {
+// OUT = __bf16: the weight as a bf16 number (8-bit weights are scaled out); OUT = uint8_t: the
+// raw E4M3 byte (8-bit weights only), for the kernels that convert in registers.
+template <typename OUT>
+__device__ __forceinline__ OUT packed_weight(const void* w, const float* scales, int fp8, int which,
+                                             int e, size_t flat, bool valid) {
+    if constexpr (sizeof(OUT) == 1) {
+        return valid ? static_cast<const uint8_t*>(w)[flat] : (uint8_t)0;
+    } else {
+        return valid ? expert_weight(w, scales, fp8, which, e, flat) : (__bf16)0.0f;
+    }
+}
+
+template <typename OUT>
+__global__ void pack_down_kernel(const void* __restrict__ w_down, const float* __restrict__ scales,
+                                 int fp8, OUT* __restrict__ w2f, int E, int m, int d, int KS) {
     const size_t n = (size_t)E * d * KS * 32;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -66,15 +79,19 @@ __global__ void pack_down_kernel(const __bf16* __restrict__ w_down, __bf16* __re
         const int e = (int)(f / (d / 16));
         const int q = lane >> 4, c = lane & 15;
         const int neuron = 8 * (4 * ks + q) + s;  // piece 4ks + q of the H row
-        w2f[i] = neuron < m ? w_down[((size_t)e * m + neuron) * d + 16 * ct + c] : (__bf16)0.0f;
+        w2f[i] = packed_weight<OUT>(w_down, scales, fp8, 2, e,
+                                    ((size_t)e * m + min(neuron, m - 1)) * d + 16 * ct + c, neuron < m);
     }
 }
 
 // w[E][m][d] -> wf[E][MT][d/32][64][8]: lane (q, c) of fragment (e, neuron tile mt, k-step) holds
 // w[e][n(mt, c)][32 kstep + 8q + s], zero rows for neurons >= m; n(mt, c) = neuron_of_slot for the
 // expert matrices, 16mt + c for the router matrices.
-__global__ void pack_up_kernel(const __bf16* __restrict__ w, __bf16* __restrict__ wf, int E, int m,
-                               int d, int MT, int piece_order) {
+// `which`: 0 up, 1 gate (selects the scale of 8-bit weights)
+template <typename OUT>
+__global__ void pack_up_kernel(const void* __restrict__ w, const float* __restrict__ scales, int fp8,
+                               int which, OUT* __restrict__ wf, int E, int m, int d, int MT,
+                               int piece_order) {
     const size_t n = (size_t)E * MT * 16 * d;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -88,7 +105,9 @@ __global__ void pack_up_kernel(const __bf16* __restrict__ w, __bf16* __restrict_
         const int q = lane >> 4, c = lane & 15;
         // experts: the neuron order that makes H pieces consecutive; router matrices: natural
         const int neuron = piece_order ? neuron_of_slot(mt, c) : 16 * mt + c;
-        wf[i] = neuron < m ? w[((size_t)e * m + neuron) * d + 32 * kstep + 8 * q + s] : (__bf16)0.0f;
+        wf[i] = packed_weight<OUT>(w, scales, fp8, which, e,
+                                   ((size_t)e * m + min(neuron, m - 1)) * d + 32 * kstep + 8 * q + s,
+                                   neuron < m);
     }
 }
 
@@ -446,22 +465,33 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     const PackedLayout P = packed_layout(L);
     const int mp = m_pad_of(L.expert_size);
     char* pk = static_cast<char*>(packed);
-    pack_down_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_down, (__bf16*)(pk + P.w2f),
-                                          L.n_experts, L.expert_size, L.d_model, mp / 32);
+    const int fp8 = L.weight_format == DMOE_W_FP8_E4M3;
+    const int E = L.n_experts, m = L.expert_size, d = L.d_model;
+    pack_down_kernel<__bf16><<<2048, 256, 0, s>>>(L.w_down, L.w_scales, fp8, (__bf16*)(pk + P.w2f), E,
+                                                  m, d, mp / 32);
     launch_pack_down_bf16(L, pk + P.w2g, s);
-    pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_up, (__bf16*)(pk + P.wupf), L.n_experts,
-                                        L.expert_size, L.d_model, mp / 16, 1);
+    pack_up_kernel<__bf16><<<2048, 256, 0, s>>>(L.w_up, L.w_scales, fp8, 0, (__bf16*)(pk + P.wupf), E,
+                                                m, d, mp / 16, 1);
     if (L.gated)
-        pack_up_kernel<<<2048, 256, 0, s>>>((const __bf16*)L.w_gate, (__bf16*)(pk + P.wgatef),
-                                            L.n_experts, L.expert_size, L.d_model, mp / 16, 1);
+        pack_up_kernel<__bf16><<<2048, 256, 0, s>>>(L.w_gate, L.w_scales, fp8, 1,
+                                                    (__bf16*)(pk + P.wgatef), E, m, d, mp / 16, 1);
+    if (fp8) {  // byte fragments for the small-token kernels
+        pack_down_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_down, L.w_scales, 1, (uint8_t*)(pk + P.w2f8),
+                                                       E, m, d, mp / 32);
+        pack_up_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_up, L.w_scales, 1, 0, (uint8_t*)(pk + P.wupf8),
+                                                     E, m, d, mp / 16, 1);
+        if (L.gated)
+            pack_up_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_gate, L.w_scales, 1, 1,
+                                                         (uint8_t*)(pk + P.wgatef8), E, m, d, mp / 16, 1);
+    }
     // the router matrices use the same fragment format: "one expert" whose rows are the hidden
     // units (r_w1) or the experts (r_w2)
     const int dh = L.router_hidden;
     if (L.r_w1 && L.r_w2 && dh > 0 && dh % 32 == 0 && L.d_model % 32 == 0) {
-        pack_up_kernel<<<512, 256, 0, s>>>((const __bf16*)L.r_w1, (__bf16*)(pk + P.r1f), 1, dh,
-                                           L.d_model, dh / 16, 0);
-        pack_up_kernel<<<512, 256, 0, s>>>((const __bf16*)L.r_w2, (__bf16*)(pk + P.r2f), 1,
-                                           L.n_experts, dh, div_up(L.n_experts, 16), 0);
+        pack_up_kernel<__bf16><<<512, 256, 0, s>>>(L.r_w1, nullptr, 0, 0, (__bf16*)(pk + P.r1f), 1, dh,
+                                                   L.d_model, dh / 16, 0);
+        pack_up_kernel<__bf16><<<512, 256, 0, s>>>(L.r_w2, nullptr, 0, 0, (__bf16*)(pk + P.r2f), 1,
+                                                   L.n_experts, dh, div_up(L.n_experts, 16), 0);
     }
 }
 

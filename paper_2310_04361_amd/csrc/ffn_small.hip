@@ -44,7 +44,9 @@ __device__ __forceinline__ float activate_s(int act, float v) {
 // issued together), the KQ partial products are added through LDS.
 constexpr int kUpSmallWaves = 16;
 
-template <int MT, bool GATED>
+// W8: the weight fragments hold one E4M3 byte per weight (half the stream); they are converted to
+// bf16 in registers, and the per-expert power-of-two scales are applied to the fp32 sums.
+template <int MT, bool GATED, bool W8>
 __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
     const SmallGroup G, const __bf16* __restrict__ x, int T, int d, int m, int act, int KQ) {
     const SmallMod& M = G.m[blockIdx.z];
@@ -77,8 +79,11 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
 #pragma unroll
     for (int br = 0; br < BR; ++br) acc[br] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (kq < KQ) {
-        const __bf16* au = wupf + (((size_t)e * MT + mt) * NK32 * 64 + lane) * 8;
-        const __bf16* ag = wgatef + (((size_t)e * MT + mt) * NK32 * 64 + lane) * 8;
+        const size_t frag0 = (((size_t)e * MT + mt) * NK32 * 64 + lane) * 8;  // elements
+        const __bf16* au = wupf + frag0;
+        const __bf16* ag = wgatef + frag0;
+        const uint8_t* au8 = M.wupf8 + frag0;
+        const uint8_t* ag8 = M.wgatef8 + frag0;
         const char* bsrc = xs + c * row_bytes + q * 16;
         const int k0 = kq * per;
         for (int kb = 0; kb < per; kb += 8) {
@@ -86,8 +91,14 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int ks = k0 + min(kb + i, per - 1);  // past the slice: a block already read
-                a[i][0] = load8(au + (size_t)ks * 512);
-                if (GATED) a[i][BR - 1] = load8(ag + (size_t)ks * 512);
+                if (W8) {
+                    a[i][0] = e4m3x8_to_bf16(*reinterpret_cast<const uint2*>(au8 + (size_t)ks * 512));
+                    if (GATED)
+                        a[i][BR - 1] = e4m3x8_to_bf16(*reinterpret_cast<const uint2*>(ag8 + (size_t)ks * 512));
+                } else {
+                    a[i][0] = load8(au + (size_t)ks * 512);
+                    if (GATED) a[i][BR - 1] = load8(ag + (size_t)ks * 512);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -115,17 +126,24 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
         acc[br] = sum;
     }
     const bool keep = c < T && ((cm >> c) & 1ull);
+    float s_up = 1.0f, s_gate = 1.0f, s_down = 1.0f;
+    if (W8) {
+        s_up = M.w_scales[3 * e + 0];
+        s_gate = M.w_scales[3 * e + 1];
+        s_down = M.w_scales[3 * e + 2];  // folded into H: the down kernel sums over experts
+    }
     bf16x4 hv;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int n = neuron_of_slot(mt, 4 * q + r);
         float v;
         if (GATED) {
-            v = activate_s(act, acc[BR - 1][r]) * acc[0][r];
+            v = activate_s(act, acc[BR - 1][r] * s_gate) * (acc[0][r] * s_up);
         } else {
             const float bias = b_up ? (float)b_up[(size_t)e * m + min(n, m - 1)] : 0.0f;
-            v = activate_s(act, acc[0][r] + bias);
+            v = activate_s(act, acc[0][r] * s_up + bias);
         }
+        v *= s_down;
         if (n >= m || !keep) v = 0.0f;
         hv[r] = (__bf16)v;
     }
@@ -135,7 +153,7 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
 constexpr int kSmallPerGroup = 256;  // experts per group at most
 
 // grid = (column-tile groups of 4, expert groups); KS = m_pad / 32.
-template <int KS>
+template <int KS, bool W8>
 __global__ __launch_bounds__(256) void down_small_kernel(const SmallGroup G, int T, int d, int E,
                                                          int per) {
     const SmallMod& M = G.m[blockIdx.z];
@@ -164,6 +182,7 @@ __global__ __launch_bounds__(256) void down_small_kernel(const SmallGroup G, int
     const int ct = blockIdx.x * 4 + w;
     if (ct >= d / 16) return;
     const __bf16* wa = w2f + ((size_t)ct * KS * 64 + lane) * 8;
+    const uint8_t* wa8 = M.w2f8 + ((size_t)ct * KS * 64 + lane) * 8;
     const size_t w_expert_stride = (size_t)(d / 16) * KS * 512;
     const __bf16* hb = Hs + lane * 8;
     f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -172,7 +191,9 @@ __global__ __launch_bounds__(256) void down_small_kernel(const SmallGroup G, int
         const int e = s_list[i];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            acc = mfma16(load8(wa + (size_t)e * w_expert_stride + ks * 512),
+            acc = mfma16(W8 ? e4m3x8_to_bf16(*reinterpret_cast<const uint2*>(
+                                  wa8 + (size_t)e * w_expert_stride + ks * 512))
+                            : load8(wa + (size_t)e * w_expert_stride + ks * 512),
                          load8(hb + ((size_t)e * KS + ks) * 512), acc);
     }
     // lane (q, c): columns 16ct + 4q .. +3 of token c
@@ -206,22 +227,29 @@ __global__ void finish_small_kernel(const SmallGroup G, int T, int d, int EG) {
     y[i] = (__bf16)v;
 }
 
-template <int MT, bool GATED>
+template <int MT, bool GATED, bool W8>
 void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
                        hipStream_t s) {
     const size_t lds = 16 * (2 * (size_t)L.d_model + 16) +
                        sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4;
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_small_kernel<MT, GATED>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_small_kernel<MT, GATED, W8>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
     // K slices: as many as the sixteen wavefronts allow and the k-steps divide into
     int KQ = kUpSmallWaves / MT;
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
-    up_small_kernel<MT, GATED><<<dim3(L.n_experts, 1, n_layers), 64 * kUpSmallWaves, lds, s>>>(
+    up_small_kernel<MT, GATED, W8><<<dim3(L.n_experts, 1, n_layers), 64 * kUpSmallWaves, lds, s>>>(
         G, (const __bf16*)x, T, L.d_model, L.expert_size, L.act, KQ);
+}
+
+template <int MT, bool GATED>
+void launch_up_small_w(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
+                       hipStream_t s) {
+    if (L.weight_format == DMOE_W_FP8_E4M3) launch_up_small_t<MT, GATED, true>(L, G, n_layers, x, T, s);
+    else launch_up_small_t<MT, GATED, false>(L, G, n_layers, x, T, s);
 }
 
 }  // namespace
@@ -239,13 +267,13 @@ void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
     {
         LaunchTimer tm(kSlotSmallUp, s);
         if (L.gated) {
-            if (mt == 2) launch_up_small_t<2, true>(L, G, n_layers, x, T, s);
-            else if (mt == 4) launch_up_small_t<4, true>(L, G, n_layers, x, T, s);
-            else launch_up_small_t<8, true>(L, G, n_layers, x, T, s);
+            if (mt == 2) launch_up_small_w<2, true>(L, G, n_layers, x, T, s);
+            else if (mt == 4) launch_up_small_w<4, true>(L, G, n_layers, x, T, s);
+            else launch_up_small_w<8, true>(L, G, n_layers, x, T, s);
         } else {
-            if (mt == 2) launch_up_small_t<2, false>(L, G, n_layers, x, T, s);
-            else if (mt == 4) launch_up_small_t<4, false>(L, G, n_layers, x, T, s);
-            else launch_up_small_t<8, false>(L, G, n_layers, x, T, s);
+            if (mt == 2) launch_up_small_w<2, false>(L, G, n_layers, x, T, s);
+            else if (mt == 4) launch_up_small_w<4, false>(L, G, n_layers, x, T, s);
+            else launch_up_small_w<8, false>(L, G, n_layers, x, T, s);
         }
     }
     // expert groups: enough workgroups to fill the chip, at most kSmallMaxGroups partial sums
@@ -259,9 +287,13 @@ void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
     const int ks = mt / 2;
     {
         LaunchTimer tm(kSlotSmallDown, s);
-        if (ks == 1) down_small_kernel<1><<<grid, 256, 0, s>>>(G, T, d, E, per);
-        else if (ks == 2) down_small_kernel<2><<<grid, 256, 0, s>>>(G, T, d, E, per);
-        else down_small_kernel<4><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        const bool w8 = L.weight_format == DMOE_W_FP8_E4M3;
+        if (ks == 1 && !w8) down_small_kernel<1, false><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        else if (ks == 2 && !w8) down_small_kernel<2, false><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        else if (!w8) down_small_kernel<4, false><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        else if (ks == 1) down_small_kernel<1, true><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        else if (ks == 2) down_small_kernel<2, true><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        else down_small_kernel<4, true><<<grid, 256, 0, s>>>(G, T, d, E, per);
     }
     LaunchTimer tm(kSlotSmallFinish, s);
     finish_small_kernel<<<dim3(div_up(T * d, 256), 1, n_layers), 256, 0, s>>>(G, T, d, EG);

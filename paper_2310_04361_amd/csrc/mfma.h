@@ -53,6 +53,40 @@ __device__ __forceinline__ bf16x8 load8(const __bf16* p) {
     return *reinterpret_cast<const bf16x8*>(p);
 }
 
+// OCP E4M3 byte -> value (exact in bf16): 1 sign, 4 exponent bits (bias 7), 3 mantissa bits,
+// subnormals m / 8 * 2^-6, no infinities.  Plain arithmetic, used by the one-time packing.
+__device__ __forceinline__ float e4m3_value(uint32_t b) {
+    const int e = (b >> 3) & 15, m = b & 7;
+    const float mag = e == 0 ? ldexpf((float)m, -9) : ldexpf((float)(8 + m), e - 10);
+    return (b & 0x80u) ? -mag : mag;
+}
+
+// Element `flat` of expert e's matrix `which` (0 up, 1 gate, 2 down) as a bf16 number: the stored
+// bf16 value, or scale * e4m3(byte) for 8-bit weights (exact: the scales are powers of two).
+__device__ __forceinline__ __bf16 expert_weight(const void* w, const float* scales, int fp8, int which,
+                                               int e, size_t flat) {
+    if (!fp8) return static_cast<const __bf16*>(w)[flat];
+    return (__bf16)(scales[3 * e + which] * e4m3_value(static_cast<const uint8_t*>(w)[flat]));
+}
+
+// Eight E4M3 bytes (one lane's share of a weight fragment) -> eight bf16 numbers, exactly, with
+// the hardware converter (two bytes per instruction) and a byte permute that keeps the upper
+// halves of the fp32 results.
+__device__ __forceinline__ bf16x8 e4m3x8_to_bf16(uint2 v) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+    u32x4v out;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t word = i < 2 ? v.x : v.y;
+        const f32x2 f = (i & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8(word, true)
+                                : __builtin_amdgcn_cvt_pk_f32_fp8(word, false);
+        // bytes 2,3 of f[0] -> low half, bytes 2,3 of f[1] -> high half
+        out[i] = __builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u);
+    }
+    return __builtin_bit_cast(bf16x8, out);
+}
+
 __device__ __forceinline__ bf16x8 zero8() {
     bf16x8 z;
 #pragma unroll

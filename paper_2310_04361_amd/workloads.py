@@ -167,3 +167,33 @@ def random_scores(T: int, E: int, seed: int = 0, kind: str = "halfnormal") -> np
     else:
         raise ValueError(kind)
     return np.ascontiguousarray(s.astype(np.float32))
+
+
+def quantize_experts_e4m3(layer: dict) -> dict:
+    """The layer with its expert matrices stored in 8-bit floating point (OCP E4M3: 4 exponent
+    bits, 3 mantissa bits, largest value 448) with one power-of-two scale per expert and matrix,
+    chosen so that the largest weight of the matrix just fits.  Returns a copy whose w_up / w_gate
+    / w_down hold the DEQUANTISED values as fp64 (each exactly a bf16 number), so that the oracle
+    sees the numbers the library computes with, plus "w8": the uint8 codes [E, m, d] and the
+    float32 scales [E, 3] (up, gate, down) that the library is given.  Rounding to the format is
+    storage rounding like the bf16 rounding above, done by torch's float8_e4m3fn cast (round to
+    nearest even)."""
+    import torch
+    out = dict(layer)
+    E = layer["w_up"].shape[0]
+    scales = np.ones((E, 3), np.float32)
+    w8 = {}
+    for which, key in enumerate(("w_up", "w_gate", "w_down")):
+        w = layer.get(key)
+        if w is None:
+            w8[key] = None
+            continue
+        amax = np.abs(w).reshape(E, -1).max(axis=1)
+        s = np.exp2(np.ceil(np.log2(np.maximum(amax, 1e-30) / 448.0)))
+        scales[:, which] = s
+        q = torch.from_numpy((w / s[:, None, None]).astype(np.float32)).to(torch.float8_e4m3fn)
+        w8[key] = q.view(torch.uint8).numpy().copy()
+        out[key] = q.to(torch.float32).numpy().astype(np.float64) * s[:, None, None]
+    w8["scales"] = scales
+    out["w8"] = w8
+    return out

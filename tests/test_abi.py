@@ -21,8 +21,8 @@ def lib():
 
 def _layer(**kw):
     base = dict(d_model=128, n_experts=16, expert_size=16, router_hidden=32, gated=0, act=0,
-                dtype=B.DMOE_F32, reserved=0, w_up=0x1000, w_gate=None, b_up=None, w_down=0x1000,
-                b_down=None, r_w1=0x1000, r_b1=None, r_w2=0x1000, r_b2=None, packed=None)
+                dtype=B.DMOE_F32, weight_format=0, w_up=0x1000, w_gate=None, b_up=None, w_down=0x1000,
+                b_down=None, r_w1=0x1000, r_b1=None, r_w2=0x1000, r_b2=None, packed=None, w_scales=None)
     base.update(kw)
     return B.DmoeLayerStruct(**base)
 
@@ -38,8 +38,8 @@ def test_exports_match_header(lib):
 
 
 def test_struct_layout_matches_header():
-    # 8 int32 followed by 10 pointers
-    assert ctypes.sizeof(B.DmoeLayerStruct) == 8 * 4 + 10 * 8
+    # 8 int32 followed by 11 pointers
+    assert ctypes.sizeof(B.DmoeLayerStruct) == 8 * 4 + 11 * 8
     assert B.DmoeLayerStruct.w_up.offset == 32 and B.DmoeLayerStruct.packed.offset == 32 + 9 * 8
 
 
@@ -71,7 +71,9 @@ def test_layer_validation(lib):
         (_layer(d_model=0), B.DMOE_ERR_SHAPE),
         (_layer(n_experts=-3), B.DMOE_ERR_SHAPE),
         (_layer(dtype=7), B.DMOE_ERR_UNSUPPORTED),
-        (_layer(reserved=1), B.DMOE_ERR_UNSUPPORTED),
+        (_layer(weight_format=2), B.DMOE_ERR_UNSUPPORTED),
+        (_layer(weight_format=1), B.DMOE_ERR_UNSUPPORTED),                      # 8-bit weights need bf16
+        (_layer(weight_format=1, dtype=B.DMOE_BF16), B.DMOE_ERR_NULL),          # ... and scales
         (_layer(gated=2), B.DMOE_ERR_UNSUPPORTED),
     ]
     for L, code in bad:

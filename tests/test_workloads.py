@@ -48,3 +48,25 @@ def test_cost_model_matches_appendix_b():
     assert cost_model.dense_ffn_macs(d, e * d) == 2 * e * d * d
     assert cost_model.expert_macs(d, m) * n == cost_model.dense_ffn_macs(d, e * d)
     assert cost_model.executed_flops(10, 2048, 64, gated=True) == 10 * 786432
+
+
+def test_e4m3_quantiser_is_exact_storage_rounding():
+    """Every code decodes (by the format's definition, written out here) to the value the harness
+    hands to the oracle; scales are powers of two; the largest weight of a matrix uses the top
+    binade; quantising twice changes nothing."""
+    cfg = wl.with_tokens(wl.CONFIGS["cfg5b"], 4)
+    layer = wl.make_layer(cfg, 5)
+    q = wl.quantize_experts_e4m3(layer)
+    codes, scales = q["w8"]["w_up"], q["w8"]["scales"]
+    assert codes.dtype == np.uint8 and codes.shape == layer["w_up"].shape
+    assert np.all(np.exp2(np.round(np.log2(scales))) == scales)
+    sign = np.where(codes & 0x80, -1.0, 1.0)
+    e, m = ((codes >> 3) & 15).astype(np.int64), (codes & 7).astype(np.float64)
+    mag = np.where(e == 0, m * 2.0 ** -9, (8 + m) * np.exp2((e - 10).astype(np.float64)))
+    assert not np.any((codes & 0x7f) == 0x7f)                       # no NaN codes
+    assert np.array_equal(sign * mag * scales[:, 0][:, None, None], q["w_up"])
+    assert (mag.reshape(cfg.E, -1).max(axis=1) >= 256).all()        # top binade of 448 used
+    rel = np.abs(q["w_up"] - layer["w_up"]).max() / np.abs(layer["w_up"]).max()
+    assert rel <= 2.0 ** -4                                         # 3 mantissa bits
+    q2 = wl.quantize_experts_e4m3({k: v for k, v in q.items() if k != "w8"})
+    assert np.array_equal(q2["w_up"], q["w_up"]) and np.array_equal(q2["w8"]["w_up"], codes)

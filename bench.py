@@ -332,6 +332,19 @@ def main() -> int:
     if sweep:
         out["tau_sweep"] = sweep
 
+    # the same forward recorded as HIP graphs (one per rotated input) and replayed: what a caller
+    # that captures the layer pays, without the launch gaps between its six kernels
+    graphs = []
+    for gi in range(N_ROTATE):
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph):
+            B.dmoe_forward(w.layers[0], w.xs[gi], tau, y=w.ys[gi])
+        graphs.append(gph)
+    for gph in graphs:
+        gph.replay()
+    out["ms_per_step_graph_replay"] = round(_time_ms(lambda i: graphs[i % N_ROTATE].replay(), args.steps), 5)
+    del graphs
+
     if args.top_k:
         k = args.top_k
         for i in range(5):

@@ -280,13 +280,23 @@ __global__ __launch_bounds__(256) void scan_groups_kernel(int32_t* __restrict__ 
     const int lane = lane_id();
     const int e = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     if (e >= E) return;
+    // eight chunks of 64 groups per pass with all their loads in flight together (one memory round
+    // trip per 512 groups instead of one per 64)
     int carry = 0;
-    for (int base = 0; base < NG; base += kWave) {
-        const int g = base + lane;
-        const int v = g < NG ? group_cnt[(size_t)g * E + e] : 0;
-        const int incl = wave_inclusive_scan(v);
-        if (g < NG) group_cnt[(size_t)g * E + e] = carry + incl - v;
-        carry += __shfl(incl, kWave - 1, kWave);
+    for (int base = 0; base < NG; base += 8 * kWave) {
+        int v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int g = base + k * kWave + lane;
+            v[k] = g < NG ? group_cnt[(size_t)g * E + e] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int g = base + k * kWave + lane;
+            const int incl = wave_inclusive_scan(v[k]);
+            if (g < NG) group_cnt[(size_t)g * E + e] = carry + incl - v[k];
+            carry += __shfl(incl, kWave - 1, kWave);
+        }
     }
     if (lane == 0) group_cnt[(size_t)NG * E + e] = carry;
 }

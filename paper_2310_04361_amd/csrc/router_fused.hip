@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     int T, int d, int E, float tau, int do_select, uint64_t* __restrict__ mask,
     int32_t* __restrict__ k_per_token, int32_t* __restrict__ group_cnt,
     uint64_t* __restrict__ colmask) {
-    constexpr int dh = NH * 16, HT = NH / 4, KS2 = dh / 32;
+    constexpr int dh = NH * 16, HT = NH / 4;
     constexpr int kHRow = dh * 2 + 16;  // bytes per hidden row in LDS
     constexpr int kXRowC = KBC * 128 + 16;  // bytes per staged x row: KBC blocks + bank skew
     extern __shared__ char smem[];
@@ -122,6 +122,18 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
     }
 
+    // R2 fragments of this wavefront's first expert tile: requested now, so that their latency
+    // passes while the hidden tile is finished and stored
+    constexpr int KS2 = dh / 32;
+    const int NE = (E + 15) >> 4;
+    bf16x8 r2a[2][KS2];
+    auto load_r2 = [&](int et, bf16x8 (&a)[KS2]) {
+        et = min(et, NE - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS2; ++ks) a[ks] = load8(r2f + (((size_t)et * KS2 + ks) * 64 + lane) * 8);
+    };
+    load_r2(w, r2a[0]);
+
     // lane (q, c) of tile (h, tt): hidden units 16*(w*HT + h) + 4q + r of token 16tt + c
 #pragma unroll
     for (int h = 0; h < HT; ++h) {
@@ -142,17 +154,9 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     __syncthreads();
 
     // ---------------------------------------------------------------- stage 2
-    const int NE = (E + 15) >> 4;
     float sc[ETW][4][4];  // [my tile][token tile][r]
     float vmax[4] = {0.f, 0.f, 0.f, 0.f};
     // R2 fragments of the next tile are requested before the current one is multiplied
-    bf16x8 r2a[2][KS2];
-    auto load_r2 = [&](int et, bf16x8 (&a)[KS2]) {
-        et = min(et, NE - 1);
-#pragma unroll
-        for (int ks = 0; ks < KS2; ++ks) a[ks] = load8(r2f + (((size_t)et * KS2 + ks) * 64 + lane) * 8);
-    };
-    load_r2(w, r2a[0]);
 #pragma unroll
     for (int j = 0; j < ETW; ++j) {
         const int et = w + 4 * j;
@@ -248,17 +252,19 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         if (t < T && k_per_token) k_per_token[t] = kt;
     }
     __syncthreads();
-    // ballot transpose: lane = token; wavefront w handles words w, w+4, ...
-    for (int wi = w; wi < W; wi += 4) {
+    // ballot transpose: lane = token; wavefront w handles the experts 64wi + 16w .. +15 of every
+    // word wi (sixteen ballots per word and wavefront)
+    for (int wi = 0; wi < W; ++wi) {
         const uint64_t word = fin[lane * W + wi];
         uint64_t col = 0;  // lane b: which tokens of the group keep expert 64wi + b
-#pragma unroll 8
-        for (int b = 0; b < 64; ++b) {
+#pragma unroll
+        for (int bi = 0; bi < 16; ++bi) {
+            const int b = 16 * w + bi;
             const uint64_t bal = __ballot((word >> b) & 1ull);
             if (lane == b) col = bal;
         }
         const int e = 64 * wi + lane;
-        if (e < E) {
+        if ((lane >> 4) == w && e < E) {
             group_cnt[(size_t)g * E + e] = __popcll(col);
             if (colmask) colmask[(size_t)g * E + e] = col;
         }

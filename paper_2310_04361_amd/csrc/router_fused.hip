@@ -215,26 +215,24 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         const float m = fmaxf(fmaxf(pmax[tk], pmax[64 + tk]), fmaxf(pmax[128 + tk], pmax[192 + tk]));
         thr[tt] = (double)tau * (double)m;  // exact: at most 48 significant bits
     }
-    // this wavefront's bits of each token: tile et fills bits 16*(et%4) .. +15 of word et/4
-    for (int i = tid; i < 4 * 64 * W; i += 256) pw[i] = 0ull;  // (only words we own are rewritten)
-    __syncthreads();
+    // this wavefront's bits of each token: its tile et = w + 4j is the only one it has in word j
+    // (bits 16w .. 16w+15), so the word is stored whole, zero where the tile lies beyond E
 #pragma unroll
     for (int j = 0; j < ETW; ++j) {
         const int et = w + 4 * j;
-        if (et < NE) {
-            const int e0 = 16 * et + 4 * q;
+        const int e0 = 16 * et + 4 * q;
+        if (j < W) {  // uniform
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) {
                 uint32_t bits = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const bool keep = (tau == 0.0f) || ((double)sc[j][tt][r] >= thr[tt]);
-                    bits |= (uint32_t)(keep && e0 + r < E) << (4 * q + r);
+                    bits |= (uint32_t)(keep && et < NE && e0 + r < E) << (4 * q + r);
                 }
                 bits |= __shfl_xor(bits, 16, 64);
                 bits |= __shfl_xor(bits, 32, 64);  // 16 bits: experts 16et .. 16et+15 of token c
-                if (q == (et & 3))                   // one lane group per tile does the write
-                    pw[(w * 64 + 16 * tt + c) * W + (et >> 2)] |= (uint64_t)bits << (16 * (et & 3));
+                if (q == 0) pw[(w * 64 + 16 * tt + c) * W + j] = (uint64_t)bits << (16 * w);
             }
         }
     }

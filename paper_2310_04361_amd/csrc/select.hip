@@ -385,10 +385,14 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
                 // the expert's items are dealt to the windows in proportion to its rows there
                 // (cutting at ceil(row / rows_per_item) would hand every expert's first,
                 // rounded-up item to window 0 and overload its XCD)
-                const long long cnt = totals[e];
-                const long long items = (cnt + rows_per_item - 1) / rows_per_item;
-                const int k0 = cnt ? (int)((r_lo[e] * items + cnt / 2) / cnt) : 0;
-                const int k1 = cnt ? (int)((r_hi[e] * items + cnt / 2) / cnt) : 0;
+                // (in double: exact far beyond any real size, monotone in the row, and identical for
+                // the shared boundary of two neighbouring windows -- a 64-bit integer division
+                // costs hundreds of instructions)
+                const int cnt = totals[e];
+                const int items = (cnt + rows_per_item - 1) / rows_per_item;
+                const double scale = cnt ? (double)items / (double)cnt : 0.0;
+                const int k0 = min(items, (int)((double)r_lo[e] * scale + 0.5));
+                const int k1 = r_hi[e] >= cnt ? items : min(items, (int)((double)r_hi[e] * scale + 0.5));
                 n = k1 - k0;
                 first = s_item[e] + k0;
             }

@@ -42,11 +42,16 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
     if (L.dtype != DMOE_BF16) return P;
     const size_t one =
         (2 * (size_t)L.n_experts * L.d_model * m_pad_of(L.expert_size) + 255) / 256 * 256;
+    // the 32x32x16 down fragments pack the experts' real 8-neuron pieces in stages of one or two
+    // experts: never more than m_pad neurons per expert, but a last half-filled stage counts as
+    // two experts
+    const size_t one_g =
+        (2 * ((size_t)L.n_experts + 1) * L.d_model * m_pad_of(L.expert_size) + 255) / 256 * 256;
     P.w2f = 0;          // down-projection, 16x16x32 fragments (small-token path)
     P.w2g = one;        // down-projection, 32x32x16 fragments (down_bf16.hip)
-    P.wupf = 2 * one;
-    P.wgatef = 3 * one;
-    size_t o = (L.gated ? 4 : 3) * one;
+    P.wupf = one + one_g;
+    P.wgatef = P.wupf + one;
+    size_t o = P.wupf + (L.gated ? 2 : 1) * one;
     // router weights as fragments: r1f[d_h/16][d/32][64][8], r2f[ceil(E/16)][d_h/32][64][8]
     P.r1f = o;
     o += (2 * (size_t)round_up(L.router_hidden > 0 ? L.router_hidden : 0, 16) * L.d_model + 255) / 256 * 256;

@@ -30,11 +30,14 @@ def _cfg(T, d, E, m, gated):
                      (0.5,), ffn_bias=not gated)
 
 
-# one narrow workgroup per CU (few tokens): every k-step packing, plain and gated, E not a
-# multiple of the 32-expert mask batch or of the 4-stage loop trip
+# one narrow workgroup per CU (few tokens): every k-step packing, plain and gated; expert counts
+# from 1 up, not multiples of the 32-expert mask batch or of the 4-stage loop trip, and beyond
+# several batches
 ONE_PER_CU = [(300, 256, 20, m, False) for m in (8, 16, 24, 32, 40, 48, 64, 100, 128)] + \
              [(300, 256, 37, m, True) for m in (16, 32, 48, 64)] + \
-             [(200, 256, 70, 24, False)]
+             [(200, 256, 70, 24, False)] + \
+             [(200, 256, E, 24, False) for E in (1, 3, 5, 33, 65, 130, 300)] + \
+             [(200, 256, E, 64, False) for E in (1, 33, 100)]
 # 384-column workgroups: d = 768 and 10880 < T <= 16384
 WIDE = [(11000, 768, 16, m, False) for m in (16, 32, 48, 64, 128)] + [(12000, 768, 12, 32, True)]
 # more narrow workgroups than CUs (two per CU up to 4 k-steps per stage, else several rounds)
@@ -50,7 +53,8 @@ def test_down_projection_shapes(B, oracle, T, d, E, m, gated):
     L = B.Layer(layer, cfg.dtype)
     mask = wl.bernoulli_mask(T, E, 0.3, seed=m + T)
     mask[1] = 0          # a token with no expert
-    mask[:, E - 1] = 0   # an expert with no token
+    if E > 1:
+        mask[:, E - 1] = 0   # an expert with no token
     offsets, lists = lists_from_mask(mask)
     lists_dev = torch.from_numpy(np.concatenate([lists, np.zeros(1, np.int32)])).cuda()
     y = B.dmoe_expert_ffn(L, B.to_device(x, cfg.dtype), torch.from_numpy(offsets).cuda(), lists_dev)

@@ -51,6 +51,12 @@ CASES = [
     ("cfg4", 300, None, 0.05),
     ("cfg4", 300, None, 0.12),
     ("paper", 200, None, 0.05),
+    # token counts at the edges of the small-token path (up to 16 tokens) and of a 64-token group
+    ("cfg2", 1, None, 1.0),
+    ("cfg2", 17, None, 0.3),
+    ("cfg4", 17, 16, 0.4),
+    ("cfg2", 63, None, 0.2),
+    ("cfg2", 65, None, 0.2),
 ]
 
 

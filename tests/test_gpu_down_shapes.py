@@ -37,7 +37,8 @@ ONE_PER_CU = [(300, 256, 20, m, False) for m in (8, 16, 24, 32, 40, 48, 64, 100,
              [(300, 256, 37, m, True) for m in (16, 32, 48, 64)] + \
              [(200, 256, 70, 24, False)] + \
              [(200, 256, E, 24, False) for E in (1, 3, 5, 33, 65, 130, 300)] + \
-             [(200, 256, E, 64, False) for E in (1, 33, 100)]
+             [(200, 256, E, 64, False) for E in (1, 33, 100)] + \
+             [(128, 256, 2048, 8, False), (96, 512, 4096, 16, True)]   # many small experts (the largest count)
 # 384-column workgroups: d = 768 and 10880 < T <= 16384
 WIDE = [(11000, 768, 16, m, False) for m in (16, 32, 48, 64, 128)] + [(12000, 768, 12, 32, True)]
 # more narrow workgroups than CUs (two per CU up to 4 k-steps per stage, else several rounds)
@@ -62,7 +63,8 @@ def test_down_projection_shapes(B, oracle, T, d, E, m, gated):
     got = B.from_device(y, cfg.dtype)
     assert np.isfinite(got).all()
     rng = np.random.default_rng(7)
-    idx = np.unique(np.concatenate([[0, 1, 63, 64, 127, 128, T - 1], rng.choice(T, 96, replace=False)]))
+    idx = np.unique(np.concatenate([[i for i in (0, 1, 63, 64, 127, 128, T - 1) if i < T],
+                                    rng.choice(T, min(96, T), replace=False)]))
     ref = oracle_ffn(oracle, layer, x[idx], mask[idx])
     err = tokenwise_rel_err(got[idx], ref)
     print(f"  err={err:.3e}", flush=True)

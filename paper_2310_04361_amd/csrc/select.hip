@@ -102,6 +102,35 @@ __global__ __launch_bounds__(256) void mask_count_kernel(const float* __restrict
     if (valid && k_per_token) k_per_token[t] = kt;
 }
 
+// Dynamic-k gate (Sec. 3.4 Eq. 4) with one wavefront per token and the lanes striding the
+// experts: the score row is read coalesced, the maximum is a wavefront reduction and a ballot IS
+// a mask word.  The per-group expert counts are then taken from the mask words by
+// mask_count_kernel<false>.  (The lane-per-token form above reads 64 rows at once, 16 bytes of
+// each: fine inside the fused router where the scores sit in registers, slow from memory.)
+__global__ __launch_bounds__(256) void tau_mask_kernel(const float* __restrict__ scores,
+                                                       uint64_t* __restrict__ mask,
+                                                       int32_t* __restrict__ k_per_token, int T,
+                                                       int E, int W, float tau) {
+    const int lane = lane_id();
+    const int t = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    if (t >= T) return;  // uniform per wavefront
+    const float* row = scores + (size_t)t * E;
+    float mx = -INFINITY;
+    for (int e = lane; e < E; e += kWave) mx = fmaxf(mx, row[e]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
+    const double thr = (double)tau * (double)mx;  // exact: at most 48 significant bits
+    int kt = 0;
+    for (int w = 0; w < W; ++w) {
+        const int e = 64 * w + lane;
+        const bool keep = e < E && (tau == 0.0f || (double)row[e] >= thr);
+        const uint64_t word = __ballot(keep);
+        kt += __popcll(word);
+        if (lane == 0) mask[(size_t)t * W + w] = word;
+    }
+    if (lane == 0 && k_per_token) k_per_token[t] = kt;
+}
+
 // Top-k gate (the conventional rule that Sec. 3.3 / 3.4 compare against): keep the k largest
 // scores of each token, ties at the k-th value going to the lower expert index, so that exactly
 // k are kept.  One wavefront per token with the lanes striding the experts (coalesced row read).
@@ -466,8 +495,9 @@ void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint6
             scores, mask, k_per_token, group_off, colmask, T, E, W, tau);
         return;
     }
-    mask_count_kernel<true><<<div_up(NG, 4), 256, 0, s>>>(scores, mask, k_per_token, group_off,
-                                                          colmask, T, E, W, tau);
+    tau_mask_kernel<<<div_up(T, 4), 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, nullptr, group_off,
+                                                           colmask, T, E, W, 0.0f);
 }
 
 void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_layers, int T,

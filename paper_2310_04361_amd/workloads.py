@@ -54,6 +54,9 @@ CONFIGS = {
                     ffn_bias=True),
     "paper": Config("paper", 256 * 197, 768, 24, 128, 128, False, "gelu_erf", "bf16", (0.5,),
                     ffn_bias=True),
+    # the paper's own conversion of its language model (Sec. 4.3 / training details): 2048
+    # experts of 8 neurons over the 16384-wide gated FFN, router hidden width 512
+    "gemma_paper": Config("gemma_paper", 4096, 2048, 2048, 8, 512, True, "gelu_tanh", "bf16", (0.5,)),
 }
 
 

@@ -23,7 +23,12 @@ def B():
                                                ("cfg4", 0.6, 64),
                                                # ragged last chunk in the token range where the
                                                # down-projection takes its 384-column shape
-                                               ("cfg2:11000", 0.3, 128)])
+                                               ("cfg2:11000", 0.3, 128),
+                                               # the paper's own split of its language model: 2048
+                                               # experts of 8 neurons, router width 512 (prefill
+                                               # and small-token path)
+                                               ("gemma_paper:600", 0.5, 32),
+                                               ("gemma_paper:12", 0.5, 12)])
 def test_full_size_sampled(B, oracle, name, tau, n_sample):
     import torch
     cfg = wl.CONFIGS[name.split(":")[0]]
@@ -58,7 +63,8 @@ def test_full_size_sampled(B, oracle, name, tau, n_sample):
 
     # ---- sampled tokens against the oracle
     rng = np.random.default_rng(5)
-    idx = np.unique(np.concatenate([[0, 63, 64, cfg.T - 1], rng.choice(cfg.T, n_sample, replace=False)]))
+    idx = np.unique(np.concatenate([[i for i in (0, 63, 64, cfg.T - 1) if i < cfg.T],
+                                    rng.choice(cfg.T, min(n_sample, cfg.T), replace=False)]))
     ref_mask, _ = oracle.select(s[idx].astype(np.float64), tau32)
     assert np.array_equal(mask[idx], ref_mask)                         # bit-exact on the GPU's scores
     ref_s = oracle.router(x[idx], layer["r_w1"], layer["r_b1"], layer["r_w2"], layer["r_b2"])

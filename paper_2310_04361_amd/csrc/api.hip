@@ -314,7 +314,7 @@ int32_t dmoe_router(const dmoe_layer* layer, const void* x, int32_t n_tokens, fl
     if (!x || !scores) return fail(DMOE_ERR_NULL, "x or scores is NULL");
     hipStream_t s = (hipStream_t)stream;
     if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
-    else if (router_fused_supported(*layer))
+    else if (router_fused_scores_supported(*layer))
         launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, nullptr, s);
     else launch_router_bf16(*layer, x, n_tokens, scores, s);
     return check_launch("router");
@@ -421,8 +421,10 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
     uint64_t* mask = mask_out ? mask_out : reinterpret_cast<uint64_t*>(ws + w.mask);
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
     uint64_t* colmask = use_small_path(*layer, n_tokens) ? reinterpret_cast<uint64_t*>(ws + w.colmask) : nullptr;
-    const bool fused_router = layer->dtype == DMOE_BF16 && router_fused_supported(*layer);
-    if (fused_router && n_tokens > kSmallTokens && gate.top_k < 0) {
+    // the MFMA router takes any number of experts; with the gate fused in, up to 512
+    const bool fused_router = layer->dtype == DMOE_BF16 && router_fused_scores_supported(*layer);
+    const bool fused_gate = fused_router && router_fused_supported(*layer);
+    if (fused_gate && n_tokens > kSmallTokens && gate.top_k < 0) {
         // router, dynamic-k gate and group counts in one kernel
         launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, colmask, s);
     } else if (fused_router && colmask && gate.top_k < 0 &&

@@ -124,8 +124,10 @@ constexpr int kMaxExperts = 4096;  // the list fill keeps 2 ints per expert in L
 // ---- router (router.hip) ----------------------------------------------------------------------
 void launch_router_f32(const dmoe_layer& L, const float* x, int T, float* scores, hipStream_t s);
 void launch_router_bf16(const dmoe_layer& L, const void* x, int T, float* scores, hipStream_t s);
-// Fused router + gate + group counts (router_fused.hip); mask == nullptr runs the router alone.
+// Fused router + gate + group counts (router_fused.hip); mask == nullptr runs the router alone,
+// which has no limit on the number of experts (router_fused_scores_supported).
 bool router_fused_supported(const dmoe_layer& L);
+bool router_fused_scores_supported(const dmoe_layer& L);
 void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,
                          uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
                          uint64_t* colmask, hipStream_t s);

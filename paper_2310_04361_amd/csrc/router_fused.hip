@@ -154,49 +154,65 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     __syncthreads();
 
     // ---------------------------------------------------------------- stage 2
+    // scores of expert tile et for the group's 64 tokens: |R2 hid + c2| to `scores` and to o
+    auto score_tile = [&](int et, const bf16x8 (&a)[KS2], float (&o)[4][4]) {
+        f32x4 a2[4];
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) a2[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS2; ++ks) {
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const bf16x8 b = *reinterpret_cast<const bf16x8*>(
+                    hid + (16 * tt + c) * kHRow + ks * 64 + q * 16);
+                a2[tt] = mfma16(a[ks], b, a2[tt]);
+            }
+        }
+        const int e0 = 16 * et + 4 * q;  // this lane: experts e0 .. e0+3
+        float b2[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r_b2 && e0 < E) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) b2[r] = (float)r_b2[e0 + r];
+        }
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const int t = t0 + 16 * tt + c;
+            float4 out;
+            out.x = fabsf(a2[tt][0] + b2[0]);
+            out.y = fabsf(a2[tt][1] + b2[1]);
+            out.z = fabsf(a2[tt][2] + b2[2]);
+            out.w = fabsf(a2[tt][3] + b2[3]);
+            if (e0 >= E) out = make_float4(0.f, 0.f, 0.f, 0.f);  // padding experts
+            if (t < T && e0 < E) *reinterpret_cast<float4*>(scores + (size_t)t * E + e0) = out;
+            o[tt][0] = out.x; o[tt][1] = out.y; o[tt][2] = out.z; o[tt][3] = out.w;
+        }
+    };
+    if (!do_select) {
+        // router alone: any number of expert tiles, two per trip so that the fragments of the
+        // next tile are requested before the current one is multiplied
+        float o[4][4];
+        for (int et = w; et < NE; et += 8) {
+            load_r2(et + 4, r2a[1]);
+            score_tile(et, r2a[0], o);
+            load_r2(et + 8, r2a[0]);
+            if (et + 4 < NE) score_tile(et + 4, r2a[1], o);  // uniform per wavefront
+        }
+        return;
+    }
     float sc[ETW][4][4];  // [my tile][token tile][r]
     float vmax[4] = {0.f, 0.f, 0.f, 0.f};
-    // R2 fragments of the next tile are requested before the current one is multiplied
 #pragma unroll
     for (int j = 0; j < ETW; ++j) {
         const int et = w + 4 * j;
         if (j + 1 < ETW) load_r2(et + 4, r2a[(j + 1) & 1]);
         if (et < NE) {  // uniform per wavefront
-            f32x4 a2[4];
+            score_tile(et, r2a[j & 1], sc[j]);
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) a2[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS2; ++ks) {
-                const bf16x8 a = r2a[j & 1][ks];
-#pragma unroll
-                for (int tt = 0; tt < 4; ++tt) {
-                    const bf16x8 b = *reinterpret_cast<const bf16x8*>(
-                        hid + (16 * tt + c) * kHRow + ks * 64 + q * 16);
-                    a2[tt] = mfma16(a, b, a2[tt]);
-                }
-            }
-            const int e0 = 16 * et + 4 * q;  // this lane: experts e0 .. e0+3
-            float b2[4] = {0.f, 0.f, 0.f, 0.f};
-            if (r_b2 && e0 < E) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) b2[r] = (float)r_b2[e0 + r];
-            }
-#pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                const int t = t0 + 16 * tt + c;
-                float4 out;
-                out.x = fabsf(a2[tt][0] + b2[0]);
-                out.y = fabsf(a2[tt][1] + b2[1]);
-                out.z = fabsf(a2[tt][2] + b2[2]);
-                out.w = fabsf(a2[tt][3] + b2[3]);
-                if (e0 >= E) out = make_float4(0.f, 0.f, 0.f, 0.f);  // padding experts
-                if (t < T && e0 < E) *reinterpret_cast<float4*>(scores + (size_t)t * E + e0) = out;
-                sc[j][tt][0] = out.x; sc[j][tt][1] = out.y; sc[j][tt][2] = out.z; sc[j][tt][3] = out.w;
-                vmax[tt] = fmaxf(vmax[tt], fmaxf(fmaxf(out.x, out.y), fmaxf(out.z, out.w)));
-            }
+            for (int tt = 0; tt < 4; ++tt)
+                vmax[tt] = fmaxf(vmax[tt], fmaxf(fmaxf(sc[j][tt][0], sc[j][tt][1]),
+                                                 fmaxf(sc[j][tt][2], sc[j][tt][3])));
         }
     }
-    if (!do_select) return;
 
     // ---------------------------------------------------------------- select
     // maximum of each token over this wavefront's experts, then over the four wavefronts
@@ -274,7 +290,8 @@ void launch_t3(const dmoe_layer& L, const void* x, int T, float* scores, float t
                int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
     const PackedLayout P = packed_layout(L);
     const int E = L.n_experts, W = div_up(E, 64);
-    const size_t lds = 64 * (KBC * 128 + 16) + 64 * (NH * 32 + 16) + 256 * 4 + (size_t)5 * 64 * W * 8;
+    const size_t lds = 64 * (KBC * 128 + 16) + 64 * (NH * 32 + 16) + 256 * 4 +
+                       (mask ? (size_t)5 * 64 * W * 8 : 0);  // the gate's words only when it runs
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_fused_kernel<NH, ETW, KBC>),
@@ -370,7 +387,7 @@ __global__ __launch_bounds__(256) void router_small_scores_kernel(const SmallGro
 template <int NH>
 void launch_t(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
               int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
-    if (L.n_experts <= 128)
+    if (L.n_experts <= 128 || !mask)  // the router alone keeps no scores in registers
         launch_t2<NH, 2>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
     else if (L.n_experts <= 256)
         launch_t2<NH, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
@@ -398,10 +415,14 @@ void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
     router_small_scores_kernel<<<dim3(div_up(div_up(E, 16), 4), 1, n_layers), 256, 0, s>>>(G, T, dh, E);
 }
 
-bool router_fused_supported(const dmoe_layer& L) {
+bool router_fused_scores_supported(const dmoe_layer& L) {
     const int dh = L.router_hidden;
     return L.packed != nullptr && (dh == 64 || dh == 128 || dh == 256 || dh == 512) &&
-           L.d_model % 256 == 0 && L.n_experts % 4 == 0 && L.n_experts <= 64 * kMaxTilesPerWave;
+           L.d_model % 256 == 0 && L.n_experts % 4 == 0;
+}
+
+bool router_fused_supported(const dmoe_layer& L) {
+    return router_fused_scores_supported(L) && L.n_experts <= 64 * kMaxTilesPerWave;
 }
 
 void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,

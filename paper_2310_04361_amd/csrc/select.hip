@@ -1,7 +1,7 @@
 // Dynamic-k gate and per-expert bucketing (Sec. 3.4 Eq. 4; the metadata of Appendix C built by
 // dedicated kernels instead of a full argsort).
 //
-// Data flow:  scores -> [mask_count] -> mask bits + per-(group, expert) counts
+// Data flow:  scores -> [tau_mask | topk_mask, count_from_mask] -> mask bits + per-(group, expert) counts
 //             -> [scan_groups] prefix over token groups per expert
 //             -> [fill] prefix over experts (list offsets, up-projection work items) and the
 //                ascending per-expert token lists, compact and work-item aligned.
@@ -29,84 +29,38 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
     return v;
 }
 
-// One wavefront per group of 64 tokens, lane = token.
-// FROM_SCORES: evaluate Eq. 4 on the token's score row and write its mask words;
-// otherwise read the mask words.  Either way, count, for every expert, the tokens of the group
-// that keep it (ballot transpose) into group_cnt[g][e]; colmask[g][e], if wanted, receives the
-// 64-bit set of those tokens itself.
-template <bool FROM_SCORES>
-__global__ __launch_bounds__(256) void mask_count_kernel(const float* __restrict__ scores,
-                                                         uint64_t* __restrict__ mask,
-                                                         int32_t* __restrict__ k_per_token,
-                                                         int32_t* __restrict__ group_cnt,
-                                                         uint64_t* __restrict__ colmask, int T,
-                                                         int E, int W, float tau) {
+// Per-group expert counts from the mask words: one wavefront per (group of 64 tokens, mask word),
+// lane = token.  The ballot transpose gives, for every expert of the word, the 64-bit set of the
+// group's tokens that keep it: its population count goes to group_cnt[g][e], the set itself to
+// colmask[g][e] if wanted.
+__global__ __launch_bounds__(256) void count_from_mask_kernel(const uint64_t* __restrict__ mask,
+                                                              int32_t* __restrict__ group_cnt,
+                                                              uint64_t* __restrict__ colmask,
+                                                              int T, int E, int W) {
     const int lane = lane_id();
-    const int g = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int NG = (T + kGroup - 1) / kGroup;
+    const int g = wave / W, w = wave - g * W;
     if (g >= NG) return;  // uniform per wavefront
     const int t = g * kGroup + lane;
-    const bool valid = t < T;
-    const float* row = scores + (size_t)(valid ? t : 0) * E;
-
-    double thr = 0.0;
-    if (FROM_SCORES) {
-        float mx = -INFINITY;
-        if (valid) {
-            if ((E & 3) == 0) {
-                const float4* r4 = reinterpret_cast<const float4*>(row);
-                for (int i = 0; i < E / 4; ++i) {
-                    float4 v = r4[i];
-                    mx = fmaxf(mx, fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w)));
-                }
-            } else {
-                for (int i = 0; i < E; ++i) mx = fmaxf(mx, row[i]);
-            }
-        }
-        // exact: the fp64 product of two fp32 values carries at most 48 significant bits
-        thr = (double)tau * (double)mx;
-    }
-
-    int kt = 0;
-    for (int w = 0; w < W; ++w) {
-        uint64_t word = 0;
-        const int nb = min(64, E - 64 * w);
-        if (FROM_SCORES) {
-            if (valid) {
-                if (tau == 0.0f) {
-                    word = nb == 64 ? ~0ull : ((1ull << nb) - 1ull);
-                } else {
-                    for (int b = 0; b < nb; ++b) {
-                        const double s = (double)row[64 * w + b];
-                        word |= (uint64_t)(s >= thr) << b;
-                    }
-                }
-                mask[(size_t)t * W + w] = word;
-            }
-        } else {
-            if (valid) word = mask[(size_t)t * W + w];
-        }
-        kt += __popcll(word);
-        uint64_t col = 0;  // lane b: which tokens of the group keep expert 64w + b
+    const uint64_t word = t < T ? mask[(size_t)t * W + w] : 0ull;
+    uint64_t col = 0;  // lane b: which tokens of the group keep expert 64w + b
 #pragma unroll 8
-        for (int b = 0; b < 64; ++b) {
-            const uint64_t bal = __ballot((word >> b) & 1ull);
-            if (lane == b) col = bal;
-        }
-        const int e = 64 * w + lane;
-        if (e < E) {
-            group_cnt[(size_t)g * E + e] = __popcll(col);
-            if (colmask) colmask[(size_t)g * E + e] = col;
-        }
+    for (int b = 0; b < 64; ++b) {
+        const uint64_t bal = __ballot((word >> b) & 1ull);
+        if (lane == b) col = bal;
     }
-    if (valid && k_per_token) k_per_token[t] = kt;
+    const int e = 64 * w + lane;
+    if (e < E) {
+        group_cnt[(size_t)g * E + e] = __popcll(col);
+        if (colmask) colmask[(size_t)g * E + e] = col;
+    }
 }
 
 // Dynamic-k gate (Sec. 3.4 Eq. 4) with one wavefront per token and the lanes striding the
 // experts: the score row is read coalesced, the maximum is a wavefront reduction and a ballot IS
 // a mask word.  The per-group expert counts are then taken from the mask words by
-// mask_count_kernel<false>.  (The lane-per-token form above reads 64 rows at once, 16 bytes of
-// each: fine inside the fused router where the scores sit in registers, slow from memory.)
+// count_from_mask_kernel.
 __global__ __launch_bounds__(256) void tau_mask_kernel(const float* __restrict__ scores,
                                                        uint64_t* __restrict__ mask,
                                                        int32_t* __restrict__ k_per_token, int T,
@@ -139,8 +93,9 @@ __global__ __launch_bounds__(256) void tau_mask_kernel(const float* __restrict__
 // then admitted in index order until k are reached.  CH = ceil(E / 64) values per lane.
 template <int CH>
 __global__ __launch_bounds__(256) void topk_mask_kernel(const float* __restrict__ scores,
-                                                        uint64_t* __restrict__ mask, int T, int E,
-                                                        int W, int k) {
+                                                        uint64_t* __restrict__ mask,
+                                                        int32_t* __restrict__ k_per_token, int T,
+                                                        int E, int W, int k) {
     const int lane = lane_id();
     const int t = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     if (t >= T) return;  // uniform per wavefront
@@ -170,6 +125,7 @@ __global__ __launch_bounds__(256) void topk_mask_kernel(const float* __restrict_
 #pragma unroll
     for (int c = 0; c < CH; ++c) above += __popcll(__ballot(key[c] > x));
     int need = k - above;  // how many of the experts equal to x are admitted, lowest index first
+    int kt = 0;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
         const int e = 64 * c + lane;
@@ -178,8 +134,10 @@ __global__ __launch_bounds__(256) void topk_mask_kernel(const float* __restrict_
         const bool take = eq && __popcll(eqb & ((1ull << lane) - 1ull)) < need;
         const uint64_t word = __ballot(k > 0 && ((key[c] > x && e < E) || take));
         need -= min(need, __popcll(eqb));
+        if (c < W) kt += __popcll(word);
         if (lane == 0 && c < W) mask[(size_t)t * W + c] = word;
     }
+    if (lane == 0 && k_per_token) k_per_token[t] = kt;
 }
 
 // T <= 16: one workgroup, wavefront t = token t with lanes striding the experts, so the score row
@@ -199,7 +157,7 @@ __device__ __forceinline__ void select_small_body(const float* __restrict__ scor
         for (int e = lane; e < E; e += kWave) mx = fmaxf(mx, row[e]);
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-        const double thr = (double)tau * (double)mx;  // exact, see mask_count_kernel
+        const double thr = (double)tau * (double)mx;  // exact, see tau_mask_kernel
         int kt = 0;
         for (int w = 0; w < W; ++w) {
             const int e = 64 * w + lane;
@@ -496,8 +454,7 @@ void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint6
         return;
     }
     tau_mask_kernel<<<div_up(T, 4), 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, nullptr, group_off,
-                                                           colmask, T, E, W, 0.0f);
+    count_from_mask_kernel<<<div_up(NG * W, 4), 256, 0, s>>>(mask, group_off, colmask, T, E, W);
 }
 
 void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_layers, int T,
@@ -535,8 +492,7 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
                                                   reinterpret_cast<unsigned long long*>(mask));
     }
     LaunchTimer tm(kSlotMask, s);
-    mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, nullptr, group_off,
-                                                           colmask, T, E, W, 0.0f);
+    count_from_mask_kernel<<<div_up(NG * W, 4), 256, 0, s>>>(mask, group_off, colmask, T, E, W);
 }
 
 void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
@@ -544,16 +500,15 @@ void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     LaunchTimer tm(kSlotMask, s);
     const int grid = div_up(T, 4);
-    if (W <= 1) topk_mask_kernel<1><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
-    else if (W <= 2) topk_mask_kernel<2><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
-    else if (W <= 4) topk_mask_kernel<4><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
-    else if (W <= 8) topk_mask_kernel<8><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
-    else if (W <= 16) topk_mask_kernel<16><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
-    else if (W <= 32) topk_mask_kernel<32><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
-    else topk_mask_kernel<64><<<grid, 256, 0, s>>>(scores, mask, T, E, W, k);
-    // counts per (group, expert), the per-token counts and, if wanted, the per-expert token sets
-    mask_count_kernel<false><<<div_up(NG, 4), 256, 0, s>>>(nullptr, mask, k_per_token, group_off,
-                                                           colmask, T, E, W, 0.0f);
+    if (W <= 1) topk_mask_kernel<1><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 2) topk_mask_kernel<2><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 4) topk_mask_kernel<4><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 8) topk_mask_kernel<8><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 16) topk_mask_kernel<16><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 32) topk_mask_kernel<32><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    else topk_mask_kernel<64><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    // counts per (group, expert) and, if wanted, the per-expert token sets
+    count_from_mask_kernel<<<div_up(NG * W, 4), 256, 0, s>>>(mask, group_off, colmask, T, E, W);
 }
 
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,

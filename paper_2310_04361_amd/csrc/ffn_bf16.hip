@@ -111,6 +111,28 @@ __global__ void pack_up_kernel(const void* __restrict__ w, const float* __restri
     }
 }
 
+// Gated experts of m <= 8 neurons: w_up, w_gate [E][m][d] -> wt[E][d/32][64][8], one 16-row tile
+// per expert and k-step whose rows 0..7 are the up rows and 8..15 the gate rows (zero rows for
+// neurons >= m); lane (q, c) holds row c, columns 32 kstep + 8q + s.
+__global__ void pack_up_tiny_kernel(const void* __restrict__ w_up, const void* __restrict__ w_gate,
+                                    const float* __restrict__ scales, int fp8,
+                                    __bf16* __restrict__ wt, int E, int m, int d) {
+    const size_t n = (size_t)E * 16 * d;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        const int s = (int)(i & 7), lane = (int)((i >> 3) & 63);
+        const size_t f = i >> 9;
+        const int kstep = (int)(f % (d / 32));
+        const int e = (int)(f / (d / 32));
+        const int q = lane >> 4, c = lane & 15;
+        const int neuron = c & 7, which = c >> 3;  // 0 up, 1 gate
+        wt[i] = packed_weight<__bf16>(which ? w_gate : w_up, scales, fp8, which, e,
+                                      ((size_t)e * m + min(neuron, m - 1)) * d + 32 * kstep + 8 * q + s,
+                                      neuron < m);
+    }
+}
+
 // ---- up-projection ---------------------------------------------------------------------------------
 // One wavefront per work item = (expert, UR = 16*TT consecutive list rows); no workgroup-level
 // synchronisation after the work-item table has been staged.  MT = m_pad / 16 neuron tiles per
@@ -272,6 +294,132 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
                 }
                 *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
             }
+        }
+    }
+    }  // windows
+}
+
+// Up-projection for gated experts of at most 8 neurons (thousands of tiny experts, Sec. 5 language
+// model split).  In the general kernel such an expert fills a quarter of the rows of four weight
+// tiles; here its up rows and gate rows share ONE 16-row tile, so a work item streams a quarter of
+// the weight bytes and issues a quarter of the MFMAs, and what remains is the gather of the x
+// rows.  Same work items, same x staging, same H rows (pieces 1..3 of the 32-neuron row are
+// written as zeros) as up_bf16_kernel<2, true, TT>.
+template <int TT>
+__global__ __launch_bounds__(256) void up_tiny_kernel(
+    const __bf16* __restrict__ x, const __bf16* __restrict__ wtf, const int32_t* __restrict__ witem,
+    const int32_t* __restrict__ wfirst, int NW, const int32_t* __restrict__ alist,
+    __bf16* __restrict__ Hf, int d, int E, int m, int act) {
+    constexpr int UR = TT * 16;
+    constexpr int NL = TT * 2;
+    extern __shared__ char smem[];
+    int32_t* s_wit = reinterpret_cast<int32_t*>(smem);
+    int32_t* s_wf = s_wit + (E + 1);
+    const int items_bytes = ((2 * E + 1) * 4 + 15) & ~15;
+    const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15;
+    const int wave_in_block = threadIdx.x >> 6;
+    char* xs = smem + items_bytes + wave_in_block * (2 * UR * kUpRowBytes);
+    const int NK32 = d / 32, NKB = d / 64;
+    const int ld_row = lane >> 3, ld_piece = lane & 7;
+
+    const bool windowed = NW > 1;
+    const int wg = windowed ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int n_wg = windowed ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    const int wave = wg * (blockDim.x >> 6) + wave_in_block;
+    const int n_waves = n_wg * (blockDim.x >> 6);
+    for (int wdx = windowed ? (int)(blockIdx.x & 7) : 0; wdx < NW; wdx += 8) {
+    __syncthreads();  // the previous window's table is no longer read
+    for (int i = threadIdx.x; i <= 2 * E; i += blockDim.x)
+        s_wit[i] = i <= E ? witem[(size_t)wdx * (E + 1) + i] : wfirst[(size_t)wdx * E + (i - E - 1)];
+    __syncthreads();
+    const int total = s_wit[E];
+    for (int j = wave; j < total; j += n_waves) {
+        int lo = 0, hi = E;  // last e with s_wit[e] <= j
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s_wit[mid] <= j) lo = mid; else hi = mid;
+        }
+        const int e = lo;
+        const int item = s_wf[e] + (j - s_wit[e]);
+        const int32_t* tl = alist + (size_t)item * UR + ld_row;
+        const __bf16* xrow[NL];
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const int tok = max(tl[8 * i], 0);  // padding rows (-1) read token 0
+            xrow[i] = x + (size_t)tok * d + 8 * ld_piece;
+        }
+        const __bf16* wf = wtf + (size_t)e * NK32 * 512 + lane * 8;
+
+        f32x4 acc[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) acc[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        bf16x8 xr[NL];
+        bf16x8 a0[2], a1[2];
+        auto load_x = [&](int kb) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) xr[i] = load8(xrow[i] + 64 * kb);
+        };
+        auto load_a = [&](int kb, bf16x8 (&a)[2]) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) a[ks] = load8(wf + (size_t)(2 * kb + ks) * 512);
+        };
+        auto store_x = [&](int buf) {
+            char* dst = xs + buf * (UR * kUpRowBytes) + ld_row * kUpRowBytes + ld_piece * 16;
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
+        };
+        auto compute = [&](int buf, const bf16x8 (&a)[2]) {
+            const char* src = xs + buf * (UR * kUpRowBytes) + c * kUpRowBytes + q * 16;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const bf16x8 b =
+                        *reinterpret_cast<const bf16x8*>(src + tt * 16 * kUpRowBytes + ks * 64);
+                    acc[tt] = mfma16(a[ks], b, acc[tt]);
+                }
+        };
+
+        load_x(0);
+        load_a(0, a0);
+        store_x(0);
+        for (int kb = 0; kb < NKB; kb += 2) {
+            load_x(kb + 1);
+            load_a(kb + 1, a1);
+            compute(0, a0);
+            store_x(1);
+            const int nb = min(kb + 2, NKB - 1);  // the last trip re-reads a block it will not use
+            load_x(nb);
+            load_a(nb, a0);
+            compute(1, a1);
+            store_x(0);
+        }
+
+        // lane (q, c) of token tile tt holds tile rows 4q + r of list row 16tt + c: q = 0, 1 the up
+        // products of neurons 4q + r, q = 2, 3 the gate products of neurons 4(q - 2) + r
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            float v[4], w[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float other = __shfl_xor(acc[tt][r], 32, 64);  // q <-> q ^ 2
+                const float up = q < 2 ? acc[tt][r] : other;
+                const float gate = q < 2 ? other : acc[tt][r];
+                v[r] = activate_fast(act, gate) * up;
+                if (4 * (q & 1) + r >= m) v[r] = 0.0f;
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) w[r] = __shfl_xor(v[r], 16, 64);  // q = 0 receives neurons 4..7
+            bf16x8 hv;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                hv[r] = (__bf16)(q == 0 ? v[r] : 0.0f);
+                hv[4 + r] = (__bf16)(q == 0 ? w[r] : 0.0f);
+            }
+            // piece q of the 32-neuron H row: piece 0 = neurons 0..7, the others padding
+            *reinterpret_cast<bf16x8*>(Hf + ((size_t)item * UR + 16 * tt + c) * 32 + 8 * q) = hv;
         }
     }
     }  // windows
@@ -475,6 +623,9 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     if (L.gated)
         pack_up_kernel<__bf16><<<2048, 256, 0, s>>>(L.w_gate, L.w_scales, fp8, 1,
                                                     (__bf16*)(pk + P.wgatef), E, m, d, mp / 16, 1);
+    if (up_tiny_supported(L))
+        pack_up_tiny_kernel<<<2048, 256, 0, s>>>(L.w_up, L.w_gate, L.w_scales, fp8,
+                                                 (__bf16*)(pk + P.wtinyf), E, m, d);
     if (fp8) {  // byte fragments for the small-token kernels
         pack_down_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_down, L.w_scales, 1, (uint8_t*)(pk + P.w2f8),
                                                        E, m, d, mp / 32);
@@ -524,6 +675,22 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
             (int)std::min<long long>((long long)T * L.n_experts / 256 + L.n_experts, 512), 8);
         if (L.gated) launch_up_wide_t<4, true, 4>(L, x, P, witem, wfirst, NW, alist, H, wgrid, s);
         else launch_up_wide_t<8, false, 4>(L, x, P, witem, wfirst, NW, alist, H, wgrid, s);
+        return;
+    }
+    if (up_tiny_supported(L)) {
+        constexpr int TT = 4;
+        const size_t lds = ((2 * (size_t)L.n_experts + 1) * 4 + 15) / 16 * 16 +
+                           4 * 2 * (size_t)TT * 16 * kUpRowBytes;
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            attr_set = true;
+        }
+        const char* pk = static_cast<const char*>(L.packed);
+        up_tiny_kernel<TT><<<grid, 256, lds, s>>>((const __bf16*)x, (const __bf16*)(pk + P.wtinyf),
+                                                  witem, wfirst, NW, alist, (__bf16*)H, L.d_model,
+                                                  L.n_experts, L.expert_size, L.act);
         return;
     }
     if (L.gated) {

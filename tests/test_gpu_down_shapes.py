@@ -38,7 +38,11 @@ ONE_PER_CU = [(300, 256, 20, m, False) for m in (8, 16, 24, 32, 40, 48, 64, 100,
              [(200, 256, 70, 24, False)] + \
              [(200, 256, E, 24, False) for E in (1, 3, 5, 33, 65, 130, 300)] + \
              [(200, 256, E, 64, False) for E in (1, 33, 100)] + \
-             [(128, 256, 2048, 8, False), (96, 512, 4096, 16, True)]   # many small experts (the largest count)
+             [(128, 256, 2048, 8, False), (96, 512, 4096, 16, True)] + \
+             [(300, 256, 37, m, True) for m in (1, 3, 5, 8)] + \
+             [(1000, 512, 600, 8, True)]
+# (many small experts up to the largest count; gated experts of at most 8 neurons take the
+# up-projection kernel that keeps an expert's up and gate rows in one weight tile)
 # 384-column workgroups: d = 768 and 10880 < T <= 16384
 WIDE = [(11000, 768, 16, m, False) for m in (16, 32, 48, 64, 128)] + [(12000, 768, 12, 32, True)]
 # more narrow workgroups than CUs (two per CU up to 4 k-steps per stage, else several rounds)

@@ -12,8 +12,8 @@
 //
 // Dense k-packing.  An H row is a sequence of 16-byte pieces of eight consecutive neurons; an
 // expert of m neurons fills PG = ceil(m / 8) of them.  The MFMA k-step is 16 = two pieces, and
-// the pieces of G consecutive experts (a "stage": G = 2 when PG is odd) are laid end to end, so
-// that a stage takes KSP = G * PG / 2 k-steps with no padded neurons: lane half h of k-step s
+// the pieces of G consecutive experts (a "stage": G = 2 when PG is odd or 2, G = 4 when PG = 1)
+// are laid end to end, so that a stage takes KSP = G * PG / 2 k-steps with no padded neurons: lane half h of k-step s
 // works on piece 2s + h of the stage.  Experts of 24 neurons cost 3 k-steps per pair instead of
 // 4.  The two halves of one k-step may thus belong to different experts, each with its own
 // selection.
@@ -60,14 +60,15 @@ struct DownPacking {
     int PG, G, KSP;
 };
 DownPacking down_packing(int m) {
-    static const int kCounts[] = {2, 3, 4, 6, 8, 16};  // H rows are 32, 64 or 128 neurons wide
+    static const int kCounts[] = {1, 2, 3, 4, 6, 8, 16};  // H rows are 32, 64 or 128 neurons wide
     int pg = div_up(m, 8);
     for (int v : kCounts)
         if (pg <= v) {
             pg = v;
             break;
         }
-    const int g = (pg == 2 || (pg & 1)) ? 2 : 1;  // an even number of pieces, at least two k-steps
+    // an even number of pieces, at least two k-steps
+    const int g = pg == 1 ? 4 : ((pg == 2 || (pg & 1)) ? 2 : 1);
     return DownPacking{pg, g, g * pg / 2};
 }
 
@@ -316,8 +317,9 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
                     acc[j][ct] = mfma32(aw[q % R][ct], bb[q & 1][j], acc[j][ct]);
                     __builtin_amdgcn_sched_barrier(0);
                     if (ks == 0) {
-                        if (n == 0) build_prepare(sh_base + i * G, 0);
-                        if (n == 1 && G == 2) build_prepare(sh_base + i * G + 1, G - 1);
+#pragma unroll
+                        for (int eo = 0; eo < G; ++eo)  // G <= 4: before the first fetch below
+                            if (n == eo) build_prepare(sh_base + i * G + eo, eo);
 #pragma unroll
                         for (int s = 1; s < KSP; ++s)
                             if (n == (s - 1) % 2) write_piece(ni, s, breg[ni]);
@@ -458,7 +460,8 @@ void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
         if (wide) DMOE_DOWN(KSP_, G_, RW_, 1, 3); \
         else DMOE_DOWN(KSP_, G_, R1_, 1, 2);      \
     } while (0)
-    if (dp.KSP == 2 && dp.G == 2) DMOE_DOWN_BY_GRID(2, 2, 8, 8, 4);
+    if (dp.KSP == 2 && dp.G == 4) DMOE_DOWN_BY_GRID(2, 4, 8, 8, 4);
+    else if (dp.KSP == 2 && dp.G == 2) DMOE_DOWN_BY_GRID(2, 2, 8, 8, 4);
     else if (dp.KSP == 2) DMOE_DOWN_BY_GRID(2, 1, 8, 8, 4);
     else if (dp.KSP == 3 && dp.G == 2) DMOE_DOWN_BY_GRID(3, 2, 12, 12, 4);
     else if (dp.KSP == 3) DMOE_DOWN_BY_GRID(3, 1, 12, 12, 4);

@@ -349,7 +349,10 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
     }
     __syncthreads();
 
-    if (blockIdx.x == 0) {
+    // gridDim.y workgroups share the mask words of one group; those with y = 0 also do the
+    // per-launch work
+    const bool first_y = blockIdx.y == 0;
+    if (blockIdx.x == 0 && first_y) {
         for (int e = tid; e <= E; e += 256) {
             offsets[e] = s_off[e];
             if (item_start) item_start[e] = s_item[e];
@@ -360,7 +363,7 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
     // the work items of expert e that window w works on are wfirst[w][e] .. + n (those whose
     // rows mostly belong to tokens of the window); witem[w][e] is the exclusive prefix of n over
     // the experts.
-    if (witem && (int)blockIdx.x < NW) {
+    if (witem && (int)blockIdx.x < NW && first_y) {
         const int wdx = blockIdx.x;
         const int32_t* r_lo = group_off + (size_t)(wdx * GW) * E;
         const int32_t* r_hi = group_off + (size_t)min(wdx * GW + GW, NG) * E;
@@ -400,7 +403,7 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
         }
         if (tid == 0) witem[(size_t)wdx * (E + 1) + E] = wcarry;
     }
-    if (alist) {  // -1 behind each expert's last token, up to its next work-item boundary
+    if (alist && first_y) {  // -1 behind each expert's last token, up to its next work-item boundary
         for (int i = blockIdx.x * 256 + tid; i < E * rows_per_item; i += gridDim.x * 256) {
             const int e = i / rows_per_item, j = i % rows_per_item;
             const int p = s_item[e] * rows_per_item + totals[e] + j;
@@ -415,7 +418,7 @@ __global__ __launch_bounds__(256) void fill_lists_kernel(
     const int t = g * kGroup + lane;
     const bool valid = t < T;
     const uint64_t below = (1ull << lane) - 1ull;
-    for (int w = 0; w < W; ++w) {
+    for (int w = blockIdx.y; w < W; w += gridDim.y) {
         const uint64_t word = valid ? mask[(size_t)t * W + w] : 0ull;
         // lane b keeps the three bases of expert 64w + b; b is uniform in the loop below, so each
         // read of them is a broadcast through the scalar unit
@@ -529,7 +532,10 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         attr_set = true;
     }
-    fill_lists_kernel<<<std::max(1, NG), 256, lds, s>>>(
+    // with few token groups and many experts the mask words of a group are split over several
+    // workgroups (each repeats the prefix sums over the experts)
+    const int ny = NG >= 256 ? 1 : std::min(W, div_up(512, std::max(1, NG)));
+    fill_lists_kernel<<<dim3(std::max(1, NG), ny), 256, lds, s>>>(
         mask, T, E, W, group_off, rows_per_item, counts, offsets, item_start, token_lists,
         aligned_lists, window_groups, NW, witem, wfirst);
 }

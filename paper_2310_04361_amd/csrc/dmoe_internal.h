@@ -16,7 +16,12 @@ constexpr int kTilePad = 64;      // entries the expert kernels may read past th
 
 inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 inline int div_up(int a, int b) { return (a + b - 1) / b; }
-inline int m_pad_of(int m) { return round_up(m, 32); }
+// Hidden units per H row: 32, 64 or 128 (the widths the expert kernels are compiled for), so
+// experts of 65 .. 96 neurons take 128.
+inline int m_pad_of(int m) {
+    const int p = round_up(m, 32);
+    return p == 96 ? 128 : p;
+}
 
 // List rows per up-projection work item (a multiple of 16); every expert's region of H starts
 // at a multiple of this many rows.

@@ -33,7 +33,7 @@ def _cfg(T, d, E, m, gated):
 # one narrow workgroup per CU (few tokens): every k-step packing, plain and gated; expert counts
 # from 1 up, not multiples of the 32-expert mask batch or of the 4-stage loop trip, and beyond
 # several batches
-ONE_PER_CU = [(300, 256, 20, m, False) for m in (8, 16, 24, 32, 40, 48, 64, 100, 128)] + \
+ONE_PER_CU = [(300, 256, 20, m, False) for m in (8, 16, 24, 32, 40, 48, 64, 72, 96, 100, 128)] + \
              [(300, 256, 37, m, True) for m in (16, 32, 48, 64)] + \
              [(200, 256, 70, 24, False)] + \
              [(200, 256, E, 24, False) for E in (1, 3, 5, 33, 65, 130, 300)] + \

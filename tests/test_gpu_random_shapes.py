@@ -1,0 +1,81 @@
+"""Whole bf16 layers of seeded random shapes against the oracle (Sec. 3.2 - 3.4, Appendix G).
+
+The benchmark configurations and the per-kernel shape tests fix one parameter at a time; here
+every case draws all of them together -- token count (small-token path, a ragged few hundred,
+over a thousand), width, number and size of experts, router width, gated or plain experts,
+biases, threshold or top-k gate -- so that combinations nobody listed by hand are exercised.
+The gate is checked bit for bit on the library's own fp32 scores, the lists against the mask,
+and the output of sampled tokens against the oracle's experts on that mask."""
+import numpy as np
+import pytest
+
+from helpers import TOL, oracle_ffn, tokenwise_rel_err
+from paper_2310_04361_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+N_CASES = 72
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2310_04361_amd import binding
+    binding.lib()
+    return binding
+
+
+def draw_case(i):
+    rng = np.random.default_rng(1000 + i)
+    gated = bool(rng.integers(2))
+    T = int((rng.integers(1, 17), rng.integers(17, 400), rng.integers(400, 1600))[i % 3])
+    d = int(rng.choice([256, 512, 768, 1024]))
+    E = 4 * int(rng.integers(1, 60)) if i % 5 else 4 * int(rng.integers(100, 300))
+    m = int(rng.integers(1, 65 if gated else 129))
+    if i % 4 == 1:
+        m = int(rng.integers(1, 17))  # small experts: the packings with several experts per stage
+    d_h = int(rng.choice([32, 64, 128, 256]))
+    act = "gelu_tanh" if gated else str(rng.choice(["relu", "gelu_erf", "gelu_tanh"]))
+    cfg = wl.Config(f"rand{i}", T, d, E, m, d_h, gated, act, "bf16", (0.5,),
+                    ffn_bias=(not gated) and bool(rng.integers(2)),
+                    router_bias=bool(rng.integers(2)))
+    tau = float(np.float32(rng.choice([0.0, 0.2, 0.5, 0.8, 0.95])))
+    k = int(rng.integers(1, E + 1)) if i % 7 == 3 else None
+    return cfg, tau, k
+
+
+@pytest.mark.parametrize("i", range(N_CASES))
+def test_random_layer_matches_oracle(B, oracle, i):
+    import torch
+    cfg, tau, k = draw_case(i)
+    print(f"random layer {i}: T={cfg.T} d={cfg.d} E={cfg.E} m={cfg.m} d_h={cfg.d_h} "
+          f"gated={cfg.gated} act={cfg.act} ffn_bias={cfg.ffn_bias} router_bias={cfg.router_bias} "
+          f"tau={tau} k={k}", flush=True)
+    layer, x = wl.make_layer(cfg, i), wl.make_input(cfg, i)
+    L = B.Layer(layer, cfg.dtype)
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau, want_scores=True, want_mask=True,
+                           want_lists=True, top_k=k)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy()
+    assert np.isfinite(s).all() and (s >= 0).all()
+    if k is None:
+        ref_mask, _ = oracle.select(s.astype(np.float64), tau)
+    else:
+        ref_mask = oracle.select_topk(s.astype(np.float64), k)
+    got_mask = B.mask_bits_to_bool(ex["mask_bits"], cfg.E)
+    assert np.array_equal(got_mask, ref_mask)
+    offsets = ex["offsets"].cpu().numpy()
+    lists = ex["token_lists"].cpu().numpy()
+    assert offsets[0] == 0 and offsets[-1] == ref_mask.sum()
+    for e in range(cfg.E):
+        assert lists[offsets[e]:offsets[e + 1]].tolist() == np.flatnonzero(ref_mask[:, e]).tolist()
+    got = B.from_device(y, cfg.dtype)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(i)
+    idx = np.unique(np.concatenate([[t for t in (0, 15, 16, 63, 64, 127, 128, cfg.T - 1) if t < cfg.T],
+                                    rng.choice(cfg.T, min(48, cfg.T), replace=False)]))
+    ref_y = oracle_ffn(oracle, layer, x[idx], ref_mask[idx])
+    err = tokenwise_rel_err(got[idx], ref_y)
+    print(f"  density={ref_mask.mean():.3f} err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]

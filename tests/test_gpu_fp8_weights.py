@@ -22,7 +22,8 @@ def B():
 
 
 @pytest.mark.parametrize("name,T,E", [("cfg5b", 16, None), ("cfg5b", 3, None), ("cfg5a", 16, 64),
-                                      ("cfg2", 300, 32), ("cfg4", 200, 16), ("paper", 150, None)])
+                                      ("cfg2", 300, 32), ("cfg4", 200, 16), ("paper", 150, None),
+                                      ("gemma_paper", 200, 64), ("gemma_paper", 9, 64)])
 def test_forward_with_e4m3_weights(B, oracle, name, T, E):
     import torch
     cfg = small_cfg(name, T, E)

@@ -3,7 +3,7 @@
 The benchmark configurations and the per-kernel shape tests fix one parameter at a time; here
 every case draws all of them together -- token count (small-token path, a ragged few hundred,
 over a thousand), width, number and size of experts, router width, gated or plain experts,
-biases, threshold or top-k gate -- so that combinations nobody listed by hand are exercised.
+biases, threshold or top-k gate, bf16 or 8-bit expert weights -- so that combinations nobody listed by hand are exercised.
 The gate is checked bit for bit on the library's own fp32 scores, the lists against the mask,
 and the output of sampled tokens against the oracle's experts on that mask."""
 import numpy as np
@@ -42,17 +42,19 @@ def draw_case(i):
                     router_bias=bool(rng.integers(2)))
     tau = float(np.float32(rng.choice([0.0, 0.2, 0.5, 0.8, 0.95])))
     k = int(rng.integers(1, E + 1)) if i % 7 == 3 else None
-    return cfg, tau, k
+    return cfg, tau, k, i % 6 == 2   # every sixth layer stores its expert matrices in E4M3
 
 
 @pytest.mark.parametrize("i", range(N_CASES))
 def test_random_layer_matches_oracle(B, oracle, i):
     import torch
-    cfg, tau, k = draw_case(i)
+    cfg, tau, k, e4m3 = draw_case(i)
     print(f"random layer {i}: T={cfg.T} d={cfg.d} E={cfg.E} m={cfg.m} d_h={cfg.d_h} "
           f"gated={cfg.gated} act={cfg.act} ffn_bias={cfg.ffn_bias} router_bias={cfg.router_bias} "
-          f"tau={tau} k={k}", flush=True)
+          f"tau={tau} k={k} e4m3={e4m3}", flush=True)
     layer, x = wl.make_layer(cfg, i), wl.make_input(cfg, i)
+    if e4m3:  # the oracle gets the dequantised weights, which are bf16 numbers
+        layer = wl.quantize_experts_e4m3(layer)
     L = B.Layer(layer, cfg.dtype)
     y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau, want_scores=True, want_mask=True,
                            want_lists=True, top_k=k)

@@ -237,8 +237,11 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
         void* H = ws + w.H;
         launch_up_bf16(L, x, T, witem, wfirst, alist, H, s);
         const long long max_sparse = down_max_pairs_sparse(L, T);
-        launch_down_rmw_bf16(L, T, item_start, group_off, alist, offsets, H, y, max_sparse, s);
-        launch_down_bf16(L, T, item_start, group_off, mask, offsets, H, y, max_sparse, s);
+        // both are launched and the pair count on the device decides, unless the limit already does
+        if (max_sparse > 0)
+            launch_down_rmw_bf16(L, T, item_start, group_off, alist, offsets, H, y, max_sparse, s);
+        if (max_sparse != 0x7fffffffffffffffLL)
+            launch_down_bf16(L, T, item_start, group_off, mask, offsets, H, y, max_sparse, s);
     }
     return check_launch("expert kernels");
 }

@@ -231,12 +231,15 @@ void launch_down_rmw_t(const dmoe_layer& L, const PackedLayout& P, int T, const 
 
 }  // namespace
 
-// Density (executed pairs / (T * E)) up to which the pair-proportional kernel is the faster one:
-// measured crossovers, about 0.05 for 32-neuron rows of H and 0.08 for wider ones.  Sizes that
-// the matrix-core kernel cannot address all go to this one.
+// Density (executed pairs / (T * E)) up to which the pair-proportional kernel is the faster one.
+// Measured crossovers: about 0.03 for H rows of 64 or 128 neurons (4096 tokens x 256 gated
+// experts of 64, d = 2048; 50432 tokens x 24 experts of 128, d = 768); with 32-neuron rows the
+// matrix-core kernel wins at every density (16384 tokens x 128 experts of 24: 59 us against 81 us
+// at 1 %), so this kernel is not launched there at all.  Sizes that the matrix-core kernel
+// cannot address all go to this one.
 long long down_max_pairs_sparse(const dmoe_layer& L, int T) {
     if (!down_bf16_addressable(L, T)) return 0x7fffffffffffffffLL;
-    const double dens = m_pad_of(L.expert_size) <= 32 ? 0.05 : 0.08;
+    const double dens = m_pad_of(L.expert_size) <= 32 ? 0.0 : 0.03;
     return (long long)(dens * (double)T * (double)L.n_experts);
 }
 

@@ -45,11 +45,14 @@ CASES = [
     ("cfg5b", 16, None, 0.25),
     ("paper", 200, None, 0.4),      # 24 experts of 128 neurons
     # densities on both sides of the switch between the two down-projection kernels
-    # (pair-proportional below about 0.05 / 0.08, matrix-core merge above)
+    # (H rows of 64 or 128 neurons: pair-proportional below about 0.03, matrix-core merge above;
+    # 32-neuron rows always take the matrix-core merge)
     ("cfg2", 700, None, 0.04),
     ("cfg2", 700, None, 0.06),
+    ("cfg4", 300, None, 0.02),
     ("cfg4", 300, None, 0.05),
     ("cfg4", 300, None, 0.12),
+    ("paper", 200, None, 0.02),
     ("paper", 200, None, 0.05),
     # token counts at the edges of the small-token path (up to 16 tokens) and of a 64-token group
     ("cfg2", 1, None, 1.0),

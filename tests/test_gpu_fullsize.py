@@ -78,3 +78,35 @@ def test_full_size_sampled(B, oracle, name, tau, n_sample):
     y2, _ = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+
+
+def test_sizes_beyond_32bit_offsets_take_the_pair_kernel(B, oracle):
+    """The matrix-core merge addresses H through 32-bit buffer offsets (below 2 GiB); a layer
+    whose worst-case H is larger -- 8200 tokens x 4096 experts of 32-neuron rows -- must go to the
+    pair-proportional kernel at any density, and give the same sums (Sec. 3.2)."""
+    import torch
+    cfg = wl.Config("big_h", 8200, 256, 4096, 8, 64, False, "relu", "bf16", (0.5,), ffn_bias=True)
+    print(f"beyond 32-bit offsets: T={cfg.T} E={cfg.E}", flush=True)
+    layer, x = wl.make_layer(cfg, 5), wl.make_input(cfg, 5)
+    L = B.Layer(layer, cfg.dtype)
+    mask = wl.bernoulli_mask(cfg.T, cfg.E, 0.01, seed=5)
+    mask[3] = 0
+    cols = [np.flatnonzero(mask[:, e]).astype(np.int32) for e in range(cfg.E)]
+    offsets = np.concatenate([[0], np.cumsum([len(c) for c in cols])]).astype(np.int32)
+    lists = np.concatenate(cols + [np.zeros(1, np.int32)])
+    xd = B.to_device(x, cfg.dtype)
+    od, ld = torch.from_numpy(offsets).cuda(), torch.from_numpy(lists).cuda()
+    B.timing(True)
+    y = B.dmoe_expert_ffn(L, xd, od, ld)
+    torch.cuda.synchronize()
+    t = B.timing_read()
+    B.timing(False)
+    assert t["expert_down_sparse"][0] == 1 and t["expert_down"][0] == 0
+    got = B.from_device(y, cfg.dtype)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(5)
+    idx = np.unique(np.concatenate([[0, 3, 127, 128, cfg.T - 1], rng.choice(cfg.T, 60, replace=False)]))
+    ref = oracle_ffn(oracle, layer, x[idx], mask[idx])
+    err = tokenwise_rel_err(got[idx], ref)
+    print(f"  pairs={offsets[-1]} err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]

@@ -138,7 +138,7 @@ SelectWs select_ws(int T, int E, bool need_mask) {
 }
 
 struct LayerWs {
-    size_t scores, mask, group_off, counts, offsets, item_start, witem, wfirst, lists, H, colmask, partial, hid, total;
+    size_t scores, mask, group_off, sub_cnt, counts, offsets, item_start, witem, wfirst, lists, H, colmask, partial, hid, total;
 };
 LayerWs layer_ws(const dmoe_layer& L, int T) {
     LayerWs w{};
@@ -147,6 +147,10 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     w.scores = o;     o += align_up(sizeof(float) * (size_t)T * E);
     w.mask = o;       o += align_up(sizeof(uint64_t) * (size_t)T * div_up(E, 64));
     w.group_off = o;  o += align_up(sizeof(int32_t) * (size_t)(div_up(T, kGroup) + 1) * E);
+    // counts per part of a group when the router runs several workgroups per group
+    w.sub_cnt = o;
+    if (L.dtype == DMOE_BF16 && router_fused_split(L, T) > 1)
+        o += align_up(sizeof(int32_t) * (size_t)div_up(T, 16) * E);
     w.counts = o;     o += align_up(sizeof(int32_t) * (size_t)E);
     w.offsets = o;    o += align_up(sizeof(int32_t) * (size_t)(E + 1));
     w.item_start = o; o += align_up(sizeof(int32_t) * (size_t)(E + 2));
@@ -209,8 +213,10 @@ SmallMod small_mod(const dmoe_layer& L, char* ws, const LayerWs& w, float* score
 // Experts from mask bits whose group counts are already in group_off (both in the workspace).
 int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const LayerWs& w,
                 const uint64_t* mask, int32_t* offsets_out, int32_t* lists_out, void* y,
-                hipStream_t s) {
+                hipStream_t s, int split = 1) {
+    // split > 1: the counts are in sub_cnt, split rows per group (bf16 prefill path only)
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
+    const int32_t* sub_cnt = split > 1 ? reinterpret_cast<const int32_t*>(ws + w.sub_cnt) : nullptr;
     int32_t* counts = reinterpret_cast<int32_t*>(ws + w.counts);
     int32_t* offsets = offsets_out ? offsets_out : reinterpret_cast<int32_t*>(ws + w.offsets);
     // the kernels read the work-item-aligned copy in the workspace; the caller's is compact
@@ -233,7 +239,7 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
         int32_t* wfirst = reinterpret_cast<int32_t*>(ws + w.wfirst);
         launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, item_start,
                              up_rows_bf16(L), lists_out, alist, up_window_groups(L, T), witem,
-                             wfirst, s);
+                             wfirst, s, sub_cnt, split);
         void* H = ws + w.H;
         launch_up_bf16(L, x, T, witem, wfirst, alist, H, s);
         const long long max_sparse = down_max_pairs_sparse(L, T);
@@ -318,7 +324,8 @@ int32_t dmoe_router(const dmoe_layer* layer, const void* x, int32_t n_tokens, fl
     hipStream_t s = (hipStream_t)stream;
     if (layer->dtype == DMOE_F32) launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
     else if (router_fused_scores_supported(*layer))
-        launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, nullptr, s);
+        launch_router_fused(*layer, x, n_tokens, router_fused_split(*layer, n_tokens), scores, 0.0f,
+                            nullptr, nullptr, nullptr, nullptr, s);
     else launch_router_bf16(*layer, x, n_tokens, scores, s);
     return check_launch("router");
 }
@@ -427,9 +434,13 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
     // the MFMA router takes any number of experts; with the gate fused in, up to 512
     const bool fused_router = layer->dtype == DMOE_BF16 && router_fused_scores_supported(*layer);
     const bool fused_gate = fused_router && router_fused_supported(*layer);
+    int split = 1;
     if (fused_gate && n_tokens > kSmallTokens && gate.top_k < 0) {
-        // router, dynamic-k gate and group counts in one kernel
-        launch_router_fused(*layer, x, n_tokens, scores, tau, mask, nullptr, group_off, colmask, s);
+        // router, dynamic-k gate and group counts in one kernel (with few token groups: several
+        // workgroups per group, each with its own row of counts)
+        if (!colmask) split = router_fused_split(*layer, n_tokens);
+        int32_t* cnt = split > 1 ? reinterpret_cast<int32_t*>(ws + w.sub_cnt) : group_off;
+        launch_router_fused(*layer, x, n_tokens, split, scores, tau, mask, nullptr, cnt, colmask, s);
     } else if (fused_router && colmask && gate.top_k < 0 &&
                layer->n_experts <= kSmallFusedSelectMaxE) {
         // small-token path: hidden product, then scores + gate in one workgroup
@@ -443,7 +454,8 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
             launch_router_small(*layer, G, 1, x, n_tokens, s);
         }
         else if (fused_router)
-            launch_router_fused(*layer, x, n_tokens, scores, 0.0f, nullptr, nullptr, nullptr, nullptr, s);
+            launch_router_fused(*layer, x, n_tokens, router_fused_split(*layer, n_tokens), scores,
+                                0.0f, nullptr, nullptr, nullptr, nullptr, s);
         else if (layer->dtype == DMOE_F32)
             launch_router_f32(*layer, (const float*)x, n_tokens, scores, s);
         else
@@ -455,7 +467,7 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
             launch_mask_topk(scores, n_tokens, layer->n_experts, gate.top_k, mask, nullptr,
                              group_off, colmask, s);
     }
-    return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s);
+    return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s, split);
 }
 
 }  // namespace

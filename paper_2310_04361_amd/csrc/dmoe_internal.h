@@ -125,10 +125,13 @@ void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
                       int32_t* k_per_token, int32_t* group_off, uint64_t* colmask, hipStream_t s);
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,
                             uint64_t* mask, int32_t* group_off, uint64_t* colmask, hipStream_t s);
+// sub_cnt (nullable): the counts come as `split` rows per group (ceil(T * split / 64) rows) that
+// are added up into group_off on the way.
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
                           int32_t* token_lists, int32_t* aligned_lists, int window_groups,
-                          int32_t* witem, int32_t* wfirst, hipStream_t s);
+                          int32_t* witem, int32_t* wfirst, hipStream_t s,
+                          const int32_t* sub_cnt = nullptr, int split = 1);
 // The up-projection walks its work items window by window (window = window_groups consecutive
 // 64-token groups, window w on XCD w % 8) so that the x rows an XCD gathers stay in its L2:
 // witem[NW][E+1], wfirst[NW][E] are built with the lists (nullable: no tables).  A single window
@@ -143,8 +146,13 @@ void launch_router_bf16(const dmoe_layer& L, const void* x, int T, float* scores
 // which has no limit on the number of experts (router_fused_scores_supported).
 bool router_fused_supported(const dmoe_layer& L);
 bool router_fused_scores_supported(const dmoe_layer& L);
-void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,
-                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
+// split = 1, 2 or 4 workgroups per group of 64 tokens (router_fused_split: more where the groups
+// alone would leave most of the chip idle).  With the gate and split > 1, group_cnt is a table
+// of split rows per group -- row r holds the counts of the tokens 64 r / split .. -- that
+// launch_scan_and_fill adds up; colmask forces split = 1.
+int router_fused_split(const dmoe_layer& L, int T);
+void launch_router_fused(const dmoe_layer& L, const void* x, int T, int split, float* scores,
+                         float tau, uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
                          uint64_t* colmask, hipStream_t s);
 
 // ---- small-token path (T <= kSmallTokens): up to kGroupMax layers of one shape per launch ----

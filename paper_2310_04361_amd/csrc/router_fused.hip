@@ -26,25 +26,30 @@ constexpr int kMaxTilesPerWave = 8;   // expert tiles per wavefront: E <= 4 * 8 
 // NH = d_h / 16; ETW = expert tiles per wavefront (E <= 64 * ETW); KBC = K blocks (64 wide) of x
 // that sit in LDS at a time: 12 (all of d = 768) when there is at most about one workgroup per
 // CU and its own latency is what counts, 4 when several workgroups share a CU and hide it.
-template <int NH, int ETW, int KBC>
+// TT = tiles of 16 tokens per workgroup: 4 (a whole select group of 64 tokens), or 2 / 1 when
+// there are too few groups to fill the chip -- a workgroup then handles a half or a quarter of a
+// group and writes its expert counts to its own row of a table with 4 / TT rows per group, which
+// the scan over the groups adds up.
+template <int NH, int ETW, int KBC, int TT>
 __global__ __launch_bounds__(256) void router_fused_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
     const __bf16* __restrict__ r2f, const __bf16* __restrict__ r_b2, float* __restrict__ scores,
     int T, int d, int E, float tau, int do_select, uint64_t* __restrict__ mask,
     int32_t* __restrict__ k_per_token, int32_t* __restrict__ group_cnt,
     uint64_t* __restrict__ colmask) {
-    constexpr int dh = NH * 16, HT = NH / 4;
+    constexpr int dh = NH * 16, HT = NH / 4, TOK = 16 * TT;
+    constexpr int NR = (TOK + 31) / 32;  // staging passes of 32 rows
     constexpr int kHRow = dh * 2 + 16;  // bytes per hidden row in LDS
     constexpr int kXRowC = KBC * 128 + 16;  // bytes per staged x row: KBC blocks + bank skew
     extern __shared__ char smem[];
-    char* xs = smem;                                            // [64][kXRowC]
-    char* hid = smem + 64 * kXRowC;                             // [64][kHRow]
-    float* pmax = reinterpret_cast<float*>(hid + 64 * kHRow);   // [4][64]
+    char* xs = smem;                                            // [TOK][kXRowC]
+    char* hid = smem + TOK * kXRowC;                            // [TOK][kHRow]
+    float* pmax = reinterpret_cast<float*>(hid + TOK * kHRow);  // [4][64]
     uint64_t* pw = reinterpret_cast<uint64_t*>(pmax + 256);     // [4][64][W]
     const int W = (E + 63) >> 6;
     uint64_t* fin = pw + 4 * 64 * W;                            // [64][W]
 
-    const int g = blockIdx.x, t0 = g * 64;
+    const int g = blockIdx.x, t0 = g * TOK;  // g: row of the count table
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
     const int NK32 = d / 32, NKB = d / 64;
 
@@ -54,16 +59,17 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     // inside the K loop would hold up the R1 fragments behind it).  The K loop itself has no
     // barrier and only L2-resident loads.
     const int ld_row = tid >> 3, ld_piece = tid & 7;
+    const bool ld_ok = ld_row < TOK;  // 16 tokens: half of the threads stage nothing
     const __bf16* xp0 = x + (size_t)min(t0 + ld_row, T - 1) * d + 8 * ld_piece;
     const __bf16* xp1 = x + (size_t)min(t0 + ld_row + 32, T - 1) * d + 8 * ld_piece;
     char* xst = xs + ld_row * kXRowC + ld_piece * 16;
     const __bf16* af = r1f + ((size_t)w * HT * NK32 * 64 + lane) * 8;
 
-    f32x4 acc[HT][4];
+    f32x4 acc[HT][TT];
 #pragma unroll
     for (int h = 0; h < HT; ++h)
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) acc[h][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int tt = 0; tt < TT; ++tt) acc[h][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // R1 fragments: a ring of four K blocks, requested three blocks before their use (an L2
     // round trip takes longer than the 16 to 32 MFMAs of one block)
@@ -79,33 +85,34 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         const char* src = xs + c * kXRowC + kbl * 128 + q * 16;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 b[4];
+            bf16x8 b[TT];
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+            for (int tt = 0; tt < TT; ++tt)
                 b[tt] = *reinterpret_cast<const bf16x8*>(src + tt * 16 * kXRowC + ks * 64);
 #pragma unroll
             for (int h = 0; h < HT; ++h)
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt) acc[h][tt] = mfma16(a[ks][h], b[tt], acc[h][tt]);
+                for (int tt = 0; tt < TT; ++tt) acc[h][tt] = mfma16(a[ks][h], b[tt], acc[h][tt]);
         }
     };
 
     for (int kb0 = 0; kb0 < NKB; kb0 += KBC) {
         const int nkb = min(KBC, NKB - kb0);  // a multiple of 4: d is a multiple of 256
         {
-            bf16x8 xr[2 * KBC];
+            bf16x8 xr[NR * KBC];
 #pragma unroll
             for (int i = 0; i < KBC; ++i)
-                if (i < nkb) {
-                    xr[2 * i] = load8(xp0 + 64 * (kb0 + i));
-                    xr[2 * i + 1] = load8(xp1 + 64 * (kb0 + i));
+                if (i < nkb && ld_ok) {
+                    xr[NR * i] = load8(xp0 + 64 * (kb0 + i));
+                    if (NR == 2) xr[NR * i + NR - 1] = load8(xp1 + 64 * (kb0 + i));
                 }
             if (kb0 > 0) lds_barrier();  // the previous chunk has been consumed
 #pragma unroll
             for (int i = 0; i < KBC; ++i)
-                if (i < nkb) {
-                    *reinterpret_cast<bf16x8*>(xst + i * 128) = xr[2 * i];
-                    *reinterpret_cast<bf16x8*>(xst + 32 * kXRowC + i * 128) = xr[2 * i + 1];
+                if (i < nkb && ld_ok) {
+                    *reinterpret_cast<bf16x8*>(xst + i * 128) = xr[NR * i];
+                    if (NR == 2)
+                        *reinterpret_cast<bf16x8*>(xst + 32 * kXRowC + i * 128) = xr[NR * i + NR - 1];
                 }
         }
         if (kb0 == 0) {
@@ -144,7 +151,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
             for (int r = 0; r < 4; ++r) b1[r] = (float)r_b1[hu0 + r];
         }
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
+        for (int tt = 0; tt < TT; ++tt) {
             bf16x4 hv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) hv[r] = (__bf16)fmaxf(acc[h][tt][r] + b1[r], 0.0f);
@@ -155,14 +162,14 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
 
     // ---------------------------------------------------------------- stage 2
     // scores of expert tile et for the group's 64 tokens: |R2 hid + c2| to `scores` and to o
-    auto score_tile = [&](int et, const bf16x8 (&a)[KS2], float (&o)[4][4]) {
-        f32x4 a2[4];
+    auto score_tile = [&](int et, const bf16x8 (&a)[KS2], float (&o)[TT][4]) {
+        f32x4 a2[TT];
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) a2[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int tt = 0; tt < TT; ++tt) a2[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS2; ++ks) {
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
+            for (int tt = 0; tt < TT; ++tt) {
                 const bf16x8 b = *reinterpret_cast<const bf16x8*>(
                     hid + (16 * tt + c) * kHRow + ks * 64 + q * 16);
                 a2[tt] = mfma16(a[ks], b, a2[tt]);
@@ -175,7 +182,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
             for (int r = 0; r < 4; ++r) b2[r] = (float)r_b2[e0 + r];
         }
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
+        for (int tt = 0; tt < TT; ++tt) {
             const int t = t0 + 16 * tt + c;
             float4 out;
             out.x = fabsf(a2[tt][0] + b2[0]);
@@ -190,7 +197,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     if (!do_select) {
         // router alone: any number of expert tiles, two per trip so that the fragments of the
         // next tile are requested before the current one is multiplied
-        float o[4][4];
+        float o[TT][4];
         for (int et = w; et < NE; et += 8) {
             load_r2(et + 4, r2a[1]);
             score_tile(et, r2a[0], o);
@@ -199,8 +206,10 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
         return;
     }
-    float sc[ETW][4][4];  // [my tile][token tile][r]
-    float vmax[4] = {0.f, 0.f, 0.f, 0.f};
+    float sc[ETW][TT][4];  // [my tile][token tile][r]
+    float vmax[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) vmax[tt] = 0.f;
 #pragma unroll
     for (int j = 0; j < ETW; ++j) {
         const int et = w + 4 * j;
@@ -208,7 +217,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         if (et < NE) {  // uniform per wavefront
             score_tile(et, r2a[j & 1], sc[j]);
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
+            for (int tt = 0; tt < TT; ++tt)
                 vmax[tt] = fmaxf(vmax[tt], fmaxf(fmaxf(sc[j][tt][0], sc[j][tt][1]),
                                                  fmaxf(sc[j][tt][2], sc[j][tt][3])));
         }
@@ -217,16 +226,16 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     // ---------------------------------------------------------------- select
     // maximum of each token over this wavefront's experts, then over the four wavefronts
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
+    for (int tt = 0; tt < TT; ++tt) {
         float m = vmax[tt];
         m = fmaxf(m, __shfl_xor(m, 16, 64));
         m = fmaxf(m, __shfl_xor(m, 32, 64));
         if (q == 0) pmax[w * 64 + 16 * tt + c] = m;
     }
     __syncthreads();
-    double thr[4];
+    double thr[TT];
 #pragma unroll
-    for (int tt = 0; tt < 4; ++tt) {
+    for (int tt = 0; tt < TT; ++tt) {
         const int tk = 16 * tt + c;
         const float m = fmaxf(fmaxf(pmax[tk], pmax[64 + tk]), fmaxf(pmax[128 + tk], pmax[192 + tk]));
         thr[tt] = (double)tau * (double)m;  // exact: at most 48 significant bits
@@ -239,7 +248,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         const int e0 = 16 * et + 4 * q;
         if (j < W) {  // uniform
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
+            for (int tt = 0; tt < TT; ++tt) {
                 uint32_t bits = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -255,15 +264,18 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     __syncthreads();
     if (tid < 64) {
         const int t = t0 + tid;
+        const bool mine = tid < TOK && t < T;  // lanes from TOK up: no token, an all-zero row
         int kt = 0;
         for (int wi = 0; wi < W; ++wi) {
-            const uint64_t word = pw[(0 * 64 + tid) * W + wi] | pw[(1 * 64 + tid) * W + wi] |
-                                  pw[(2 * 64 + tid) * W + wi] | pw[(3 * 64 + tid) * W + wi];
-            fin[tid * W + wi] = t < T ? word : 0ull;
-            if (t < T) mask[(size_t)t * W + wi] = word;
+            uint64_t word = 0ull;
+            if (tid < TOK)
+                word = pw[(0 * 64 + tid) * W + wi] | pw[(1 * 64 + tid) * W + wi] |
+                       pw[(2 * 64 + tid) * W + wi] | pw[(3 * 64 + tid) * W + wi];
+            fin[tid * W + wi] = mine ? word : 0ull;
+            if (mine) mask[(size_t)t * W + wi] = word;
             kt += __popcll(word);
         }
-        if (t < T && k_per_token) k_per_token[t] = kt;
+        if (mine && k_per_token) k_per_token[t] = kt;
     }
     __syncthreads();
     // ballot transpose: lane = token; wavefront w handles the experts 64wi + 16w .. +15 of every
@@ -285,34 +297,41 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     }
 }
 
-template <int NH, int ETW, int KBC>
+template <int NH, int ETW, int KBC, int TT>
 void launch_t3(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
                int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
     const PackedLayout P = packed_layout(L);
     const int E = L.n_experts, W = div_up(E, 64);
-    const size_t lds = 64 * (KBC * 128 + 16) + 64 * (NH * 32 + 16) + 256 * 4 +
+    constexpr int TOK = 16 * TT;
+    const size_t lds = TOK * (KBC * 128 + 16) + TOK * (NH * 32 + 16) + 256 * 4 +
                        (mask ? (size_t)5 * 64 * W * 8 : 0);  // the gate's words only when it runs
     static bool attr_set = false;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_fused_kernel<NH, ETW, KBC>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_fused_kernel<NH, ETW, KBC, TT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    router_fused_kernel<NH, ETW, KBC><<<div_up(T, 64), 256, lds, s>>>(
+    router_fused_kernel<NH, ETW, KBC, TT><<<div_up(T, TOK), 256, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1,
         (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, L.d_model, E, tau,
         mask != nullptr, mask, k_per_token, group_cnt, colmask);
 }
 
 template <int NH, int ETW>
-void launch_t2(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
-               int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
+void launch_t2(const dmoe_layer& L, const void* x, int T, int split, float* scores, float tau,
+               uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask,
+               hipStream_t s) {
     constexpr int kBig = NH <= 8 ? 12 : (NH == 16 ? 8 : 4);
-    if (kBig > 4 && div_up(T, 64) <= 512)
-        launch_t3<NH, ETW, kBig>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+    // parts of a group per workgroup: only where workgroups are few, so with the large x chunk
+    if (split == 4)
+        launch_t3<NH, ETW, kBig, 1>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+    else if (split == 2)
+        launch_t3<NH, ETW, kBig, 2>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+    else if (kBig > 4 && div_up(T, 64) <= 512)
+        launch_t3<NH, ETW, kBig, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
     else
-        launch_t3<NH, ETW, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+        launch_t3<NH, ETW, 4, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
 }
 
 // ---- T <= 16: the same two products spread over many workgroups --------------------------------
@@ -385,14 +404,15 @@ __global__ __launch_bounds__(256) void router_small_scores_kernel(const SmallGro
 }
 
 template <int NH>
-void launch_t(const dmoe_layer& L, const void* x, int T, float* scores, float tau, uint64_t* mask,
-              int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask, hipStream_t s) {
+void launch_t(const dmoe_layer& L, const void* x, int T, int split, float* scores, float tau,
+              uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt, uint64_t* colmask,
+              hipStream_t s) {
     if (L.n_experts <= 128 || !mask)  // the router alone keeps no scores in registers
-        launch_t2<NH, 2>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+        launch_t2<NH, 2>(L, x, T, split, scores, tau, mask, k_per_token, group_cnt, colmask, s);
     else if (L.n_experts <= 256)
-        launch_t2<NH, 4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+        launch_t2<NH, 4>(L, x, T, split, scores, tau, mask, k_per_token, group_cnt, colmask, s);
     else
-        launch_t2<NH, 8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s);
+        launch_t2<NH, 8>(L, x, T, split, scores, tau, mask, k_per_token, group_cnt, colmask, s);
 }
 
 }  // namespace
@@ -425,15 +445,21 @@ bool router_fused_supported(const dmoe_layer& L) {
     return router_fused_scores_supported(L) && L.n_experts <= 64 * kMaxTilesPerWave;
 }
 
-void launch_router_fused(const dmoe_layer& L, const void* x, int T, float* scores, float tau,
-                         uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
+int router_fused_split(const dmoe_layer& L, int T) {
+    const int NG = div_up(T, kGroup);
+    return NG >= 192 ? 1 : (NG >= 96 ? 2 : 4);
+}
+
+void launch_router_fused(const dmoe_layer& L, const void* x, int T, int split, float* scores,
+                         float tau, uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
                          uint64_t* colmask, hipStream_t s) {
     LaunchTimer tm(kSlotRouter, s);
+    if (colmask) split = 1;  // the token sets of an expert are per whole group
     switch (L.router_hidden) {
-    case 64: launch_t<4>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
-    case 128: launch_t<8>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
-    case 256: launch_t<16>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
-    case 512: launch_t<32>(L, x, T, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
+    case 64: launch_t<4>(L, x, T, split, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
+    case 128: launch_t<8>(L, x, T, split, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
+    case 256: launch_t<16>(L, x, T, split, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
+    case 512: launch_t<32>(L, x, T, split, scores, tau, mask, k_per_token, group_cnt, colmask, s); break;
     default: break;  // refused by router_fused_supported
     }
 }

@@ -261,9 +261,11 @@ __global__ void lists_to_mask_kernel(const int32_t* __restrict__ offsets,
 }
 
 // One wavefront per expert: exclusive prefix sum of group_cnt[.][e] over the groups, in place;
-// row NG receives the total.
+// row NG receives the total.  With sub != nullptr the counts of group g are read as the sum of
+// the rows split * g .. split * g + split - 1 of sub (n_sub rows in all).
 __global__ __launch_bounds__(256) void scan_groups_kernel(int32_t* __restrict__ group_cnt, int NG,
-                                                          int E) {
+                                                          int E, const int32_t* __restrict__ sub,
+                                                          int split, int n_sub) {
     const int lane = lane_id();
     const int e = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     if (e >= E) return;
@@ -275,7 +277,13 @@ __global__ __launch_bounds__(256) void scan_groups_kernel(int32_t* __restrict__ 
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int g = base + k * kWave + lane;
-            v[k] = g < NG ? group_cnt[(size_t)g * E + e] : 0;
+            if (sub) {
+                v[k] = 0;
+                for (int j = 0; j < split; ++j)
+                    if (g < NG && split * g + j < n_sub) v[k] += sub[(size_t)(split * g + j) * E + e];
+            } else {
+                v[k] = g < NG ? group_cnt[(size_t)g * E + e] : 0;
+            }
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -517,12 +525,14 @@ void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
                           int32_t* offsets, int32_t* item_start, int rows_per_item,
                           int32_t* token_lists, int32_t* aligned_lists, int window_groups,
-                          int32_t* witem, int32_t* wfirst, hipStream_t s) {
+                          int32_t* witem, int32_t* wfirst, hipStream_t s, const int32_t* sub_cnt,
+                          int split) {
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     const int NW = witem ? div_up(NG, window_groups) : 0;
     {
         LaunchTimer tm(kSlotScanGroups, s);
-        scan_groups_kernel<<<div_up(E, 4), 256, 0, s>>>(group_off, NG, E);
+        scan_groups_kernel<<<div_up(E, 4), 256, 0, s>>>(group_off, NG, E, sub_cnt, split,
+                                                        div_up(T, kGroup / split));
     }
     LaunchTimer tm(kSlotFill, s);
     const size_t lds = sizeof(int32_t) * 2 * ((size_t)E + 1);

@@ -24,6 +24,8 @@ def B():
                                                # ragged last chunk in the token range where the
                                                # down-projection takes its 384-column shape
                                                ("cfg2:11000", 0.3, 128),
+                                               # ragged last group with whole-group router workgroups
+                                               ("cfg2:12345", 0.5, 96),
                                                # the paper's own split of its language model: 2048
                                                # experts of 8 neurons, router width 512 (prefill
                                                # and small-token path)

@@ -58,9 +58,10 @@ __global__ __launch_bounds__(256) void count_from_mask_kernel(const uint64_t* __
 }
 
 // Dynamic-k gate (Sec. 3.4 Eq. 4) with one wavefront per token and the lanes striding the
-// experts: the score row is read coalesced, the maximum is a wavefront reduction and a ballot IS
-// a mask word.  The per-group expert counts are then taken from the mask words by
-// count_from_mask_kernel.
+// experts: the score row is read coalesced and once (CH = ceil(E / 64) values per lane, all
+// loads in flight together), the maximum is a wavefront reduction and a ballot IS a mask word.
+// The per-group expert counts are then taken from the mask words by count_from_mask_kernel.
+template <int CH>
 __global__ __launch_bounds__(256) void tau_mask_kernel(const float* __restrict__ scores,
                                                        uint64_t* __restrict__ mask,
                                                        int32_t* __restrict__ k_per_token, int T,
@@ -69,18 +70,26 @@ __global__ __launch_bounds__(256) void tau_mask_kernel(const float* __restrict__
     const int t = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     if (t >= T) return;  // uniform per wavefront
     const float* row = scores + (size_t)t * E;
+    float v[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int e = 64 * c + lane;
+        v[c] = e < E ? row[e] : -INFINITY;
+    }
     float mx = -INFINITY;
-    for (int e = lane; e < E; e += kWave) mx = fmaxf(mx, row[e]);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) mx = fmaxf(mx, v[c]);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
     const double thr = (double)tau * (double)mx;  // exact: at most 48 significant bits
     int kt = 0;
-    for (int w = 0; w < W; ++w) {
-        const int e = 64 * w + lane;
-        const bool keep = e < E && (tau == 0.0f || (double)row[e] >= thr);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int e = 64 * c + lane;
+        const bool keep = e < E && (tau == 0.0f || (double)v[c] >= thr);
         const uint64_t word = __ballot(keep);
         kt += __popcll(word);
-        if (lane == 0) mask[(size_t)t * W + w] = word;
+        if (lane == 0 && c < W) mask[(size_t)t * W + c] = word;
     }
     if (lane == 0 && k_per_token) k_per_token[t] = kt;
 }
@@ -464,7 +473,14 @@ void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint6
             scores, mask, k_per_token, group_off, colmask, T, E, W, tau);
         return;
     }
-    tau_mask_kernel<<<div_up(T, 4), 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    const int grid = div_up(T, 4);
+    if (W <= 1) tau_mask_kernel<1><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 2) tau_mask_kernel<2><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 4) tau_mask_kernel<4><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 8) tau_mask_kernel<8><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 16) tau_mask_kernel<16><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 32) tau_mask_kernel<32><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
+    else tau_mask_kernel<64><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
     count_from_mask_kernel<<<div_up(NG * W, 4), 256, 0, s>>>(mask, group_off, colmask, T, E, W);
 }
 

@@ -148,9 +148,10 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     w.mask = o;       o += align_up(sizeof(uint64_t) * (size_t)T * div_up(E, 64));
     w.group_off = o;  o += align_up(sizeof(int32_t) * (size_t)(div_up(T, kGroup) + 1) * E);
     // counts per part of a group when the router runs several workgroups per group
+    // (sized so that the workspace never shrinks as T grows: at most 4 parts x 192 groups)
     w.sub_cnt = o;
-    if (L.dtype == DMOE_BF16 && router_fused_split(L, T) > 1)
-        o += align_up(sizeof(int32_t) * (size_t)div_up(T, 16) * E);
+    if (L.dtype == DMOE_BF16)
+        o += align_up(sizeof(int32_t) * (size_t)std::min(div_up(T, 16), 4 * 192) * E);
     w.counts = o;     o += align_up(sizeof(int32_t) * (size_t)E);
     w.offsets = o;    o += align_up(sizeof(int32_t) * (size_t)(E + 1));
     w.item_start = o; o += align_up(sizeof(int32_t) * (size_t)(E + 2));
@@ -165,7 +166,7 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     // small-token path: which tokens keep each expert, and the per-expert-group partial outputs
     w.colmask = o;
     w.partial = o;
-    if (L.dtype == DMOE_BF16 && T <= kSmallTokens) {
+    if (L.dtype == DMOE_BF16) {  // also above kSmallTokens: the workspace never shrinks as T grows
         o += align_up(sizeof(uint64_t) * (size_t)E);
         w.partial = o;
         o += align_up(sizeof(float) * (size_t)kSmallMaxGroups * 16 * L.d_model);

@@ -653,7 +653,7 @@ int up_window_groups(const dmoe_layer& L, int T) {
     const int NG = div_up(T, kGroup);
     // wide experts: per window the XCD would stream every expert's weights (far more than its
     // L2) through the same cache, and the 256-row items span more than a window; measured slower
-    if (up_rows_bf16(L) != 64) return NG;
+    if (up_rows_bf16(L) != 64) return std::max(1, NG);
     const double x_bytes = 2.0 * (double)NG * kGroup * L.d_model;
     const double window_bytes = 3.2 * 1048576.0;
     const int n_windows = 8 * std::max(1, (int)ceil(x_bytes / (8.0 * window_bytes)));

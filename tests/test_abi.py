@@ -65,6 +65,25 @@ def test_workspace_sizes(lib):
     assert lib.dmoe_packed_bytes(ctypes.byref(L), ctypes.byref(n)) == B.DMOE_OK and n.value == 0
 
 
+def test_workspace_never_shrinks_as_tokens_grow(lib):
+    """A caller may size the workspace once for its largest batch: the requirement must be
+    monotone in n_tokens, also across the token counts where the launch shapes change (small-token
+    path up to 16, router workgroups per 64-token group at 96 and 192 groups, window tables)."""
+    n = ctypes.c_size_t(0)
+    shapes = [dict(d_model=768, n_experts=128, expert_size=24, router_hidden=128),
+              dict(d_model=2048, n_experts=256, expert_size=64, router_hidden=256, gated=1, w_gate=0x1000),
+              dict(d_model=2048, n_experts=2048, expert_size=8, router_hidden=512, gated=1, w_gate=0x1000),
+              dict(d_model=256, n_experts=4, expert_size=128, router_hidden=32)]
+    for kw in shapes:
+        L = _layer(dtype=B.DMOE_BF16, **kw)
+        last = 0
+        for T in sorted(set(list(range(0, 40)) + list(range(40, 20000, 61)) +
+                            [6143, 6144, 6145, 12287, 12288, 12289])):
+            assert lib.dmoe_workspace_bytes(ctypes.byref(L), T, ctypes.byref(n)) == B.DMOE_OK
+            assert n.value >= last, (kw, T, n.value, last)
+            last = n.value
+
+
 def test_layer_validation(lib):
     n = ctypes.c_size_t(0)
     bad = [

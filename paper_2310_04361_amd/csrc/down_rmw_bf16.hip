@@ -2,10 +2,11 @@
 // (token, expert) pairs (Sec. 3.2; the merge the paper's kernel does with global atomics).
 //
 // down_bf16.hip sums over experts inside the matrix cores at a cost that does not depend on how
-// many experts a token selected; below a density of a few per cent to ~20 % (depending on the
-// expert size) it is cheaper to touch only the executed rows.  Both kernels are launched; each
-// reads the pair count that the list-building kernel left in offsets[E] and the one that does
-// not apply exits at once, so no host synchronisation is needed to choose.
+// many experts a token selected; for H rows of 64 or 128 neurons it is cheaper, below a density
+// of a few per cent, to touch only the executed rows (see down_max_pairs_sparse for the measured
+// crossovers).  Where both could apply, both kernels are launched; each reads the pair count that
+// the list-building kernel left in offsets[E] and the one that does not apply exits at once, so
+// no host synchronisation is needed to choose.
 //
 // One workgroup per (128-token chunk, 256-column slice); KS = m_pad / 32 MFMA k-steps.
 // The fp32 output tile Y[128][256] lives in LDS.  The eight wavefronts own 32 columns each, so

@@ -318,7 +318,10 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
     const int items_bytes = ((2 * E + 1) * 4 + 15) & ~15;
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15;
     const int wave_in_block = threadIdx.x >> 6;
-    char* xs = smem + items_bytes + wave_in_block * (2 * UR * kUpRowBytes);
+    // one staging buffer per wavefront (its LDS accesses keep their order, so a second one buys
+    // nothing): with thousands of experts the work-item table already takes 16 KiB or more, and
+    // the LDS left decides how many wavefronts a CU holds
+    char* xs = smem + items_bytes + wave_in_block * (UR * kUpRowBytes);
     const int NK32 = d / 32, NKB = d / 64;
     const int ld_row = lane >> 3, ld_piece = lane & 7;
 
@@ -364,14 +367,14 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) a[ks] = load8(wf + (size_t)(2 * kb + ks) * 512);
         };
-        auto store_x = [&](int buf) {
-            char* dst = xs + buf * (UR * kUpRowBytes) + ld_row * kUpRowBytes + ld_piece * 16;
+        auto store_x = [&]() {
+            char* dst = xs + ld_row * kUpRowBytes + ld_piece * 16;
 #pragma unroll
             for (int i = 0; i < NL; ++i)
                 *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
         };
-        auto compute = [&](int buf, const bf16x8 (&a)[2]) {
-            const char* src = xs + buf * (UR * kUpRowBytes) + c * kUpRowBytes + q * 16;
+        auto compute = [&](const bf16x8 (&a)[2]) {
+            const char* src = xs + c * kUpRowBytes + q * 16;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -384,17 +387,17 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
 
         load_x(0);
         load_a(0, a0);
-        store_x(0);
+        store_x();
         for (int kb = 0; kb < NKB; kb += 2) {
             load_x(kb + 1);
             load_a(kb + 1, a1);
-            compute(0, a0);
-            store_x(1);
+            compute(a0);
+            store_x();
             const int nb = min(kb + 2, NKB - 1);  // the last trip re-reads a block it will not use
             load_x(nb);
             load_a(nb, a0);
-            compute(1, a1);
-            store_x(0);
+            compute(a1);
+            store_x();
         }
 
         // lane (q, c) of token tile tt holds tile rows 4q + r of list row 16tt + c: q = 0, 1 the up
@@ -680,7 +683,9 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
     if (up_tiny_supported(L)) {
         constexpr int TT = 4;
         const size_t lds = ((2 * (size_t)L.n_experts + 1) * 4 + 15) / 16 * 16 +
-                           4 * 2 * (size_t)TT * 16 * kUpRowBytes;
+                           4 * (size_t)TT * 16 * kUpRowBytes;
+        // up to three workgroups per CU
+        const int grid = round_up((int)std::min<long long>((worst + 3) / 4, 256 * 3), 8);
         static bool attr_set = false;
         if (!attr_set) {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT>),

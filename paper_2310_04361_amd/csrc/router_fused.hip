@@ -133,9 +133,9 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     // passes while the hidden tile is finished and stored
     constexpr int KS2 = dh / 32;
     const int NE = (E + 15) >> 4;
-    // sets of R2 fragments in flight (the gate below uses two); the widest router with whole
-    // groups has no registers for a third
-    constexpr int kR2Ring = (NH == 32 && TT == 4) ? 2 : 3;
+    // two sets of R2 fragments alternate (a third in flight measured the same on a router of
+    // 2048 experts and d_h = 512)
+    constexpr int kR2Ring = 2;
     bf16x8 r2a[kR2Ring][KS2];
     auto load_r2 = [&](int et, bf16x8 (&a)[KS2]) {
         et = min(et, NE - 1);
@@ -198,12 +198,10 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
     };
     if (!do_select) {
-        // router alone: any number of expert tiles, walked with the fragments of the next two
-        // tiles on their way while the current one is multiplied (a tile is up to 16 KiB per
-        // wavefront and comes from L2: one tile ahead does not cover the round trip)
+        // router alone: any number of expert tiles, the fragments of the next tile on their way
+        // while the current one is multiplied
         float o[TT][4];
         load_r2(w + 4, r2a[1]);
-        if constexpr (kR2Ring > 2) load_r2(w + 8, r2a[kR2Ring - 1]);
         for (int et = w; et < NE; et += 4 * kR2Ring) {
 #pragma unroll
             for (int i = 0; i < kR2Ring; ++i) {

@@ -171,7 +171,10 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
         w.partial = o;
         o += align_up(sizeof(float) * (size_t)kSmallMaxGroups * 16 * L.d_model);
     }
-    w.hid = o;        o += align_up(2 * 16 * (size_t)std::max(L.router_hidden, 16));
+    // hidden rows of the router: 16 for the small-token kernels, all T for a router that runs as
+    // two launches
+    const size_t hid_rows = (L.dtype == DMOE_BF16 && router_sliced(L)) ? std::max(T, 16) : 16;
+    w.hid = o;        o += align_up(2 * hid_rows * (size_t)std::max(L.router_hidden, 16));
     w.total = o;
     return w;
 }
@@ -454,6 +457,8 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
             G.m[0] = small_mod(*layer, ws, w, scores, mask, y, tau);
             launch_router_small(*layer, G, 1, x, n_tokens, s);
         }
+        else if (fused_router && router_sliced(*layer))
+            launch_router_sliced(*layer, x, n_tokens, ws + w.hid, scores, s);
         else if (fused_router)
             launch_router_fused(*layer, x, n_tokens, router_fused_split(*layer, n_tokens), scores,
                                 0.0f, nullptr, nullptr, nullptr, nullptr, s);

@@ -151,6 +151,11 @@ bool router_fused_scores_supported(const dmoe_layer& L);
 // of split rows per group -- row r holds the counts of the tokens 64 r / split .. -- that
 // launch_scan_and_fill adds up; colmask forces split = 1.
 int router_fused_split(const dmoe_layer& L, int T);
+// Large routers (2 MB of matrices or more) without the gate: two launches with the matrices split
+// over the workgroups; hid is a [T][d_h] bf16 scratch buffer.
+bool router_sliced(const dmoe_layer& L);
+void launch_router_sliced(const dmoe_layer& L, const void* x, int T, void* hid, float* scores,
+                          hipStream_t s);
 void launch_router_fused(const dmoe_layer& L, const void* x, int T, int split, float* scores,
                          float tau, uint64_t* mask, int32_t* k_per_token, int32_t* group_cnt,
                          uint64_t* colmask, hipStream_t s);

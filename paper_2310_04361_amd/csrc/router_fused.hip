@@ -30,20 +30,26 @@ constexpr int kMaxTilesPerWave = 8;   // expert tiles per wavefront: E <= 4 * 8 
 // there are too few groups to fill the chip -- a workgroup then handles a half or a quarter of a
 // group and writes its expert counts to its own row of a table with 4 / TT rows per group, which
 // the scan over the groups adds up.
-template <int NH, int ETW, int KBC, int TT>
+// MODE: kWhole: both products (and the gate) in one workgroup.  A router whose two matrices take
+// megabytes (d_h = 512, thousands of experts) would stream all of them through every CU; it runs
+// as two launches instead, with the matrices split over blockIdx.y: kHiddenSlice computes the NH * 16
+// hidden units from blockIdx.y * NH * 16 on and stores them to hid_g[T][dh_g]; kScoresSlice (NH * 16 =
+// d_h) reads the stored hidden rows and computes the expert tiles blockIdx.y * tiles_y .. + tiles_y - 1.
+enum { kWhole = 0, kHiddenSlice = 1, kScoresSlice = 2 };
+template <int NH, int ETW, int KBC, int TT, int MODE = kWhole>
 __global__ __launch_bounds__(256) void router_fused_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ r1f, const __bf16* __restrict__ r_b1,
     const __bf16* __restrict__ r2f, const __bf16* __restrict__ r_b2, float* __restrict__ scores,
     int T, int d, int E, float tau, int do_select, uint64_t* __restrict__ mask,
     int32_t* __restrict__ k_per_token, int32_t* __restrict__ group_cnt,
-    uint64_t* __restrict__ colmask) {
+    uint64_t* __restrict__ colmask, __bf16* __restrict__ hid_g, int dh_g, int tiles_y) {
     constexpr int dh = NH * 16, HT = NH / 4, TOK = 16 * TT;
     constexpr int NR = (TOK + 31) / 32;  // staging passes of 32 rows
     constexpr int kHRow = dh * 2 + 16;  // bytes per hidden row in LDS
     constexpr int kXRowC = KBC * 128 + 16;  // bytes per staged x row: KBC blocks + bank skew
     extern __shared__ char smem[];
     char* xs = smem;                                            // [TOK][kXRowC]
-    char* hid = smem + TOK * kXRowC;                            // [TOK][kHRow]
+    char* hid = MODE == kScoresSlice ? smem : smem + TOK * kXRowC;  // [TOK][kHRow]
     float* pmax = reinterpret_cast<float*>(hid + TOK * kHRow);  // [4][64]
     uint64_t* pw = reinterpret_cast<uint64_t*>(pmax + 256);     // [4][64][W]
     const int W = (E + 63) >> 6;
@@ -63,7 +69,8 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
     const __bf16* xp0 = x + (size_t)min(t0 + ld_row, T - 1) * d + 8 * ld_piece;
     const __bf16* xp1 = x + (size_t)min(t0 + ld_row + 32, T - 1) * d + 8 * ld_piece;
     char* xst = xs + ld_row * kXRowC + ld_piece * 16;
-    const __bf16* af = r1f + ((size_t)w * HT * NK32 * 64 + lane) * 8;
+    // (a hidden slice starts at hidden tile blockIdx.y * NH)
+    const __bf16* af = r1f + (((size_t)(MODE == kHiddenSlice ? blockIdx.y * NH : 0) + w * HT) * NK32 * 64 + lane) * 8;
 
     f32x4 acc[HT][TT];
 #pragma unroll
@@ -96,6 +103,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
     };
 
+    if constexpr (MODE != kScoresSlice) {
     for (int kb0 = 0; kb0 < NKB; kb0 += KBC) {
         const int nkb = min(KBC, NKB - kb0);  // a multiple of 4: d is a multiple of 256
         {
@@ -129,6 +137,8 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
     }
 
+    }  // stage 1
+
     // R2 fragments of this wavefront's first expert tile: requested now, so that their latency
     // passes while the hidden tile is finished and stored
     constexpr int KS2 = dh / 32;
@@ -142,23 +152,47 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
 #pragma unroll
         for (int ks = 0; ks < KS2; ++ks) a[ks] = load8(r2f + (((size_t)et * KS2 + ks) * 64 + lane) * 8);
     };
-    load_r2(w, r2a[0]);
+    if constexpr (MODE == kScoresSlice) load_r2(blockIdx.y * tiles_y + w, r2a[0]);
+    else if constexpr (MODE == kWhole) load_r2(w, r2a[0]);
 
     // lane (q, c) of tile (h, tt): hidden units 16*(w*HT + h) + 4q + r of token 16tt + c
 #pragma unroll
-    for (int h = 0; h < HT; ++h) {
-        const int hu0 = 16 * (w * HT + h) + 4 * q;
+    for (int h = 0; h < HT && MODE != kScoresSlice; ++h) {
+        const int hu0 = 16 * (w * HT + h) + 4 * q;                      // within this workgroup's units
+        const int hu_g = (MODE == kHiddenSlice ? blockIdx.y * dh : 0) + hu0;  // within the layer's
         float b1[4] = {0.f, 0.f, 0.f, 0.f};
         if (r_b1) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) b1[r] = (float)r_b1[hu0 + r];
+            for (int r = 0; r < 4; ++r) b1[r] = (float)r_b1[hu_g + r];
         }
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             bf16x4 hv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) hv[r] = (__bf16)fmaxf(acc[h][tt][r] + b1[r], 0.0f);
-            *reinterpret_cast<bf16x4*>(hid + (16 * tt + c) * kHRow + hu0 * 2) = hv;
+            if constexpr (MODE == kHiddenSlice) {
+                const int t = t0 + 16 * tt + c;
+                if (t < T) *reinterpret_cast<bf16x4*>(hid_g + (size_t)t * dh_g + hu_g) = hv;
+            } else {
+                *reinterpret_cast<bf16x4*>(hid + (16 * tt + c) * kHRow + hu0 * 2) = hv;
+            }
+        }
+    }
+    if constexpr (MODE == kHiddenSlice) return;
+    if constexpr (MODE == kScoresSlice) {
+        // the stored hidden rows of the group's tokens: 16-byte pieces, rows past T read row T - 1
+        // (all loads of a thread in flight before the first store)
+        constexpr int kPieces = dh / 8, kTrips = TOK * kPieces / 256;
+        bf16x8 hr[kTrips];
+#pragma unroll
+        for (int j = 0; j < kTrips; ++j) {
+            const int i = tid + 256 * j, row = i / kPieces, piece = i % kPieces;
+            hr[j] = load8(hid_g + (size_t)min(t0 + row, T - 1) * dh_g + piece * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < kTrips; ++j) {
+            const int i = tid + 256 * j, row = i / kPieces, piece = i % kPieces;
+            *reinterpret_cast<bf16x8*>(hid + row * kHRow + piece * 16) = hr[j];
         }
     }
     __syncthreads();
@@ -201,11 +235,13 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         // router alone: any number of expert tiles, the fragments of the next tile on their way
         // while the current one is multiplied
         float o[TT][4];
-        load_r2(w + 4, r2a[1]);
-        for (int et = w; et < NE; et += 4 * kR2Ring) {
+        const int et0 = MODE == kScoresSlice ? blockIdx.y * tiles_y : 0;
+        const int et1 = MODE == kScoresSlice ? min(NE, et0 + tiles_y) : NE;
+        load_r2(et0 + w + 4, r2a[1]);
+        for (int et = et0 + w; et < et1; et += 4 * kR2Ring) {
 #pragma unroll
             for (int i = 0; i < kR2Ring; ++i) {
-                if (et + 4 * i < NE) score_tile(et + 4 * i, r2a[i], o);  // uniform per wavefront
+                if (et + 4 * i < et1) score_tile(et + 4 * i, r2a[i], o);  // uniform per wavefront
                 load_r2(et + 4 * (i + kR2Ring), r2a[i]);  // past the end: the last tile again
             }
         }
@@ -320,7 +356,7 @@ void launch_t3(const dmoe_layer& L, const void* x, int T, float* scores, float t
     router_fused_kernel<NH, ETW, KBC, TT><<<div_up(T, TOK), 256, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1,
         (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, L.d_model, E, tau,
-        mask != nullptr, mask, k_per_token, group_cnt, colmask);
+        mask != nullptr, mask, k_per_token, group_cnt, colmask, nullptr, 0, 0);
 }
 
 template <int NH, int ETW>
@@ -449,6 +485,61 @@ bool router_fused_scores_supported(const dmoe_layer& L) {
 
 bool router_fused_supported(const dmoe_layer& L) {
     return router_fused_scores_supported(L) && L.n_experts <= 64 * kMaxTilesPerWave;
+}
+
+// A router whose two matrices take 2 MB or more runs as two launches with the matrices split over
+// the workgroups (see router_fused_kernel); needs a [T][d_h] bf16 buffer for the hidden rows.
+bool router_sliced(const dmoe_layer& L) {
+    const int dh = L.router_hidden;
+    return router_fused_scores_supported(L) && (dh == 256 || dh == 512) &&
+           2 * (size_t)dh * ((size_t)L.d_model + L.n_experts) >= (2u << 20);
+}
+
+template <int NH>
+static void launch_scores_slices(const dmoe_layer& L, const PackedLayout& P, int T,
+                                 const __bf16* hid, float* scores, hipStream_t s) {
+    const int NG = div_up(T, kGroup), NE = div_up(L.n_experts, 16);
+    // expert slices: enough workgroups for the chip, at least one tile per wavefront
+    const int want = std::max(1, std::min(NE / 4, div_up(256, NG)));
+    const int tiles_y = round_up(div_up(NE, want), 4);
+    const size_t lds = 64 * (NH * 32 + 16) + 256 * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&router_fused_kernel<NH, 2, 4, 4, kScoresSlice>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    const char* pk = static_cast<const char*>(L.packed);
+    router_fused_kernel<NH, 2, 4, 4, kScoresSlice><<<dim3(NG, div_up(NE, tiles_y)), 256, lds, s>>>(
+        nullptr, nullptr, nullptr, (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T,
+        L.d_model, L.n_experts, 0.0f, 0, nullptr, nullptr, nullptr, nullptr,
+        const_cast<__bf16*>(hid), L.router_hidden, tiles_y);
+}
+
+void launch_router_sliced(const dmoe_layer& L, const void* x, int T, void* hid, float* scores,
+                          hipStream_t s) {
+    LaunchTimer tm(kSlotRouter, s);
+    const PackedLayout P = packed_layout(L);
+    const int NG = div_up(T, kGroup), dh = L.router_hidden;
+    const char* pk = static_cast<const char*>(L.packed);
+    {   // hidden rows: 128 hidden units per workgroup
+        constexpr int NH = 8, KBC = 12;
+        const size_t lds = 64 * (KBC * 128 + 16) + 64 * (NH * 32 + 16) + 256 * 4;
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(
+                reinterpret_cast<const void*>(&router_fused_kernel<NH, 2, KBC, 4, kHiddenSlice>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            attr_set = true;
+        }
+        router_fused_kernel<NH, 2, KBC, 4, kHiddenSlice><<<dim3(NG, dh / 128), 256, lds, s>>>(
+            (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1, nullptr, nullptr,
+            nullptr, T, L.d_model, L.n_experts, 0.0f, 0, nullptr, nullptr, nullptr, nullptr,
+            (__bf16*)hid, dh, 0);
+    }
+    if (dh == 256) launch_scores_slices<16>(L, P, T, (const __bf16*)hid, scores, s);
+    else launch_scores_slices<32>(L, P, T, (const __bf16*)hid, scores, s);
 }
 
 int router_fused_split(const dmoe_layer& L, int T) {

@@ -4,7 +4,8 @@ The benchmark configurations and the per-kernel shape tests fix one parameter at
 every case draws all of them together -- token count (small-token path, a ragged few hundred,
 over a thousand), width, number and size of experts, router width, gated or plain experts,
 biases, threshold or top-k gate, bf16 or 8-bit expert weights -- so that combinations nobody listed by hand are exercised.
-The gate is checked bit for bit on the library's own fp32 scores, the lists against the mask,
+The scores of sampled tokens are checked against the oracle's router, the gate bit for bit on
+the library's own fp32 scores, the lists against the mask,
 and the output of sampled tokens against the oracle's experts on that mask."""
 import numpy as np
 import pytest
@@ -77,6 +78,8 @@ def test_random_layer_matches_oracle(B, oracle, i):
     rng = np.random.default_rng(i)
     idx = np.unique(np.concatenate([[t for t in (0, 15, 16, 63, 64, 127, 128, cfg.T - 1) if t < cfg.T],
                                     rng.choice(cfg.T, min(48, cfg.T), replace=False)]))
+    ref_s = oracle.router(x[idx], layer["r_w1"], layer["r_b1"], layer["r_w2"], layer["r_b2"])
+    assert tokenwise_rel_err(s[idx], ref_s) <= TOL[cfg.dtype]
     ref_y = oracle_ffn(oracle, layer, x[idx], ref_mask[idx])
     err = tokenwise_rel_err(got[idx], ref_y)
     print(f"  density={ref_mask.mean():.3f} err={err:.3e}", flush=True)

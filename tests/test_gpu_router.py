@@ -35,3 +35,31 @@ def test_router_matches_oracle(B, oracle, name, T, E):
     got = s.cpu().numpy().astype(np.float64)
     assert (got >= 0).all()
     assert tokenwise_rel_err(got, ref) <= TOL[cfg.dtype]
+
+
+# Routers inside dmoe_forward: large ones (2 MB of matrices or more) run without the fused gate as
+# two launches with the matrices split over the workgroups -- more than 512 experts with the
+# threshold gate, any expert count with the top-k gate -- at token counts with a ragged last group
+# and expert counts that are not a multiple of a 16-expert tile or of a workgroup's slice.
+@pytest.mark.parametrize("T,d,E,d_h,k", [
+    (300, 2048, 2048, 512, None), (70, 2048, 2052, 256, None), (700, 1024, 1100, 512, None),
+    (333, 2048, 256, 512, 7), (1500, 2048, 516, 512, None), (100, 4096, 64, 256, 3),
+])
+def test_forward_scores_of_large_routers(B, oracle, T, d, E, d_h, k):
+    import torch
+    cfg = wl.Config("big_router", T, d, E, 8, d_h, True, "gelu_tanh", "bf16", (0.5,), router_bias=True)
+    print(f"large router T={T} d={d} E={E} d_h={d_h} k={k}", flush=True)
+    layer, x = wl.make_layer(cfg, 6), wl.make_input(cfg, 6)
+    L = B.Layer(layer, cfg.dtype)
+    _, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), float(np.float32(0.5)), want_scores=True,
+                           want_mask=True, top_k=k)
+    torch.cuda.synchronize()
+    got = ex["scores"].cpu().numpy().astype(np.float64)
+    ref = oracle.router(x, layer["r_w1"], layer["r_b1"], layer["r_w2"], layer["r_b2"])
+    assert (got >= 0).all()
+    err = tokenwise_rel_err(got, ref)
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]
+    # and the stand-alone router gives the same scores to the same tolerance
+    s2 = B.dmoe_router(L, B.to_device(x, cfg.dtype)).cpu().numpy().astype(np.float64)
+    assert tokenwise_rel_err(s2, ref) <= TOL[cfg.dtype]

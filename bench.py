@@ -35,7 +35,8 @@ MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 61.2e6 + 25.3e6,
 N_ROTATE = 8                   # distinct x / y buffers cycled through, so that inputs come from HBM
 N_LAYER_COPIES_DECODE = 4      # distinct weight copies cycled through at decode sizes: together
                                # they exceed the 256 MB last-level cache, so weights come from HBM
-OTHERS = (("cfg3", 0.5), ("cfg4", 0.3), ("cfg4", 0.6), ("gemma_paper", 0.5), ("cfg5a", 0.5), ("cfg5b", 0.5))
+OTHERS = (("cfg3", 0.5), ("cfg4", 0.3), ("cfg4", 0.6), ("gemma_paper", 0.5), ("bert_paper", 0.5),
+          ("cfg5a", 0.5), ("cfg5b", 0.5))
 
 
 def _time_ms(fn, steps):

@@ -57,6 +57,10 @@ CONFIGS = {
     # the paper's own conversion of its language model (Sec. 4.3 / training details): 2048
     # experts of 8 neurons over the 16384-wide gated FFN, router hidden width 512
     "gemma_paper": Config("gemma_paper", 4096, 2048, 2048, 8, 512, True, "gelu_tanh", "bf16", (0.5,)),
+    # the paper's own conversion of its text classifier (training details: expert size 6): 512
+    # experts of 6 neurons over the 3072-wide FFN of a BERT-base layer
+    "bert_paper": Config("bert_paper", 128 * 128, 768, 512, 6, 128, False, "gelu_erf", "bf16",
+                         (0.5,), ffn_bias=True),
 }
 
 

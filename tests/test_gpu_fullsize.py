@@ -30,6 +30,8 @@ def B():
                                                # experts of 8 neurons, router width 512 (prefill
                                                # and small-token path)
                                                ("gemma_paper:600", 0.5, 32),
+                                               # ... and of its text classifier: 512 experts of 6
+                                               ("bert_paper:700", 0.5, 48),
                                                ("gemma_paper:12", 0.5, 12)])
 def test_full_size_sampled(B, oracle, name, tau, n_sample):
     import torch

@@ -38,10 +38,10 @@ inline size_t h_fragments(const dmoe_layer& L, int T) {
     return ((size_t)T * L.n_experts + (size_t)L.n_experts * up_rows_bf16(L)) / 16 + 4;
 }
 
-// Gated experts of at most 8 neurons take the up-projection kernel whose single 16-row weight
-// tile holds the expert's up rows and gate rows together.
+// Experts that fit ONE 16-row weight tile -- at most 16 neurons, or gated with at most 8 (up rows
+// and gate rows together) -- take the up-projection kernel built around that tile.
 inline bool up_tiny_supported(const dmoe_layer& L) {
-    return L.dtype == DMOE_BF16 && L.gated && L.expert_size <= 8;
+    return L.dtype == DMOE_BF16 && L.expert_size <= (L.gated ? 8 : 16);
 }
 
 // Sub-buffers of the packed-weights buffer (bytes from its start).
@@ -78,7 +78,7 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
         P.wgatef8 = o + 2 * half;
         o += (L.gated ? 3 : 2) * half;
     }
-    // gated experts of at most 8 neurons: up and gate rows of an expert share one 16-row tile
+    // experts of one 16-row weight tile (at most 16 neurons; gated: 8 up rows + 8 gate rows)
     // (ffn_bf16.hip, up_tiny_kernel): wtinyf[E][d/32][64][8]
     P.wtinyf = o;
     if (up_tiny_supported(L)) o += (2 * (size_t)L.n_experts * 16 * L.d_model + 255) / 256 * 256;

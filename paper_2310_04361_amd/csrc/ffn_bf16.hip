@@ -111,12 +111,13 @@ __global__ void pack_up_kernel(const void* __restrict__ w, const float* __restri
     }
 }
 
-// Gated experts of m <= 8 neurons: w_up, w_gate [E][m][d] -> wt[E][d/32][64][8], one 16-row tile
-// per expert and k-step whose rows 0..7 are the up rows and 8..15 the gate rows (zero rows for
-// neurons >= m); lane (q, c) holds row c, columns 32 kstep + 8q + s.
+// Experts of one weight tile: w_up (, w_gate) [E][m][d] -> wt[E][d/32][64][8], one 16-row tile per
+// expert and k-step.  Gated (m <= 8): rows 0..7 are the up rows and 8..15 the gate rows; plain
+// (m <= 16): row c is neuron c.  Zero rows for neurons >= m; lane (q, c) holds row c, columns
+// 32 kstep + 8q + s.
 __global__ void pack_up_tiny_kernel(const void* __restrict__ w_up, const void* __restrict__ w_gate,
                                     const float* __restrict__ scales, int fp8,
-                                    __bf16* __restrict__ wt, int E, int m, int d) {
+                                    __bf16* __restrict__ wt, int E, int m, int d, int gated) {
     const size_t n = (size_t)E * 16 * d;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -126,7 +127,7 @@ __global__ void pack_up_tiny_kernel(const void* __restrict__ w_up, const void* _
         const int kstep = (int)(f % (d / 32));
         const int e = (int)(f / (d / 32));
         const int q = lane >> 4, c = lane & 15;
-        const int neuron = c & 7, which = c >> 3;  // 0 up, 1 gate
+        const int neuron = gated ? (c & 7) : c, which = gated ? (c >> 3) : 0;  // 0 up, 1 gate
         wt[i] = packed_weight<__bf16>(which ? w_gate : w_up, scales, fp8, which, e,
                                       ((size_t)e * m + min(neuron, m - 1)) * d + 32 * kstep + 8 * q + s,
                                       neuron < m);
@@ -299,17 +300,19 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
     }  // windows
 }
 
-// Up-projection for gated experts of at most 8 neurons (thousands of tiny experts, Sec. 5 language
-// model split).  In the general kernel such an expert fills a quarter of the rows of four weight
-// tiles; here its up rows and gate rows share ONE 16-row tile, so a work item streams a quarter of
-// the weight bytes and issues a quarter of the MFMAs, and what remains is the gather of the x
-// rows.  Same work items, same x staging, same H rows (pieces 1..3 of the 32-neuron row are
-// written as zeros) as up_bf16_kernel<2, true, TT>.
-template <int TT>
+// Up-projection for experts that fit one 16-row weight tile: at most 16 neurons, or gated with at
+// most 8 (the paper's own splits: experts of 6 for its text classifier, 2048 gated experts of 8
+// for its language model).  In the general kernel a gated expert of 8 fills a quarter of the rows
+// of four weight tiles and a plain one of 6 to 16 half of two; here the expert is ONE tile (gated:
+// up rows and gate rows together), so a work item streams a quarter / half of the weight bytes
+// and issues a quarter / half of the MFMAs, and what remains is the gather of the x rows.  Same
+// work items, same x staging, same H rows (the unused pieces of the 32-neuron row are written as
+// zeros) as up_bf16_kernel<2, GATED, TT>.
+template <int TT, bool GATED>
 __global__ __launch_bounds__(256) void up_tiny_kernel(
-    const __bf16* __restrict__ x, const __bf16* __restrict__ wtf, const int32_t* __restrict__ witem,
-    const int32_t* __restrict__ wfirst, int NW, const int32_t* __restrict__ alist,
-    __bf16* __restrict__ Hf, int d, int E, int m, int act) {
+    const __bf16* __restrict__ x, const __bf16* __restrict__ wtf, const __bf16* __restrict__ b_up,
+    const int32_t* __restrict__ witem, const int32_t* __restrict__ wfirst, int NW,
+    const int32_t* __restrict__ alist, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
     constexpr int UR = TT * 16;
     constexpr int NL = TT * 2;
     extern __shared__ char smem[];
@@ -400,29 +403,44 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
             store_x();
         }
 
-        // lane (q, c) of token tile tt holds tile rows 4q + r of list row 16tt + c: q = 0, 1 the up
-        // products of neurons 4q + r, q = 2, 3 the gate products of neurons 4(q - 2) + r
+        // lane (q, c) of token tile tt holds tile rows 4q + r of list row 16tt + c.
+        // Gated: q = 0, 1 the up products of neurons 4q + r, q = 2, 3 the gate products of
+        // neurons 4(q - 2) + r.  Plain: neuron 4q + r (plus its bias).
+        float bias[4] = {0.f, 0.f, 0.f, 0.f};
+        if (!GATED && b_up) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bias[r] = (float)b_up[(size_t)e * m + min(4 * q + r, m - 1)];
+        }
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             float v[4], w[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float other = __shfl_xor(acc[tt][r], 32, 64);  // q <-> q ^ 2
-                const float up = q < 2 ? acc[tt][r] : other;
-                const float gate = q < 2 ? other : acc[tt][r];
-                v[r] = activate_fast(act, gate) * up;
-                if (4 * (q & 1) + r >= m) v[r] = 0.0f;
+                if (GATED) {
+                    const float other = __shfl_xor(acc[tt][r], 32, 64);  // q <-> q ^ 2
+                    const float up = q < 2 ? acc[tt][r] : other;
+                    const float gate = q < 2 ? other : acc[tt][r];
+                    v[r] = activate_fast(act, gate) * up;
+                    if (4 * (q & 1) + r >= m) v[r] = 0.0f;
+                } else {
+                    v[r] = activate_fast(act, acc[tt][r] + bias[r]);
+                    if (4 * q + r >= m) v[r] = 0.0f;
+                }
             }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) w[r] = __shfl_xor(v[r], 16, 64);  // q = 0 receives neurons 4..7
+            for (int r = 0; r < 4; ++r) w[r] = __shfl_xor(v[r], 16, 64);  // the other half of a piece
+            // piece p of the 32-neuron H row = neurons 8p .. 8p+7.  Gated: lane q = 0 has piece 0,
+            // the others write the zero pieces 1..3.  Plain: lane q = 0 has piece 0, q = 2 piece 1,
+            // q = 1 and 3 write the zero pieces 2 and 3.
+            const bool real = GATED ? q == 0 : (q & 1) == 0;
+            const int piece = GATED ? q : (real ? (q >> 1) : 2 + (q >> 1));
             bf16x8 hv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                hv[r] = (__bf16)(q == 0 ? v[r] : 0.0f);
-                hv[4 + r] = (__bf16)(q == 0 ? w[r] : 0.0f);
+                hv[r] = (__bf16)(real ? v[r] : 0.0f);
+                hv[4 + r] = (__bf16)(real ? w[r] : 0.0f);
             }
-            // piece q of the 32-neuron H row: piece 0 = neurons 0..7, the others padding
-            *reinterpret_cast<bf16x8*>(Hf + ((size_t)item * UR + 16 * tt + c) * 32 + 8 * q) = hv;
+            *reinterpret_cast<bf16x8*>(Hf + ((size_t)item * UR + 16 * tt + c) * 32 + 8 * piece) = hv;
         }
     }
     }  // windows
@@ -628,7 +646,7 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
                                                     (__bf16*)(pk + P.wgatef), E, m, d, mp / 16, 1);
     if (up_tiny_supported(L))
         pack_up_tiny_kernel<<<2048, 256, 0, s>>>(L.w_up, L.w_gate, L.w_scales, fp8,
-                                                 (__bf16*)(pk + P.wtinyf), E, m, d);
+                                                 (__bf16*)(pk + P.wtinyf), E, m, d, L.gated);
     if (fp8) {  // byte fragments for the small-token kernels
         pack_down_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_down, L.w_scales, 1, (uint8_t*)(pk + P.w2f8),
                                                        E, m, d, mp / 32);
@@ -688,14 +706,21 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
         const int grid = round_up((int)std::min<long long>((worst + 3) / 4, 256 * 3), 8);
         static bool attr_set = false;
         if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT>),
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT, true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT, false>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             attr_set = true;
         }
         const char* pk = static_cast<const char*>(L.packed);
-        up_tiny_kernel<TT><<<grid, 256, lds, s>>>((const __bf16*)x, (const __bf16*)(pk + P.wtinyf),
-                                                  witem, wfirst, NW, alist, (__bf16*)H, L.d_model,
-                                                  L.n_experts, L.expert_size, L.act);
+        if (L.gated)
+            up_tiny_kernel<TT, true><<<grid, 256, lds, s>>>(
+                (const __bf16*)x, (const __bf16*)(pk + P.wtinyf), nullptr, witem, wfirst, NW, alist,
+                (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
+        else
+            up_tiny_kernel<TT, false><<<grid, 256, lds, s>>>(
+                (const __bf16*)x, (const __bf16*)(pk + P.wtinyf), (const __bf16*)L.b_up, witem, wfirst,
+                NW, alist, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
         return;
     }
     if (L.gated) {

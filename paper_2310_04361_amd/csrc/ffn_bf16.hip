@@ -140,8 +140,8 @@ __global__ void pack_up_tiny_kernel(const void* __restrict__ w_up, const void* _
 // branch.  K advances in blocks of 64: the wavefront loads the next block of its x rows
 // (lane = (row % 8, 16-byte piece of the 128-byte row segment)) and of the weight fragments
 // while the MFMAs run on the current block out of LDS / registers.
-template <int MT, bool GATED, int TT>
-__global__ __launch_bounds__(256) void up_bf16_kernel(
+template <int MT, bool GATED, int TT, int NBUF>
+__global__ __launch_bounds__(256, NBUF == 1 ? 3 : 1) void up_bf16_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
     const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
     const int32_t* __restrict__ witem, const int32_t* __restrict__ wfirst, int NW,
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
     const int items_bytes = ((2 * E + 1) * 4 + 15) & ~15;
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15;
     const int wave_in_block = threadIdx.x >> 6;
-    char* xs = smem + items_bytes + wave_in_block * (2 * UR * kUpRowBytes);
+    char* xs = smem + items_bytes + wave_in_block * (NBUF * UR * kUpRowBytes);
     const int NK32 = d / 32, NKB = d / 64;
     const int ld_row = lane >> 3, ld_piece = lane & 7;
 
@@ -187,39 +187,41 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
         // rows of the aligned list past the expert's last token hold -1: they read token 0 and
         // produce H rows that nobody merges
         const int32_t* tl = alist + (size_t)item * UR + ld_row;
-        const __bf16* xrow[NL];
+        // x rows as 32-bit offsets in 16-byte units (T * d / 8 fits): half the registers of pointers
+        uint32_t xoff[NL];
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             const int tok = max(tl[8 * i], 0);
-            xrow[i] = x + (size_t)tok * d + 8 * ld_piece;
+            xoff[i] = (uint32_t)(((size_t)tok * d) >> 3) + ld_piece;
         }
         const __bf16* wf[BR];
         wf[0] = wupf + (size_t)e * MT * NK32 * 512 + lane * 8;
         if (GATED) wf[BR - 1] = wgatef + (size_t)e * MT * NK32 * 512 + lane * 8;
 
-        // biases of this lane's neurons, fetched now so that their latency hides under the K loop
-        float bias[MT][4];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int n = neuron_of_slot(mt, 4 * q + r);
-                bias[mt][r] = (!GATED && b_up) ? (float)b_up[(size_t)e * m + min(n, m - 1)] : 0.0f;
-            }
-
+        // the accumulators start at the biases of this lane's neurons (no registers held for them
+        // through the K loop)
         f32x4 acc[BR][MT][TT];
 #pragma unroll
-        for (int br = 0; br < BR; ++br)
+        for (int mt = 0; mt < MT; ++mt) {
+            f32x4 bias = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (!GATED && b_up) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
+                for (int r = 0; r < 4; ++r) {
+                    const int n = neuron_of_slot(mt, 4 * q + r);
+                    bias[r] = (float)b_up[(size_t)e * m + min(n, m - 1)];
+                }
+            }
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[br][mt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int br = 0; br < BR; ++br)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[br][mt][tt] = br == 0 ? bias : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 
         bf16x8 xr[NL];
         bf16x8 a0[2][BR][MT], a1[2][BR][MT];
         auto load_x = [&](int kb) {
 #pragma unroll
-            for (int i = 0; i < NL; ++i) xr[i] = load8(xrow[i] + 64 * kb);
+            for (int i = 0; i < NL; ++i) xr[i] = load8(x + (((size_t)xoff[i] + 8 * kb) << 3));
         };
         auto load_a = [&](int kb, bf16x8 (&a)[2][BR][MT]) {
 #pragma unroll
@@ -231,13 +233,13 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
                         a[ks][br][mt] = load8(wf[br] + ((size_t)mt * NK32 + 2 * kb + ks) * 512);
         };
         auto store_x = [&](int buf) {
-            char* dst = xs + buf * (UR * kUpRowBytes) + ld_row * kUpRowBytes + ld_piece * 16;
+            char* dst = xs + (buf % NBUF) * (UR * kUpRowBytes) + ld_row * kUpRowBytes + ld_piece * 16;
 #pragma unroll
             for (int i = 0; i < NL; ++i)
                 *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
         };
         auto compute = [&](int buf, const bf16x8 (&a)[2][BR][MT]) {
-            const char* src = xs + buf * (UR * kUpRowBytes) + c * kUpRowBytes + q * 16;
+            const char* src = xs + (buf % NBUF) * (UR * kUpRowBytes) + c * kUpRowBytes + q * 16;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 bf16x8 b[TT];
@@ -287,7 +289,7 @@ __global__ __launch_bounds__(256) void up_bf16_kernel(
                         if (GATED) {
                             v = activate_fast(act, acc[BR - 1][mt][tt][r]) * acc[0][mt][tt][r];
                         } else {
-                            v = activate_fast(act, acc[0][mt][tt][r] + bias[mt][r]);
+                            v = activate_fast(act, acc[0][mt][tt][r]);
                         }
                         if (n0 + r >= m) v = 0.0f;
                         hv[half * 4 + r] = (__bf16)v;
@@ -583,20 +585,20 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
 }
 
 // ---- launchers ---------------------------------------------------------------------------------------
-template <int MT, bool GATED, int TT>
+template <int MT, bool GATED, int TT, int NBUF = 2>
 void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, const int32_t* witem,
                  const int32_t* wfirst, int NW, const int32_t* alist, void* H, int grid,
                  hipStream_t s) {
     const size_t lds = ((2 * (size_t)L.n_experts + 1) * 4 + 15) / 16 * 16 +
-                       4 * 2 * (size_t)TT * 16 * kUpRowBytes;
+                       4 * NBUF * (size_t)TT * 16 * kUpRowBytes;
     static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_bf16_kernel<MT, GATED, TT>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_bf16_kernel<MT, GATED, TT, NBUF>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    up_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
+    up_bf16_kernel<MT, GATED, TT, NBUF><<<grid, 256, lds, s>>>(
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
         (const __bf16*)L.b_up, witem, wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts,
         L.expert_size, L.act);
@@ -727,7 +729,11 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
         if (mt == 2) launch_up_t<2, true, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
         else launch_up_t<4, true, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
     } else {
-        if (mt == 2) launch_up_t<2, false, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
+        if (mt == 2) {
+            // 32-neuron rows: one staging buffer, three workgroups per CU
+            const int grid3 = round_up((int)std::min<long long>((worst + 3) / 4, 256 * 3), 8);
+            launch_up_t<2, false, 4, 1>(L, x, P, witem, wfirst, NW, alist, H, grid3, s);
+        }
         else if (mt == 4) launch_up_t<4, false, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
         else launch_up_t<8, false, 4>(L, x, P, witem, wfirst, NW, alist, H, grid, s);
     }

@@ -318,9 +318,9 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
     constexpr int UR = TT * 16;
     constexpr int NL = TT * 2;
     extern __shared__ char smem[];
-    int32_t* s_wit = reinterpret_cast<int32_t*>(smem);
-    int32_t* s_wf = s_wit + (E + 1);
-    const int items_bytes = ((2 * E + 1) * 4 + 15) & ~15;
+    int32_t* s_wit = reinterpret_cast<int32_t*>(smem);  // witem[w][0..E-1], then wfirst[w][0..E-1]
+    int32_t* s_wf = s_wit + E;
+    const int items_bytes = (2 * E * 4 + 15) & ~15;
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15;
     const int wave_in_block = threadIdx.x >> 6;
     // one staging buffer per wavefront (its LDS accesses keep their order, so a second one buys
@@ -337,10 +337,10 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
     const int n_waves = n_wg * (blockDim.x >> 6);
     for (int wdx = windowed ? (int)(blockIdx.x & 7) : 0; wdx < NW; wdx += 8) {
     __syncthreads();  // the previous window's table is no longer read
-    for (int i = threadIdx.x; i <= 2 * E; i += blockDim.x)
-        s_wit[i] = i <= E ? witem[(size_t)wdx * (E + 1) + i] : wfirst[(size_t)wdx * E + (i - E - 1)];
+    for (int i = threadIdx.x; i < 2 * E; i += blockDim.x)
+        s_wit[i] = i < E ? witem[(size_t)wdx * (E + 1) + i] : wfirst[(size_t)wdx * E + (i - E)];
+    const int total = witem[(size_t)wdx * (E + 1) + E];
     __syncthreads();
-    const int total = s_wit[E];
     for (int j = wave; j < total; j += n_waves) {
         int lo = 0, hi = E;  // last e with s_wit[e] <= j
         while (hi - lo > 1) {
@@ -702,10 +702,12 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
     }
     if (up_tiny_supported(L)) {
         constexpr int TT = 4;
-        const size_t lds = ((2 * (size_t)L.n_experts + 1) * 4 + 15) / 16 * 16 +
+        const size_t lds = (2 * (size_t)L.n_experts * 4 + 15) / 16 * 16 +
                            4 * (size_t)TT * 16 * kUpRowBytes;
-        // up to three workgroups per CU
-        const int grid = round_up((int)std::min<long long>((worst + 3) / 4, 256 * 3), 8);
+        // as many workgroups per CU as LDS allows, at most the three that the registers allow
+        // (squeezed into a fourth wavefront per SIMD's share of registers the kernel got slower)
+        const int per_cu = std::max(1, std::min(3, (int)(160 * 1024 / lds)));
+        const int grid = round_up((int)std::min<long long>((worst + 3) / 4, 256 * per_cu), 8);
         static bool attr_set = false;
         if (!attr_set) {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT, true>),

@@ -560,7 +560,7 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
     }
     // with few token groups and many experts the mask words of a group are split over several
     // workgroups (each repeats the prefix sums over the experts)
-    const int ny = NG >= 256 ? 1 : std::min(W, div_up(512, std::max(1, NG)));
+    const int ny = std::max(1, std::min(W, div_up(2048, std::max(1, NG))));
     fill_lists_kernel<<<dim3(std::max(1, NG), ny), 256, lds, s>>>(
         mask, T, E, W, group_off, rows_per_item, counts, offsets, item_start, token_lists,
         aligned_lists, window_groups, NW, witem, wfirst);

@@ -30,8 +30,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from separate `rocprofv3 --pmc FETCH_SIZE` /
 # `WRITE_SIZE` runs of this script, scaled by the same counters' readings for a plain 256 MiB copy
 # (profiles/dmoe_forward_cfg2_tau0.5_hbm_traffic.txt).  Only valid for the exact workload named.
-MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 61.2e6 + 25.3e6,
-                    ("cfg2", 0.5, "expert_up"): 156.8e6 + 22.1e6}
+MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 61.2e6 + 25.4e6,
+                    ("cfg2", 0.5, "expert_up"): 127.2e6 + 26.8e6}
 N_ROTATE = 8                   # distinct x / y buffers cycled through, so that inputs come from HBM
 N_LAYER_COPIES_DECODE = 4      # distinct weight copies cycled through at decode sizes: together
                                # they exceed the 256 MB last-level cache, so weights come from HBM

@@ -26,10 +26,10 @@ inline int m_pad_of(int m) {
 // List rows per up-projection work item (a multiple of 16); every expert's region of H starts
 // at a multiple of this many rows.
 inline int up_rows_bf16(const dmoe_layer& L) {
-    // wide experts (8 neuron tiles per K step, no up bias) use the kernel that shares the weights
-    // of a 256-row item through LDS; everything else uses one wavefront per 64 rows
+    // wide experts (8 neuron tiles per K step) use the kernel that shares the weights of a 256-row
+    // item through LDS; everything else uses one wavefront per 64 rows
     const int tiles = (L.gated ? 2 : 1) * (m_pad_of(L.expert_size) / 16);
-    return (tiles == 8 && !L.b_up) ? 256 : 64;
+    return tiles == 8 ? 256 : 64;
 }
 
 // H capacity in 16-row fragments for T tokens: every expert may round up to a whole work item,

@@ -456,9 +456,9 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
 template <int MT, bool GATED, int TT>
 __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
-    const __bf16* __restrict__ wgatef, const int32_t* __restrict__ witem,
-    const int32_t* __restrict__ wfirst, int NW, const int32_t* __restrict__ alist,
-    __bf16* __restrict__ Hf, int d, int E, int m, int act) {
+    const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
+    const int32_t* __restrict__ witem, const int32_t* __restrict__ wfirst, int NW,
+    const int32_t* __restrict__ alist, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
     constexpr int BR = GATED ? 2 : 1;
     constexpr int KS = MT / 2;
     constexpr int NT = BR * MT;         // neuron tiles per K step
@@ -471,6 +471,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
     char* wbuf = smem;                                   // [2][NWF][1024]
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15, w = threadIdx.x >> 6;
     char* xs = smem + 2 * NWF * 1024 + w * (WR * kUpRowBytes);   // [WR][kUpRowBytes], private
+    float* sbias = reinterpret_cast<float*>(smem + 2 * NWF * 1024 + 4 * (WR * kUpRowBytes));  // [MT * 16]
     const int NK32 = d / 32, NKB = d / 64;
     const int ld_row = lane >> 3, ld_piece = lane & 7;
     // windows as in the kernel above: XCD k takes the windows k, k+8, ...; a single window is
@@ -509,6 +510,11 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) acc[nt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // bias of neuron threadIdx.x of a plain expert: requested with the first loads, parked in
+        // LDS once they have arrived, read back in the epilogue (no registers held for it)
+        float bias_reg = 0.0f;
+        if (!GATED && b_up && (int)threadIdx.x < MT * 16)
+            bias_reg = (float)b_up[(size_t)e * m + min((int)threadIdx.x, m - 1)];
 
         bf16x8 xr[NL], wr[NWF / 4];
         auto load_next = [&](int kb) {
@@ -533,6 +539,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
         __syncthreads();  // the previous item's last K block has been consumed by every wavefront
         load_next(0);
         store_next(0);
+        if (!GATED && (int)threadIdx.x < MT * 16) sbias[threadIdx.x] = bias_reg;
         __syncthreads();
         for (int kb = 0; kb < NKB; ++kb) {
             load_next(min(kb + 1, NKB - 1));  // the last trip re-reads a block it will not use
@@ -571,7 +578,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
                         for (int r = 0; r < 4; ++r) {
                             float v;
                             if (GATED) v = activate_fast(act, acc[MT + mt][tt][r]) * acc[mt][tt][r];
-                            else v = activate_fast(act, acc[mt][tt][r]);
+                            else v = activate_fast(act, acc[mt][tt][r] + sbias[neuron_of_slot(mt, 4 * q + r)]);
                             if (neuron_of_slot(mt, 4 * q + r) >= m) v = 0.0f;
                             hv[half * 4 + r] = (__bf16)v;
                         }
@@ -609,7 +616,7 @@ void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
                       const int32_t* witem, const int32_t* wfirst, int NW, const int32_t* alist,
                       void* H, int grid, hipStream_t s) {
     constexpr int NWF = 2 * (GATED ? 2 : 1) * MT;
-    const size_t lds = 2 * NWF * 1024 + 4 * (size_t)TT * 16 * kUpRowBytes;
+    const size_t lds = 2 * NWF * 1024 + 4 * (size_t)TT * 16 * kUpRowBytes + MT * 16 * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_wide_bf16_kernel<MT, GATED, TT>),
@@ -618,8 +625,9 @@ void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
     }
     const char* pk = static_cast<const char*>(L.packed);
     up_wide_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
-        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef), witem,
-        wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
+        (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
+        (const __bf16*)L.b_up, witem, wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts,
+        L.expert_size, L.act);
 }
 
 }  // namespace
@@ -693,7 +701,7 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
     const long long worst = (long long)T * L.n_experts / up_rows_bf16(L) + L.n_experts;
     const int grid = round_up((int)std::min<long long>((worst + 3) / 4, 256 * 2), 8);
     const int mt = m_pad_of(L.expert_size) / 16;
-    if (up_rows_bf16(L) == 256) {  // wide experts without b_up: weights shared through LDS
+    if (up_rows_bf16(L) == 256) {  // wide experts: weights shared through LDS
         const int wgrid = round_up(
             (int)std::min<long long>((long long)T * L.n_experts / 256 + L.n_experts, 512), 8);
         if (L.gated) launch_up_wide_t<4, true, 4>(L, x, P, witem, wfirst, NW, alist, H, wgrid, s);

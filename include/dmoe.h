@@ -102,7 +102,8 @@ const char *dmoe_last_error(void);
 /* ---- sizes (host only, nothing is launched) ------------------------------------------------ */
 
 /* Workspace that dmoe_forward / dmoe_expert_ffn need for n_tokens tokens (worst case: every
- * token selects every expert). */
+ * token selects every expert).  The requirement never shrinks as n_tokens grows, so a buffer
+ * sized for the largest batch serves every smaller one. */
 int32_t dmoe_workspace_bytes(const dmoe_layer *layer, int32_t n_tokens, size_t *out_bytes);
 /* Workspace of dmoe_select. */
 int32_t dmoe_select_workspace_bytes(int32_t n_tokens, int32_t n_experts, size_t *out_bytes);

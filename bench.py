@@ -78,7 +78,7 @@ class Workload:
         B.dmoe_forward(L, self.xs[i % N_ROTATE], tau, y=self.ys[i % N_ROTATE])
 
     def measure(self, tau_arg, steps, warmup, traffic_ok=True):
-        """Whole-forward time, per-kernel times (HIP events on the launch stream) and the
+        """Whole-forward time, per-kernel times (HIP events stamped by the launches themselves) and the
         roofline object of the dominant expert kernel."""
         import torch
         from paper_2310_04361_amd import binding as B, cost_model

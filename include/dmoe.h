@@ -222,9 +222,11 @@ int32_t dmoe_forward_group(const dmoe_layer *const *layers, int32_t n_layers, co
 /* ---- per-kernel timing (measurement aid) ----------------------------------------------------- */
 
 /*
- * When enabled, every kernel the library launches is bracketed by HIP events on the launch
- * stream.  dmoe_timing_read() waits for those events and returns, for kernel slot `index`
- * (0 .. dmoe_timing_slots()-1), its name, the number of launches and the summed duration in
+ * When enabled, every kernel launch of the library stamps a pair of HIP events with the start and
+ * the end of that kernel on the device (hipExtLaunchKernel on the launch stream), so the sums
+ * are kernel time without the gaps around event records.  dmoe_timing_read() waits for those
+ * events and returns, for kernel slot `index` (0 .. dmoe_timing_slots()-1), its name, the number
+ * of launches (a step that takes two kernels counts once) and the summed duration in
  * milliseconds since the last dmoe_timing_reset().  Enabling allocates the event pool (the only
  * allocation the library ever makes); launches beyond the pool are not timed.  Not thread-safe;
  * meant for a benchmark's separate measurement pass.

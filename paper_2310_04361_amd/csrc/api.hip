@@ -29,19 +29,22 @@ const char* const kSlotNames[kSlotCount] = {
 constexpr int kEventPairs = 8192;
 bool g_timing = false;
 std::vector<hipEvent_t> g_ev;      // 2 * kEventPairs once enabled
-std::vector<int> g_ev_slot;        // slot of each recorded pair
+std::vector<int> g_ev_slot;        // slot of each pair; -1: reserved but never stamped
+std::vector<char> g_ev_first;      // the pair is the first of its scope (counts as a launch)
 int g_ev_used = 0;
+thread_local LaunchTimer* g_scope = nullptr;
 int64_t g_launches[kSlotCount];
 double g_ms[kSlotCount];
 
 int collect_events() {
     for (int i = 0; i < g_ev_used; ++i) {
+        if (g_ev_slot[i] < 0) continue;
         hipError_t e = hipEventSynchronize(g_ev[2 * i + 1]);
         if (e != hipSuccess) return fail(DMOE_ERR_HIP, "hipEventSynchronize: %s", hipGetErrorString(e));
         float ms = 0.f;
         e = hipEventElapsedTime(&ms, g_ev[2 * i], g_ev[2 * i + 1]);
         if (e != hipSuccess) return fail(DMOE_ERR_HIP, "hipEventElapsedTime: %s", hipGetErrorString(e));
-        g_launches[g_ev_slot[i]] += 1;
+        g_launches[g_ev_slot[i]] += g_ev_first[i] ? 1 : 0;
         g_ms[g_ev_slot[i]] += ms;
     }
     g_ev_used = 0;
@@ -258,15 +261,31 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
 
 }  // namespace
 
-LaunchTimer::LaunchTimer(int slot, hipStream_t stream) : slot_(slot), index_(-1), stream_(stream) {
+LaunchTimer::LaunchTimer(int slot, hipStream_t stream)
+    : slot_(slot), index_(-1), used_(false), prev_(g_scope), stream_(stream) {
     if (g_timing && g_ev_used < kEventPairs) {
         index_ = g_ev_used++;
-        g_ev_slot[index_] = slot;
-        (void)hipEventRecord(g_ev[2 * index_], stream_);
+        g_ev_slot[index_] = -1;  // until a launch takes the pair
+        g_ev_first[index_] = 1;
     }
+    g_scope = this;
 }
-LaunchTimer::~LaunchTimer() {
-    if (index_ >= 0) (void)hipEventRecord(g_ev[2 * index_ + 1], stream_);
+LaunchTimer::~LaunchTimer() { g_scope = prev_; }
+
+bool timer_events_for_launch(hipEvent_t* start, hipEvent_t* stop) {
+    LaunchTimer* t = g_scope;
+    if (!t || t->index_ < 0) return false;
+    int idx = t->index_;
+    if (t->used_) {  // a further kernel of the same scope
+        if (g_ev_used >= kEventPairs) return false;
+        idx = g_ev_used++;
+        g_ev_first[idx] = 0;
+    }
+    t->used_ = true;
+    g_ev_slot[idx] = t->slot_;
+    *start = g_ev[2 * idx];
+    *stop = g_ev[2 * idx + 1];
+    return true;
 }
 
 }  // namespace dmoe
@@ -571,6 +590,7 @@ int32_t dmoe_timing_enable(int32_t on) {
     if (on && g_ev.empty()) {
         g_ev.resize(2 * kEventPairs);
         g_ev_slot.resize(kEventPairs);
+        g_ev_first.resize(kEventPairs);
         for (auto& ev : g_ev) {
             hipError_t e = hipEventCreate(&ev);
             if (e != hipSuccess) {

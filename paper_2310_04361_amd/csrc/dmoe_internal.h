@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/dmoe.h"
@@ -104,14 +105,34 @@ enum Slot {
     kSlotCount
 };
 
-// Brackets one kernel launch with events when timing is enabled (see dmoe_timing_enable).
+// Scope of the kernel launches that are accounted to one timing slot (see dmoe_timing_enable).
+// With timing enabled, launch_kernel() inside the scope has the launch itself stamp an event pair
+// with the start and the end of the kernel on the device, so what is summed is kernel time, not
+// the gaps around event records.  One scope counts as one launch of its slot however many
+// kernels it holds.
 struct LaunchTimer {
     LaunchTimer(int slot, hipStream_t stream);
     ~LaunchTimer();
     int slot_;
-    int index_;
+    int index_;          // event pair reserved for the first launch, -1: timing off
+    bool used_;          // that pair has been handed to a launch
+    LaunchTimer* prev_;
     hipStream_t stream_;
 };
+// Event pair for the next launch of the calling thread's innermost scope (false: launch untimed).
+bool timer_events_for_launch(hipEvent_t* start, hipEvent_t* stop);
+
+// Every kernel of the library is launched through here.
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t s,
+                          Args&&... args) {
+    hipEvent_t ev0, ev1;
+    if (timer_events_for_launch(&ev0, &ev1))
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, s, ev0, ev1, 0u,
+                              static_cast<KArgs>(args)...);
+    else
+        kernel<<<grid, block, lds, s>>>(static_cast<KArgs>(args)...);
+}
 
 // ---- select / bucket (select.hip) -----------------------------------------------------------
 // group_off is [(NG+1)][E] int32 with NG = ceil(T/64): after the scans, group_off[g][e] is the

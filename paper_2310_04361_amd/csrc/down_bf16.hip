@@ -399,7 +399,7 @@ void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int3
     const int row_bytes = 2 * m_pad_of(L.expert_size);
     int row_shift = 0;
     while ((1 << row_shift) < row_bytes) ++row_shift;
-    down_bf16_kernel<KSP, G, R, WPS, CT><<<round_up(NC, 8) * NS, 256, lds, s>>>(
+    launch_kernel(down_bf16_kernel<KSP, G, R, WPS, CT>, round_up(NC, 8) * NS, 256, lds, s, 
         (const __bf16*)(pk + P.w2g), (const __bf16*)L.b_down, item_start, group_off,
         reinterpret_cast<const uint32_t*>(mask), offsets, (const __bf16*)H, (__bf16*)y, T,
         L.d_model, L.n_experts, NG, 2 * div_up(L.n_experts, 64), up_rows_bf16(L), row_shift,
@@ -421,7 +421,7 @@ bool down_bf16_addressable(const dmoe_layer& L, int T) {
 
 void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s) {
     const DownPacking dp = down_packing(L.expert_size);
-    pack_down32_kernel<<<2048, 256, 0, s>>>(L.w_down, L.w_scales,
+    launch_kernel(pack_down32_kernel, 2048, 256, 0, s, L.w_down, L.w_scales,
                                             L.weight_format == DMOE_W_FP8_E4M3, (__bf16*)w2g,
                                             L.n_experts, L.expert_size, L.d_model, dp.PG, dp.G, dp.KSP);
 }

@@ -225,7 +225,7 @@ void launch_down_rmw_t(const dmoe_layer& L, const PackedLayout& P, int T, const 
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    down_rmw_bf16_kernel<KS><<<round_up(NC, 8) * NS, kDownWaves * 64, kDownLds, s>>>(
+    launch_kernel(down_rmw_bf16_kernel<KS>, round_up(NC, 8) * NS, kDownWaves * 64, kDownLds, s, 
         (const __bf16*)(pk + P.w2f), (const __bf16*)L.b_down, item_start, group_off, alist, offsets,
         (const __bf16*)H, (__bf16*)y, T, L.d_model, L.n_experts, NG, up_rows_bf16(L), max_pairs);
 }

@@ -605,7 +605,7 @@ void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, cons
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    up_bf16_kernel<MT, GATED, TT, NBUF><<<grid, 256, lds, s>>>(
+    launch_kernel(up_bf16_kernel<MT, GATED, TT, NBUF>, grid, 256, lds, s, 
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
         (const __bf16*)L.b_up, witem, wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts,
         L.expert_size, L.act);
@@ -624,7 +624,7 @@ void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    up_wide_bf16_kernel<MT, GATED, TT><<<grid, 256, lds, s>>>(
+    launch_kernel(up_wide_bf16_kernel<MT, GATED, TT>, grid, 256, lds, s, 
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
         (const __bf16*)L.b_up, witem, wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts,
         L.expert_size, L.act);
@@ -646,33 +646,33 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     char* pk = static_cast<char*>(packed);
     const int fp8 = L.weight_format == DMOE_W_FP8_E4M3;
     const int E = L.n_experts, m = L.expert_size, d = L.d_model;
-    pack_down_kernel<__bf16><<<2048, 256, 0, s>>>(L.w_down, L.w_scales, fp8, (__bf16*)(pk + P.w2f), E,
+    launch_kernel(pack_down_kernel<__bf16>, 2048, 256, 0, s, L.w_down, L.w_scales, fp8, (__bf16*)(pk + P.w2f), E,
                                                   m, d, mp / 32);
     launch_pack_down_bf16(L, pk + P.w2g, s);
-    pack_up_kernel<__bf16><<<2048, 256, 0, s>>>(L.w_up, L.w_scales, fp8, 0, (__bf16*)(pk + P.wupf), E,
+    launch_kernel(pack_up_kernel<__bf16>, 2048, 256, 0, s, L.w_up, L.w_scales, fp8, 0, (__bf16*)(pk + P.wupf), E,
                                                 m, d, mp / 16, 1);
     if (L.gated)
-        pack_up_kernel<__bf16><<<2048, 256, 0, s>>>(L.w_gate, L.w_scales, fp8, 1,
+        launch_kernel(pack_up_kernel<__bf16>, 2048, 256, 0, s, L.w_gate, L.w_scales, fp8, 1,
                                                     (__bf16*)(pk + P.wgatef), E, m, d, mp / 16, 1);
     if (up_tiny_supported(L))
-        pack_up_tiny_kernel<<<2048, 256, 0, s>>>(L.w_up, L.w_gate, L.w_scales, fp8,
+        launch_kernel(pack_up_tiny_kernel, 2048, 256, 0, s, L.w_up, L.w_gate, L.w_scales, fp8,
                                                  (__bf16*)(pk + P.wtinyf), E, m, d, L.gated);
     if (fp8) {  // byte fragments for the small-token kernels
-        pack_down_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_down, L.w_scales, 1, (uint8_t*)(pk + P.w2f8),
+        launch_kernel(pack_down_kernel<uint8_t>, 2048, 256, 0, s, L.w_down, L.w_scales, 1, (uint8_t*)(pk + P.w2f8),
                                                        E, m, d, mp / 32);
-        pack_up_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_up, L.w_scales, 1, 0, (uint8_t*)(pk + P.wupf8),
+        launch_kernel(pack_up_kernel<uint8_t>, 2048, 256, 0, s, L.w_up, L.w_scales, 1, 0, (uint8_t*)(pk + P.wupf8),
                                                      E, m, d, mp / 16, 1);
         if (L.gated)
-            pack_up_kernel<uint8_t><<<2048, 256, 0, s>>>(L.w_gate, L.w_scales, 1, 1,
+            launch_kernel(pack_up_kernel<uint8_t>, 2048, 256, 0, s, L.w_gate, L.w_scales, 1, 1,
                                                          (uint8_t*)(pk + P.wgatef8), E, m, d, mp / 16, 1);
     }
     // the router matrices use the same fragment format: "one expert" whose rows are the hidden
     // units (r_w1) or the experts (r_w2)
     const int dh = L.router_hidden;
     if (L.r_w1 && L.r_w2 && dh > 0 && dh % 32 == 0 && L.d_model % 32 == 0) {
-        pack_up_kernel<__bf16><<<512, 256, 0, s>>>(L.r_w1, nullptr, 0, 0, (__bf16*)(pk + P.r1f), 1, dh,
+        launch_kernel(pack_up_kernel<__bf16>, 512, 256, 0, s, L.r_w1, nullptr, 0, 0, (__bf16*)(pk + P.r1f), 1, dh,
                                                    L.d_model, dh / 16, 0);
-        pack_up_kernel<__bf16><<<512, 256, 0, s>>>(L.r_w2, nullptr, 0, 0, (__bf16*)(pk + P.r2f), 1,
+        launch_kernel(pack_up_kernel<__bf16>, 512, 256, 0, s, L.r_w2, nullptr, 0, 0, (__bf16*)(pk + P.r2f), 1,
                                                    L.n_experts, dh, div_up(L.n_experts, 16), 0);
     }
 }
@@ -726,11 +726,11 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
         }
         const char* pk = static_cast<const char*>(L.packed);
         if (L.gated)
-            up_tiny_kernel<TT, true><<<grid, 256, lds, s>>>(
+            launch_kernel(up_tiny_kernel<TT, true>, grid, 256, lds, s, 
                 (const __bf16*)x, (const __bf16*)(pk + P.wtinyf), nullptr, witem, wfirst, NW, alist,
                 (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
         else
-            up_tiny_kernel<TT, false><<<grid, 256, lds, s>>>(
+            launch_kernel(up_tiny_kernel<TT, false>, grid, 256, lds, s, 
                 (const __bf16*)x, (const __bf16*)(pk + P.wtinyf), (const __bf16*)L.b_up, witem, wfirst,
                 NW, alist, (__bf16*)H, L.d_model, L.n_experts, L.expert_size, L.act);
         return;

@@ -63,7 +63,7 @@ void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* 
     LaunchTimer tm(kSlotFfnF32, s);
     const int W = div_up(L.n_experts, 64);
     const size_t lds = sizeof(float) * (size_t)(2 * L.d_model + L.expert_size);
-    ffn_f32_kernel<<<T, 256, lds, s>>>(x, (const float*)L.w_up,
+    launch_kernel(ffn_f32_kernel, T, 256, lds, s, x, (const float*)L.w_up,
                                        L.gated ? (const float*)L.w_gate : nullptr,
                                        (const float*)L.b_up, (const float*)L.w_down,
                                        (const float*)L.b_down, mask, y, L.d_model, L.n_experts,

@@ -241,7 +241,7 @@ void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
     // K slices: as many as the sixteen wavefronts allow and the k-steps divide into
     int KQ = kUpSmallWaves / MT;
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
-    up_small_kernel<MT, GATED, W8><<<dim3(L.n_experts, 1, n_layers), 64 * kUpSmallWaves, lds, s>>>(
+    launch_kernel(up_small_kernel<MT, GATED, W8>, dim3(L.n_experts, 1, n_layers), 64 * kUpSmallWaves, lds, s, 
         G, (const __bf16*)x, T, L.d_model, L.expert_size, L.act, KQ);
 }
 
@@ -288,15 +288,15 @@ void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
     {
         LaunchTimer tm(kSlotSmallDown, s);
         const bool w8 = L.weight_format == DMOE_W_FP8_E4M3;
-        if (ks == 1 && !w8) down_small_kernel<1, false><<<grid, 256, 0, s>>>(G, T, d, E, per);
-        else if (ks == 2 && !w8) down_small_kernel<2, false><<<grid, 256, 0, s>>>(G, T, d, E, per);
-        else if (!w8) down_small_kernel<4, false><<<grid, 256, 0, s>>>(G, T, d, E, per);
-        else if (ks == 1) down_small_kernel<1, true><<<grid, 256, 0, s>>>(G, T, d, E, per);
-        else if (ks == 2) down_small_kernel<2, true><<<grid, 256, 0, s>>>(G, T, d, E, per);
-        else down_small_kernel<4, true><<<grid, 256, 0, s>>>(G, T, d, E, per);
+        if (ks == 1 && !w8) launch_kernel(down_small_kernel<1, false>, grid, 256, 0, s, G, T, d, E, per);
+        else if (ks == 2 && !w8) launch_kernel(down_small_kernel<2, false>, grid, 256, 0, s, G, T, d, E, per);
+        else if (!w8) launch_kernel(down_small_kernel<4, false>, grid, 256, 0, s, G, T, d, E, per);
+        else if (ks == 1) launch_kernel(down_small_kernel<1, true>, grid, 256, 0, s, G, T, d, E, per);
+        else if (ks == 2) launch_kernel(down_small_kernel<2, true>, grid, 256, 0, s, G, T, d, E, per);
+        else launch_kernel(down_small_kernel<4, true>, grid, 256, 0, s, G, T, d, E, per);
     }
     LaunchTimer tm(kSlotSmallFinish, s);
-    finish_small_kernel<<<dim3(div_up(T * d, 256), 1, n_layers), 256, 0, s>>>(G, T, d, EG);
+    launch_kernel(finish_small_kernel, dim3(div_up(T * d, 256), 1, n_layers), 256, 0, s, G, T, d, EG);
 }
 
 }  // namespace dmoe

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void router_bf16_kernel(const __bf16* __restri
 template <int NH>
 void launch_router_bf16_t(const dmoe_layer& L, const void* x, int T, float* scores, hipStream_t s) {
     const int tiles = div_up(T, 16);
-    router_bf16_kernel<NH><<<div_up(tiles, 4), 256, 0, s>>>(
+    launch_kernel(router_bf16_kernel<NH>, div_up(tiles, 4), 256, 0, s, 
         (const __bf16*)x, (const __bf16*)L.r_w1, (const __bf16*)L.r_b1, (const __bf16*)L.r_w2,
         (const __bf16*)L.r_b2, scores, T, L.d_model, L.n_experts);
 }
@@ -142,7 +142,7 @@ bool router_bf16_supported(const dmoe_layer& L) {
 void launch_router_f32(const dmoe_layer& L, const float* x, int T, float* scores, hipStream_t s) {
     LaunchTimer tm(kSlotRouter, s);
     const size_t lds = sizeof(float) * (size_t)(L.d_model + L.router_hidden);
-    router_f32_kernel<<<T, 256, lds, s>>>(x, (const float*)L.r_w1, (const float*)L.r_b1,
+    launch_kernel(router_f32_kernel, T, 256, lds, s, x, (const float*)L.r_w1, (const float*)L.r_b1,
                                           (const float*)L.r_w2, (const float*)L.r_b2, scores,
                                           L.d_model, L.router_hidden, L.n_experts);
 }

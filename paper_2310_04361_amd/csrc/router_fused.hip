@@ -353,7 +353,7 @@ void launch_t3(const dmoe_layer& L, const void* x, int T, float* scores, float t
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    router_fused_kernel<NH, ETW, KBC, TT><<<div_up(T, TOK), 256, lds, s>>>(
+    launch_kernel(router_fused_kernel<NH, ETW, KBC, TT>, div_up(T, TOK), 256, lds, s, 
         (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1,
         (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T, L.d_model, E, tau,
         mask != nullptr, mask, k_per_token, group_cnt, colmask, nullptr, 0, 0);
@@ -465,7 +465,7 @@ void launch_router_small_hidden(const dmoe_layer& L, const SmallGroup& G, int n_
     const int dh = L.router_hidden;
     int KQ = 16;  // wavefronts that split K: as many as divide the k-steps
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
-    router_small_hidden_kernel<<<dim3(dh / 16, 1, n_layers), 1024, 0, s>>>(G, (const __bf16*)x, T,
+    launch_kernel(router_small_hidden_kernel, dim3(dh / 16, 1, n_layers), 1024, 0, s, G, (const __bf16*)x, T,
                                                                           L.d_model, dh, KQ);
 }
 
@@ -474,7 +474,7 @@ void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
     launch_router_small_hidden(L, G, n_layers, x, T, s);
     LaunchTimer tm(kSlotRouter, s);
     const int dh = L.router_hidden, E = L.n_experts;
-    router_small_scores_kernel<<<dim3(div_up(div_up(E, 16), 4), 1, n_layers), 256, 0, s>>>(G, T, dh, E);
+    launch_kernel(router_small_scores_kernel, dim3(div_up(div_up(E, 16), 4), 1, n_layers), 256, 0, s, G, T, dh, E);
 }
 
 bool router_fused_scores_supported(const dmoe_layer& L) {
@@ -511,7 +511,7 @@ static void launch_scores_slices(const dmoe_layer& L, const PackedLayout& P, int
         attr_set = true;
     }
     const char* pk = static_cast<const char*>(L.packed);
-    router_fused_kernel<NH, 2, 4, 4, kScoresSlice><<<dim3(NG, div_up(NE, tiles_y)), 256, lds, s>>>(
+    launch_kernel(router_fused_kernel<NH, 2, 4, 4, kScoresSlice>, dim3(NG, div_up(NE, tiles_y)), 256, lds, s, 
         nullptr, nullptr, nullptr, (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T,
         L.d_model, L.n_experts, 0.0f, 0, nullptr, nullptr, nullptr, nullptr,
         const_cast<__bf16*>(hid), L.router_hidden, tiles_y);
@@ -533,7 +533,7 @@ void launch_router_sliced(const dmoe_layer& L, const void* x, int T, void* hid, 
                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             attr_set = true;
         }
-        router_fused_kernel<NH, 2, KBC, 4, kHiddenSlice><<<dim3(NG, dh / 128), 256, lds, s>>>(
+        launch_kernel(router_fused_kernel<NH, 2, KBC, 4, kHiddenSlice>, dim3(NG, dh / 128), 256, lds, s, 
             (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1, nullptr, nullptr,
             nullptr, T, L.d_model, L.n_experts, 0.0f, 0, nullptr, nullptr, nullptr, nullptr,
             (__bf16*)hid, dh, 0);

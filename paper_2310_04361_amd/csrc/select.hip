@@ -469,26 +469,26 @@ void launch_mask_from_scores(const float* scores, int T, int E, float tau, uint6
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     LaunchTimer tm(kSlotMask, s);
     if (T <= 16) {
-        select_small_kernel<<<1, 1024, sizeof(uint64_t) * 16 * W, s>>>(
+        launch_kernel(select_small_kernel, 1, 1024, sizeof(uint64_t) * 16 * W, s, 
             scores, mask, k_per_token, group_off, colmask, T, E, W, tau);
         return;
     }
     const int grid = div_up(T, 4);
-    if (W <= 1) tau_mask_kernel<1><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    else if (W <= 2) tau_mask_kernel<2><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    else if (W <= 4) tau_mask_kernel<4><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    else if (W <= 8) tau_mask_kernel<8><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    else if (W <= 16) tau_mask_kernel<16><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    else if (W <= 32) tau_mask_kernel<32><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    else tau_mask_kernel<64><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, tau);
-    count_from_mask_kernel<<<div_up(NG * W, 4), 256, 0, s>>>(mask, group_off, colmask, T, E, W);
+    if (W <= 1) launch_kernel(tau_mask_kernel<1>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 2) launch_kernel(tau_mask_kernel<2>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 4) launch_kernel(tau_mask_kernel<4>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 8) launch_kernel(tau_mask_kernel<8>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 16) launch_kernel(tau_mask_kernel<16>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, tau);
+    else if (W <= 32) launch_kernel(tau_mask_kernel<32>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, tau);
+    else launch_kernel(tau_mask_kernel<64>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, tau);
+    launch_kernel(count_from_mask_kernel, div_up(NG * W, 4), 256, 0, s, mask, group_off, colmask, T, E, W);
 }
 
 void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_layers, int T,
                                hipStream_t s) {
     const int E = L.n_experts, W = div_up(E, 64);
     LaunchTimer tm(kSlotMask, s);
-    select_small_group_kernel<<<dim3(1, 1, n_layers), 1024, sizeof(uint64_t) * 16 * W, s>>>(G, T, E, W);
+    launch_kernel(select_small_group_kernel, dim3(1, 1, n_layers), 1024, sizeof(uint64_t) * 16 * W, s, G, T, E, W);
 }
 
 void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
@@ -505,7 +505,7 @@ void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         attr_set = true;
     }
-    router_scores_select_small_kernel<<<dim3(1, 1, n_layers), 1024, lds, s>>>(G, T, L.router_hidden, E, W);
+    launch_kernel(router_scores_select_small_kernel, dim3(1, 1, n_layers), 1024, lds, s, G, T, L.router_hidden, E, W);
 }
 
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,
@@ -514,12 +514,12 @@ void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T,
     {
         LaunchTimer tm(kSlotListsToMask, s);
         const size_t n = (size_t)T * W;
-        zero_u64_kernel<<<(int)std::min<size_t>(1024, (n + 255) / 256), 256, 0, s>>>(mask, n);
-        lists_to_mask_kernel<<<1024, 256, 0, s>>>(offsets, lists, T, E, W,
+        launch_kernel(zero_u64_kernel, (int)std::min<size_t>(1024, (n + 255) / 256), 256, 0, s, mask, n);
+        launch_kernel(lists_to_mask_kernel, 1024, 256, 0, s, offsets, lists, T, E, W,
                                                   reinterpret_cast<unsigned long long*>(mask));
     }
     LaunchTimer tm(kSlotMask, s);
-    count_from_mask_kernel<<<div_up(NG * W, 4), 256, 0, s>>>(mask, group_off, colmask, T, E, W);
+    launch_kernel(count_from_mask_kernel, div_up(NG * W, 4), 256, 0, s, mask, group_off, colmask, T, E, W);
 }
 
 void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
@@ -527,15 +527,15 @@ void launch_mask_topk(const float* scores, int T, int E, int k, uint64_t* mask,
     const int W = div_up(E, 64), NG = div_up(T, kGroup);
     LaunchTimer tm(kSlotMask, s);
     const int grid = div_up(T, 4);
-    if (W <= 1) topk_mask_kernel<1><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
-    else if (W <= 2) topk_mask_kernel<2><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
-    else if (W <= 4) topk_mask_kernel<4><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
-    else if (W <= 8) topk_mask_kernel<8><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
-    else if (W <= 16) topk_mask_kernel<16><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
-    else if (W <= 32) topk_mask_kernel<32><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
-    else topk_mask_kernel<64><<<grid, 256, 0, s>>>(scores, mask, k_per_token, T, E, W, k);
+    if (W <= 1) launch_kernel(topk_mask_kernel<1>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 2) launch_kernel(topk_mask_kernel<2>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 4) launch_kernel(topk_mask_kernel<4>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 8) launch_kernel(topk_mask_kernel<8>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 16) launch_kernel(topk_mask_kernel<16>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, k);
+    else if (W <= 32) launch_kernel(topk_mask_kernel<32>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, k);
+    else launch_kernel(topk_mask_kernel<64>, grid, 256, 0, s, scores, mask, k_per_token, T, E, W, k);
     // counts per (group, expert) and, if wanted, the per-expert token sets
-    count_from_mask_kernel<<<div_up(NG * W, 4), 256, 0, s>>>(mask, group_off, colmask, T, E, W);
+    launch_kernel(count_from_mask_kernel, div_up(NG * W, 4), 256, 0, s, mask, group_off, colmask, T, E, W);
 }
 
 void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off, int32_t* counts,
@@ -547,7 +547,7 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
     const int NW = witem ? div_up(NG, window_groups) : 0;
     {
         LaunchTimer tm(kSlotScanGroups, s);
-        scan_groups_kernel<<<div_up(E, 4), 256, 0, s>>>(group_off, NG, E, sub_cnt, split,
+        launch_kernel(scan_groups_kernel, div_up(E, 4), 256, 0, s, group_off, NG, E, sub_cnt, split,
                                                         div_up(T, kGroup / split));
     }
     LaunchTimer tm(kSlotFill, s);
@@ -561,7 +561,7 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
     // with few token groups and many experts the mask words of a group are split over several
     // workgroups (each repeats the prefix sums over the experts)
     const int ny = std::max(1, std::min(W, div_up(2048, std::max(1, NG))));
-    fill_lists_kernel<<<dim3(std::max(1, NG), ny), 256, lds, s>>>(
+    launch_kernel(fill_lists_kernel, dim3(std::max(1, NG), ny), 256, lds, s, 
         mask, T, E, W, group_off, rows_per_item, counts, offsets, item_start, token_lists,
         aligned_lists, window_groups, NW, witem, wfirst);
 }

@@ -28,7 +28,7 @@
  *   - Unsupported shapes/dtypes are refused with DMOE_ERR_UNSUPPORTED; there is no fallback path.
  *     Supported: any n_tokens >= 0 with n_tokens * n_experts < 2^31 - 64 and n_experts <= 4096.
  *     bf16 layers: d_model a multiple of 256, expert_size 1 .. 128 (1 .. 64 if gated), router with
- *     n_experts a multiple of 4 and router_hidden in {32, 64, 128, 256, 512}.  fp32 layers (the
+ *     router_hidden in {32, 64, 128, 256, 512}.  fp32 layers (the
  *     exactness configuration, one workgroup per token): d_model + router_hidden <= 16384 and
  *     2 d_model + expert_size <= 16384.
  */

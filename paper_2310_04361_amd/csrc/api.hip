@@ -73,7 +73,7 @@ int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
         if (!L->r_w1 || !L->r_w2) return fail(DMOE_ERR_NULL, "router weights are NULL");
         if (L->dtype == DMOE_BF16 && !router_bf16_supported(*L))
             return fail(DMOE_ERR_UNSUPPORTED,
-                        "bf16 router needs d %% 32 == 0, E %% 4 == 0 and d_h in {32,64,128,256,512}");
+                        "bf16 router needs d %% 32 == 0 and d_h in {32,64,128,256,512}");
         if (L->dtype == DMOE_F32 && (size_t)(L->d_model + L->router_hidden) * 4 > 65536)
             return fail(DMOE_ERR_UNSUPPORTED, "fp32 router needs d + d_h <= 16384");
     }

@@ -53,6 +53,30 @@ __device__ __forceinline__ bf16x8 load8(const __bf16* p) {
     return *reinterpret_cast<const bf16x8*>(p);
 }
 
+// Router scores (Sec. 3.3) of the experts e0 .. e0+3 of one token from the second product's
+// accumulator: |acc + c2|, and 0 for the components from E on (E need not be a multiple of 4;
+// e0 is one, and e0 < E).
+__device__ __forceinline__ float4 router_scores4(const f32x4& acc, const __bf16* __restrict__ r_b2,
+                                                 int e0, int E) {
+    float v[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        v[r] = e0 + r < E ? fabsf(acc[r] + (r_b2 ? (float)r_b2[e0 + r] : 0.0f)) : 0.0f;
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
+// ... and their store to row[e0 .. e0+3] of a [.][E] array: 16 bytes at once where the rows keep
+// that alignment, else element by element up to E.
+__device__ __forceinline__ void store_scores4(float* __restrict__ row, int e0, int E, const float4& v) {
+    if ((E & 3) == 0) {
+        *reinterpret_cast<float4*>(row + e0) = v;
+    } else {
+        row[e0] = v.x;
+        if (e0 + 1 < E) row[e0 + 1] = v.y;
+        if (e0 + 2 < E) row[e0 + 2] = v.z;
+        if (e0 + 3 < E) row[e0 + 3] = v.w;
+    }
+}
+
 // OCP E4M3 byte -> value (exact in bf16): 1 sign, 4 exponent bits (bias 7), 3 mantissa bits,
 // subnormals m / 8 * 2^-6, no infinities.  Plain arithmetic, used by the one-time packing.
 __device__ __forceinline__ float e4m3_value(uint32_t b) {

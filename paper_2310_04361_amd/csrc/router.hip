@@ -113,12 +113,7 @@ __global__ __launch_bounds__(256) void router_bf16_kernel(const __bf16* __restri
         }
         const int e0 = et * 16 + 4 * q;  // this lane: experts e0 .. e0+3 of token t0 + c
         if (t0 + c < T && e0 < E) {
-            float4 out;
-            out.x = fabsf(acc2[0] + (r_b2 ? (float)r_b2[e0 + 0] : 0.0f));
-            out.y = fabsf(acc2[1] + (r_b2 ? (float)r_b2[e0 + 1] : 0.0f));
-            out.z = fabsf(acc2[2] + (r_b2 ? (float)r_b2[e0 + 2] : 0.0f));
-            out.w = fabsf(acc2[3] + (r_b2 ? (float)r_b2[e0 + 3] : 0.0f));
-            *reinterpret_cast<float4*>(scores + (size_t)(t0 + c) * E + e0) = out;
+            store_scores4(scores + (size_t)(t0 + c) * E, e0, E, router_scores4(acc2, r_b2, e0, E));
         }
     }
 }
@@ -136,7 +131,7 @@ void launch_router_bf16_t(const dmoe_layer& L, const void* x, int T, float* scor
 bool router_bf16_supported(const dmoe_layer& L) {
     const int dh = L.router_hidden;
     const bool dh_ok = dh == 32 || dh == 64 || dh == 128 || dh == 256 || dh == 512;
-    return dh_ok && L.d_model % 32 == 0 && L.n_experts % 4 == 0;
+    return dh_ok && L.d_model % 32 == 0;
 }
 
 void launch_router_f32(const dmoe_layer& L, const float* x, int T, float* scores, hipStream_t s) {

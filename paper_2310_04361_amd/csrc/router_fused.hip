@@ -213,21 +213,20 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
             }
         }
         const int e0 = 16 * et + 4 * q;  // this lane: experts e0 .. e0+3
-        float b2[4] = {0.f, 0.f, 0.f, 0.f};
-        if (r_b2 && e0 < E) {
+        // the second-layer biases as an accumulator-shaped vector (0 for experts from E on)
+        f32x4 b2 = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (r_b2) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) b2[r] = (float)r_b2[e0 + r];
+            for (int r = 0; r < 4; ++r)
+                if (e0 + r < E) b2[r] = (float)r_b2[e0 + r];
         }
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             const int t = t0 + 16 * tt + c;
-            float4 out;
-            out.x = fabsf(a2[tt][0] + b2[0]);
-            out.y = fabsf(a2[tt][1] + b2[1]);
-            out.z = fabsf(a2[tt][2] + b2[2]);
-            out.w = fabsf(a2[tt][3] + b2[3]);
-            if (e0 >= E) out = make_float4(0.f, 0.f, 0.f, 0.f);  // padding experts
-            if (t < T && e0 < E) *reinterpret_cast<float4*>(scores + (size_t)t * E + e0) = out;
+            // padding experts (from E on) score 0
+            const float4 out = e0 < E ? router_scores4(a2[tt] + b2, nullptr, e0, E)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < T && e0 < E) store_scores4(scores + (size_t)t * E, e0, E, out);
             o[tt][0] = out.x; o[tt][1] = out.y; o[tt][2] = out.z; o[tt][3] = out.w;
         }
     };
@@ -436,12 +435,7 @@ __global__ __launch_bounds__(256) void router_small_scores_kernel(const SmallGro
         acc = mfma16(load8(af + (size_t)ks * 512), load8(hb + 32 * ks), acc);
     const int e0 = 16 * et + 4 * q;
     if (c < T && e0 < E) {
-        float4 out;
-        out.x = fabsf(acc[0] + (r_b2 ? (float)r_b2[e0 + 0] : 0.0f));
-        out.y = fabsf(acc[1] + (r_b2 ? (float)r_b2[e0 + 1] : 0.0f));
-        out.z = fabsf(acc[2] + (r_b2 ? (float)r_b2[e0 + 2] : 0.0f));
-        out.w = fabsf(acc[3] + (r_b2 ? (float)r_b2[e0 + 3] : 0.0f));
-        *reinterpret_cast<float4*>(scores + (size_t)c * E + e0) = out;
+        store_scores4(scores + (size_t)c * E, e0, E, router_scores4(acc, r_b2, e0, E));
     }
 }
 
@@ -480,7 +474,7 @@ void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
 bool router_fused_scores_supported(const dmoe_layer& L) {
     const int dh = L.router_hidden;
     return L.packed != nullptr && (dh == 64 || dh == 128 || dh == 256 || dh == 512) &&
-           L.d_model % 256 == 0 && L.n_experts % 4 == 0;
+           L.d_model % 256 == 0;
 }
 
 bool router_fused_supported(const dmoe_layer& L) {

@@ -218,13 +218,9 @@ __global__ __launch_bounds__(1024) void router_scores_select_small_kernel(const 
             acc = mfma16(load8(af + (size_t)ks * 512), load8(hb + 32 * ks), acc);
         const int e0 = 16 * et + 4 * q;  // lane (q, c): experts e0 .. e0+3 of token c
         if (c < T && e0 < E) {
-            float4 out;
-            out.x = fabsf(acc[0] + (M.r_b2 ? (float)M.r_b2[e0 + 0] : 0.0f));
-            out.y = fabsf(acc[1] + (M.r_b2 ? (float)M.r_b2[e0 + 1] : 0.0f));
-            out.z = fabsf(acc[2] + (M.r_b2 ? (float)M.r_b2[e0 + 2] : 0.0f));
-            out.w = fabsf(acc[3] + (M.r_b2 ? (float)M.r_b2[e0 + 3] : 0.0f));
-            *reinterpret_cast<float4*>(M.scores + (size_t)c * E + e0) = out;
-            *reinterpret_cast<float4*>(sc + (size_t)c * E + e0) = out;
+            const float4 out = router_scores4(acc, M.r_b2, e0, E);
+            store_scores4(M.scores + (size_t)c * E, e0, E, out);
+            store_scores4(sc + (size_t)c * E, e0, E, out);
         }
     }
     __syncthreads();

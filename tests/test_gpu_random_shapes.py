@@ -32,7 +32,7 @@ def draw_case(i):
     gated = bool(rng.integers(2))
     T = int((rng.integers(1, 17), rng.integers(17, 400), rng.integers(400, 1600))[i % 3])
     d = int(rng.choice([256, 512, 768, 1024]))
-    E = 4 * int(rng.integers(1, 60)) if i % 5 else 4 * int(rng.integers(100, 300))
+    E = int(rng.integers(1, 240)) if i % 5 else int(rng.integers(400, 1200))
     m = int(rng.integers(1, 65 if gated else 129))
     if i % 4 == 1:
         m = int(rng.integers(1, 17))  # small experts: the packings with several experts per stage

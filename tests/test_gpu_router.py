@@ -22,6 +22,9 @@ def B():
     ("cfg2", 300, None), ("cfg2", 16, None), ("cfg2", 1, None),
     ("cfg3", 333, None),            # router biases + log-normal row scales
     ("cfg4", 150, None), ("cfg5b", 16, None), ("paper", 100, None),
+    # expert counts that are not a multiple of 4 (score rows without 16-byte alignment), of a
+    # 16-expert tile or of a mask word
+    ("cfg2", 300, 30), ("cfg2", 9, 30), ("cfg4", 100, 65), ("cfg2", 70, 1), ("cfg5b", 16, 7),
 ])
 def test_router_matches_oracle(B, oracle, name, T, E):
     import torch

@@ -96,8 +96,6 @@ __global__ void pack_down32_kernel(const void* __restrict__ w_down, const float*
     }
 }
 
-constexpr int const_gcd(int a, int b) { return b == 0 ? a : const_gcd(b, a % b); }
-
 // Buffer descriptor flags of a raw (unstructured) buffer: offsets at or beyond num_records read
 // as zero and move no data.
 constexpr int kRawBuffer = 0x00020000;

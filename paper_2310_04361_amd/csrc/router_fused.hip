@@ -536,7 +536,7 @@ void launch_router_sliced(const dmoe_layer& L, const void* x, int T, void* hid, 
     else launch_scores_slices<32>(L, P, T, (const __bf16*)hid, scores, s);
 }
 
-int router_fused_split(const dmoe_layer& L, int T) {
+int router_fused_split(const dmoe_layer&, int T) {
     // measured (router alone, 1 / 2 / 4 workgroups per group): 4096 tokens, d = 2048, d_h = 256:
     // 39 / 31 / 28 us; the same with d_h = 512 and 2048 experts: 101 / 72 / 67 us; 16384 tokens,
     // d = 768: 21 / 21 / 26 us

@@ -140,9 +140,9 @@ __global__ __launch_bounds__(256) void topk_mask_kernel(const float* __restrict_
         const int e = 64 * c + lane;
         const bool eq = key[c] == x && e < E;
         const uint64_t eqb = __ballot(eq);
-        const bool take = eq && __popcll(eqb & ((1ull << lane) - 1ull)) < need;
+        const bool take = eq && (int)__popcll(eqb & ((1ull << lane) - 1ull)) < need;
         const uint64_t word = __ballot(k > 0 && ((key[c] > x && e < E) || take));
-        need -= min(need, __popcll(eqb));
+        need -= min(need, (int)__popcll(eqb));
         if (c < W) kt += __popcll(word);
         if (lane == 0 && c < W) mask[(size_t)t * W + c] = word;
     }

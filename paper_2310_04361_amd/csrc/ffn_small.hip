@@ -62,7 +62,9 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
     extern __shared__ char smem[];
     const int row_bytes = 2 * d + 16;
     char* xs = smem;                                                    // [16][2d + 16]
-    float* red = reinterpret_cast<float*>(smem + 16 * row_bytes);       // [16 waves][BR][64][4]
+    // [16 waves][BR][64][4] partial sums: they take the place of the x rows once every wavefront
+    // has finished reading those
+    float* red = reinterpret_cast<float*>(smem);
     const int tid = threadIdx.x, lane = tid & 63, q = lane >> 4, c = lane & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mt = w % MT, kq = w / MT;
@@ -110,6 +112,7 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
             }
         }
     }
+    __syncthreads();  // the x rows have been consumed
 #pragma unroll
     for (int br = 0; br < BR; ++br)
         *reinterpret_cast<f32x4*>(red + ((w * BR + br) * 64 + lane) * 4) = acc[br];
@@ -230,8 +233,8 @@ __global__ void finish_small_kernel(const SmallGroup G, int T, int d, int EG) {
 template <int MT, bool GATED, bool W8>
 void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
                        hipStream_t s) {
-    const size_t lds = 16 * (2 * (size_t)L.d_model + 16) +
-                       sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4;
+    const size_t lds = std::max(16 * (2 * (size_t)L.d_model + 16),
+                                sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4);
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_small_kernel<MT, GATED, W8>),
@@ -256,8 +259,10 @@ void launch_up_small_w(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
 
 bool small_bf16_supported(const dmoe_layer& L) {
     const int mp = m_pad_of(L.expert_size);
+    // LDS of the up kernel: the 16 x rows (the partial sums of its wavefronts reuse the space)
+    const size_t up_lds = 16 * (2 * (size_t)L.d_model + 16);
     return L.packed != nullptr && (mp == 32 || mp == 64 || mp == 128) && L.d_model % 32 == 0 &&
-           16 * (2 * (size_t)L.d_model + 16) <= 160 * 1024 - 16 * 1024 &&
+           up_lds <= 160 * 1024 &&
            div_up(L.n_experts, kSmallMaxGroups) <= kSmallPerGroup;
 }
 

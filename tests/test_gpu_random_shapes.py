@@ -84,3 +84,28 @@ def test_random_layer_matches_oracle(B, oracle, i):
     err = tokenwise_rel_err(got[idx], ref_y)
     print(f"  density={ref_mask.mean():.3f} err={err:.3e}", flush=True)
     assert err <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("T,d,E,m,gated", [(300, 4096, 16, 64, True), (9, 4096, 16, 64, True),
+                                           (9, 8192, 8, 24, False), (130, 8192, 8, 24, False)])
+def test_wide_models(B, oracle, T, d, E, m, gated):
+    """Model widths beyond the benchmark shapes: 4096 (the widest whose 16 x rows the small-token
+    kernels keep in LDS) and 8192 (where up to 16 tokens take the general kernels instead)."""
+    import torch
+    cfg = wl.Config(f"wide{d}", T, d, E, m, 128, gated, "gelu_tanh", "bf16", (0.5,),
+                    ffn_bias=not gated, router_bias=True)
+    print(f"wide model T={T} d={d} E={E} m={m} gated={gated}", flush=True)
+    layer, x = wl.make_layer(cfg, 11), wl.make_input(cfg, 11)
+    L = B.Layer(layer, cfg.dtype)
+    tau = float(np.float32(0.5))
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau, want_scores=True, want_mask=True)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy()
+    ref_mask, _ = oracle.select(s.astype(np.float64), tau)
+    assert np.array_equal(B.mask_bits_to_bool(ex["mask_bits"], cfg.E), ref_mask)
+    idx = np.arange(min(T, 40))
+    ref_s = oracle.router(x[idx], layer["r_w1"], layer["r_b1"], layer["r_w2"], layer["r_b2"])
+    assert tokenwise_rel_err(s[idx], ref_s) <= TOL[cfg.dtype]
+    err = tokenwise_rel_err(B.from_device(y, cfg.dtype)[idx], oracle_ffn(oracle, layer, x[idx], ref_mask[idx]))
+    print(f"  err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]

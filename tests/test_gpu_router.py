@@ -47,6 +47,8 @@ def test_router_matches_oracle(B, oracle, name, T, E):
 @pytest.mark.parametrize("T,d,E,d_h,k", [
     (300, 2048, 2048, 512, None), (70, 2048, 2052, 256, None), (700, 1024, 1100, 512, None),
     (333, 2048, 256, 512, 7), (1500, 2048, 516, 512, None), (100, 4096, 64, 256, 3),
+    # the largest expert count, prefill and small-token path, both gates
+    (100, 256, 4096, 64, None), (9, 256, 4096, 64, None), (9, 512, 2048, 128, 5), (40, 256, 4095, 32, 9),
 ])
 def test_forward_scores_of_large_routers(B, oracle, T, d, E, d_h, k):
     import torch
@@ -63,6 +65,8 @@ def test_forward_scores_of_large_routers(B, oracle, T, d, E, d_h, k):
     err = tokenwise_rel_err(got, ref)
     print(f"  err={err:.3e}", flush=True)
     assert err <= TOL[cfg.dtype]
+    gate = oracle.select_topk(got, k) if k is not None else oracle.select(got, float(np.float32(0.5)))[0]
+    assert np.array_equal(B.mask_bits_to_bool(ex["mask_bits"], cfg.E), gate)
     # and the stand-alone router gives the same scores to the same tolerance
     s2 = B.dmoe_router(L, B.to_device(x, cfg.dtype)).cpu().numpy().astype(np.float64)
     assert tokenwise_rel_err(s2, ref) <= TOL[cfg.dtype]

@@ -24,7 +24,10 @@ def B():
 # (16 experts of 24 neurons, hidden width d/2; Sec. 3.5)
 @pytest.mark.parametrize("name,T,n_layers", [("cfg5b", 16, 3), ("cfg5b", 5, 4), ("cfg5b", 1, 1),
                                              ("cfg5a", 16, 2), ("cfg5b", 100, 3),
-                                             ("cfg5b/16", 16, 3), ("cfg5b/16", 300, 3)])
+                                             ("cfg5b/16", 16, 3), ("cfg5b/16", 300, 3),
+                                             # more experts than the fused small-token gate takes,
+                                             # and a count that is no multiple of 4
+                                             ("cfg5b/1100", 12, 2), ("cfg5b/30", 16, 3)])
 def test_group_matches_single_layers_and_oracle(B, oracle, name, T, n_layers):
     import torch
     from dataclasses import replace

@@ -44,7 +44,8 @@ def _check(B, oracle, scores, tau):
 
 
 @pytest.mark.parametrize("T,E", [(1, 16), (63, 16), (64, 128), (65, 32), (257, 24), (1000, 128),
-                                 (700, 256), (130, 70), (4099, 128)])
+                                 (700, 256), (130, 70), (4099, 128),
+                                 (12, 4096), (100, 2100), (17, 1), (16, 3), (70, 4096)])
 @pytest.mark.parametrize("kind", ["halfnormal", "grid", "zipf"])
 def test_select_matches_oracle(B, oracle, T, E, kind):
     scores = wl.random_scores(T, E, seed=T + E, kind=kind)
@@ -112,7 +113,7 @@ def _check_topk(B, oracle, scores, k):
 
 
 @pytest.mark.parametrize("T,E", [(1, 16), (65, 32), (257, 24), (1000, 128), (300, 256), (130, 70),
-                                 (40, 700), (4099, 128)])
+                                 (40, 700), (4099, 128), (9, 4096), (70, 2100)])
 @pytest.mark.parametrize("kind", ["halfnormal", "grid", "zipf"])
 def test_select_topk_matches_oracle(B, oracle, T, E, kind):
     scores = wl.random_scores(T, E, seed=T + E + 1, kind=kind)   # "grid" is full of ties

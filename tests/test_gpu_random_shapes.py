@@ -109,3 +109,31 @@ def test_wide_models(B, oracle, T, d, E, m, gated):
     err = tokenwise_rel_err(B.from_device(y, cfg.dtype)[idx], oracle_ffn(oracle, layer, x[idx], ref_mask[idx]))
     print(f"  err={err:.3e}", flush=True)
     assert err <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("T,d,E,m,d_h,gated,act,tau", [
+    (50, 96, 7, 5, 16, False, "relu", 0.5), (33, 256, 20, 33, 64, True, "gelu_tanh", 0.3),
+    (200, 64, 130, 3, 32, False, "gelu_erf", 0.7), (17, 1000, 4, 200, 100, False, "relu", 0.0),
+    (1, 40, 3, 9, 8, True, "gelu_tanh", 0.9),
+])
+def test_fp32_layers_of_other_shapes(B, oracle, T, d, E, m, d_h, gated, act, tau):
+    """The fp32 kernels (the exactness configuration) away from the 64-wide benchmark layer: both
+    sides compute their own scores, so tokens with a score within 1e-6 of the threshold are left
+    out of the comparison (at most a tenth of them)."""
+    import torch
+    cfg = wl.Config("f32", T, d, E, m, d_h, gated, act, "f32", (tau,), ffn_bias=not gated,
+                    router_bias=True)
+    print(f"fp32 layer T={T} d={d} E={E} m={m} d_h={d_h} gated={gated} {act} tau={tau}", flush=True)
+    layer, x = wl.make_layer(cfg, 21), wl.make_input(cfg, 21)
+    L = B.Layer(layer, cfg.dtype)
+    tau32 = float(np.float32(tau))
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32, want_scores=True, want_mask=True)
+    torch.cuda.synchronize()
+    ref_y, ref_s, ref_mask = oracle.forward(layer, x, tau32)
+    mx = ref_s.max(axis=1, keepdims=True)
+    near = (np.abs(ref_s - tau32 * mx) <= 1e-6 * np.maximum(1.0, mx)).any(axis=1) if tau > 0 else np.zeros(T, bool)
+    keep = ~near
+    assert keep.sum() >= T * 0.9
+    assert tokenwise_rel_err(ex["scores"].cpu().numpy(), ref_s) <= 1e-5
+    assert np.array_equal(B.mask_bits_to_bool(ex["mask_bits"], E)[keep], ref_mask[keep])
+    assert tokenwise_rel_err(B.from_device(y, cfg.dtype)[keep], ref_y[keep]) <= 1e-5

@@ -19,6 +19,18 @@ def tokenwise_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float((num[~zero] / den[~zero]).max()) if (~zero).any() else 0.0
 
 
+def elementwise_rel_err(got: np.ndarray, ref: np.ndarray, eps: float = 1e-3) -> float:
+    """max over all elements of |got - ref| / (|ref| + eps * ||ref_t||_inf): the element-wise
+    companion of tokenwise_rel_err (reported next to it; eps keeps near-zero outputs, whose
+    error is the rounding noise of the whole sum, from dividing by nothing)."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    if got.size == 0:
+        return 0.0
+    den = np.abs(ref) + eps * np.abs(ref).max(axis=1, keepdims=True)
+    ok = den > 0
+    return float((np.abs(got - ref)[ok] / den[ok]).max()) if ok.any() else 0.0
+
+
 def lists_from_mask(mask: np.ndarray, shuffle_seed=None):
     """Expert-major lists (offsets[E+1], token_lists[P]) of a 0/1 mask, optionally with each
     expert's list shuffled (the order inside a list is not part of the contract)."""

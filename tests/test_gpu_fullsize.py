@@ -1,12 +1,26 @@
-"""Full-size runs (the shapes and launch configuration that bench.py times) checked on sampled
-tokens the oracle can compute one by one, plus properties that hold at any size."""
+"""Full-size runs (the shapes and launch configuration that bench.py times): EVERY token of the
+benchmark configurations is compared with the oracle, the large ragged shapes on sampled tokens
+of every 128-token chunk, plus properties that hold at any size."""
 import numpy as np
 import pytest
 
-from helpers import TOL, oracle_ffn, tokenwise_rel_err
+from helpers import TOL, elementwise_rel_err, lists_from_mask, oracle_ffn, tokenwise_rel_err
 from paper_2310_04361_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
+
+
+_made = {}
+
+
+def _layer_and_input(cfg, seed):
+    """Layer and input of a configuration; the last one drawn is kept (drawing and rounding the
+    200 MB of the Gemma-shaped layer takes a minute, and consecutive cases share it)."""
+    key = (cfg, seed)
+    if key not in _made:
+        _made.clear()
+        _made[key] = (wl.make_layer(cfg, seed), wl.make_input(cfg, seed))
+    return _made[key]
 
 
 @pytest.fixture(scope="module")
@@ -18,9 +32,10 @@ def B():
     return binding
 
 
-@pytest.mark.parametrize("name,tau,n_sample", [("cfg2", 0.5, 256), ("cfg2", 0.9, 256),
-                                               ("cfg3", 0.5, 192), ("cfg4", 0.3, 48),
-                                               ("cfg4", 0.6, 64),
+# n_sample = 0: every token goes to the oracle
+@pytest.mark.parametrize("name,tau,n_sample", [("cfg2", 0.5, 0), ("cfg2", 0.9, 0),
+                                               ("cfg3", 0.5, 0), ("cfg4", 0.3, 0),
+                                               ("cfg4", 0.6, 0),
                                                # ragged last chunk in the token range where the
                                                # down-projection takes its 384-column shape
                                                ("cfg2:11000", 0.3, 128),
@@ -39,7 +54,7 @@ def test_full_size_sampled(B, oracle, name, tau, n_sample):
     if ":" in name:
         cfg = wl.with_tokens(cfg, int(name.split(":")[1]))
     print(f"full size {name} T={cfg.T} tau={tau}", flush=True)
-    layer, x = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
+    layer, x = _layer_and_input(cfg, 0)
     L = B.Layer(layer, cfg.dtype)
     tau32 = float(np.float32(tau))
     y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32, want_scores=True, want_mask=True,
@@ -67,21 +82,56 @@ def test_full_size_sampled(B, oracle, name, tau, n_sample):
 
     # ---- sampled tokens against the oracle
     rng = np.random.default_rng(5)
-    idx = np.unique(np.concatenate([[i for i in (0, 63, 64, cfg.T - 1) if i < cfg.T],
-                                    rng.choice(cfg.T, min(n_sample, cfg.T), replace=False)]))
+    if n_sample == 0:
+        idx = np.arange(cfg.T)
+    else:
+        idx = np.unique(np.concatenate([[i for i in (0, 63, 64, cfg.T - 1) if i < cfg.T],
+                                        rng.choice(cfg.T, min(n_sample, cfg.T), replace=False)]))
     ref_mask, _ = oracle.select(s[idx].astype(np.float64), tau32)
     assert np.array_equal(mask[idx], ref_mask)                         # bit-exact on the GPU's scores
     ref_s = oracle.router(x[idx], layer["r_w1"], layer["r_b1"], layer["r_w2"], layer["r_b2"])
     assert tokenwise_rel_err(s[idx], ref_s) <= TOL[cfg.dtype]
     ref_y = oracle_ffn(oracle, layer, x[idx], ref_mask)
     err = tokenwise_rel_err(yh[idx], ref_y)
-    print(f"  density={mask.mean():.4f} sampled err={err:.3e}", flush=True)
+    print(f"  density={mask.mean():.4f} tokens compared={len(idx)} of {cfg.T} err={err:.3e} "
+          f"element-wise err={elementwise_rel_err(yh[idx], ref_y):.3e}", flush=True)
     assert err <= TOL[cfg.dtype]
 
     # ---- run-to-run reproducibility (the merge order is fixed)
     y2, _ = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+
+
+def test_paper_shape_full_size_bernoulli(B, oracle):
+    """The shape of the latency experiment of Sec. 4.4 (24 experts of 128 neurons, d = 768,
+    256 x 197 tokens) under Bernoulli(0.5) decisions through dmoe_expert_ffn: four tokens of
+    every 128-token chunk (first, last, two random) against the oracle."""
+    import torch
+    cfg = wl.CONFIGS["paper"]
+    print(f"paper shape T={cfg.T} E={cfg.E} m={cfg.m} Bernoulli(0.5)", flush=True)
+    layer, x = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
+    L = B.Layer(layer, cfg.dtype)
+    mask = wl.bernoulli_mask(cfg.T, cfg.E, 0.5, seed=3)
+    mask[777] = 0                                                     # a token with no expert
+    offs, lst = lists_from_mask(mask)
+    y = B.dmoe_expert_ffn(L, B.to_device(x, cfg.dtype), torch.from_numpy(offs).cuda(),
+                          torch.from_numpy(np.concatenate([lst, np.zeros(1, np.int32)])).cuda())
+    torch.cuda.synchronize()
+    yh = B.from_device(y, cfg.dtype)
+    assert np.isfinite(yh).all()
+    rng = np.random.default_rng(9)
+    starts = np.arange(0, cfg.T, 128)
+    idx = np.unique(np.concatenate([starts, np.minimum(starts + 127, cfg.T - 1),
+                                    np.minimum(starts + rng.integers(1, 127, len(starts)), cfg.T - 1),
+                                    np.minimum(starts + rng.integers(1, 127, len(starts)), cfg.T - 1),
+                                    [777]]))
+    ref = oracle_ffn(oracle, layer, x[idx], mask[idx])
+    err = tokenwise_rel_err(yh[idx], ref)
+    print(f"  pairs={offs[-1]} tokens compared={len(idx)} err={err:.3e} "
+          f"element-wise err={elementwise_rel_err(yh[idx], ref):.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]
+    assert np.array_equal(yh[777], layer["b_down"])
 
 
 def test_sizes_beyond_32bit_offsets_take_the_pair_kernel(B, oracle):

@@ -16,7 +16,9 @@
  *   - All argument errors are found on the host BEFORE anything is launched, so a failing call
  *     leaves every buffer untouched.
  *   - Pointers are DEVICE pointers unless the name says host.  The caller owns every buffer; the
- *     library allocates nothing, frees nothing and never synchronises the stream.  Work is
+ *     library allocates nothing, frees nothing and never synchronises the stream (its only state
+ *     between calls: the per-GPU address of dmoe_forward_static's array, the one-time kernel
+ *     attributes and, when enabled, the event pool of the timing aid).  Work is
  *     enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
  *   - Row-major, innermost index last.  x[T][d] and y[T][d] have the layer's dtype; scores are
  *     always fp32.  Expert-major weights: w_up[E][m][d], w_gate[E][m][d] (gated only),
@@ -175,6 +177,23 @@ int32_t dmoe_forward(const dmoe_layer *layer, const void *x, int32_t n_tokens, f
                      void *y, float *scores_out, uint64_t *mask_out, int32_t *offsets_out,
                      int32_t *token_lists_out, void *workspace, size_t workspace_bytes,
                      void *stream);
+
+/*
+ * dmoe_forward for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same result as dmoe_forward
+ * (bit for bit: the same kernels run), without the optional outputs.  The workspace is a 32 MiB
+ * array that lives in the library's device image -- every GPU the library runs on holds its own
+ * copy until the process ends -- so the call refuses (DMOE_ERR_WORKSPACE, nothing launched) any
+ * layer / n_tokens whose dmoe_workspace_bytes() exceeds 32 MiB: e.g. the 256 x 64 gated layer of
+ * the 16-token decode configuration needs 14 MiB, 128 experts of 24 fit up to about 3000 tokens.
+ * It calls no hipMalloc / hipFree or other allocating routine.  The first call on a GPU looks the
+ * array's address up once (make that call outside a graph capture).  All calls on one GPU share
+ * that GPU's array, which keeps the previous call's contents -- nothing in it needs to start at
+ * zero -- so calls that overlap on one GPU (different streams, different threads) race: order
+ * them on one stream or with events.
+ */
+int32_t dmoe_forward_static(const dmoe_layer *layer, const void *x, int32_t n_tokens, float tau,
+                            void *y, void *stream);
 
 /* ---- the conventional top-k gate (the rule Sec. 3.3 / 3.4 compare dynamic-k against) --------- */
 

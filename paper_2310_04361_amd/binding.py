@@ -25,7 +25,7 @@ DMOE_W_NATIVE, DMOE_W_FP8_E4M3 = 0, 1
 EXPORTS = (
     "dmoe_version", "dmoe_last_error", "dmoe_workspace_bytes", "dmoe_select_workspace_bytes",
     "dmoe_packed_bytes", "dmoe_pack_weights", "dmoe_router", "dmoe_select", "dmoe_expert_ffn",
-    "dmoe_forward", "dmoe_select_topk", "dmoe_forward_topk", "dmoe_group_workspace_bytes",
+    "dmoe_forward", "dmoe_forward_static", "dmoe_select_topk", "dmoe_forward_topk", "dmoe_group_workspace_bytes",
     "dmoe_forward_group", "dmoe_timing_enable", "dmoe_timing_reset", "dmoe_timing_slots",
     "dmoe_timing_read",
 )
@@ -75,6 +75,7 @@ def lib() -> ctypes.CDLL:
         L.dmoe_select.argtypes = [V, I, I, F, V, V, V, V, V, V, SZ, V]
         L.dmoe_expert_ffn.argtypes = [LP, V, I, V, V, V, V, SZ, V]
         L.dmoe_forward.argtypes = [LP, V, I, F, V, V, V, V, V, V, SZ, V]
+        L.dmoe_forward_static.argtypes = [LP, V, I, F, V, V]
         L.dmoe_select_topk.argtypes = [V, I, I, I, V, V, V, V, V, V, SZ, V]
         L.dmoe_forward_topk.argtypes = [LP, V, I, I, V, V, V, V, V, V, SZ, V]
         L.dmoe_group_workspace_bytes.argtypes = [P(LP), I, I, P(SZ)]
@@ -257,6 +258,17 @@ def dmoe_forward(layer: Layer, x, tau: float, want_scores=False, want_mask=False
     else:
         check(lib().dmoe_forward_topk(layer.ref(), x.data_ptr(), T, int(top_k), *tail))
     return y, ex
+
+
+def dmoe_forward_static(layer: Layer, x, tau: float, y=None):
+    """Whole layer on the library's static per-GPU workspace (no allocation inside the call;
+    y is allocated here only when the caller passes none)."""
+    import torch
+    T = x.shape[0]
+    if y is None:
+        y = torch.empty((T, layer.d), dtype=_torch_dtype(layer.dtype), device=x.device)
+    check(lib().dmoe_forward_static(layer.ref(), x.data_ptr(), T, float(tau), y.data_ptr(), _stream()))
+    return y
 
 
 _group_ws = {}

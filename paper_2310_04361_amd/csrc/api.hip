@@ -4,9 +4,16 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "dmoe_internal.h"
+
+// Workspace of dmoe_forward_static: one array per GPU, held from the moment the library's code
+// object is loaded on that GPU until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress (static_scratch_of_current_device below); it is never passed to a kernel.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace dmoe {
 
@@ -20,6 +27,30 @@ int fail(int code, const char* fmt, ...) {
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
     return code;
+}
+
+// ---- static workspace ------------------------------------------------------------------------------
+// Device address of `scratch` on the current GPU, looked up once per GPU (each GPU has its own
+// copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(DMOE_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(DMOE_ERR_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(DMOE_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DMOE_OK;
 }
 
 // ---- timing ------------------------------------------------------------------------------------
@@ -505,6 +536,26 @@ int32_t dmoe_forward(const dmoe_layer* layer, const void* x, int32_t n_tokens, f
                      void* stream) {
     return forward_impl(layer, x, n_tokens, Gate{tau, -1}, y, scores_out, mask_out, offsets_out,
                         token_lists_out, workspace, workspace_bytes, stream);
+}
+
+int32_t dmoe_forward_static(const dmoe_layer* layer, const void* x, int32_t n_tokens, float tau,
+                            void* y, void* stream) {
+    // sizes first: a layer / batch that does not fit is refused before anything else happens
+    if (int rc = check_layer(layer, true, true)) return rc;
+    if (int rc = check_tokens(n_tokens, layer->n_experts)) return rc;
+    if (int rc = check_tau(tau)) return rc;
+    if (n_tokens == 0) return DMOE_OK;
+    if (!x || !y) return fail(DMOE_ERR_NULL, "x or y is NULL");
+    const size_t need = layer_ws(*layer, n_tokens).total;
+    if (need > kStaticScratchBytes)
+        return fail(DMOE_ERR_WORKSPACE,
+                    "dmoe_forward_static: %d tokens of this layer need %zu bytes of workspace, the "
+                    "static one holds %zu; use dmoe_forward with a caller-owned workspace",
+                    n_tokens, need, kStaticScratchBytes);
+    void* ws = nullptr;
+    if (int rc = static_scratch_of_current_device(&ws)) return rc;
+    return forward_impl(layer, x, n_tokens, Gate{tau, -1}, y, nullptr, nullptr, nullptr, nullptr,
+                        ws, kStaticScratchBytes, stream);
 }
 
 int32_t dmoe_forward_topk(const dmoe_layer* layer, const void* x, int32_t n_tokens, int32_t k,

@@ -156,6 +156,16 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert fwd(L=_layer(r_w2=None)) == B.DMOE_ERR_NULL
     assert fwd(T=0, ws=None, wsb=0) == B.DMOE_OK
     assert b"workspace" in lib.dmoe_last_error() or lib.dmoe_last_error() is not None
+    # forward on the library's static workspace: the same checks, and a size limit
+    sfw = lambda L=L, **k: lib.dmoe_forward_static(ref(L), *[k.get(a, d) for a, d in (
+        ("x", x), ("T", 8), ("tau", ctypes.c_float(0.5)), ("y", y), ("stream", None))])
+    assert sfw(tau=ctypes.c_float(2.0)) == B.DMOE_ERR_TAU
+    assert sfw(y=None) == B.DMOE_ERR_NULL
+    assert sfw(L=_layer(r_w2=None)) == B.DMOE_ERR_NULL
+    assert sfw(T=-1) == B.DMOE_ERR_SHAPE
+    assert sfw(T=0) == B.DMOE_OK
+    assert sfw(T=2 ** 20) == B.DMOE_ERR_WORKSPACE                            # beyond the 32 MiB array
+    assert b"static" in lib.dmoe_last_error()
     # pack
     Lb = _layer(dtype=B.DMOE_BF16, d_model=256)
     assert lib.dmoe_pack_weights(ref(Lb), None, 0, None) == B.DMOE_ERR_NULL

@@ -2,14 +2,16 @@
 """Benchmark of the dynamic-k MoE FFN forward on one MI355X.
 
 One step = one dmoe_forward (router, gate, bucketing, experts) over one batch of synthetic
-tokens that already sit in HBM.  The headline workload is the BERT-base-shaped bf16 layer
-(d=768, 128 experts of 24 neurons, GELU, 128x128 tokens) at tau = 0.5.  Prints ONE JSON line;
-its "other_workloads" list carries the remaining shapes (ViT-shaped ragged batch, the gated
-Gemma-shaped layer at prefill and at 16-token decode, the attention-projection module), each
-with its own roofline object.
+tokens that already sit in HBM.  The headline workload is the largest single-GPU configuration:
+the Gemma-2B-shaped gated bf16 layer (d=2048, 256 experts of 64 neurons, gated GELU, 4096
+tokens) at tau = 0.3.  Prints ONE JSON line; its "other_workloads" list carries the remaining
+shapes (BERT- and ViT-shaped layers, the same gated layer at tau = 0.6 and at 16-token decode,
+the attention-projection module), each with its own roofline object, and the line also holds
+the speed-up-versus-density curves (tau sweep of the BERT-shaped layer, Bernoulli(p) sweep on
+the shape of the paper's latency experiment) and the whole-block timing.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--tau 0.5]
-                    [--sweep] [--no-others] [--no-cpu] [--no-dense]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4] [--tau 0.3]
+                    [--no-curves] [--no-others] [--no-cpu] [--no-dense]
 """
 from __future__ import annotations
 
@@ -27,16 +29,12 @@ import numpy as np
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
-# HBM bytes per launch of the dominant kernel from separate `rocprofv3 --pmc FETCH_SIZE` /
-# `WRITE_SIZE` runs of this script, scaled by the same counters' readings for a plain 256 MiB copy
-# (profiles/dmoe_forward_cfg2_tau0.5_hbm_traffic.txt).  Only valid for the exact workload named.
-MEASURED_TRAFFIC = {("cfg2", 0.5, "expert_down"): 61.2e6 + 25.4e6,
-                    ("cfg2", 0.5, "expert_up"): 127.2e6 + 26.8e6}
+PROFILES = os.path.join(ROOT, "profiles")
 N_ROTATE = 8                   # distinct x / y buffers cycled through, so that inputs come from HBM
 N_LAYER_COPIES_DECODE = 4      # distinct weight copies cycled through at decode sizes: together
                                # they exceed the 256 MB last-level cache, so weights come from HBM
-OTHERS = (("cfg3", 0.5), ("cfg4", 0.3), ("cfg4", 0.6), ("gemma_paper", 0.5), ("bert_paper", 0.5),
-          ("cfg5a", 0.5), ("cfg5b", 0.5))
+OTHERS = (("cfg4", 0.3), ("cfg4", 0.6), ("cfg2", 0.5), ("cfg3", 0.5), ("gemma_paper", 0.5),
+          ("bert_paper", 0.5), ("cfg5a", 0.5), ("cfg5b", 0.5))
 
 
 def _time_ms(fn, steps):
@@ -47,6 +45,61 @@ def _time_ms(fn, steps):
         fn(i)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def _event_times_ms(fn, steps):
+    """Per-step device time from a HIP event pair around every step on the launch stream (the
+    library launches on torch's current stream): (median, min)."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(ev):
+        a.record()
+        fn(i)
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in ev)
+    return t[len(t) // 2], t[0]
+
+
+def profile_traffic(name, tau, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this exact
+    workload (profiles/dmoe_forward_<name>_tau<tau>_hbm_traffic.txt, lines
+    `traffic <kernel> <fetch bytes> <write bytes>`), or (None, None) if there is none.  The run
+    itself cannot read these counters; the file names the command that produced it."""
+    path = os.path.join(PROFILES, f"dmoe_forward_{name}_tau{tau}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    with open(path) as f:
+        for line in f:
+            w = line.split()
+            if len(w) == 4 and w[0] == "traffic" and w[1] == kernel:
+                return float(w[2]) + float(w[3]), os.path.relpath(path, ROOT)
+    return None, None
+
+
+def achieved_peaks():
+    """What this GPU delivers on the two plain limits the rooflines are quoted against: a device
+    copy of 1 GiB (bytes read + written per second) and a square bf16 GEMM of 8192 (vendor
+    library).  Context for the fractions of the published peaks."""
+    import torch
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    copy_ms = _time_ms(lambda i: dst.copy_(src), 10)
+    del src, dst
+    a = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(8192, 8192, device="cuda", dtype=torch.bfloat16)
+    for _ in range(2):
+        a @ b
+    gemm_ms = _time_ms(lambda i: a @ b, 10)
+    del a, b
+    torch.cuda.empty_cache()
+    return {"hbm_copy_GBs": round(2 * (1 << 30) / (copy_ms * 1e-3) / 1e9, 1),
+            "bf16_gemm_8192_TFLOPs": round(2 * 8192 ** 3 / (gemm_ms * 1e-3) / 1e12, 1),
+            "note": "measured in this run: 1 GiB device copy (read + write), 8192^3 bf16 vendor GEMM"}
 
 
 class Workload:
@@ -95,6 +148,7 @@ class Workload:
         for i in range(warmup):
             self.step(i, tau)
         ms = _time_ms(lambda i: self.step(i, tau), steps)
+        ev_median, ev_min = _event_times_ms(lambda i: self.step(i, tau), min(steps, 200))
 
         B.timing(True)
         for i in range(min(steps, 200)):
@@ -124,13 +178,16 @@ class Workload:
             dom = max(kflops, key=lambda k: kt.get(k, 0.0))
             achieved = kflops[dom] / (kt[dom] * 1e-3) / 1e12
             experts_ms = sum(kt.get(k, 0.0) for k in ("expert_up", "expert_down", "expert_down_sparse"))
+            traffic, source = profile_traffic(cfg.name, tau_arg, dom) if traffic_ok else (None, None)
             roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                        "traffic": MEASURED_TRAFFIC.get((cfg.name, tau_arg, dom)) if traffic_ok else None,
+                        "traffic": traffic, "traffic_source": source,
                         "avg_kernel_ms": round(kt[dom], 5),
-                        "experts_tflops": round(flops / (experts_ms * 1e-3) / 1e12, 2)}
-        return {"ms": ms, "pairs": pairs, "density": pairs / (cfg.T * cfg.E), "flops": flops,
+                        "experts_tflops": round(flops / (experts_ms * 1e-3) / 1e12, 2),
+                        "experts_frac": round(flops / (experts_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+        return {"ms": ms, "ms_event_median": ev_median, "ms_event_min": ev_min, "pairs": pairs,
+                "density": pairs / (cfg.T * cfg.E), "flops": flops,
                 "kernel_ms": {k: round(v, 5) for k, v in kt.items()}, "roofline": roofline}
 
     def dense_ms(self):
@@ -233,10 +290,13 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--tau", type=float, default=0.5)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--tau", type=float, default=0.3)
     ap.add_argument("--tokens", type=int, default=0, help="override the token count")
-    ap.add_argument("--sweep", action="store_true", help="also time every tau of the workload")
+    ap.add_argument("--sweep", action="store_true", help="also time every tau of the headline workload")
+    ap.add_argument("--no-curves", action="store_true",
+                    help="skip the speed-up-versus-density curves (tau sweep of the BERT-shaped layer, "
+                         "Bernoulli(p) sweep on the shape of Sec. 4.4) and the whole-block timing")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-others", action="store_true", help="skip the other workloads")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -244,12 +304,13 @@ def main() -> int:
     ap.add_argument("--top-k", type=int, default=0,
                     help="also time the headline workload with the top-k gate (k experts per token)")
     ap.add_argument("--paper-sweep", action="store_true",
-                    help="also time dmoe_expert_ffn on the paper's benchmark shape (24 experts x 128, "
-                         "d=768, 256x197 tokens) under Bernoulli(p) decisions, p = 0 .. 1 (Sec. 4.4)")
+                    help="(default unless --no-curves) time dmoe_expert_ffn on the paper's benchmark "
+                         "shape (24 experts x 128, d=768, 256x197 tokens) under Bernoulli(p) "
+                         "decisions, p = 0 .. 1 (Sec. 4.4)")
     ap.add_argument("--block", action="store_true",
-                    help="also time a ViT-B-shaped encoder block (LayerNorm, 12-head attention, "
-                         "residuals, FFN) on 256x197 tokens with the dense FFN and with the "
-                         "dynamic-k layer in its place (Sec. 4.4: what survives end to end)")
+                    help="(default unless --no-curves) time a ViT-B-shaped encoder block (LayerNorm, "
+                         "12-head attention, residuals, FFN) on 256x197 tokens with the dense FFN and "
+                         "with the dynamic-k layer in its place (Sec. 4.4: what survives end to end)")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense-FFN comparisons (keeps a profile to the timed workload)")
     args = ap.parse_args()
@@ -285,29 +346,87 @@ def main() -> int:
             w.step(i, 0.0)
         own_dense_ms = _time_ms(lambda i: w.step(i, 0.0), 20)
 
-    sweep = None
-    if args.sweep:
-        sweep = []
-        for t in cfg.taus:
+    def tau_sweep(wl_, dms):
+        rows = []
+        c = wl_.cfg
+        for t in c.taus:
             t32 = float(np.float32(t))
-            _, e2 = B.dmoe_forward(w.layers[0], w.xs[0], t32, want_lists=True)
+            _, e2 = B.dmoe_forward(wl_.layers[0], wl_.xs[0], t32, want_lists=True)
             torch.cuda.synchronize()
             p = int(e2["offsets"][-1].item())
             for i in range(5):
-                w.step(i, t32)
-            m = _time_ms(lambda i: w.step(i, t32), 50)
-            sweep.append({"tau": t, "density": round(p / (cfg.T * cfg.E), 4), "ms": round(m, 4),
-                          "tokens_per_s": round(cfg.T / (m * 1e-3)),
-                          "executed_tflops": round(cost_model.executed_flops(p, cfg.d, cfg.m, cfg.gated) / (m * 1e-3) / 1e12, 2),
-                          "speedup_vs_dense": round(dense_ms / m, 3) if dense_ms else None})
+                wl_.step(i, t32)
+            m = _time_ms(lambda i: wl_.step(i, t32), 50)
+            rows.append({"tau": t, "density": round(p / (c.T * c.E), 4), "ms": round(m, 4),
+                         "tokens_per_s": round(c.T / (m * 1e-3)),
+                         "executed_tflops": round(cost_model.executed_flops(p, c.d, c.m, c.gated) / (m * 1e-3) / 1e12, 2),
+                         "speedup_vs_dense": round(dms / m, 3) if dms else None})
+        return rows
+
+    def measure_other(wo, name, t, dms):
+        steps = 100 if wo.cfg.T > 16 else 400
+        ro = wo.measure(t, steps, 10)
+        entry = {"workload": wo.describe(t), "ms_per_step": round(ro["ms"], 5),
+                 "ms_per_step_event_median": round(ro["ms_event_median"], 5),
+                 "ms_per_step_event_min": round(ro["ms_event_min"], 5),
+                 "tokens_per_s": round(wo.cfg.T / (ro["ms"] * 1e-3), 1),
+                 "density": round(ro["density"], 4), "pairs": ro["pairs"],
+                 "executed_expert_tflops": round(ro["flops"] / (ro["ms"] * 1e-3) / 1e12, 2),
+                 "dense_vendor_gemm_ms": round(dms, 4) if dms else None,
+                 "speedup_vs_dense": round(dms / ro["ms"], 3) if dms else None,
+                 "kernel_ms": ro["kernel_ms"], "roofline": ro["roofline"]}
+        if wo.decode:
+            t32 = float(np.float32(t))
+            hot = _time_ms(lambda i: wo.step(i, t32, hot=True), steps)
+            entry["ms_per_step_weights_cached"] = round(hot, 5)
+            # the same forward recorded once per weight copy as a HIP graph and replayed
+            graphs = []
+            for li, Lc in enumerate(wo.layers):
+                gph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gph):
+                    B.dmoe_forward(Lc, wo.xs[li], t32, y=wo.ys[li])
+                graphs.append(gph)
+            for gph in graphs:
+                gph.replay()
+            entry["ms_per_step_graph_replay"] = round(
+                _time_ms(lambda i: graphs[i % len(graphs)].replay(), steps), 5)
+            del graphs
+            if name == "cfg5b":
+                # the query / key / value modules of one attention layer (Sec. 3.5): three
+                # layers of this shape on one input, one launch per stage for the group
+                qkv = wo.layers[:3]
+                ys3 = [torch.empty_like(wo.ys[0]) for _ in range(3)]
+                taus3 = [t32] * 3
+                for i in range(5):
+                    B.dmoe_forward_group(qkv, wo.xs[i % N_ROTATE], taus3, ys=ys3)
+                grp = _time_ms(lambda i: B.dmoe_forward_group(qkv, wo.xs[i % N_ROTATE], taus3, ys=ys3), steps)
+
+                def three(i):
+                    for li in range(3):
+                        B.dmoe_forward(qkv[li], wo.xs[i % N_ROTATE], t32, y=ys3[li])
+                sep = _time_ms(three, steps)
+                gph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(gph):
+                    B.dmoe_forward_group(qkv, wo.xs[0], taus3, ys=ys3)
+                gph.replay()
+                rep = _time_ms(lambda i: gph.replay(), steps)
+                entry["qkv_group"] = {"layers": 3, "ms_group_call": round(grp, 5),
+                                      "ms_three_single_calls": round(sep, 5),
+                                      "ms_group_graph_replay": round(rep, 5)}
+                del gph
+        return entry
+
+    sweep = tau_sweep(w, dense_ms) if args.sweep else None
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu:
         from oracle import dmoe_oracle as oracle
-        n = min(cfg.T, 16384)
+        # about 10 s of CPU work: a sample of at most 16384 tokens, fewer for the wide gated layer
+        # whose tokens cost ten times as much
+        n = min(cfg.T, 16384 if cfg.d * cfg.m * (3 if cfg.gated else 2) < 100000 else 1024)
         runs, t0 = 0, time.perf_counter()
-        while runs < 50 and time.perf_counter() - t0 < 10.0:   # about 10 s of CPU work
+        while runs < 50 and time.perf_counter() - t0 < 10.0:
             oracle.forward(w.layer_np, w.x_np[:n], tau)
             runs += 1
         dt = time.perf_counter() - t0
@@ -322,13 +441,17 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": w.describe(args.tau), "density": round(r["density"], 4),
                    "pairs": r["pairs"]},
+        "ms_per_step_event_median": round(r["ms_event_median"], 5),
+        "ms_per_step_event_min": round(r["ms_event_min"], 5),
         "executed_expert_tflops": round(r["flops"] / (ms * 1e-3) / 1e12, 2),
+        "executed_expert_frac_of_mfma_peak": round(r["flops"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "dense_ffn_ms": ({"vendor_gemm": round(dense_ms, 4), "own_kernels_tau0": round(own_dense_ms, 4)}
                          if dense_ms else None),
         "speedup_vs_dense": round(dense_ms / ms, 3) if dense_ms else None,
         "kernel_ms": r["kernel_ms"],
         "roofline": r["roofline"],
         "cpu_baseline": cpu,
+        "achieved_peak": achieved_peaks(),
     }
     if sweep:
         out["tau_sweep"] = sweep
@@ -356,7 +479,28 @@ def main() -> int:
                              "tokens_per_s": round(cfg.T / (m * 1e-3), 1),
                              "speedup_vs_dense": round(dense_ms / m, 3) if dense_ms else None}
 
-    if args.paper_sweep:
+    # the headline layer at its other thresholds, while it is on the device
+    others, done_names = [], set()
+    if not args.no_others and not args.tokens:
+        for name, t in OTHERS:
+            if name == args.workload and t != args.tau:
+                others.append(measure_other(w, name, t, dense_ms))
+        done_names.add(args.workload)
+    del w
+    torch.cuda.empty_cache()
+
+    curves = not args.no_curves
+    if curves and not args.tokens:
+        # speed-up against density on the BERT-shaped layer (tau = 0.1 .. 0.9)
+        w2 = Workload("cfg2")
+        d2 = None if args.no_dense else w2.dense_ms()
+        out["cfg2_tau_sweep"] = {"workload": w2.describe("0.1..0.9"),
+                                 "dense_vendor_gemm_ms": round(d2, 4) if d2 else None,
+                                 "rows": tau_sweep(w2, d2)}
+        del w2
+        torch.cuda.empty_cache()
+
+    if args.paper_sweep or curves:
         from paper_2310_04361_amd import workloads as wl
         pw = Workload("paper")
         pc, pL = pw.cfg, pw.layers[0]
@@ -378,84 +522,31 @@ def main() -> int:
                                               "rows": rows}
         del pw
 
-    if args.block:
+    if args.block or curves:
         out["encoder_block"] = encoder_block_timing()
 
     if not args.no_others:
-        del w
-        torch.cuda.empty_cache()
-        others, cache = [], {}
         for name, t in OTHERS:
-            if (name, t) == (args.workload, args.tau) and not args.tokens:
+            if (name, t) == (args.workload, args.tau) or name in done_names:
                 continue
-            if name not in cache:
-                cache.clear()
+            wo = Workload(name)
+            dms = None if args.no_dense else wo.dense_ms()
+            for name2, t2 in OTHERS:
+                if name2 == name:
+                    others.append(measure_other(wo, name, t2, dms))
+            done_names.add(name)
+            if name == "cfg5a":
+                # the same layer with its expert matrices stored in 8-bit E4M3: half the weight
+                # bytes per touched expert
+                del wo
                 torch.cuda.empty_cache()
-                cache[name] = Workload(name)
-                cache[name + "/dense"] = None if args.no_dense else cache[name].dense_ms()
-            wo, dms = cache[name], cache[name + "/dense"]
-            steps = 100 if wo.cfg.T > 16 else 400
-            ro = wo.measure(t, steps, 10, traffic_ok=False)
-            entry = {"workload": wo.describe(t), "ms_per_step": round(ro["ms"], 5),
-                     "tokens_per_s": round(wo.cfg.T / (ro["ms"] * 1e-3), 1),
-                     "density": round(ro["density"], 4), "pairs": ro["pairs"],
-                     "executed_expert_tflops": round(ro["flops"] / (ro["ms"] * 1e-3) / 1e12, 2),
-                     "dense_vendor_gemm_ms": round(dms, 4) if dms else None,
-                     "speedup_vs_dense": round(dms / ro["ms"], 3) if dms else None,
-                     "kernel_ms": ro["kernel_ms"], "roofline": ro["roofline"]}
-            if wo.decode:
-                t32 = float(np.float32(t))
-                hot = _time_ms(lambda i: wo.step(i, t32, hot=True), steps)
-                entry["ms_per_step_weights_cached"] = round(hot, 5)
-                # the same forward recorded once per weight copy as a HIP graph and replayed: the
-                # launch gaps between its six kernels go away
-                graphs = []
-                for li, Lc in enumerate(wo.layers):
-                    gph = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(gph):
-                        B.dmoe_forward(Lc, wo.xs[li], t32, y=wo.ys[li])
-                    graphs.append(gph)
-                for gph in graphs:
-                    gph.replay()
-                entry["ms_per_step_graph_replay"] = round(
-                    _time_ms(lambda i: graphs[i % len(graphs)].replay(), steps), 5)
-                del graphs
-                if name == "cfg5a":
-                    # the same layer with its expert matrices stored in 8-bit E4M3: half the
-                    # weight bytes per touched expert
-                    del wo
-                    cache.clear()
-                    torch.cuda.empty_cache()
-                    w8 = Workload(name, e4m3=True)
-                    r8 = w8.measure(t, steps, 10, traffic_ok=False)
-                    entry["e4m3_weights"] = {"ms_per_step": round(r8["ms"], 5),
-                                             "kernel_ms": r8["kernel_ms"], "roofline": r8["roofline"]}
-                    del w8
-                    wo = None
-                if name == "cfg5b":
-                    # the query / key / value modules of one attention layer (Sec. 3.5): three
-                    # layers of this shape on one input, one launch per stage for the group
-                    qkv = wo.layers[:3]
-                    ys3 = [torch.empty_like(wo.ys[0]) for _ in range(3)]
-                    taus3 = [t32] * 3
-                    for i in range(5):
-                        B.dmoe_forward_group(qkv, wo.xs[i % N_ROTATE], taus3, ys=ys3)
-                    grp = _time_ms(lambda i: B.dmoe_forward_group(qkv, wo.xs[i % N_ROTATE], taus3, ys=ys3), steps)
-
-                    def three(i):
-                        for li in range(3):
-                            B.dmoe_forward(qkv[li], wo.xs[i % N_ROTATE], t32, y=ys3[li])
-                    sep = _time_ms(three, steps)
-                    gph = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(gph):
-                        B.dmoe_forward_group(qkv, wo.xs[0], taus3, ys=ys3)
-                    gph.replay()
-                    rep = _time_ms(lambda i: gph.replay(), steps)
-                    entry["qkv_group"] = {"layers": 3, "ms_group_call": round(grp, 5),
-                                          "ms_three_single_calls": round(sep, 5),
-                                          "ms_group_graph_replay": round(rep, 5)}
-                    del gph
-            others.append(entry)
+                w8 = Workload(name, e4m3=True)
+                r8 = w8.measure(t, 400, 10)
+                others[-1]["e4m3_weights"] = {"ms_per_step": round(r8["ms"], 5),
+                                              "kernel_ms": r8["kernel_ms"], "roofline": r8["roofline"]}
+                del w8
+            wo = None
+            torch.cuda.empty_cache()
         out["other_workloads"] = others
     print(json.dumps(out))
     return 0

@@ -92,8 +92,10 @@ typedef struct {
  * Every scale must be a power of two: then each weight is exactly a bf16 number, and the layer
  * computes what a DMOE_W_NATIVE bf16 layer with those weights computes -- the prefill kernels
  * run on bf16 copies made by dmoe_pack_weights, the small-token kernels (up to 16 tokens, where
- * the weights are the traffic) stream the bytes and convert in registers.  x, y, biases and the
- * router stay bf16.
+ * the weights are the traffic) stream the bytes and convert in registers.  dmoe_pack_weights
+ * replaces a scale that is not a power of two by the nearest one (in log2; zero stays zero) and
+ * every kernel uses that copy, so all batch sizes compute the same layer.  w_scales is read by
+ * dmoe_pack_weights only.  x, y, biases and the router stay bf16.
  */
 
 /* Library version (major*10000 + minor*100 + patch) and the text of the last error of the
@@ -169,7 +171,10 @@ int32_t dmoe_expert_ffn(const dmoe_layer *layer, const void *x, int32_t n_tokens
                         void *y, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * The whole layer: router, gate, bucketing, experts.  Optional outputs (each nullable):
+ * The whole layer on one stream with no host synchronisation: router (Sec. 3.3), dynamic-k gate
+ * (Sec. 3.4, Eq. 4), bucketing (the metadata of Appendix C) and the selected experts summed on
+ * top of b_down (Sec. 3.2; gated experts Appendix G) -- what dmoe_router, dmoe_select and
+ * dmoe_expert_ffn compute one after the other.  Optional outputs (each nullable):
  * scores_out [T][E] fp32, mask_out [T][ceil(E/64)], offsets_out [E+1] and token_lists_out
  * (capacity T*E; both or neither).
  */

@@ -234,7 +234,8 @@ SmallMod small_mod(const dmoe_layer& L, char* ws, const LayerWs& w, float* score
     M.wupf8 = (const uint8_t*)(pk + P.wupf8);
     M.wgatef8 = (const uint8_t*)(pk + P.wgatef8);
     M.w2f8 = (const uint8_t*)(pk + P.w2f8);
-    M.w_scales = L.weight_format == DMOE_W_FP8_E4M3 ? L.w_scales : nullptr;
+    // the power-of-two copy of the scales made by dmoe_pack_weights
+    M.w_scales = L.weight_format == DMOE_W_FP8_E4M3 ? (const float*)(pk + P.scales) : nullptr;
     M.b_down = (const __bf16*)L.b_down;
     M.hid = (__bf16*)(ws + w.hid);
     M.Hs = (__bf16*)(ws + w.H);
@@ -357,6 +358,12 @@ int32_t dmoe_pack_weights(const dmoe_layer* layer, void* packed, size_t packed_b
     if (layer->dtype == DMOE_F32) return DMOE_OK;
     if (!layer->w_down || !layer->w_up || (layer->gated && !layer->w_gate))
         return fail(DMOE_ERR_NULL, "expert weights are NULL");
+    // a layer with a router is packed with it: the router kernels read only the packed matrices
+    if (layer->router_hidden > 0 && (!layer->r_w1 || !layer->r_w2))
+        return fail(DMOE_ERR_NULL, "router_hidden > 0 but r_w1 / r_w2 is NULL (set router_hidden = 0 "
+                                   "for a layer that is only used through dmoe_expert_ffn)");
+    if (layer->router_hidden > 0 && !router_bf16_supported(*layer))
+        return fail(DMOE_ERR_UNSUPPORTED, "bf16 router needs d %% 32 == 0 and d_h in {32,64,128,256,512}");
     if (!experts_bf16_supported(*layer))
         return fail(DMOE_ERR_UNSUPPORTED,
                     "bf16 experts need d %% 256 == 0 and expert_size <= 128 (<= 64 if gated)");
@@ -610,7 +617,7 @@ int32_t dmoe_forward_group(const dmoe_layer* const* layers, int32_t n_layers, co
     hipStream_t s = (hipStream_t)stream;
     const dmoe_layer& L0 = *layers[0];
     bool fused = use_small_path(L0, n_tokens);
-    for (int i = 0; i < n_layers; ++i) fused = fused && router_fused_supported(*layers[i]);
+    for (int i = 0; i < n_layers; ++i) fused = fused && router_fused_scores_supported(*layers[i]);
     if (!fused) {  // larger batches: one layer after the other, each in its share of the workspace
         for (int i = 0; i < n_layers; ++i) {
             const size_t share = align_up(layer_ws(*layers[i], n_tokens).total);
@@ -634,7 +641,7 @@ int32_t dmoe_forward_group(const dmoe_layer* const* layers, int32_t n_layers, co
         launch_select_small_group(L0, G, n_layers, n_tokens, s);
     }
     launch_small_bf16(L0, G, n_layers, x, n_tokens, s);
-    return DMOE_OK;
+    return check_launch("group kernels");
 }
 
 int32_t dmoe_timing_enable(int32_t on) {

@@ -5,6 +5,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/dmoe.h"
 
 namespace dmoe {
@@ -12,7 +14,7 @@ namespace dmoe {
 // ---- fixed granularities -------------------------------------------------------------------
 constexpr int kGroup = 64;        // tokens per select group (one wavefront, lane = token)
 constexpr int kChunkGroups = 2;   // groups per down-projection token chunk
-constexpr int kChunk = kGroup * kChunkGroups;   // 64 tokens whose outputs live in LDS together
+constexpr int kChunk = kGroup * kChunkGroups;   // 128 tokens whose outputs live in LDS together
 constexpr int kTilePad = 64;      // entries the expert kernels may read past the end of the lists
 
 inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
@@ -47,7 +49,7 @@ inline bool up_tiny_supported(const dmoe_layer& L) {
 
 // Sub-buffers of the packed-weights buffer (bytes from its start).
 struct PackedLayout {
-    size_t w2f, w2g, wupf, wgatef, r1f, r2f, w2f8, wupf8, wgatef8, wtinyf, total;
+    size_t w2f, w2g, wupf, wgatef, r1f, r2f, w2f8, wupf8, wgatef8, wtinyf, scales, total;
 };
 inline PackedLayout packed_layout(const dmoe_layer& L) {
     PackedLayout P{};
@@ -83,6 +85,10 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
     // (ffn_bf16.hip, up_tiny_kernel): wtinyf[E][d/32][64][8]
     P.wtinyf = o;
     if (up_tiny_supported(L)) o += (2 * (size_t)L.n_experts * 16 * L.d_model + 255) / 256 * 256;
+    // 8-bit weights: the caller's scales snapped to powers of two, [E][3] fp32 -- the copy every
+    // kernel uses, so that all paths compute the same layer whatever the caller passed
+    P.scales = o;
+    if (L.weight_format == DMOE_W_FP8_E4M3) o += (sizeof(float) * 3 * (size_t)L.n_experts + 255) / 256 * 256;
     P.total = o;
     return P;
 }

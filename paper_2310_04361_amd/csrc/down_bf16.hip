@@ -387,12 +387,11 @@ void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int3
                    const void* H, void* y, long long max_pairs_sparse, hipStream_t s) {
     const int NG = div_up(T, kGroup), NC = div_up(T, kDnTokens), NS = L.d_model / (CT * kDnColStep);
     constexpr size_t lds = (size_t)kDnTrip * kDnTiles * KSP * 1024;
-    static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KSP, G, R, WPS, CT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        attr_set = true;
-    }
+    });
     const char* pk = static_cast<const char*>(L.packed);
     const int row_bytes = 2 * m_pad_of(L.expert_size);
     int row_shift = 0;
@@ -419,7 +418,11 @@ bool down_bf16_addressable(const dmoe_layer& L, int T) {
 
 void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s) {
     const DownPacking dp = down_packing(L.expert_size);
-    launch_kernel(pack_down32_kernel, 2048, 256, 0, s, L.w_down, L.w_scales,
+    // 8-bit weights: the snapped scales that launch_pack_bf16 wrote into the packed buffer
+    const float* scales = L.weight_format == DMOE_W_FP8_E4M3
+                              ? (const float*)(static_cast<const char*>(w2g) - packed_layout(L).w2g + packed_layout(L).scales)
+                              : nullptr;
+    launch_kernel(pack_down32_kernel, 2048, 256, 0, s, L.w_down, scales,
                                             L.weight_format == DMOE_W_FP8_E4M3, (__bf16*)w2g,
                                             L.n_experts, L.expert_size, L.d_model, dp.PG, dp.G, dp.KSP);
 }

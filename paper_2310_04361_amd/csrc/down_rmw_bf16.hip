@@ -218,12 +218,11 @@ void launch_down_rmw_t(const dmoe_layer& L, const PackedLayout& P, int T, const 
                        const int32_t* group_off, const int32_t* alist, const int32_t* offsets,
                        const void* H, void* y, long long max_pairs, hipStream_t s) {
     const int NG = div_up(T, kGroup), NC = div_up(T, kChunk), NS = L.d_model / kDownCols;
-    static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_rmw_bf16_kernel<KS>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDownLds);
-        attr_set = true;
-    }
+    });
     const char* pk = static_cast<const char*>(L.packed);
     launch_kernel(down_rmw_bf16_kernel<KS>, round_up(NC, 8) * NS, kDownWaves * 64, kDownLds, s, 
         (const __bf16*)(pk + P.w2f), (const __bf16*)L.b_down, item_start, group_off, alist, offsets,

@@ -27,28 +27,6 @@ namespace {
 
 constexpr int kUpRowBytes = 144;               // 64 bf16 of one x row + 16 bytes of bank skew
 
-// ---- activations (fp32 in, fp32 out) -------------------------------------------------------------
-// erf by the rational-times-exponential approximation 7.1.26 of Abramowitz & Stegun
-// (absolute error below 1.5e-7, far inside bf16 resolution), tanh through one exponential.
-__device__ __forceinline__ float fast_erf(float v) {
-    const float a = fabsf(v);
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, a, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    const float r = 1.0f - p * t * __expf(-a * a);
-    return copysignf(r, v);
-}
-
-__device__ __forceinline__ float activate_fast(int act, float v) {
-    if (act == DMOE_ACT_RELU) return fmaxf(v, 0.0f);
-    if (act == DMOE_ACT_GELU_ERF) return 0.5f * v * (1.0f + fast_erf(v * 0.70710678118654752440f));
-    const float u = 0.79788456080286535588f * (v + 0.044715f * v * v * v);
-    const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * u));  // tanh(u)
-    return 0.5f * v * (1.0f + th);
-}
-
 // ---- one-time weight packing ------------------------------------------------------------------------
 // (small-token path) w_down[E][m][d] -> w2f[E][d/16][KS][64][8]: lane (q, c) of fragment (e, column tile ct, ks)
 // holds W_down[e][8*(4ks + q) + s][16ct + c] (piece 4ks + q of an H row), zero for neurons >= m.
@@ -62,6 +40,19 @@ __device__ __forceinline__ OUT packed_weight(const void* w, const float* scales,
     } else {
         return valid ? expert_weight(w, scales, fp8, which, e, flat) : (__bf16)0.0f;
     }
+}
+
+// Scales of 8-bit weights -> the nearest power of two (in log2; the sign is kept, zero stays
+// zero): with such a scale scale * e4m3(byte) is exactly a bf16 number, which is what makes the
+// bf16 copies of the prefill kernels and the in-register conversion of the small-token kernels
+// the same layer.
+__global__ void snap_scales_kernel(const float* __restrict__ in, float* __restrict__ out, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float v = in[i], a = fabsf(v);
+    float r = 0.0f;
+    if (a > 0.0f && a < INFINITY) r = copysignf(exp2f(rintf(log2f(a))), v);
+    out[i] = r;
 }
 
 template <typename OUT>
@@ -598,12 +589,11 @@ void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, cons
                  hipStream_t s) {
     const size_t lds = ((2 * (size_t)L.n_experts + 1) * 4 + 15) / 16 * 16 +
                        4 * NBUF * (size_t)TT * 16 * kUpRowBytes;
-    static bool attr_set = false;  // per-function, idempotent: allow more than 64 KiB of LDS
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_bf16_kernel<MT, GATED, TT, NBUF>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
-    }
+    });
     const char* pk = static_cast<const char*>(L.packed);
     launch_kernel(up_bf16_kernel<MT, GATED, TT, NBUF>, grid, 256, lds, s, 
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
@@ -617,12 +607,11 @@ void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
                       void* H, int grid, hipStream_t s) {
     constexpr int NWF = 2 * (GATED ? 2 : 1) * MT;
     const size_t lds = 2 * NWF * 1024 + 4 * (size_t)TT * 16 * kUpRowBytes + MT * 16 * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_wide_bf16_kernel<MT, GATED, TT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
-    }
+    });
     const char* pk = static_cast<const char*>(L.packed);
     launch_kernel(up_wide_bf16_kernel<MT, GATED, TT>, grid, 256, lds, s, 
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
@@ -636,7 +625,7 @@ bool experts_bf16_supported(const dmoe_layer& L) {
     const int mp = m_pad_of(L.expert_size);
     if (!(mp == 32 || mp == 64 || mp == 128)) return false;
     if (L.gated && mp == 128) return false;  // accumulators of both branches would not fit
-    return down_bf16_supported(L) && L.n_experts <= 8192;
+    return down_bf16_supported(L) && L.n_experts <= kMaxExperts;
 }
 
 void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
@@ -646,24 +635,30 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     char* pk = static_cast<char*>(packed);
     const int fp8 = L.weight_format == DMOE_W_FP8_E4M3;
     const int E = L.n_experts, m = L.expert_size, d = L.d_model;
-    launch_kernel(pack_down_kernel<__bf16>, 2048, 256, 0, s, L.w_down, L.w_scales, fp8, (__bf16*)(pk + P.w2f), E,
+    const float* scales = nullptr;   // the snapped copy inside the packed buffer
+    if (fp8) {
+        launch_kernel(snap_scales_kernel, div_up(3 * E, 256), 256, 0, s, L.w_scales,
+                      (float*)(pk + P.scales), 3 * E);
+        scales = (const float*)(pk + P.scales);
+    }
+    launch_kernel(pack_down_kernel<__bf16>, 2048, 256, 0, s, L.w_down, scales, fp8, (__bf16*)(pk + P.w2f), E,
                                                   m, d, mp / 32);
     launch_pack_down_bf16(L, pk + P.w2g, s);
-    launch_kernel(pack_up_kernel<__bf16>, 2048, 256, 0, s, L.w_up, L.w_scales, fp8, 0, (__bf16*)(pk + P.wupf), E,
+    launch_kernel(pack_up_kernel<__bf16>, 2048, 256, 0, s, L.w_up, scales, fp8, 0, (__bf16*)(pk + P.wupf), E,
                                                 m, d, mp / 16, 1);
     if (L.gated)
-        launch_kernel(pack_up_kernel<__bf16>, 2048, 256, 0, s, L.w_gate, L.w_scales, fp8, 1,
+        launch_kernel(pack_up_kernel<__bf16>, 2048, 256, 0, s, L.w_gate, scales, fp8, 1,
                                                     (__bf16*)(pk + P.wgatef), E, m, d, mp / 16, 1);
     if (up_tiny_supported(L))
-        launch_kernel(pack_up_tiny_kernel, 2048, 256, 0, s, L.w_up, L.w_gate, L.w_scales, fp8,
+        launch_kernel(pack_up_tiny_kernel, 2048, 256, 0, s, L.w_up, L.w_gate, scales, fp8,
                                                  (__bf16*)(pk + P.wtinyf), E, m, d, L.gated);
     if (fp8) {  // byte fragments for the small-token kernels
-        launch_kernel(pack_down_kernel<uint8_t>, 2048, 256, 0, s, L.w_down, L.w_scales, 1, (uint8_t*)(pk + P.w2f8),
+        launch_kernel(pack_down_kernel<uint8_t>, 2048, 256, 0, s, L.w_down, scales, 1, (uint8_t*)(pk + P.w2f8),
                                                        E, m, d, mp / 32);
-        launch_kernel(pack_up_kernel<uint8_t>, 2048, 256, 0, s, L.w_up, L.w_scales, 1, 0, (uint8_t*)(pk + P.wupf8),
+        launch_kernel(pack_up_kernel<uint8_t>, 2048, 256, 0, s, L.w_up, scales, 1, 0, (uint8_t*)(pk + P.wupf8),
                                                      E, m, d, mp / 16, 1);
         if (L.gated)
-            launch_kernel(pack_up_kernel<uint8_t>, 2048, 256, 0, s, L.w_gate, L.w_scales, 1, 1,
+            launch_kernel(pack_up_kernel<uint8_t>, 2048, 256, 0, s, L.w_gate, scales, 1, 1,
                                                          (uint8_t*)(pk + P.wgatef8), E, m, d, mp / 16, 1);
     }
     // the router matrices use the same fragment format: "one expert" whose rows are the hidden
@@ -716,14 +711,13 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
         // (squeezed into a fourth wavefront per SIMD's share of registers the kernel got slower)
         const int per_cu = std::max(1, std::min(3, (int)(160 * 1024 / lds)));
         const int grid = round_up((int)std::min<long long>((worst + 3) / 4, 256 * per_cu), 8);
-        static bool attr_set = false;
-        if (!attr_set) {
+        static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+        std::call_once(attr_once, [&] {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT, true>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_tiny_kernel<TT, false>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            attr_set = true;
-        }
+        });
         const char* pk = static_cast<const char*>(L.packed);
         if (L.gated)
             launch_kernel(up_tiny_kernel<TT, true>, grid, 256, lds, s, 

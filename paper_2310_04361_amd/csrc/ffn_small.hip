@@ -19,24 +19,6 @@ namespace dmoe {
 
 namespace {
 
-__device__ __forceinline__ float fast_erf_s(float v) {
-    // Abramowitz & Stegun 7.1.26, |error| < 1.5e-7
-    const float a = fabsf(v);
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, a, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    return copysignf(1.0f - p * t * __expf(-a * a), v);
-}
-
-__device__ __forceinline__ float activate_s(int act, float v) {
-    if (act == DMOE_ACT_RELU) return fmaxf(v, 0.0f);
-    if (act == DMOE_ACT_GELU_ERF) return 0.5f * v * (1.0f + fast_erf_s(v * 0.70710678118654752440f));
-    const float u = 0.79788456080286535588f * (v + 0.044715f * v * v * v);
-    const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * u));
-    return 0.5f * v * (1.0f + th);
-}
 
 // Sixteen wavefronts per workgroup = MT neuron tiles (m_pad / 16) x KQ slices of the K range: an
 // expert's weights are a pure stream, so what counts is how many bytes a CU keeps in flight.
@@ -141,10 +123,10 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
         const int n = neuron_of_slot(mt, 4 * q + r);
         float v;
         if (GATED) {
-            v = activate_s(act, acc[BR - 1][r] * s_gate) * (acc[0][r] * s_up);
+            v = activate_fast(act, acc[BR - 1][r] * s_gate) * (acc[0][r] * s_up);
         } else {
             const float bias = b_up ? (float)b_up[(size_t)e * m + min(n, m - 1)] : 0.0f;
-            v = activate_s(act, acc[0][r] * s_up + bias);
+            v = activate_fast(act, acc[0][r] * s_up + bias);
         }
         v *= s_down;
         if (n >= m || !keep) v = 0.0f;
@@ -235,12 +217,11 @@ void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
                        hipStream_t s) {
     const size_t lds = std::max(16 * (2 * (size_t)L.d_model + 16),
                                 sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4);
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_small_kernel<MT, GATED, W8>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
-    }
+    });
     // K slices: as many as the sixteen wavefronts allow and the k-steps divide into
     int KQ = kUpSmallWaves / MT;
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;

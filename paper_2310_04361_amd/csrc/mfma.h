@@ -128,4 +128,26 @@ __device__ __forceinline__ float activate(int act, float v) {
     return 0.5f * v * (1.0f + tanhf(u));
 }
 
+// Activations of the bf16 kernels (fp32 in, fp32 out).
+// erf by the rational-times-exponential approximation 7.1.26 of Abramowitz & Stegun
+// (absolute error below 1.5e-7, far inside bf16 resolution), tanh through one exponential.
+__device__ __forceinline__ float fast_erf(float v) {
+    const float a = fabsf(v);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, a, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float r = 1.0f - p * t * __expf(-a * a);
+    return copysignf(r, v);
+}
+
+__device__ __forceinline__ float activate_fast(int act, float v) {
+    if (act == DMOE_ACT_RELU) return fmaxf(v, 0.0f);
+    if (act == DMOE_ACT_GELU_ERF) return 0.5f * v * (1.0f + fast_erf(v * 0.70710678118654752440f));
+    const float u = 0.79788456080286535588f * (v + 0.044715f * v * v * v);
+    const float th = 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * u));  // tanh(u)
+    return 0.5f * v * (1.0f + th);
+}
+
 }  // namespace dmoe

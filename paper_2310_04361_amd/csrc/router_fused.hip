@@ -345,12 +345,11 @@ void launch_t3(const dmoe_layer& L, const void* x, int T, float* scores, float t
     constexpr int TOK = 16 * TT;
     const size_t lds = TOK * (KBC * 128 + 16) + TOK * (NH * 32 + 16) + 256 * 4 +
                        (mask ? (size_t)5 * 64 * W * 8 : 0);  // the gate's words only when it runs
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_fused_kernel<NH, ETW, KBC, TT>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
-    }
+    });
     const char* pk = static_cast<const char*>(L.packed);
     launch_kernel(router_fused_kernel<NH, ETW, KBC, TT>, div_up(T, TOK), 256, lds, s, 
         (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1,
@@ -497,13 +496,12 @@ static void launch_scores_slices(const dmoe_layer& L, const PackedLayout& P, int
     const int want = std::max(1, std::min(NE / 4, div_up(256, NG)));
     const int tiles_y = round_up(div_up(NE, want), 4);
     const size_t lds = 64 * (NH * 32 + 16) + 256 * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(
             reinterpret_cast<const void*>(&router_fused_kernel<NH, 2, 4, 4, kScoresSlice>),
             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
-    }
+    });
     const char* pk = static_cast<const char*>(L.packed);
     launch_kernel(router_fused_kernel<NH, 2, 4, 4, kScoresSlice>, dim3(NG, div_up(NE, tiles_y)), 256, lds, s, 
         nullptr, nullptr, nullptr, (const __bf16*)(pk + P.r2f), (const __bf16*)L.r_b2, scores, T,
@@ -520,13 +518,12 @@ void launch_router_sliced(const dmoe_layer& L, const void* x, int T, void* hid, 
     {   // hidden rows: 128 hidden units per workgroup
         constexpr int NH = 8, KBC = 12;
         const size_t lds = 64 * (KBC * 128 + 16) + 64 * (NH * 32 + 16) + 256 * 4;
-        static bool attr_set = false;
-        if (!attr_set) {
+        static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+        std::call_once(attr_once, [&] {
             (void)hipFuncSetAttribute(
                 reinterpret_cast<const void*>(&router_fused_kernel<NH, 2, KBC, 4, kHiddenSlice>),
                 hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            attr_set = true;
-        }
+        });
         launch_kernel(router_fused_kernel<NH, 2, KBC, 4, kHiddenSlice>, dim3(NG, dh / 128), 256, lds, s, 
             (const __bf16*)x, (const __bf16*)(pk + P.r1f), (const __bf16*)L.r_b1, nullptr, nullptr,
             nullptr, T, L.d_model, L.n_experts, 0.0f, 0, nullptr, nullptr, nullptr, nullptr,

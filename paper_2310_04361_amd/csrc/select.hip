@@ -495,12 +495,11 @@ void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_
     launch_router_small_hidden(L, G, n_layers, x, T, s);
     LaunchTimer tm(kSlotMask, s);
     const size_t lds = sizeof(uint64_t) * 16 * W + sizeof(float) * 16 * (size_t)E;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_scores_select_small_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        attr_set = true;
-    }
+    });
     launch_kernel(router_scores_select_small_kernel, dim3(1, 1, n_layers), 1024, lds, s, G, T, L.router_hidden, E, W);
 }
 
@@ -548,12 +547,11 @@ void launch_scan_and_fill(const uint64_t* mask, int T, int E, int32_t* group_off
     }
     LaunchTimer tm(kSlotFill, s);
     const size_t lds = sizeof(int32_t) * 2 * ((size_t)E + 1);
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&fill_lists_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
-        attr_set = true;
-    }
+    });
     // with few token groups and many experts the mask words of a group are split over several
     // workgroups (each repeats the prefix sums over the experts)
     const int ny = std::max(1, std::min(W, div_up(2048, std::max(1, NG))));

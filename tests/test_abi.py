@@ -172,6 +172,14 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert lib.dmoe_pack_weights(ref(_layer(dtype=B.DMOE_BF16)), 0x10000, 1 << 30, None) == B.DMOE_ERR_UNSUPPORTED
     assert lib.dmoe_pack_weights(ref(Lb), 0x10000, 16, None) == B.DMOE_ERR_WORKSPACE
     assert lib.dmoe_pack_weights(ref(L), None, 0, None) == B.DMOE_OK          # fp32: no-op
+    # a layer with a router is packed with its router: missing router matrices are an error, not
+    # a silently unpacked router (router_hidden = 0 declares a layer without one)
+    assert lib.dmoe_pack_weights(ref(_layer(dtype=B.DMOE_BF16, d_model=256, r_w1=None)), 0x10000,
+                                 1 << 30, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_pack_weights(ref(_layer(dtype=B.DMOE_BF16, d_model=256, r_w2=None)), 0x10000,
+                                 1 << 30, None) == B.DMOE_ERR_NULL
+    assert lib.dmoe_pack_weights(ref(_layer(dtype=B.DMOE_BF16, d_model=256, router_hidden=48)), 0x10000,
+                                 1 << 30, None) == B.DMOE_ERR_UNSUPPORTED
     # timing slots are readable without enabling
     assert lib.dmoe_timing_slots() >= 8
     assert lib.dmoe_timing_read(999, None, None, None) == B.DMOE_ERR_SHAPE

@@ -51,3 +51,29 @@ def test_forward_with_e4m3_weights(B, oracle, name, T, E):
     y2, _ = B.dmoe_forward(B.Layer(plain, cfg.dtype), B.to_device(x, cfg.dtype), tau)
     torch.cuda.synchronize()
     assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("T", [12, 200])
+def test_scales_that_are_not_powers_of_two_are_snapped_on_every_path(B, oracle, T):
+    """The header asks for power-of-two scales; a scale that is not one is replaced by the nearest
+    power of two at packing time, and the small-token kernels (T <= 16) and the prefill kernels
+    use the same snapped copy: both must equal the layer with the snapped scales."""
+    import torch
+    cfg = small_cfg("cfg5b", T)
+    print(f"e4m3 scales off powers of two, T={T}", flush=True)
+    layer = wl.quantize_experts_e4m3(wl.make_layer(cfg, 6))
+    x = wl.make_input(cfg, 6)
+    snapped = dict(layer)                      # the reference layer: scales as powers of two
+    bent = dict(layer)
+    bent["w8"] = dict(layer["w8"])
+    # 1.3 s and 0.8 s both lie closer (in log2) to s than to 2 s or s / 2
+    factor = np.where(np.arange(cfg.E)[:, None] % 2 == 0, 1.3, 0.8).astype(np.float32)
+    bent["w8"]["scales"] = layer["w8"]["scales"] * factor
+    tau = float(np.float32(0.4))
+    xd = B.to_device(x, cfg.dtype)
+    y_bent, _ = B.dmoe_forward(B.Layer(bent, cfg.dtype), xd, tau)
+    y_ref, ex = B.dmoe_forward(B.Layer(snapped, cfg.dtype), xd, tau, want_scores=True)
+    torch.cuda.synchronize()
+    assert torch.equal(y_bent, y_ref)
+    mask, _ = oracle.select(ex["scores"].cpu().numpy().astype(np.float64), tau)
+    assert tokenwise_rel_err(B.from_device(y_bent, cfg.dtype), oracle_ffn(oracle, snapped, x, mask)) <= TOL["bf16"]

@@ -27,7 +27,10 @@ def B():
                                              ("cfg5b/16", 16, 3), ("cfg5b/16", 300, 3),
                                              # more experts than the fused small-token gate takes,
                                              # and a count that is no multiple of 4
-                                             ("cfg5b/1100", 12, 2), ("cfg5b/30", 16, 3)])
+                                             ("cfg5b/1100", 12, 2), ("cfg5b/30", 16, 3),
+                                             # between the fused prefill gate (512) and the
+                                             # fused small-token gate (1024)
+                                             ("cfg5b/600", 16, 2)])
 def test_group_matches_single_layers_and_oracle(B, oracle, name, T, n_layers):
     import torch
     from dataclasses import replace

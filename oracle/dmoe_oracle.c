@@ -25,6 +25,12 @@
  *               selected experts' outputs: the experts partition a dense FFN, so selecting all of
  *               them must reproduce it.
  *
+ *   quantize    Appendix C (lower-precision layers): row-wise 8-bit floating-point quantisation
+ *               of the experts' input.  The format is a published one and pins the rounding; the
+ *               scale rule is this build's reading (the paper gives none): "parity unpinned by
+ *               the paper" for the rule itself, pinned against the format definition and an
+ *               independent converter for the arithmetic.
+ *
  * Parity pins live in tests/test_oracle_*.py.  The GELU flavour (erf or tanh form) and the
  * placement of a bias in a gated expert are not fixed by the paper: "parity unpinned" for those
  * two readings (the gated-with-bias case is rejected here, see dmoe_oracle_expert_ffn).
@@ -209,6 +215,43 @@ int dmoe_oracle_expert_ffn(const double *x, const double *w_up, const double *w_
                 for (int c = 0; c < d; ++c) yt[c] += h * w_down[row + c];
             }
         }
+    }
+    return 0;
+}
+
+/*
+ * Row-wise 8-bit quantisation of the experts' input: the lower-precision layers whose timings
+ * Appendix C reports, with 8-bit floating point (OCP E4M3: 1 sign bit, 4 exponent bits with bias 7,
+ * 3 mantissa bits, subnormals m/8 * 2^-6, largest value 448) in place of int8.  The paper fixes
+ * no quantisation rule; the one taken here (and stated in the library's header) is
+ *   s_t  = the smallest power of two with max_j |x_tj| / s_t <= 448   (1 for a zero row; the
+ *          exponent of s_t is kept within -100 .. 100),
+ *   xq_t = s_t * nearest E4M3 value of x_t / s_t, ties to the even mantissa.
+ * xq [T][d] receives the quantised rows, scales [T] the s_t.
+ */
+static double e4m3_nearest(double v) {
+    const double a = fabs(v);
+    if (a == 0.0) return v;
+    int e = 0;                          /* floor(log2 a), but not below the subnormal range */
+    while (ldexp(1.0, e + 1) <= a) ++e;
+    while (ldexp(1.0, e) > a && e > -6) --e;
+    const double step = ldexp(1.0, e - 3);   /* spacing of the E4M3 grid at this magnitude */
+    return copysign(nearbyint(a / step) * step, v);   /* default rounding mode: ties to even */
+}
+
+int dmoe_oracle_quantize_rows_e4m3(const double *x, int T, int d, double *xq, double *scales) {
+    if (!x || !xq || !scales || T < 0 || d <= 0) return 1;
+    for (int t = 0; t < T; ++t) {
+        double amax = 0.0;
+        for (int j = 0; j < d; ++j) amax = fmax(amax, fabs(x[(size_t)t * d + j]));
+        int k = 0;                      /* s_t = 2^k */
+        if (amax > 0.0) {
+            while (amax / ldexp(1.0, k) > 448.0 && k < 100) ++k;
+            while (amax / ldexp(1.0, k - 1) <= 448.0 && k > -100) --k;
+        }
+        const double s = ldexp(1.0, k);
+        scales[t] = s;
+        for (int j = 0; j < d; ++j) xq[(size_t)t * d + j] = s * e4m3_nearest(x[(size_t)t * d + j] / s);
     }
     return 0;
 }

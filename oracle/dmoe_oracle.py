@@ -52,6 +52,8 @@ def _load():
         lib.dmoe_oracle_bucket.argtypes = [u8p, ci, ci, i32p, i32p, i32p]
         lib.dmoe_oracle_expert_ffn.argtypes = [dp, dp, dp, dp, dp, dp, ci, ci, ci, ci, ci, ci,
                                                u8p, dp]
+        lib.dmoe_oracle_quantize_rows_e4m3.argtypes = [dp, ci, ci, dp, dp]
+        lib.dmoe_oracle_quantize_rows_e4m3.restype = ci
         for f in (lib.dmoe_oracle_router, lib.dmoe_oracle_select, lib.dmoe_oracle_select_topk,
                   lib.dmoe_oracle_bucket, lib.dmoe_oracle_expert_ffn):
             f.restype = ci
@@ -168,6 +170,19 @@ def expert_ffn(x, w_up, w_gate, b_up, w_down, b_down, mask, act, gated=False):
     if rc:
         raise RuntimeError(f"dmoe_oracle_expert_ffn failed: {rc}")
     return y
+
+
+def quantize_rows_e4m3(x):
+    """Row-wise 8-bit (E4M3, power-of-two scale per row) quantisation of the experts' input.
+    Returns (xq[T, d] -- the quantised rows as fp64 numbers --, scales[T])."""
+    x = _f64(x)
+    T, d = x.shape
+    xq = np.empty((T, d), dtype=np.float64)
+    scales = np.empty((T,), dtype=np.float64)
+    rc = _load().dmoe_oracle_quantize_rows_e4m3(_dp(x), T, d, _dp(xq), _dp(scales))
+    if rc:
+        raise RuntimeError(f"dmoe_oracle_quantize_rows_e4m3 failed: {rc}")
+    return xq, scales
 
 
 def forward(layer: dict, x, tau):

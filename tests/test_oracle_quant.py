@@ -1,0 +1,83 @@
+"""Pins of the oracle's row-wise E4M3 quantiser (the 8-bit expert input of the lower-precision
+layers, Appendix C).  The format -- OCP 8-bit floating point E4M3: 1 sign, 4 exponent bits with
+bias 7, 3 mantissa bits, subnormals m/8 * 2^-6, no infinities, largest value 448 -- is written
+out here from its definition, and torch's float8_e4m3fn cast serves as an independent converter."""
+import numpy as np
+import pytest
+
+
+def e4m3_values():
+    """All non-negative finite E4M3 values, ascending, with their codes (from the definition)."""
+    vals = []
+    for code in range(0x7f):                       # 0x7f is NaN
+        e, m = code >> 3, code & 7
+        vals.append((m / 8.0 * 2.0 ** -6) if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7))
+    assert vals == sorted(vals) and vals[-1] == 448.0 and vals[1] == 2.0 ** -9
+    return np.asarray(vals)
+
+
+def test_representable_values_are_fixed_points(oracle):
+    v = e4m3_values()
+    for k in (-20, -3, 0, 5, 31):
+        s = 2.0 ** k
+        row = np.concatenate([v, -v, [448.0]]) * s            # the row maximum is 448 s
+        xq, scales = oracle.quantize_rows_e4m3(row[None, :])
+        assert scales[0] == s
+        assert np.array_equal(xq[0], row)
+
+
+def test_midpoints_go_to_the_even_mantissa_and_neighbours_round_to_nearest(oracle):
+    v = e4m3_values()
+    mid = (v[:-1] + v[1:]) / 2
+    even = np.where(np.arange(len(v) - 1) % 2 == 0, v[:-1], v[1:])   # code parity = mantissa parity
+    row = np.concatenate([mid, [448.0]])
+    xq, _ = oracle.quantize_rows_e4m3(np.stack([row, -row]))
+    assert np.array_equal(xq[0, :-1], even) and np.array_equal(xq[1, :-1], -even)
+    # a hair below / above a midpoint goes down / up
+    lo = np.concatenate([mid * (1 - 2.0 ** -30), [448.0]])
+    hi = np.concatenate([mid * (1 + 2.0 ** -30), [448.0]])
+    xq, _ = oracle.quantize_rows_e4m3(np.stack([lo, hi]))
+    assert np.array_equal(xq[0, :-1], v[:-1]) and np.array_equal(xq[1, :-1], v[1:])
+
+
+def test_scale_is_the_smallest_power_of_two_that_fits(oracle):
+    rows = np.zeros((6, 8))
+    rows[0, 3] = 448.0                 # fits with s = 1
+    rows[1, 3] = -448.0 * (1 + 2.0 ** -20)   # just above: s = 2
+    rows[2, 0] = 224.0                 # s = 0.5 would give exactly 448
+    rows[3, 5] = 448.0 * 2.0 ** -40
+    rows[4, 1] = 3.0                   # 3 / 448 = 0.0067 -> s = 2^-7 (0.0078)
+    xq, s = oracle.quantize_rows_e4m3(rows)
+    assert s.tolist() == [1.0, 2.0, 0.5, 2.0 ** -40, 2.0 ** -7, 1.0]
+    assert np.array_equal(xq[5], np.zeros(8))            # a zero row stays zero, scale 1
+    assert xq[1, 3] == -448.0                            # 224.0001.. * 2 -> nearest value
+    # every row's largest element lands in (224, 448] in units of its scale
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((50, 64)) * np.exp(rng.normal(0, 4, (50, 1)))
+    _, s = oracle.quantize_rows_e4m3(x)
+    top = np.abs(x).max(axis=1) / s
+    assert ((top > 224.0) & (top <= 448.0)).all()
+    assert np.array_equal(np.log2(s), np.round(np.log2(s)))
+
+
+def test_power_of_two_row_scaling_moves_only_the_scale(oracle):
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((20, 96))
+    xq, s = oracle.quantize_rows_e4m3(x)
+    xq2, s2 = oracle.quantize_rows_e4m3(x * 2.0 ** 11)
+    assert np.array_equal(s2, s * 2.0 ** 11) and np.array_equal(xq2, xq * 2.0 ** 11)
+
+
+def test_against_an_independent_converter_and_the_half_step_bound(oracle):
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((64, 256)) * np.exp(rng.normal(0, 2, (64, 1)))
+    x = x.astype(np.float32).astype(np.float64)
+    xq, s = oracle.quantize_rows_e4m3(x)
+    cast = torch.from_numpy((x / s[:, None]).astype(np.float32)).to(torch.float8_e4m3fn)
+    ref = cast.to(torch.float32).numpy().astype(np.float64) * s[:, None]
+    assert np.array_equal(xq, ref)
+    # nearest value: the error is at most half a grid step (2^-4 relative, 2^-10 s absolute below 2^-6 s)
+    err = np.abs(xq - x)
+    bound = np.maximum(np.abs(x) * 2.0 ** -4, s[:, None] * 2.0 ** -10)
+    assert (err <= bound).all()

@@ -105,7 +105,7 @@ def achieved_peaks():
 class Workload:
     """One layer + its rotated inputs on the device."""
 
-    def __init__(self, name, tokens=0, e4m3=False):
+    def __init__(self, name, tokens=0, e4m3=False, x8=False):
         import torch
         from paper_2310_04361_amd import binding as B, workloads as wl
         cfg = wl.CONFIGS[name]
@@ -114,8 +114,10 @@ class Workload:
         self.cfg = cfg
         self.e4m3 = e4m3   # expert matrices stored in 8-bit E4M3 (one byte per weight)
         self.layer_np, self.x_np = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
-        if e4m3:
+        if e4m3 or x8:
             self.layer_np = wl.quantize_experts_e4m3(self.layer_np)
+        if x8:   # ... and the experts' input quantised row-wise to E4M3 as well
+            self.layer_np["x8"] = True
         self.decode = cfg.T <= 16
         n_layers = N_LAYER_COPIES_DECODE if self.decode else 1
         self.layers = [B.Layer(self.layer_np, cfg.dtype) for _ in range(n_layers)]
@@ -177,6 +179,8 @@ class Workload:
             kflops = {"expert_up": flops * (g - 1) / g, down: flops / g}
             dom = max(kflops, key=lambda k: kt.get(k, 0.0))
             achieved = kflops[dom] / (kt[dom] * 1e-3) / 1e12
+            # (layers with 8-bit inputs run their up-projection on the fp8 matrix pipe, whose peak
+            # is twice this one: their line is context, the bf16 layers are the roofline claim)
             experts_ms = sum(kt.get(k, 0.0) for k in ("expert_up", "expert_down", "expert_down_sparse"))
             traffic, source = profile_traffic(cfg.name, tau_arg, dom) if traffic_ok else (None, None)
             roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
@@ -311,6 +315,8 @@ def main() -> int:
                     help="(default unless --no-curves) time a ViT-B-shaped encoder block (LayerNorm, "
                          "12-head attention, residuals, FFN) on 256x197 tokens with the dense FFN and "
                          "with the dynamic-k layer in its place (Sec. 4.4: what survives end to end)")
+    ap.add_argument("--x8", action="store_true",
+                    help="with --no-others: still time the headline layer with 8-bit weights and inputs")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense-FFN comparisons (keeps a profile to the timed workload)")
     args = ap.parse_args()
@@ -488,6 +494,21 @@ def main() -> int:
         done_names.add(args.workload)
     del w
     torch.cuda.empty_cache()
+
+    if (not args.no_others or args.x8) and not args.tokens and cfg.dtype == "bf16":
+        # the same layer with 8-bit expert weights and 8-bit (row-wise E4M3) expert inputs: the
+        # up-projection of wide experts runs on the fp8 matrix pipe (Appendix C's lower precisions)
+        w8 = Workload(args.workload, x8=True)
+        rows = []
+        for name, t in [(args.workload, args.tau)] + [o for o in OTHERS if o[0] == args.workload and o[1] != args.tau]:
+            r8 = w8.measure(t, 100, 10)
+            rows.append({"workload": w8.describe(t), "ms_per_step": round(r8["ms"], 5),
+                         "executed_expert_tflops": round(r8["flops"] / (r8["ms"] * 1e-3) / 1e12, 2),
+                         "kernel_ms": r8["kernel_ms"]})
+        out["fp8_inputs_and_weights"] = {"note": "weight_format DMOE_W_FP8_E4M3_X8: same shapes, a "
+                                         "different (lower) precision -- not the bf16 headline", "rows": rows}
+        del w8
+        torch.cuda.empty_cache()
 
     curves = not args.no_curves
     if curves and not args.tokens:

@@ -56,7 +56,7 @@ typedef enum {
 
 enum { DMOE_F32 = 0, DMOE_BF16 = 1 };
 /* storage of the expert matrices w_up, w_gate, w_down (dmoe_layer.weight_format) */
-enum { DMOE_W_NATIVE = 0, DMOE_W_FP8_E4M3 = 1 };
+enum { DMOE_W_NATIVE = 0, DMOE_W_FP8_E4M3 = 1, DMOE_W_FP8_E4M3_X8 = 2 };
 enum { DMOE_ACT_RELU = 0, DMOE_ACT_GELU_ERF = 1, DMOE_ACT_GELU_TANH = 2 };
 
 /*
@@ -96,6 +96,20 @@ typedef struct {
  * replaces a scale that is not a power of two by the nearest one (in log2; zero stays zero) and
  * every kernel uses that copy, so all batch sizes compute the same layer.  w_scales is read by
  * dmoe_pack_weights only.  x, y, biases and the router stay bf16.
+ *
+ * DMOE_W_FP8_E4M3_X8 is DMOE_W_FP8_E4M3 with the experts' input quantised as well, so that the
+ * up-projection (and gate) multiplies 8-bit operands on the matrix cores -- the counterpart of
+ * the int8 layers Appendix C times.  The experts (not the router) read, instead of x_t,
+ *   xq_t = s_t * e4m3(x_t / s_t),   s_t = 2^ceil(log2(max_j |x_tj| / 448))   (s_t = 1 for a zero row;
+ *                                   its exponent is clamped to -100 .. 100),
+ * where e4m3(.) rounds to the nearest E4M3 value, ties to the even mantissa (the largest
+ * element of a row lands in (224, 448], so nothing overflows; magnitudes below 2^-10 s_t become
+ * zero).  Every xq element is a bf16 number, and every product of an 8-bit weight and an 8-bit
+ * input is exact in fp32, so the layer computes -- up to the order of the fp32 additions -- what
+ * a bf16 layer with the same weights computes on the input xq; the hidden activations and the
+ * down-projection are as in DMOE_W_FP8_E4M3.  The definition holds for every batch size; the
+ * 8-bit matrix-core kernel runs for batches above 16 tokens on experts of 128 neurons (64 if
+ * gated), other shapes run their bf16 kernels on xq.
  */
 
 /* Library version (major*10000 + minor*100 + patch) and the text of the last error of the

@@ -56,7 +56,8 @@ int static_scratch_of_current_device(void** out) {
 // ---- timing ------------------------------------------------------------------------------------
 const char* const kSlotNames[kSlotCount] = {
     "router", "mask_count", "lists_to_mask", "scan_groups", "fill_lists",
-    "expert_up", "expert_down", "expert_down_sparse", "ffn_f32", "small_up", "small_down", "small_finish", "pack_weights"};
+    "expert_up", "expert_down", "expert_down_sparse", "ffn_f32", "small_up", "small_down", "small_finish", "pack_weights",
+    "quantize_x"};
 constexpr int kEventPairs = 8192;
 bool g_timing = false;
 std::vector<hipEvent_t> g_ev;      // 2 * kEventPairs once enabled
@@ -92,9 +93,9 @@ int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
         return fail(DMOE_ERR_SHAPE, "d_model, n_experts and expert_size must be positive");
     if (L->dtype != DMOE_F32 && L->dtype != DMOE_BF16)
         return fail(DMOE_ERR_UNSUPPORTED, "dtype %d is not DMOE_F32 or DMOE_BF16", L->dtype);
-    if (L->weight_format != DMOE_W_NATIVE && L->weight_format != DMOE_W_FP8_E4M3)
-        return fail(DMOE_ERR_UNSUPPORTED, "weight_format %d is not DMOE_W_NATIVE or DMOE_W_FP8_E4M3", L->weight_format);
-    if (L->weight_format == DMOE_W_FP8_E4M3) {
+    if (L->weight_format != DMOE_W_NATIVE && !weights_fp8(*L))
+        return fail(DMOE_ERR_UNSUPPORTED, "weight_format %d is not one of DMOE_W_NATIVE, DMOE_W_FP8_E4M3, DMOE_W_FP8_E4M3_X8", L->weight_format);
+    if (weights_fp8(*L)) {
         if (L->dtype != DMOE_BF16) return fail(DMOE_ERR_UNSUPPORTED, "8-bit expert weights need a bf16 layer");
         if (!L->w_scales) return fail(DMOE_ERR_NULL, "8-bit expert weights need w_scales");
     }
@@ -172,7 +173,7 @@ SelectWs select_ws(int T, int E, bool need_mask) {
 }
 
 struct LayerWs {
-    size_t scores, mask, group_off, sub_cnt, counts, offsets, item_start, witem, wfirst, lists, H, colmask, partial, hid, total;
+    size_t scores, mask, group_off, sub_cnt, counts, offsets, item_start, witem, wfirst, lists, H, colmask, partial, hid, x8, xscale, xhat, total;
 };
 LayerWs layer_ws(const dmoe_layer& L, int T) {
     LayerWs w{};
@@ -209,6 +210,14 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     // two launches
     const size_t hid_rows = (L.dtype == DMOE_BF16 && router_sliced(L)) ? std::max(T, 16) : 16;
     w.hid = o;        o += align_up(2 * hid_rows * (size_t)std::max(L.router_hidden, 16));
+    // 8-bit expert inputs: codes, scales and the quantised rows as bf16 (the latter for the
+    // kernels that are not 8-bit: small-token path, shapes without the 8-bit up-projection)
+    w.x8 = w.xscale = w.xhat = o;
+    if (acts_fp8(L)) {
+        w.x8 = o;     o += align_up((size_t)std::max(T, 16) * L.d_model);
+        w.xscale = o; o += align_up(sizeof(float) * (size_t)std::max(T, 16));
+        w.xhat = o;   o += align_up(2 * (size_t)std::max(T, 16) * L.d_model);
+    }
     w.total = o;
     return w;
 }
@@ -235,7 +244,7 @@ SmallMod small_mod(const dmoe_layer& L, char* ws, const LayerWs& w, float* score
     M.wgatef8 = (const uint8_t*)(pk + P.wgatef8);
     M.w2f8 = (const uint8_t*)(pk + P.w2f8);
     // the power-of-two copy of the scales made by dmoe_pack_weights
-    M.w_scales = L.weight_format == DMOE_W_FP8_E4M3 ? (const float*)(pk + P.scales) : nullptr;
+    M.w_scales = weights_fp8(L) ? (const float*)(pk + P.scales) : nullptr;
     M.b_down = (const __bf16*)L.b_down;
     M.hid = (__bf16*)(ws + w.hid);
     M.Hs = (__bf16*)(ws + w.H);
@@ -261,6 +270,18 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
     // the kernels read the work-item-aligned copy in the workspace; the caller's is compact
     int32_t* alist = reinterpret_cast<int32_t*>(ws + w.lists);
     int32_t* item_start = reinterpret_cast<int32_t*>(ws + w.item_start);
+    const uint8_t* x8 = nullptr;
+    const float* xscale = nullptr;
+    if (acts_fp8(L)) {
+        // the experts read the row-wise quantised input: as codes + scales where the 8-bit
+        // up-projection runs, as bf16 numbers everywhere else
+        const bool codes = up_x8_supported(L) && !use_small_path(L, T);
+        launch_quantize_x(L, x, T, reinterpret_cast<uint8_t*>(ws + w.x8),
+                          reinterpret_cast<float*>(ws + w.xscale), codes ? nullptr : ws + w.xhat, s);
+        x8 = reinterpret_cast<const uint8_t*>(ws + w.x8);
+        xscale = reinterpret_cast<const float*>(ws + w.xscale);
+        if (!codes) x = ws + w.xhat;
+    }
     if (L.dtype == DMOE_F32) {
         if (offsets_out)
             launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
@@ -280,7 +301,8 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
                              up_rows_bf16(L), lists_out, alist, up_window_groups(L, T), witem,
                              wfirst, s, sub_cnt, split);
         void* H = ws + w.H;
-        launch_up_bf16(L, x, T, witem, wfirst, alist, H, s);
+        if (up_x8_supported(L)) launch_up_x8(L, x8, xscale, T, witem, wfirst, alist, H, s);
+        else launch_up_bf16(L, x, T, witem, wfirst, alist, H, s);
         const long long max_sparse = down_max_pairs_sparse(L, T);
         // both are launched and the pair count on the device decides, unless the limit already does
         if (max_sparse > 0)
@@ -616,7 +638,8 @@ int32_t dmoe_forward_group(const dmoe_layer* const* layers, int32_t n_layers, co
     char* ws = static_cast<char*>(workspace);
     hipStream_t s = (hipStream_t)stream;
     const dmoe_layer& L0 = *layers[0];
-    bool fused = use_small_path(L0, n_tokens);
+    // (layers with 8-bit inputs quantise x per layer call: they take the layer-by-layer route)
+    bool fused = use_small_path(L0, n_tokens) && !acts_fp8(L0);
     for (int i = 0; i < n_layers; ++i) fused = fused && router_fused_scores_supported(*layers[i]);
     if (!fused) {  // larger batches: one layer after the other, each in its share of the workspace
         for (int i = 0; i < n_layers; ++i) {

@@ -41,6 +41,15 @@ inline size_t h_fragments(const dmoe_layer& L, int T) {
     return ((size_t)T * L.n_experts + (size_t)L.n_experts * up_rows_bf16(L)) / 16 + 4;
 }
 
+// 8-bit expert weights (both 8-bit formats); 8-bit expert inputs as well.
+inline bool weights_fp8(const dmoe_layer& L) {
+    return L.weight_format == DMOE_W_FP8_E4M3 || L.weight_format == DMOE_W_FP8_E4M3_X8;
+}
+inline bool acts_fp8(const dmoe_layer& L) { return L.weight_format == DMOE_W_FP8_E4M3_X8; }
+// ... and whether the 8-bit matrix-core up-projection covers the shape (the 256-row work items of
+// the wide-expert kernel); other shapes run the bf16 kernels on the quantised input.
+inline bool up_x8_supported(const dmoe_layer& L) { return acts_fp8(L) && up_rows_bf16(L) == 256; }
+
 // Experts that fit ONE 16-row weight tile -- at most 16 neurons, or gated with at most 8 (up rows
 // and gate rows together) -- take the up-projection kernel built around that tile.
 inline bool up_tiny_supported(const dmoe_layer& L) {
@@ -49,7 +58,7 @@ inline bool up_tiny_supported(const dmoe_layer& L) {
 
 // Sub-buffers of the packed-weights buffer (bytes from its start).
 struct PackedLayout {
-    size_t w2f, w2g, wupf, wgatef, r1f, r2f, w2f8, wupf8, wgatef8, wtinyf, scales, total;
+    size_t w2f, w2g, wupf, wgatef, r1f, r2f, w2f8, wupf8, wgatef8, wtinyf, scales, wupx8, wgatex8, total;
 };
 inline PackedLayout packed_layout(const dmoe_layer& L) {
     PackedLayout P{};
@@ -74,7 +83,7 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
     // 8-bit expert weights: the same fragments with one byte per weight for the small-token
     // kernels (w2f8, wupf8, wgatef8: half of `one` each)
     P.w2f8 = P.wupf8 = P.wgatef8 = o;
-    if (L.weight_format == DMOE_W_FP8_E4M3) {
+    if (weights_fp8(L)) {
         const size_t half = (one / 2 + 255) / 256 * 256;
         P.w2f8 = o;
         P.wupf8 = o + half;
@@ -88,7 +97,16 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
     // 8-bit weights: the caller's scales snapped to powers of two, [E][3] fp32 -- the copy every
     // kernel uses, so that all paths compute the same layer whatever the caller passed
     P.scales = o;
-    if (L.weight_format == DMOE_W_FP8_E4M3) o += (sizeof(float) * 3 * (size_t)L.n_experts + 255) / 256 * 256;
+    if (weights_fp8(L)) o += (sizeof(float) * 3 * (size_t)L.n_experts + 255) / 256 * 256;
+    // 8-bit inputs: the up (and gate) matrices as operands of the 16x16x128 8-bit MFMA,
+    // wupx8[E][m_pad/16][d/128][64][32] (ffn_x8.hip), one byte per weight
+    P.wupx8 = P.wgatex8 = o;
+    if (up_x8_supported(L)) {
+        const size_t half = (one / 2 + 255) / 256 * 256;
+        P.wupx8 = o;
+        P.wgatex8 = o + half;
+        o += (L.gated ? 2 : 1) * half;
+    }
     P.total = o;
     return P;
 }
@@ -108,6 +126,7 @@ enum Slot {
     kSlotSmallDown,
     kSlotSmallFinish,
     kSlotPack,
+    kSlotQuantX,
     kSlotCount
 };
 
@@ -253,6 +272,17 @@ void launch_down_rmw_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
                           const int32_t* group_off, const int32_t* alist, const int32_t* offsets,
                           const void* H, void* y, long long max_pairs_sparse, hipStream_t s);
 long long down_max_pairs_sparse(const dmoe_layer& L, int T);
+
+// ---- 8-bit expert inputs (ffn_x8.hip) -------------------------------------------------------------
+// Row-wise quantisation of x (see DMOE_W_FP8_E4M3_X8 in dmoe.h): x8[T][d] E4M3 codes, xscale[T]
+// the power-of-two scales, xhat[T][d] (nullable) the quantised rows as bf16 numbers.
+void launch_quantize_x(const dmoe_layer& L, const void* x, int T, uint8_t* x8, float* xscale,
+                       void* xhat, hipStream_t s);
+void launch_pack_x8(const dmoe_layer& L, void* packed, hipStream_t s);
+// Up-projection on 8-bit operands; same work items, lists and H rows as launch_up_bf16.
+void launch_up_x8(const dmoe_layer& L, const uint8_t* x8, const float* xscale, int T,
+                  const int32_t* witem, const int32_t* wfirst, const int32_t* alist, void* H,
+                  hipStream_t s);
 
 bool experts_bf16_supported(const dmoe_layer& L);
 bool router_bf16_supported(const dmoe_layer& L);

@@ -419,11 +419,11 @@ bool down_bf16_addressable(const dmoe_layer& L, int T) {
 void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s) {
     const DownPacking dp = down_packing(L.expert_size);
     // 8-bit weights: the snapped scales that launch_pack_bf16 wrote into the packed buffer
-    const float* scales = L.weight_format == DMOE_W_FP8_E4M3
+    const float* scales = weights_fp8(L)
                               ? (const float*)(static_cast<const char*>(w2g) - packed_layout(L).w2g + packed_layout(L).scales)
                               : nullptr;
     launch_kernel(pack_down32_kernel, 2048, 256, 0, s, L.w_down, scales,
-                                            L.weight_format == DMOE_W_FP8_E4M3, (__bf16*)w2g,
+                                            weights_fp8(L), (__bf16*)w2g,
                                             L.n_experts, L.expert_size, L.d_model, dp.PG, dp.G, dp.KSP);
 }
 

@@ -633,7 +633,7 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
     const PackedLayout P = packed_layout(L);
     const int mp = m_pad_of(L.expert_size);
     char* pk = static_cast<char*>(packed);
-    const int fp8 = L.weight_format == DMOE_W_FP8_E4M3;
+    const int fp8 = weights_fp8(L);
     const int E = L.n_experts, m = L.expert_size, d = L.d_model;
     const float* scales = nullptr;   // the snapped copy inside the packed buffer
     if (fp8) {
@@ -661,6 +661,7 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
             launch_kernel(pack_up_kernel<uint8_t>, 2048, 256, 0, s, L.w_gate, scales, 1, 1,
                                                          (uint8_t*)(pk + P.wgatef8), E, m, d, mp / 16, 1);
     }
+    if (up_x8_supported(L)) launch_pack_x8(L, packed, s);  // operands of the 8-bit up-projection
     // the router matrices use the same fragment format: "one expert" whose rows are the hidden
     // units (r_w1) or the experts (r_w2)
     const int dh = L.router_hidden;

@@ -232,7 +232,7 @@ void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
 template <int MT, bool GATED>
 void launch_up_small_w(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
                        hipStream_t s) {
-    if (L.weight_format == DMOE_W_FP8_E4M3) launch_up_small_t<MT, GATED, true>(L, G, n_layers, x, T, s);
+    if (weights_fp8(L)) launch_up_small_t<MT, GATED, true>(L, G, n_layers, x, T, s);
     else launch_up_small_t<MT, GATED, false>(L, G, n_layers, x, T, s);
 }
 
@@ -273,7 +273,7 @@ void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
     const int ks = mt / 2;
     {
         LaunchTimer tm(kSlotSmallDown, s);
-        const bool w8 = L.weight_format == DMOE_W_FP8_E4M3;
+        const bool w8 = weights_fp8(L);
         if (ks == 1 && !w8) launch_kernel(down_small_kernel<1, false>, grid, 256, 0, s, G, T, d, E, per);
         else if (ks == 2 && !w8) launch_kernel(down_small_kernel<2, false>, grid, 256, 0, s, G, T, d, E, per);
         else if (!w8) launch_kernel(down_small_kernel<4, false>, grid, 256, 0, s, G, T, d, E, per);

@@ -112,7 +112,7 @@ class Workload:
         if tokens:
             cfg = wl.with_tokens(cfg, tokens)
         self.cfg = cfg
-        self.e4m3 = e4m3   # expert matrices stored in 8-bit E4M3 (one byte per weight)
+        self.e4m3 = e4m3 or x8   # expert matrices stored in 8-bit E4M3 (one byte per weight)
         self.layer_np, self.x_np = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
         if e4m3 or x8:
             self.layer_np = wl.quantize_experts_e4m3(self.layer_np)
@@ -167,9 +167,10 @@ class Workload:
             dom = max(kbytes, key=lambda k: kt.get(k, 0.0))
             achieved = kbytes[dom] / (kt[dom] * 1e-3) / 1e9
             both_ms = kt["small_up"] + kt["small_down"]
+            traffic, source = profile_traffic(cfg.name, tau_arg, dom) if (traffic_ok and not self.e4m3) else (None, None)
             roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1),
                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
-                        "traffic": None, "avg_kernel_ms": round(kt[dom], 5),
+                        "traffic": traffic, "traffic_source": source, "avg_kernel_ms": round(kt[dom], 5),
                         "touched_experts": touched,
                         "experts_gbs": round(sum(kbytes.values()) / (both_ms * 1e-3) / 1e9, 1),
                         "weight_copies_rotated": len(self.layers)}
@@ -182,7 +183,7 @@ class Workload:
             # (layers with 8-bit inputs run their up-projection on the fp8 matrix pipe, whose peak
             # is twice this one: their line is context, the bf16 layers are the roofline claim)
             experts_ms = sum(kt.get(k, 0.0) for k in ("expert_up", "expert_down", "expert_down_sparse"))
-            traffic, source = profile_traffic(cfg.name, tau_arg, dom) if traffic_ok else (None, None)
+            traffic, source = profile_traffic(cfg.name, tau_arg, dom) if (traffic_ok and not self.e4m3) else (None, None)
             roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2),
                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(achieved / PEAK_BF16_TFLOPS, 4),

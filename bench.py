@@ -501,7 +501,8 @@ def main() -> int:
         # up-projection of wide experts runs on the fp8 matrix pipe (Appendix C's lower precisions)
         w8 = Workload(args.workload, x8=True)
         rows = []
-        for name, t in [(args.workload, args.tau)] + [o for o in OTHERS if o[0] == args.workload and o[1] != args.tau]:
+        same_layer = [] if args.no_others else [o for o in OTHERS if o[0] == args.workload and o[1] != args.tau]
+        for name, t in [(args.workload, args.tau)] + same_layer:
             r8 = w8.measure(t, 100, 10)
             rows.append({"workload": w8.describe(t), "ms_per_step": round(r8["ms"], 5),
                          "executed_expert_tflops": round(r8["flops"] / (r8["ms"] * 1e-3) / 1e12, 2),

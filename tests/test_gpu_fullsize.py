@@ -103,6 +103,32 @@ def test_full_size_sampled(B, oracle, name, tau, n_sample):
     assert torch.equal(y, y2)
 
 
+def test_full_size_8bit_inputs_every_token(B, oracle):
+    """The Gemma-shaped prefill layer at full size with 8-bit expert weights and 8-bit expert
+    inputs (the fp8 matrix-core up-projection): every token against the oracle's experts on the
+    oracle's quantised rows."""
+    import torch
+    cfg = wl.CONFIGS["cfg4"]
+    print(f"full size cfg4 T={cfg.T} tau=0.3, 8-bit weights and inputs", flush=True)
+    base, x = _layer_and_input(cfg, 0)
+    layer = wl.quantize_experts_e4m3(base)
+    layer["x8"] = True
+    L = B.Layer(layer, cfg.dtype)
+    tau32 = float(np.float32(0.3))
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32, want_scores=True, want_mask=True)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy().astype(np.float64)
+    mask, _ = oracle.select(s, tau32)
+    assert np.array_equal(B.mask_bits_to_bool(ex["mask_bits"], cfg.E), mask)
+    xq, _ = oracle.quantize_rows_e4m3(x)
+    ref = oracle_ffn(oracle, layer, xq, mask)
+    yh = B.from_device(y, cfg.dtype)
+    err = tokenwise_rel_err(yh, ref)
+    print(f"  density={mask.mean():.4f} tokens compared={cfg.T} err={err:.3e} "
+          f"element-wise err={elementwise_rel_err(yh, ref):.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]
+
+
 def test_paper_shape_full_size_bernoulli(B, oracle):
     """The shape of the latency experiment of Sec. 4.4 (24 experts of 128 neurons, d = 768,
     256 x 197 tokens) under Bernoulli(0.5) decisions through dmoe_expert_ffn: four tokens of

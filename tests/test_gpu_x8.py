@@ -99,3 +99,94 @@ def test_forward_with_8bit_inputs(B, oracle, name, T, E):
                            torch.from_numpy(np.concatenate([lst, np.zeros(1, np.int32)])).cuda())
     torch.cuda.synchronize()
     assert tokenwise_rel_err(B.from_device(y2, cfg.dtype), oracle_ffn(oracle, layer, xq, m2)) <= TOL[cfg.dtype]
+
+
+def _oracle_x8(oracle, layer, x, mask):
+    xq, _ = oracle.quantize_rows_e4m3(x)
+    return oracle_ffn(oracle, layer, xq, mask)
+
+
+@pytest.mark.parametrize("name,T,E,k", [("cfg4", 300, 16, 3), ("cfg2", 200, 32, 5), ("cfg5a", 9, 64, 4)])
+def test_top_k_gate_with_8bit_inputs(B, oracle, name, T, E, k):
+    import torch
+    cfg = small_cfg(name, T, E)
+    print(f"8-bit inputs, top-{k} gate, {name} T={T}", flush=True)
+    layer, x = _x8_layer(cfg, 6), wl.make_input(cfg, 6)
+    y, ex = B.dmoe_forward_topk(B.Layer(layer, cfg.dtype), B.to_device(x, cfg.dtype), k,
+                                want_scores=True, want_mask=True)
+    torch.cuda.synchronize()
+    mask = oracle.select_topk(ex["scores"].cpu().numpy().astype(np.float64), k)
+    assert np.array_equal(B.mask_bits_to_bool(ex["mask_bits"], cfg.E), mask)
+    assert tokenwise_rel_err(B.from_device(y, cfg.dtype), _oracle_x8(oracle, layer, x, mask)) <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("name,T,E", [("cfg5b", 16, None), ("cfg5b", 40, None), ("cfg4", 100, 16)])
+def test_group_of_layers_with_8bit_inputs(B, oracle, name, T, E):
+    """Three layers of one shape on one input (Sec. 3.5): the same outputs as three single calls,
+    bit for bit, and the oracle's on its own quantised rows."""
+    import torch
+    cfg = small_cfg(name, T, E)
+    print(f"8-bit inputs, group of 3, {name} T={T}", flush=True)
+    layers = [_x8_layer(cfg, 20 + i) for i in range(3)]
+    Ls = [B.Layer(l, cfg.dtype) for l in layers]
+    x = wl.make_input(cfg, 20)
+    xd = B.to_device(x, cfg.dtype)
+    taus = [float(np.float32(t)) for t in (0.3, 0.5, 0.7)]
+    ys = B.dmoe_forward_group(Ls, xd, taus)
+    torch.cuda.synchronize()
+    for L, layer, tau, y in zip(Ls, layers, taus, ys):
+        y1, ex = B.dmoe_forward(L, xd, tau, want_scores=True)
+        torch.cuda.synchronize()
+        assert torch.equal(y, y1)
+        mask, _ = oracle.select(ex["scores"].cpu().numpy().astype(np.float64), tau)
+        assert tokenwise_rel_err(B.from_device(y, cfg.dtype), _oracle_x8(oracle, layer, x, mask)) <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("T", [1, 15, 16, 17, 63, 64, 65, 257])
+def test_token_counts_around_the_kernel_switches_with_8bit_inputs(B, oracle, T):
+    """16 | 17 tokens is the switch from the small-token kernels to the 8-bit matrix-core
+    up-projection; 64 and 256 are its wavefront and work-item sizes."""
+    import torch
+    cfg = small_cfg("cfg4", T, 16)
+    layer, x = _x8_layer(cfg, 8), wl.make_input(cfg, 8)
+    tau = float(np.float32(0.3))
+    y, ex = B.dmoe_forward(B.Layer(layer, cfg.dtype), B.to_device(x, cfg.dtype), tau, want_scores=True)
+    torch.cuda.synchronize()
+    mask, _ = oracle.select(ex["scores"].cpu().numpy().astype(np.float64), tau)
+    err = tokenwise_rel_err(B.from_device(y, cfg.dtype), _oracle_x8(oracle, layer, x, mask))
+    print(f"8-bit inputs T={T} err={err:.3e}", flush=True)
+    assert err <= TOL[cfg.dtype]
+
+
+def test_no_tokens_with_8bit_inputs(B):
+    import torch
+    cfg = small_cfg("cfg4", 4, 16)
+    L = B.Layer(_x8_layer(cfg, 8), cfg.dtype)
+    y, _ = B.dmoe_forward(L, B.to_device(wl.make_input(cfg, 8)[:0], cfg.dtype), 0.5)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == (0, cfg.d)
+
+
+def test_static_workspace_and_graph_replay_with_8bit_inputs(B):
+    """The row quantiser is one more kernel on the same stream: the static-workspace entry gives
+    the same bits as dmoe_forward, and a captured forward replays like the eager one."""
+    import torch
+    cfg = small_cfg("cfg4", 200, 16)
+    L = B.Layer(_x8_layer(cfg, 9), cfg.dtype)
+    tau = float(np.float32(0.3))
+    xs = [B.to_device(wl.make_input(cfg, 30 + i), cfg.dtype) for i in range(3)]
+    y_ref, _ = B.dmoe_forward(L, xs[0], tau)
+    y_static = B.dmoe_forward_static(L, xs[0], tau)
+    torch.cuda.synchronize()
+    assert torch.equal(y_static, y_ref)
+    x_in, y_graph, y_eager = xs[0].clone(), torch.empty_like(xs[0]), torch.empty_like(xs[0])
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.dmoe_forward(L, x_in, tau, y=y_graph)
+    for i in range(3):
+        x_in.copy_(xs[i])
+        y_graph.zero_()
+        g.replay()
+        B.dmoe_forward(L, xs[i], tau, y=y_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager), f"replay {i}"

@@ -2,7 +2,12 @@
 // reading every touched expert's weights exactly once -- a weight-bandwidth-bound stream.
 //
 //   up_small    one workgroup of sixteen wavefronts per expert; experts nobody selected exit
-//               before touching their weights.  The 16 x rows sit in LDS; wavefront (tile, slice)
+//               before touching their weights.  With the gate folded in (gate_dh > 0) every
+//               workgroup first repeats the second router product and the threshold of Eq. 4 from
+//               the router's hidden rows -- 128 KB of router matrix out of L2 and a handful of
+//               MFMAs per wavefront -- and so knows its own expert's tokens without a gate kernel
+//               in front of it; one extra workgroup writes the scores, the mask and the
+//               per-expert token sets for the kernels and callers that follow.  The 16 x rows sit in LDS; wavefront (tile, slice)
 //               streams a K slice of one neuron tile of the up (and gate) fragments -- 1 KiB
 //               contiguous per load, 8 to 16 loads in flight per wavefront -- the slices are added
 //               through LDS and h (zero for tokens that did not select the expert) goes out as an
@@ -14,6 +19,7 @@
 // colmask[e] (bit j = token j keeps expert e) comes from the gate's ballot transpose.
 #include "dmoe_internal.h"
 #include "mfma.h"
+#include "small_gate.h"
 
 namespace dmoe {
 
@@ -30,32 +36,74 @@ constexpr int kUpSmallWaves = 16;
 // bf16 in registers, and the per-expert power-of-two scales are applied to the fp32 sums.
 template <int MT, bool GATED, bool W8>
 __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
-    const SmallGroup G, const __bf16* __restrict__ x, int T, int d, int m, int act, int KQ) {
+    const SmallGroup G, const __bf16* __restrict__ x, int T, int d, int m, int act, int KQ,
+    int E, int gate_dh) {
     const SmallMod& M = G.m[blockIdx.z];
     const __bf16* __restrict__ wupf = M.wupf;
     const __bf16* __restrict__ wgatef = M.wgatef;
     const __bf16* __restrict__ b_up = M.b_up;
-    const uint64_t* __restrict__ colmask = M.colmask;
     __bf16* __restrict__ Hs = M.Hs;
     constexpr int KS = MT / 2, kThreads = 64 * kUpSmallWaves, BR = GATED ? 2 : 1;
     const int e = blockIdx.x;
-    const uint64_t cm = colmask[e];
-    if (cm == 0ull) return;  // uniform: nobody selected this expert
     extern __shared__ char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, q = lane >> 4, c = lane & 15;
+    const int pieces = d / 8;
+    // With the gate folded in, the first x pieces of every thread are requested before the gate
+    // and parked in LDS after it (the gate's scores use the same LDS).
+    constexpr int kPre = 4;
+    bf16x8 xpre[kPre];
+    auto x_piece = [&](int i) {
+        return load8(x + (size_t)min(i / pieces, T - 1) * d + (i % pieces) * 8);
+    };
+    if (gate_dh > 0 && e < E) {
+#pragma unroll
+        for (int k = 0; k < kPre; ++k)
+            if (tid + k * kThreads < 16 * pieces) xpre[k] = x_piece(tid + k * kThreads);
+    }
+    uint64_t cm;
+    if (gate_dh > 0) {
+        // scores of all experts in LDS, then this expert's column against every token's threshold
+        const int W = (E + 63) >> 6;
+        // (all in the dynamic block: a static array next to a 160 KB dynamic limit is refused)
+        int* s_keep = reinterpret_cast<int*>(smem);                   // [16]
+        uint64_t* mw = reinterpret_cast<uint64_t*>(smem + 64);        // [16][W], output workgroup only
+        float* sc = reinterpret_cast<float*>(mw + 16 * W);            // [16][E]
+        const bool out_wg = e == E;  // the extra workgroup: scores, mask, token sets to memory
+        small_scores_to_lds(M, T, gate_dh, E, sc, out_wg);
+        __syncthreads();
+        if (out_wg) {
+            select_small_body(sc, mw, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
+            return;
+        }
+        const int t = threadIdx.x >> 6;  // wavefront t = token t
+        bool keep = false;
+        if (t < T) keep = small_keeps(sc[(size_t)t * E + e], M.tau, small_row_max(sc + (size_t)t * E, E));
+        if ((threadIdx.x & 63) == 0) s_keep[t] = keep ? 1 : 0;
+        __syncthreads();
+        cm = __ballot((threadIdx.x & 63) < 16 && s_keep[threadIdx.x & 15] != 0) & 0xffffull;
+        __syncthreads();  // the score rows make way for the x rows
+    } else {
+        cm = M.colmask[e];
+    }
+    if (cm == 0ull) return;  // uniform: nobody selected this expert
     const int row_bytes = 2 * d + 16;
     char* xs = smem;                                                    // [16][2d + 16]
     // [16 waves][BR][64][4] partial sums: they take the place of the x rows once every wavefront
     // has finished reading those
     float* red = reinterpret_cast<float*>(smem);
-    const int tid = threadIdx.x, lane = tid & 63, q = lane >> 4, c = lane & 15;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mt = w % MT, kq = w / MT;
-    const int pieces = d / 8;
-    for (int i = tid; i < 16 * pieces; i += kThreads) {
-        const int row = i / pieces, piece = i % pieces;
-        *reinterpret_cast<bf16x8*>(xs + row * row_bytes + piece * 16) =
-            load8(x + (size_t)min(row, T - 1) * d + piece * 8);
+    auto x_park = [&](int i, bf16x8 v) {
+        *reinterpret_cast<bf16x8*>(xs + (i / pieces) * row_bytes + (i % pieces) * 16) = v;
+    };
+    int i_first = tid;
+    if (gate_dh > 0) {
+#pragma unroll
+        for (int k = 0; k < kPre; ++k)
+            if (tid + k * kThreads < 16 * pieces) x_park(tid + k * kThreads, xpre[k]);
+        i_first = tid + kPre * kThreads;
     }
+    for (int i = i_first; i < 16 * pieces; i += kThreads) x_park(i, x_piece(i));
     __syncthreads();
 
     const int NK32 = d / 32, per = NK32 / KQ;  // k-steps per slice (KQ divides NK32)
@@ -214,9 +262,11 @@ __global__ void finish_small_kernel(const SmallGroup G, int T, int d, int EG) {
 
 template <int MT, bool GATED, bool W8>
 void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
-                       hipStream_t s) {
-    const size_t lds = std::max(16 * (2 * (size_t)L.d_model + 16),
-                                sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4);
+                       bool gate, hipStream_t s) {
+    const int E = L.n_experts;
+    size_t lds = std::max(16 * (2 * (size_t)L.d_model + 16),
+                          sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4);
+    if (gate) lds = std::max(lds, 64 + sizeof(uint64_t) * 16 * div_up(E, 64) + sizeof(float) * 16 * (size_t)E);
     static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
     std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_small_kernel<MT, GATED, W8>),
@@ -225,15 +275,16 @@ void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
     // K slices: as many as the sixteen wavefronts allow and the k-steps divide into
     int KQ = kUpSmallWaves / MT;
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
-    launch_kernel(up_small_kernel<MT, GATED, W8>, dim3(L.n_experts, 1, n_layers), 64 * kUpSmallWaves, lds, s, 
-        G, (const __bf16*)x, T, L.d_model, L.expert_size, L.act, KQ);
+    launch_kernel(up_small_kernel<MT, GATED, W8>, dim3(E + (gate ? 1 : 0), 1, n_layers),
+                  64 * kUpSmallWaves, lds, s, G, (const __bf16*)x, T, L.d_model, L.expert_size, L.act,
+                  KQ, E, gate ? L.router_hidden : 0);
 }
 
 template <int MT, bool GATED>
 void launch_up_small_w(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
-                       hipStream_t s) {
-    if (weights_fp8(L)) launch_up_small_t<MT, GATED, true>(L, G, n_layers, x, T, s);
-    else launch_up_small_t<MT, GATED, false>(L, G, n_layers, x, T, s);
+                       bool gate, hipStream_t s) {
+    if (weights_fp8(L)) launch_up_small_t<MT, GATED, true>(L, G, n_layers, x, T, gate, s);
+    else launch_up_small_t<MT, GATED, false>(L, G, n_layers, x, T, gate, s);
 }
 
 }  // namespace
@@ -248,18 +299,18 @@ bool small_bf16_supported(const dmoe_layer& L) {
 }
 
 void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
-                       hipStream_t s) {
+                       bool gate, hipStream_t s) {
     const int mt = m_pad_of(L.expert_size) / 16;
     {
         LaunchTimer tm(kSlotSmallUp, s);
         if (L.gated) {
-            if (mt == 2) launch_up_small_w<2, true>(L, G, n_layers, x, T, s);
-            else if (mt == 4) launch_up_small_w<4, true>(L, G, n_layers, x, T, s);
-            else launch_up_small_w<8, true>(L, G, n_layers, x, T, s);
+            if (mt == 2) launch_up_small_w<2, true>(L, G, n_layers, x, T, gate, s);
+            else if (mt == 4) launch_up_small_w<4, true>(L, G, n_layers, x, T, gate, s);
+            else launch_up_small_w<8, true>(L, G, n_layers, x, T, gate, s);
         } else {
-            if (mt == 2) launch_up_small_w<2, false>(L, G, n_layers, x, T, s);
-            else if (mt == 4) launch_up_small_w<4, false>(L, G, n_layers, x, T, s);
-            else launch_up_small_w<8, false>(L, G, n_layers, x, T, s);
+            if (mt == 2) launch_up_small_w<2, false>(L, G, n_layers, x, T, gate, s);
+            else if (mt == 4) launch_up_small_w<4, false>(L, G, n_layers, x, T, gate, s);
+            else launch_up_small_w<8, false>(L, G, n_layers, x, T, gate, s);
         }
     }
     // expert groups: enough workgroups to fill the chip, at most kSmallMaxGroups partial sums

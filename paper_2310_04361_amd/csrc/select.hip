@@ -9,6 +9,7 @@
 // transpose between "experts of a token" and "tokens of an expert" is done with ballots.
 #include "dmoe_internal.h"
 #include "mfma.h"
+#include "small_gate.h"
 
 namespace dmoe {
 
@@ -149,89 +150,35 @@ __global__ __launch_bounds__(256) void topk_mask_kernel(const float* __restrict_
     if (lane == 0 && k_per_token) k_per_token[t] = kt;
 }
 
-// T <= 16: one workgroup, wavefront t = token t with lanes striding the experts, so the score row
-// is read coalesced, the maximum is a wavefront reduction and a ballot IS a mask word.  The
-// transpose to per-expert token sets (colmask) and counts then goes through LDS.
-__device__ __forceinline__ void select_small_body(const float* __restrict__ scores,
-                                                  uint64_t* __restrict__ mask,
-                                                  int32_t* __restrict__ k_per_token,
-                                                  int32_t* __restrict__ group_cnt,
-                                                  uint64_t* __restrict__ colmask, int T, int E,
-                                                  int W, float tau) {
-    extern __shared__ uint64_t mw[];  // [16][W]
-    const int lane = lane_id(), t = threadIdx.x >> 6;
-    if (t < T) {
-        const float* row = scores + (size_t)t * E;
-        float mx = -INFINITY;
-        for (int e = lane; e < E; e += kWave) mx = fmaxf(mx, row[e]);
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, kWave));
-        const double thr = (double)tau * (double)mx;  // exact, see tau_mask_kernel
-        int kt = 0;
-        for (int w = 0; w < W; ++w) {
-            const int e = 64 * w + lane;
-            const bool keep = e < E && (tau == 0.0f || (double)row[e] >= thr);
-            const uint64_t word = __ballot(keep);
-            kt += __popcll(word);
-            if (lane == 0) {
-                mw[t * W + w] = word;
-                mask[(size_t)t * W + w] = word;
-            }
-        }
-        if (lane == 0 && k_per_token) k_per_token[t] = kt;
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < E; e += 1024) {
-        uint64_t col = 0;
-        for (int tt = 0; tt < T; ++tt) col |= ((mw[tt * W + (e >> 6)] >> (e & 63)) & 1ull) << tt;
-        group_cnt[e] = __popcll(col);
-        if (colmask) colmask[e] = col;
-    }
-}
-
 __global__ __launch_bounds__(1024) void select_small_kernel(const float* __restrict__ scores,
                                                             uint64_t* __restrict__ mask,
                                                             int32_t* __restrict__ k_per_token,
                                                             int32_t* __restrict__ group_cnt,
                                                             uint64_t* __restrict__ colmask, int T,
                                                             int E, int W, float tau) {
-    select_small_body(scores, mask, k_per_token, group_cnt, colmask, T, E, W, tau);
+    extern __shared__ uint64_t mw[];  // [16][W]
+    select_small_body(scores, mw, mask, k_per_token, group_cnt, colmask, T, E, W, tau);
 }
 
-// Second router product and the gate in one workgroup per layer (T <= 16, E <= 1024): wavefront
-// w multiplies the expert tiles w, w + 16, ... (s = |R2 hid + c2|, Sec. 3.3), the scores go to
-// global memory and to LDS, and after one barrier the gate above runs on the LDS copy.  One
+// Second router product and the gate in one workgroup per layer (T <= 16, E <= 1024): the scores
+// go to global memory and to LDS, and after one barrier the gate runs on the LDS copy.  One
 // launch less than scores + gate, which is what counts at this size.
 __global__ __launch_bounds__(1024) void router_scores_select_small_kernel(const SmallGroup G, int T,
                                                                           int dh, int E, int W) {
     extern __shared__ uint64_t mw[];  // [16][W] mask words, then [16][E] fp32 scores
     const SmallMod& M = G.m[blockIdx.z];
     float* sc = reinterpret_cast<float*>(mw + 16 * W);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, q = lane >> 4, c = lane & 15;
-    const int KS2 = dh / 32, NE = (E + 15) >> 4;
-    const __bf16* hb = M.hid + (size_t)c * dh + 8 * q;
-    for (int et = w; et < NE; et += 16) {
-        const __bf16* af = M.r2f + (((size_t)et * KS2) * 64 + lane) * 8;
-        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-        for (int ks = 0; ks < KS2; ++ks)
-            acc = mfma16(load8(af + (size_t)ks * 512), load8(hb + 32 * ks), acc);
-        const int e0 = 16 * et + 4 * q;  // lane (q, c): experts e0 .. e0+3 of token c
-        if (c < T && e0 < E) {
-            const float4 out = router_scores4(acc, M.r_b2, e0, E);
-            store_scores4(M.scores + (size_t)c * E, e0, E, out);
-            store_scores4(sc + (size_t)c * E, e0, E, out);
-        }
-    }
+    small_scores_to_lds(M, T, dh, E, sc, true);
     __syncthreads();
-    select_small_body(sc, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
+    select_small_body(sc, mw, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
 }
 
 // the same gate for every layer of a group (blockIdx.z = layer), each with its own tau
 __global__ __launch_bounds__(1024) void select_small_group_kernel(const SmallGroup G, int T, int E,
                                                                   int W) {
+    extern __shared__ uint64_t mw[];  // [16][W]
     const SmallMod& M = G.m[blockIdx.z];
-    select_small_body(M.scores, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
+    select_small_body(M.scores, mw, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
 }
 
 __global__ void zero_u64_kernel(uint64_t* p, size_t n) {
@@ -489,8 +436,7 @@ void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_l
 
 void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
                                 const void* x, int T, hipStream_t s) {
-    // first product: the many-workgroup hidden kernel of the plain small router (the scores
-    // kernel it launches as well is replaced by the fused one below)
+    // first product: the many-workgroup hidden kernel; second product + gate: one workgroup
     const int E = L.n_experts, W = div_up(E, 64);
     launch_router_small_hidden(L, G, n_layers, x, T, s);
     LaunchTimer tm(kSlotMask, s);

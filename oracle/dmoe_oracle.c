@@ -26,7 +26,8 @@
  *               them must reproduce it.
  *
  *   quantize    Appendix C (lower-precision layers): row-wise 8-bit floating-point quantisation
- *               of the experts' input.  The format is a published one and pins the rounding; the
+ *               of the experts' input and, in the fully 8-bit reading, of every selected
+ *               expert's hidden activations (dmoe_oracle_expert_ffn_q8h).  The format is a published one and pins the rounding; the
  *               scale rule is this build's reading (the paper gives none): "parity unpinned by
  *               the paper" for the rule itself, pinned against the format definition and an
  *               independent converter for the arithmetic.
@@ -253,5 +254,80 @@ int dmoe_oracle_quantize_rows_e4m3(const double *x, int T, int d, double *xq, do
         scales[t] = s;
         for (int j = 0; j < d; ++j) xq[(size_t)t * d + j] = s * e4m3_nearest(x[(size_t)t * d + j] / s);
     }
+    return 0;
+}
+
+/*
+ * Nearest bfloat16 number (8 significant bits, fp32 exponent range), ties to the even mantissa:
+ * the storage format the hidden activations pass through in the 16-bit layers.
+ */
+static double bf16_nearest(double v) {
+    if (v == 0.0 || !isfinite(v)) return v;
+    int e;
+    (void)frexp(v, &e);                 /* |v| = f * 2^e, f in [0.5, 1) */
+    int q = e - 8;                      /* exponent of the last kept bit */
+    if (q < -133) q = -133;             /* subnormal range of the format */
+    return ldexp(nearbyint(ldexp(v, -q)), q);
+}
+
+/*
+ * Expert execution with 8-bit hidden activations (the fully 8-bit reading of Appendix C's
+ * lower-precision layers; the paper gives no rule, this one is stated in the library's header):
+ * as dmoe_oracle_expert_ffn, but the m hidden activations of every selected (token, expert) pair
+ * are first rounded to bfloat16 (the format they are stored in) and then quantised as a row by
+ * the rule of dmoe_oracle_quantize_rows_e4m3 before they meet W_down.  x is taken as given (the
+ * caller passes the quantised input rows).
+ */
+int dmoe_oracle_expert_ffn_q8h(const double *x, const double *w_up, const double *w_gate,
+                               const double *b_up, const double *w_down, const double *b_down,
+                               int T, int d, int E, int m, int gated, int act,
+                               const uint8_t *mask, double *y) {
+    if (!x || !w_up || !w_down || !mask || !y || T < 0 || d <= 0 || E <= 0 || m <= 0) return 1;
+    if (gated && !w_gate) return 1;
+    if (gated && b_up) return 3;
+    if (act < 0 || act > 2) return 3;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int t = 0; t < T; ++t) {
+        const double *xt = x + (size_t)t * d;
+        double *yt = y + (size_t)t * d;
+        double *h = (double *)malloc(sizeof(double) * 2 * (size_t)m);
+        if (!h) {
+            failed = 1;
+            continue;
+        }
+        double *hq = h + m, scale;
+        for (int c = 0; c < d; ++c) yt[c] = b_down ? b_down[c] : 0.0;
+        for (int e = 0; e < E; ++e) {
+            if (!mask[(size_t)t * E + e]) continue;
+            for (int j = 0; j < m; ++j) {
+                size_t row = ((size_t)e * m + j) * d;
+                if (gated) {
+                    double g = 0.0, u = 0.0;
+                    for (int k = 0; k < d; ++k) g += w_gate[row + k] * xt[k];
+                    for (int k = 0; k < d; ++k) u += w_up[row + k] * xt[k];
+                    h[j] = activation(act, g) * u;
+                } else {
+                    double a = b_up ? b_up[(size_t)e * m + j] : 0.0;
+                    for (int k = 0; k < d; ++k) a += w_up[row + k] * xt[k];
+                    h[j] = activation(act, a);
+                }
+                h[j] = bf16_nearest(h[j]);
+            }
+            dmoe_oracle_quantize_rows_e4m3(h, 1, m, hq, &scale);
+            for (int j = 0; j < m; ++j) {
+                size_t row = ((size_t)e * m + j) * d;
+                for (int c = 0; c < d; ++c) yt[c] += hq[j] * w_down[row + c];
+            }
+        }
+        free(h);
+    }
+    return failed;
+}
+
+/* Exposed for its pin (an independent converter). */
+int dmoe_oracle_round_bf16(const double *v, size_t n, double *out) {
+    if (!v || !out) return 1;
+    for (size_t i = 0; i < n; ++i) out[i] = bf16_nearest(v[i]);
     return 0;
 }

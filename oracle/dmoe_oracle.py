@@ -54,6 +54,10 @@ def _load():
                                                u8p, dp]
         lib.dmoe_oracle_quantize_rows_e4m3.argtypes = [dp, ci, ci, dp, dp]
         lib.dmoe_oracle_quantize_rows_e4m3.restype = ci
+        lib.dmoe_oracle_expert_ffn_q8h.argtypes = lib.dmoe_oracle_expert_ffn.argtypes
+        lib.dmoe_oracle_expert_ffn_q8h.restype = ci
+        lib.dmoe_oracle_round_bf16.argtypes = [dp, ctypes.c_size_t, dp]
+        lib.dmoe_oracle_round_bf16.restype = ci
         for f in (lib.dmoe_oracle_router, lib.dmoe_oracle_select, lib.dmoe_oracle_select_topk,
                   lib.dmoe_oracle_bucket, lib.dmoe_oracle_expert_ffn):
             f.restype = ci
@@ -143,11 +147,13 @@ def bucket(mask):
     return counts, offsets, lists[: int(offsets[E])].copy()
 
 
-def expert_ffn(x, w_up, w_gate, b_up, w_down, b_down, mask, act, gated=False):
+def expert_ffn(x, w_up, w_gate, b_up, w_down, b_down, mask, act, gated=False, quantize_h=False):
     """y[T, d] = b_down + sum of the selected experts' outputs (Sec. 3.2, Appendix G).
 
     w_up / w_gate / w_down are expert-major [E, m, d]; b_up [E, m] or None; b_down [d] or None;
-    mask [T, E] of 0/1; act is an ACT_* code or its name."""
+    mask [T, E] of 0/1; act is an ACT_* code or its name.  quantize_h: every selected
+    (token, expert) row of hidden activations is rounded to bfloat16 and then quantised to E4M3
+    with a power-of-two row scale before the down-projection (the fully 8-bit layers)."""
     if isinstance(act, str):
         act = ACT_BY_NAME[act]
     x = _f64(x)
@@ -163,13 +169,22 @@ def expert_ffn(x, w_up, w_gate, b_up, w_down, b_down, mask, act, gated=False):
     if mask.shape != (T, E):
         raise ValueError(f"mask must be {(T, E)}, got {mask.shape}")
     y = np.empty((T, d), dtype=np.float64)
-    rc = _load().dmoe_oracle_expert_ffn(_dp(x), _dp(w_up), _dp(w_gate), _dp(b_up), _dp(w_down),
-                                        _dp(b_down), T, d, E, m, 1 if gated else 0, int(act),
-                                        mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
-                                        _dp(y))
+    fn = _load().dmoe_oracle_expert_ffn_q8h if quantize_h else _load().dmoe_oracle_expert_ffn
+    rc = fn(_dp(x), _dp(w_up), _dp(w_gate), _dp(b_up), _dp(w_down), _dp(b_down), T, d, E, m,
+            1 if gated else 0, int(act), mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), _dp(y))
     if rc:
         raise RuntimeError(f"dmoe_oracle_expert_ffn failed: {rc}")
     return y
+
+
+def round_bf16(v):
+    """Nearest bfloat16 numbers (ties to even) of an array, as fp64."""
+    v = _f64(v)
+    out = np.empty_like(v)
+    rc = _load().dmoe_oracle_round_bf16(_dp(v), ctypes.c_size_t(v.size), _dp(out))
+    if rc:
+        raise RuntimeError(f"dmoe_oracle_round_bf16 failed: {rc}")
+    return out
 
 
 def quantize_rows_e4m3(x):

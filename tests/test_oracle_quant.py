@@ -81,3 +81,85 @@ def test_against_an_independent_converter_and_the_half_step_bound(oracle):
     err = np.abs(xq - x)
     bound = np.maximum(np.abs(x) * 2.0 ** -4, s[:, None] * 2.0 ** -10)
     assert (err <= bound).all()
+
+
+# ---- 8-bit hidden activations (oracle.expert_ffn(..., quantize_h=True)) ---------------------------
+
+def test_bf16_rounding_against_an_independent_converter_and_ties(oracle):
+    import torch
+    rng = np.random.default_rng(7)
+    v = np.concatenate([rng.standard_normal(4000) * np.exp(rng.normal(0, 6, 4000)), [0.0, -0.0]])
+    got = oracle.round_bf16(v)
+    ref = torch.from_numpy(v.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    # (the fp32 step in between cannot move a value across a bf16 midpoint unless it sits within
+    # 2^-16 of it: none of these draws does)
+    assert np.array_equal(got, ref)
+    # exact ties: 1 + 2^-8 lies half-way between 1 and 1 + 2^-7 (mantissa 0000000 is even);
+    # 1 + 3 * 2^-8 half-way between 1 + 2^-7 (odd) and 1 + 2^-6 (even)
+    assert oracle.round_bf16(np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, -(1 + 2.0 ** -8)])).tolist() == \
+        [1.0, 1 + 2.0 ** -6, -1.0]
+
+
+def _relu_layer(w_up, w_down):
+    return dict(w_up=np.asarray(w_up, float), w_gate=None, b_up=None, w_down=np.asarray(w_down, float),
+                b_down=None, act="relu", gated=False)
+
+
+def _ffn(oracle, layer, x, mask, quantize_h):
+    return oracle.expert_ffn(x, layer["w_up"], layer["w_gate"], layer["b_up"], layer["w_down"],
+                             layer["b_down"], mask, layer["act"], layer["gated"], quantize_h=quantize_h)
+
+
+def test_hidden_rows_of_small_integers_pass_unchanged(oracle):
+    """Integers up to 15 have four significant bits: whatever power-of-two scale the row gets,
+    they are E4M3 numbers, so the 8-bit-hidden result equals the plain one exactly."""
+    rng = np.random.default_rng(1)
+    E, m, d, T = 3, 5, 4, 7
+    w_up = rng.integers(-2, 3, size=(E, m, d))
+    x = rng.integers(0, 2, size=(T, d)).astype(float)       # h = relu(w x): integers in 0 .. 8
+    w_down = rng.standard_normal((E, m, d))
+    mask = rng.integers(0, 2, size=(T, E)).astype(np.uint8)
+    layer = _relu_layer(w_up, w_down)
+    assert np.array_equal(_ffn(oracle, layer, x, mask, True), _ffn(oracle, layer, x, mask, False))
+
+
+def test_hand_worked_hidden_row(oracle):
+    """One token, one expert of two neurons with h = (17, 1): the row maximum 17 gives the scale
+    2^-4 (17 / 448 = 0.038 needs 2^-4), 17 / 2^-4 = 272 lies half-way between the E4M3 numbers
+    256 and 288 and goes to the even mantissa, 256, so the 17 becomes 16; the 1 stays.
+    y = 16 * w_down[0] + 1 * w_down[1]."""
+    layer = _relu_layer([[[17.0, 0.0], [0.0, 1.0]]], [[[1.0, 10.0], [100.0, 1000.0]]])
+    x = np.array([[1.0, 1.0]])
+    mask = np.ones((1, 1), np.uint8)
+    assert _ffn(oracle, layer, x, mask, False).tolist() == [[17.0 + 100.0, 170.0 + 1000.0]]
+    assert _ffn(oracle, layer, x, mask, True).tolist() == [[16.0 + 100.0, 160.0 + 1000.0]]
+    # ... and an unselected expert contributes nothing, quantised or not
+    assert _ffn(oracle, layer, x, np.zeros((1, 1), np.uint8), True).tolist() == [[0.0, 0.0]]
+
+
+def test_recomposed_from_the_pinned_pieces(oracle):
+    """Gated GELU experts: hidden rows by NumPy and torch, rounded to bf16 by torch, quantised
+    by the (pinned) row quantiser, multiplied out by NumPy -- the same result as the oracle's
+    one-call path."""
+    import torch
+    rng = np.random.default_rng(3)
+    E, m, d, T = 4, 6, 16, 9
+    w_up, w_gate, w_down = (rng.standard_normal((E, m, d)) for _ in range(3))
+    x = rng.standard_normal((T, d))
+    mask = rng.integers(0, 2, size=(T, E)).astype(np.uint8)
+    mask[0] = 1
+    got = oracle.expert_ffn(x, w_up, w_gate, None, w_down, None, mask, "gelu_tanh", True, quantize_h=True)
+    ref = np.zeros((T, d))
+    for t in range(T):
+        for e in range(E):
+            if not mask[t, e]:
+                continue
+            g = torch.nn.functional.gelu(torch.from_numpy(w_gate[e] @ x[t]), approximate="tanh").numpy()
+            h = g * (w_up[e] @ x[t])
+            h16 = torch.from_numpy(h.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+            hq, _ = oracle.quantize_rows_e4m3(h16[None, :])
+            ref[t] += hq[0] @ w_down[e]
+    assert np.allclose(got, ref, rtol=0, atol=1e-12 * np.abs(ref).max())
+    # the quantisation is visible against the unquantised layer
+    plain = oracle.expert_ffn(x, w_up, w_gate, None, w_down, None, mask, "gelu_tanh", True)
+    assert np.abs(got - plain).max() > 1e-3 * np.abs(plain).max()

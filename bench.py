@@ -105,19 +105,22 @@ def achieved_peaks():
 class Workload:
     """One layer + its rotated inputs on the device."""
 
-    def __init__(self, name, tokens=0, e4m3=False, x8=False):
+    def __init__(self, name, tokens=0, e4m3=False, x8=False, a8=False):
         import torch
         from paper_2310_04361_amd import binding as B, workloads as wl
         cfg = wl.CONFIGS[name]
         if tokens:
             cfg = wl.with_tokens(cfg, tokens)
         self.cfg = cfg
+        x8 = x8 or a8
         self.e4m3 = e4m3 or x8   # expert matrices stored in 8-bit E4M3 (one byte per weight)
         self.layer_np, self.x_np = wl.make_layer(cfg, 0), wl.make_input(cfg, 0)
         if e4m3 or x8:
             self.layer_np = wl.quantize_experts_e4m3(self.layer_np)
         if x8:   # ... and the experts' input quantised row-wise to E4M3 as well
             self.layer_np["x8"] = True
+        if a8:   # ... and every row of hidden activations too
+            self.layer_np["a8"] = True
         self.decode = cfg.T <= 16
         n_layers = N_LAYER_COPIES_DECODE if self.decode else 1
         self.layers = [B.Layer(self.layer_np, cfg.dtype) for _ in range(n_layers)]
@@ -499,18 +502,25 @@ def main() -> int:
     if (not args.no_others or args.x8) and not args.tokens and cfg.dtype == "bf16":
         # the same layer with 8-bit expert weights and 8-bit (row-wise E4M3) expert inputs: the
         # up-projection of wide experts runs on the fp8 matrix pipe (Appendix C's lower precisions)
-        w8 = Workload(args.workload, x8=True)
-        rows = []
         same_layer = [] if args.no_others else [o for o in OTHERS if o[0] == args.workload and o[1] != args.tau]
-        for name, t in [(args.workload, args.tau)] + same_layer:
-            r8 = w8.measure(t, 100, 10)
-            rows.append({"workload": w8.describe(t), "ms_per_step": round(r8["ms"], 5),
-                         "executed_expert_tflops": round(r8["flops"] / (r8["ms"] * 1e-3) / 1e12, 2),
-                         "kernel_ms": r8["kernel_ms"]})
-        out["fp8_inputs_and_weights"] = {"note": "weight_format DMOE_W_FP8_E4M3_X8: same shapes, a "
-                                         "different (lower) precision -- not the bf16 headline", "rows": rows}
-        del w8
-        torch.cuda.empty_cache()
+        for key, kw, note in [
+                ("fp8_inputs_and_weights", {"x8": True},
+                 "weight_format DMOE_W_FP8_E4M3_X8 (8-bit expert weights and inputs, bf16 hidden "
+                 "activations): same shapes, a different (lower) precision -- not the bf16 headline"),
+                ("fp8_fully_8bit", {"a8": True},
+                 "weight_format DMOE_W_FP8_E4M3_A8 (8-bit expert weights, inputs and hidden "
+                 "activations: both expert products on the fp8 matrix pipe): same shapes, a "
+                 "different (lower) precision -- not the bf16 headline")]:
+            w8 = Workload(args.workload, **kw)
+            rows = []
+            for name, t in [(args.workload, args.tau)] + same_layer:
+                r8 = w8.measure(t, 100, 10)
+                rows.append({"workload": w8.describe(t), "ms_per_step": round(r8["ms"], 5),
+                             "executed_expert_tflops": round(r8["flops"] / (r8["ms"] * 1e-3) / 1e12, 2),
+                             "kernel_ms": r8["kernel_ms"]})
+            out[key] = {"note": note, "rows": rows}
+            del w8
+            torch.cuda.empty_cache()
 
     curves = not args.no_curves
     if curves and not args.tokens:

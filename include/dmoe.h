@@ -56,7 +56,7 @@ typedef enum {
 
 enum { DMOE_F32 = 0, DMOE_BF16 = 1 };
 /* storage of the expert matrices w_up, w_gate, w_down (dmoe_layer.weight_format) */
-enum { DMOE_W_NATIVE = 0, DMOE_W_FP8_E4M3 = 1, DMOE_W_FP8_E4M3_X8 = 2 };
+enum { DMOE_W_NATIVE = 0, DMOE_W_FP8_E4M3 = 1, DMOE_W_FP8_E4M3_X8 = 2, DMOE_W_FP8_E4M3_A8 = 3 };
 enum { DMOE_ACT_RELU = 0, DMOE_ACT_GELU_ERF = 1, DMOE_ACT_GELU_TANH = 2 };
 
 /*
@@ -73,11 +73,11 @@ typedef struct {
     int32_t gated;         /* 0 plain two-layer FFN, 1 gated (GLU) FFN */
     int32_t act;           /* DMOE_ACT_* */
     int32_t dtype;         /* DMOE_F32 | DMOE_BF16: x, y and every parameter */
-    int32_t weight_format; /* DMOE_W_NATIVE: expert matrices in `dtype`; DMOE_W_FP8_E4M3: see below */
+    int32_t weight_format; /* DMOE_W_NATIVE: expert matrices in `dtype`; DMOE_W_FP8_E4M3*: see below */
     const void *w_up, *w_gate, *b_up, *w_down, *b_down;
     const void *r_w1, *r_b1, *r_w2, *r_b2;
     const void *packed;
-    const float *w_scales; /* DMOE_W_FP8_E4M3 only: [E][3] fp32, see below; else ignored */
+    const float *w_scales; /* DMOE_W_FP8_E4M3*: [E][3] fp32, see below; else ignored */
 } dmoe_layer;
 
 /*
@@ -104,12 +104,23 @@ typedef struct {
  *                                   its exponent is clamped to -100 .. 100),
  * where e4m3(.) rounds to the nearest E4M3 value, ties to the even mantissa (the largest
  * element of a row lands in (224, 448], so nothing overflows; magnitudes below 2^-10 s_t become
- * zero).  Every xq element is a bf16 number, and every product of an 8-bit weight and an 8-bit
- * input is exact in fp32, so the layer computes -- up to the order of the fp32 additions -- what
- * a bf16 layer with the same weights computes on the input xq; the hidden activations and the
- * down-projection are as in DMOE_W_FP8_E4M3.  The definition holds for every batch size; the
- * 8-bit matrix-core kernel runs for batches above 16 tokens on experts of 128 neurons (64 if
- * gated), other shapes run their bf16 kernels on xq.
+ * zero).  Every xq element is a bf16 number, so the layer computes what a bf16 layer with the
+ * same weights computes on the input xq, up to the summation: the 8-bit matrix-core instruction
+ * adds the products of a 32-wide block with less than fp32 precision (measured: within 3e-4 of
+ * the block's largest product).  The hidden activations and the down-projection are as in
+ * DMOE_W_FP8_E4M3.  The definition holds for every batch size; the 8-bit matrix-core kernel
+ * runs for batches above 16 tokens on experts of 128 neurons (64 if gated), other shapes run
+ * their bf16 kernels on xq.
+ *
+ * DMOE_W_FP8_E4M3_A8 is DMOE_W_FP8_E4M3_X8 with the hidden activations quantised as well, so that
+ * the down-projection multiplies 8-bit operands too (a fully 8-bit layer): the m hidden
+ * activations of every selected (token, expert) pair, rounded to bf16 as in the other formats,
+ * are replaced by
+ *   hq = s * e4m3(h / s),   s = 2^ceil(log2(max_j |h_j| / 448))   (the rule of xq, per pair)
+ * before they meet W_down.  Every batch size computes this definition; the 8-bit matrix-core
+ * down-projection runs for H rows of 64 neurons (33 .. 64 neurons per expert), other sizes
+ * quantise H in place and run their bf16 kernels on hq; batches of up to 16 tokens take the
+ * same kernels as larger ones (no weight-streaming path in this format).
  */
 
 /* Library version (major*10000 + minor*100 + patch) and the text of the last error of the

@@ -20,7 +20,7 @@ DMOE_ERR_TAU, DMOE_ERR_WORKSPACE, DMOE_ERR_HIP = 4, 5, 6
 DMOE_F32, DMOE_BF16 = 0, 1
 ACT_CODES = {"relu": 0, "gelu_erf": 1, "gelu_tanh": 2}
 DTYPE_CODES = {"f32": DMOE_F32, "bf16": DMOE_BF16}
-DMOE_W_NATIVE, DMOE_W_FP8_E4M3, DMOE_W_FP8_E4M3_X8 = 0, 1, 2
+DMOE_W_NATIVE, DMOE_W_FP8_E4M3, DMOE_W_FP8_E4M3_X8, DMOE_W_FP8_E4M3_A8 = 0, 1, 2, 3
 
 EXPORTS = (
     "dmoe_version", "dmoe_last_error", "dmoe_workspace_bytes", "dmoe_select_workspace_bytes",
@@ -140,7 +140,8 @@ class Layer:
         self.act = params["act"]
         self.t = {k: to_device(params.get(k), dtype, device)
                   for k in ("w_up", "w_gate", "b_up", "w_down", "b_down", "r_w1", "r_b1", "r_w2", "r_b2")}
-        # params["x8"] (with "w8"): the experts' input is quantised row-wise to 8 bits as well
+        # params["x8"] (with "w8"): the experts' input is quantised row-wise to 8 bits as well;
+        # params["a8"]: ... and every row of hidden activations too
         # 8-bit expert weights (params["w8"]: E4M3 codes and power-of-two scales): the library gets
         # the codes; self.t keeps the bf16 values of the same weights for dense comparisons
         w8 = params.get("w8")
@@ -154,7 +155,7 @@ class Layer:
         self.c = DmoeLayerStruct(
             d_model=d, n_experts=E, expert_size=m, router_hidden=self.d_h,
             gated=int(self.gated), act=ACT_CODES[self.act], dtype=DTYPE_CODES[dtype],
-            weight_format=(DMOE_W_FP8_E4M3_X8 if params.get("x8") else DMOE_W_FP8_E4M3) if w8 is not None else DMOE_W_NATIVE,
+            weight_format=(DMOE_W_FP8_E4M3_A8 if params.get("a8") else DMOE_W_FP8_E4M3_X8 if params.get("x8") else DMOE_W_FP8_E4M3) if w8 is not None else DMOE_W_NATIVE,
             **ptrs, packed=None, w_scales=_ptr(self.w8["scales"]) if w8 is not None else None)
         nbytes = ctypes.c_size_t(0)
         check(lib().dmoe_packed_bytes(ctypes.byref(self.c), ctypes.byref(nbytes)))

@@ -57,7 +57,7 @@ int static_scratch_of_current_device(void** out) {
 const char* const kSlotNames[kSlotCount] = {
     "router", "mask_count", "lists_to_mask", "scan_groups", "fill_lists",
     "expert_up", "expert_down", "expert_down_sparse", "ffn_f32", "small_up", "small_down", "small_finish", "pack_weights",
-    "quantize_x"};
+    "quantize_x", "quantize_h"};
 constexpr int kEventPairs = 8192;
 bool g_timing = false;
 std::vector<hipEvent_t> g_ev;      // 2 * kEventPairs once enabled
@@ -94,7 +94,7 @@ int check_layer(const dmoe_layer* L, bool need_router, bool need_experts) {
     if (L->dtype != DMOE_F32 && L->dtype != DMOE_BF16)
         return fail(DMOE_ERR_UNSUPPORTED, "dtype %d is not DMOE_F32 or DMOE_BF16", L->dtype);
     if (L->weight_format != DMOE_W_NATIVE && !weights_fp8(*L))
-        return fail(DMOE_ERR_UNSUPPORTED, "weight_format %d is not one of DMOE_W_NATIVE, DMOE_W_FP8_E4M3, DMOE_W_FP8_E4M3_X8", L->weight_format);
+        return fail(DMOE_ERR_UNSUPPORTED, "weight_format %d is not one of DMOE_W_NATIVE, DMOE_W_FP8_E4M3, DMOE_W_FP8_E4M3_X8, DMOE_W_FP8_E4M3_A8", L->weight_format);
     if (weights_fp8(*L)) {
         if (L->dtype != DMOE_BF16) return fail(DMOE_ERR_UNSUPPORTED, "8-bit expert weights need a bf16 layer");
         if (!L->w_scales) return fail(DMOE_ERR_NULL, "8-bit expert weights need w_scales");
@@ -173,7 +173,7 @@ SelectWs select_ws(int T, int E, bool need_mask) {
 }
 
 struct LayerWs {
-    size_t scores, mask, group_off, sub_cnt, counts, offsets, item_start, witem, wfirst, lists, H, colmask, partial, hid, x8, xscale, xhat, total;
+    size_t scores, mask, group_off, sub_cnt, counts, offsets, item_start, witem, wfirst, lists, H, H8, hs8, colmask, partial, hid, x8, xscale, xhat, total;
 };
 LayerWs layer_ws(const dmoe_layer& L, int T) {
     LayerWs w{};
@@ -198,6 +198,12 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     w.lists = o;      o += align_up(sizeof(int32_t) * h_fragments(L, T) * 16);
     w.H = o;
     if (L.dtype == DMOE_BF16) o += align_up(h_fragments(L, T) * (m_pad_of(L.expert_size) / 32) * 1024);
+    // 8-bit hidden activations: codes and scale bytes of the same rows
+    w.H8 = w.hs8 = o;
+    if (down_x8_shape(L)) {
+        w.H8 = o;   o += align_up(h_fragments(L, T) * 16 * 64);
+        w.hs8 = o;  o += align_up(h_fragments(L, T) * 16);
+    }
     // small-token path: which tokens keep each expert, and the per-expert-group partial outputs
     w.colmask = o;
     w.partial = o;
@@ -223,7 +229,8 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
 }
 
 bool use_small_path(const dmoe_layer& L, int T) {
-    return L.dtype == DMOE_BF16 && T <= kSmallTokens && small_bf16_supported(L);
+    // (8-bit hidden activations: every batch size takes the list-based kernels)
+    return L.dtype == DMOE_BF16 && T <= kSmallTokens && small_bf16_supported(L) && !hidden_fp8(L);
 }
 
 // Pointers of one layer for the small-token kernels (its workspace carved as in layer_ws).
@@ -303,8 +310,24 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
                              up_rows_bf16(L), lists_out, alist, up_window_groups(L, T), witem,
                              wfirst, s, sub_cnt, split);
         void* H = ws + w.H;
-        if (up_x8_supported(L)) launch_up_x8(L, x8, xscale, T, witem, wfirst, alist, H, s);
-        else launch_up_bf16(L, x, T, witem, wfirst, alist, H, s);
+        // 8-bit hidden activations on the 8-bit matrix cores: the rows as codes + scale bytes
+        const bool down8 = hidden_fp8(L) && down_x8_shape(L) && down_x8_addressable(L, T);
+        uint8_t* H8 = down8 ? reinterpret_cast<uint8_t*>(ws + w.H8) : nullptr;
+        uint8_t* hs8 = down8 ? reinterpret_cast<uint8_t*>(ws + w.hs8) : nullptr;
+        // (the 8-bit up-projection of gated experts writes them itself; after any other
+        // up-projection a kernel of its own quantises the bf16 rows)
+        const bool up_writes_codes = down8 && up_x8_supported(L) && L.gated;
+        if (up_x8_supported(L))
+            launch_up_x8(L, x8, xscale, T, witem, wfirst, alist, H, up_writes_codes ? H8 : nullptr,
+                         up_writes_codes ? hs8 : nullptr, s);
+        else
+            launch_up_bf16(L, x, T, witem, wfirst, alist, H, s);
+        if (down8) {
+            if (!up_writes_codes) launch_h_rows_to_e4m3(L, item_start, H, H8, hs8, s);
+            launch_down_x8(L, T, item_start, group_off, mask, H8, hs8, y, s);
+            return check_launch("expert kernels");
+        }
+        if (hidden_fp8(L)) launch_h_rows_quantize(L, item_start, H, s);  // the bf16 kernels read hq
         const long long max_sparse = down_max_pairs_sparse(L, T);
         // both are launched and the pair count on the device decides, unless the limit already does
         if (max_sparse > 0)

@@ -43,9 +43,19 @@ inline size_t h_fragments(const dmoe_layer& L, int T) {
 
 // 8-bit expert weights (both 8-bit formats); 8-bit expert inputs as well.
 inline bool weights_fp8(const dmoe_layer& L) {
-    return L.weight_format == DMOE_W_FP8_E4M3 || L.weight_format == DMOE_W_FP8_E4M3_X8;
+    return L.weight_format == DMOE_W_FP8_E4M3 || L.weight_format == DMOE_W_FP8_E4M3_X8 ||
+           L.weight_format == DMOE_W_FP8_E4M3_A8;
 }
-inline bool acts_fp8(const dmoe_layer& L) { return L.weight_format == DMOE_W_FP8_E4M3_X8; }
+inline bool acts_fp8(const dmoe_layer& L) {
+    return L.weight_format == DMOE_W_FP8_E4M3_X8 || L.weight_format == DMOE_W_FP8_E4M3_A8;
+}
+// 8-bit hidden activations as well (every H row quantised before the down-projection) ...
+inline bool hidden_fp8(const dmoe_layer& L) { return L.weight_format == DMOE_W_FP8_E4M3_A8; }
+// ... and whether the 8-bit matrix-core down-projection covers the shape (H rows of 64 neurons,
+// 256-column slices); other shapes quantise H in place and run the bf16 kernels.
+inline bool down_x8_shape(const dmoe_layer& L) {
+    return hidden_fp8(L) && m_pad_of(L.expert_size) == 64 && L.d_model % 256 == 0;
+}
 // ... and whether the 8-bit matrix-core up-projection covers the shape (the 256-row work items of
 // the wide-expert kernel); other shapes run the bf16 kernels on the quantised input.
 inline bool up_x8_supported(const dmoe_layer& L) { return acts_fp8(L) && up_rows_bf16(L) == 256; }
@@ -58,7 +68,7 @@ inline bool up_tiny_supported(const dmoe_layer& L) {
 
 // Sub-buffers of the packed-weights buffer (bytes from its start).
 struct PackedLayout {
-    size_t w2f, w2g, wupf, wgatef, r1f, r2f, w2f8, wupf8, wgatef8, wtinyf, scales, wupx8, wgatex8, total;
+    size_t w2f, w2g, wupf, wgatef, r1f, r2f, w2f8, wupf8, wgatef8, wtinyf, scales, wupx8, wgatex8, w2x8, wsc8, total;
 };
 inline PackedLayout packed_layout(const dmoe_layer& L) {
     PackedLayout P{};
@@ -107,6 +117,15 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
         P.wgatex8 = o + half;
         o += (L.gated ? 2 : 1) * half;
     }
+    // 8-bit hidden activations: the down matrices as operands of the 32x32x64 8-bit MFMA,
+    // w2x8[E][d/32][64][32] (down_x8.hip), and the E8M0 byte of every expert's down scale
+    P.w2x8 = P.wsc8 = o;
+    if (down_x8_shape(L)) {
+        P.w2x8 = o;
+        o += ((size_t)L.n_experts * (L.d_model / 32) * 2048 + 255) / 256 * 256;
+        P.wsc8 = o;
+        o += ((size_t)L.n_experts + 255) / 256 * 256;
+    }
     P.total = o;
     return P;
 }
@@ -127,6 +146,7 @@ enum Slot {
     kSlotSmallFinish,
     kSlotPack,
     kSlotQuantX,
+    kSlotQuantH,
     kSlotCount
 };
 
@@ -283,6 +303,20 @@ void launch_down_rmw_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
                           const void* H, void* y, long long max_pairs_sparse, hipStream_t s);
 long long down_max_pairs_sparse(const dmoe_layer& L, int T);
 
+// ---- 8-bit hidden activations (down_x8.hip) -------------------------------------------------------
+// Row-wise quantisation of the H rows that the up-projection wrote (see DMOE_W_FP8_E4M3_A8 in
+// dmoe.h; the number of rows is item_start[E] * rows per item): to codes H8[row][64] and E8M0
+// scale bytes hs8[row] for the 8-bit down-projection, or in place (the quantised rows as bf16
+// numbers) for the bf16 down-projections.
+void launch_pack_down_x8(const dmoe_layer& L, void* packed, hipStream_t s);
+bool down_x8_addressable(const dmoe_layer& L, int T);
+void launch_h_rows_to_e4m3(const dmoe_layer& L, const int32_t* item_start, const void* H,
+                           uint8_t* H8, uint8_t* hs8, hipStream_t s);
+void launch_h_rows_quantize(const dmoe_layer& L, const int32_t* item_start, void* H, hipStream_t s);
+void launch_down_x8(const dmoe_layer& L, int T, const int32_t* item_start, const int32_t* group_off,
+                    const uint64_t* mask, const uint8_t* H8, const uint8_t* hs8, void* y,
+                    hipStream_t s);
+
 // ---- 8-bit expert inputs (ffn_x8.hip) -------------------------------------------------------------
 // Row-wise quantisation of x (see DMOE_W_FP8_E4M3_X8 in dmoe.h): x8[T][d] E4M3 codes, xscale[T]
 // the power-of-two scales, xhat[T][d] (nullable) the quantised rows as bf16 numbers.
@@ -290,9 +324,11 @@ void launch_quantize_x(const dmoe_layer& L, const void* x, int T, uint8_t* x8, f
                        void* xhat, hipStream_t s);
 void launch_pack_x8(const dmoe_layer& L, void* packed, hipStream_t s);
 // Up-projection on 8-bit operands; same work items, lists and H rows as launch_up_bf16.
+// H8 / hs8 non-null (gated experts in rows of 64 only): the rows go out quantised for the 8-bit
+// down-projection instead of as bf16 rows in H.
 void launch_up_x8(const dmoe_layer& L, const uint8_t* x8, const float* xscale, int T,
                   const int32_t* witem, const int32_t* wfirst, const int32_t* alist, void* H,
-                  hipStream_t s);
+                  uint8_t* H8, uint8_t* hs8, hipStream_t s);
 
 bool experts_bf16_supported(const dmoe_layer& L);
 bool router_bf16_supported(const dmoe_layer& L);

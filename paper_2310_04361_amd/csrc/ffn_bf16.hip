@@ -662,6 +662,7 @@ void launch_pack_bf16(const dmoe_layer& L, void* packed, hipStream_t s) {
                                                          (uint8_t*)(pk + P.wgatef8), E, m, d, mp / 16, 1);
     }
     if (up_x8_supported(L)) launch_pack_x8(L, packed, s);  // operands of the 8-bit up-projection
+    if (down_x8_shape(L)) launch_pack_down_x8(L, packed, s);  // ... and of the 8-bit down-projection
     // the router matrices use the same fragment format: "one expert" whose rows are the hidden
     // units (r_w1) or the experts (r_w2)
     const int dh = L.router_hidden;

@@ -91,6 +91,9 @@ def test_layer_validation(lib):
         (_layer(n_experts=-3), B.DMOE_ERR_SHAPE),
         (_layer(dtype=7), B.DMOE_ERR_UNSUPPORTED),
         (_layer(weight_format=2), B.DMOE_ERR_UNSUPPORTED),
+        (_layer(weight_format=3), B.DMOE_ERR_UNSUPPORTED),                      # 8-bit formats need bf16
+        (_layer(weight_format=4), B.DMOE_ERR_UNSUPPORTED),                      # no such format
+        (_layer(weight_format=4, dtype=B.DMOE_BF16), B.DMOE_ERR_UNSUPPORTED),
         (_layer(weight_format=1), B.DMOE_ERR_UNSUPPORTED),                      # 8-bit weights need bf16
         (_layer(weight_format=1, dtype=B.DMOE_BF16), B.DMOE_ERR_NULL),          # ... and scales
         (_layer(gated=2), B.DMOE_ERR_UNSUPPORTED),

@@ -4,7 +4,8 @@ of every 128-token chunk, plus properties that hold at any size."""
 import numpy as np
 import pytest
 
-from helpers import TOL, elementwise_rel_err, lists_from_mask, oracle_ffn, tokenwise_rel_err
+from helpers import (TOL, check_fully_8bit, elementwise_rel_err, lists_from_mask, oracle_ffn,
+                     tokenwise_rel_err, tokenwise_rel_errs)
 from paper_2310_04361_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -127,6 +128,34 @@ def test_full_size_8bit_inputs_every_token(B, oracle):
     print(f"  density={mask.mean():.4f} tokens compared={cfg.T} err={err:.3e} "
           f"element-wise err={elementwise_rel_err(yh, ref):.3e}", flush=True)
     assert err <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("tau", [0.3, 0.6])
+def test_full_size_fully_8bit_every_token(B, oracle, tau):
+    """The same layer at full size with 8-bit hidden activations as well (both expert products
+    on the fp8 matrix cores): every token against the oracle's experts on the oracle's quantised
+    input rows, with every selected hidden row quantised by the oracle."""
+    import torch
+    cfg = wl.CONFIGS["cfg4"]
+    print(f"full size cfg4 T={cfg.T} tau={tau}, fully 8-bit", flush=True)
+    base, x = _layer_and_input(cfg, 0)
+    layer = wl.quantize_experts_e4m3(base)
+    layer["x8"] = True
+    layer["a8"] = True
+    L = B.Layer(layer, cfg.dtype)
+    tau32 = float(np.float32(tau))
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau32, want_scores=True, want_mask=True)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy().astype(np.float64)
+    mask, _ = oracle.select(s, tau32)
+    assert np.array_equal(B.mask_bits_to_bool(ex["mask_bits"], cfg.E), mask)
+    xq, _ = oracle.quantize_rows_e4m3(x)
+    ref = oracle_ffn(oracle, layer, xq, mask, quantize_h=True)
+    yh = B.from_device(y, cfg.dtype)
+    err, n_allow = check_fully_8bit(oracle, layer, xq, mask, yh, ref, TOL[cfg.dtype])
+    errs = tokenwise_rel_errs(yh, ref)
+    print(f"  density={mask.mean():.4f} tokens compared={cfg.T} err={err:.3e} median={np.median(errs):.3e} "
+          f"tokens on the one-step allowance: {n_allow}", flush=True)
 
 
 def test_paper_shape_full_size_bernoulli(B, oracle):

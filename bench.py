@@ -321,6 +321,8 @@ def main() -> int:
                          "with the dynamic-k layer in its place (Sec. 4.4: what survives end to end)")
     ap.add_argument("--x8", action="store_true",
                     help="with --no-others: still time the headline layer with 8-bit weights and inputs")
+    ap.add_argument("--a8", action="store_true",
+                    help="with --no-others: still time the headline layer fully 8-bit (hidden activations too)")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense-FFN comparisons (keeps a profile to the timed workload)")
     args = ap.parse_args()
@@ -499,7 +501,7 @@ def main() -> int:
     del w
     torch.cuda.empty_cache()
 
-    if (not args.no_others or args.x8) and not args.tokens and cfg.dtype == "bf16":
+    if (not args.no_others or args.x8 or args.a8) and not args.tokens and cfg.dtype == "bf16":
         # the same layer with 8-bit expert weights and 8-bit (row-wise E4M3) expert inputs: the
         # up-projection of wide experts runs on the fp8 matrix pipe (Appendix C's lower precisions)
         same_layer = [] if args.no_others else [o for o in OTHERS if o[0] == args.workload and o[1] != args.tau]
@@ -511,6 +513,8 @@ def main() -> int:
                  "weight_format DMOE_W_FP8_E4M3_A8 (8-bit expert weights, inputs and hidden "
                  "activations: both expert products on the fp8 matrix pipe): same shapes, a "
                  "different (lower) precision -- not the bf16 headline")]:
+            if args.no_others and not (args.a8 if "a8" in kw else args.x8):
+                continue
             w8 = Workload(args.workload, **kw)
             rows = []
             for name, t in [(args.workload, args.tau)] + same_layer:

@@ -48,7 +48,7 @@ def _check(oracle, layer, x, mask, got, dtype):
 # 64, plain experts of 64; in-place quantisation + bf16 kernels: rows of 32, of 128, one-tile
 # experts; batches of at most 16 tokens
 SHAPES = [("cfg4", 300, 16), ("cfg4", 700, 8), ("cfg4", 129, 37), ("cfg4", 1000, 70), ("cfg4", 17, 16),
-          ("cfg4", 16, 64), ("cfg4", 5, 16), ("cfg4", 1, 16),
+          ("cfg4", 16, 64), ("cfg4", 5, 16), ("cfg4", 1, 16), ("cfg4", 200, 600), ("cfg4", 70, 1),
           ("cfg2", 300, 32), ("paper", 260, 8), ("gemma_paper", 200, 64), ("cfg5b", 9, None)]
 
 

@@ -540,7 +540,8 @@ def main() -> int:
     if args.paper_sweep or curves:
         from paper_2310_04361_amd import workloads as wl
         pw = Workload("paper")
-        pc, pL = pw.cfg, pw.layers[0]
+        pw8 = Workload("paper", a8=True)   # the same layer fully 8-bit (Appendix C's precision table)
+        pc, pL, pL8 = pw.cfg, pw.layers[0], pw8.layers[0]
         pd = None if args.no_dense else pw.dense_ms()
         rows = []
         for p in (0.0, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0):
@@ -548,16 +549,20 @@ def main() -> int:
             offs = np.concatenate([[0], np.cumsum(mask.sum(axis=0))]).astype(np.int32)
             lists = np.concatenate([np.flatnonzero(mask[:, e]) for e in range(pc.E)] + [np.zeros(1)]).astype(np.int32)
             offs_d, lists_d = torch.from_numpy(offs).cuda(), torch.from_numpy(lists).cuda()
-            for i in range(3):
-                B.dmoe_expert_ffn(pL, pw.xs[i % N_ROTATE], offs_d, lists_d)
-            m = _time_ms(lambda i: B.dmoe_expert_ffn(pL, pw.xs[i % N_ROTATE], offs_d, lists_d), 20)
-            rows.append({"p": p, "ms": round(m, 4),
-                         "vs_dense": round(pd / m, 3) if pd else None})
+            ms = []
+            for lay, w in ((pL, pw), (pL8, pw8)):
+                for i in range(3):
+                    B.dmoe_expert_ffn(lay, w.xs[i % N_ROTATE], offs_d, lists_d)
+                ms.append(_time_ms(lambda i: B.dmoe_expert_ffn(lay, w.xs[i % N_ROTATE], offs_d, lists_d), 20))
+            rows.append({"p": p, "ms": round(ms[0], 4), "ms_fully_8bit": round(ms[1], 4),
+                         "vs_dense": round(pd / ms[0], 3) if pd else None})
         out["paper_shape_bernoulli_sweep"] = {"workload": pw.describe("-"), "note": "dmoe_expert_ffn "
-                                              "only (decisions given, no router), as in Sec. 4.4",
+                                              "only (decisions given, no router), as in Sec. 4.4; "
+                                              "ms: bf16 layer, ms_fully_8bit: weight format "
+                                              "DMOE_W_FP8_E4M3_A8 (the precisions of Appendix C's table)",
                                               "dense_vendor_gemm_ms": round(pd, 4) if pd else None,
                                               "rows": rows}
-        del pw
+        del pw, pw8
 
     if args.block or curves:
         out["encoder_block"] = encoder_block_timing()

@@ -118,8 +118,8 @@ typedef struct {
  * are replaced by
  *   hq = s * e4m3(h / s),   s = 2^ceil(log2(max_j |h_j| / 448))   (the rule of xq, per pair)
  * before they meet W_down.  Every batch size computes this definition; the 8-bit matrix-core
- * down-projection runs for H rows of 64 neurons (33 .. 64 neurons per expert), other sizes
- * quantise H in place and run their bf16 kernels on hq; batches of up to 16 tokens take the
+ * down-projection runs for H rows of 64 or 128 neurons (33 .. 128 neurons per expert), smaller
+ * experts quantise H in place and run their bf16 kernels on hq; batches of up to 16 tokens take the
  * same kernels as larger ones (no weight-streaming path in this format).
  */
 

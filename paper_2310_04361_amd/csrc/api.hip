@@ -201,7 +201,7 @@ LayerWs layer_ws(const dmoe_layer& L, int T) {
     // 8-bit hidden activations: codes and scale bytes of the same rows
     w.H8 = w.hs8 = o;
     if (down_x8_shape(L)) {
-        w.H8 = o;   o += align_up(h_fragments(L, T) * 16 * 64);
+        w.H8 = o;   o += align_up(h_fragments(L, T) * 16 * m_pad_of(L.expert_size));
         w.hs8 = o;  o += align_up(h_fragments(L, T) * 16);
     }
     // small-token path: which tokens keep each expert, and the per-expert-group partial outputs
@@ -316,7 +316,7 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
         uint8_t* hs8 = down8 ? reinterpret_cast<uint8_t*>(ws + w.hs8) : nullptr;
         // (the 8-bit up-projection of gated experts writes them itself; after any other
         // up-projection a kernel of its own quantises the bf16 rows)
-        const bool up_writes_codes = down8 && up_x8_supported(L) && L.gated;
+        const bool up_writes_codes = down8 && up_x8_supported(L);
         if (up_x8_supported(L))
             launch_up_x8(L, x8, xscale, T, witem, wfirst, alist, H, up_writes_codes ? H8 : nullptr,
                          up_writes_codes ? hs8 : nullptr, s);

@@ -51,10 +51,10 @@ inline bool acts_fp8(const dmoe_layer& L) {
 }
 // 8-bit hidden activations as well (every H row quantised before the down-projection) ...
 inline bool hidden_fp8(const dmoe_layer& L) { return L.weight_format == DMOE_W_FP8_E4M3_A8; }
-// ... and whether the 8-bit matrix-core down-projection covers the shape (H rows of 64 neurons,
-// 256-column slices); other shapes quantise H in place and run the bf16 kernels.
+// ... and whether the 8-bit matrix-core down-projection covers the shape (H rows of 64 or 128
+// neurons, 256-column slices); other shapes quantise H in place and run the bf16 kernels.
 inline bool down_x8_shape(const dmoe_layer& L) {
-    return hidden_fp8(L) && m_pad_of(L.expert_size) == 64 && L.d_model % 256 == 0;
+    return hidden_fp8(L) && m_pad_of(L.expert_size) >= 64 && L.d_model % 256 == 0;
 }
 // ... and whether the 8-bit matrix-core up-projection covers the shape (the 256-row work items of
 // the wide-expert kernel); other shapes run the bf16 kernels on the quantised input.
@@ -118,13 +118,15 @@ inline PackedLayout packed_layout(const dmoe_layer& L) {
         o += (L.gated ? 2 : 1) * half;
     }
     // 8-bit hidden activations: the down matrices as operands of the 32x32x64 8-bit MFMA,
-    // w2x8[E][d/32][64][32] (down_x8.hip), and the E8M0 byte of every expert's down scale
+    // w2x8[E * units][d/32][64][32] (down_x8.hip; a unit = 64 neurons of an expert), and the E8M0
+    // byte of every unit's down scale
     P.w2x8 = P.wsc8 = o;
     if (down_x8_shape(L)) {
+        const size_t units = (size_t)L.n_experts * (m_pad_of(L.expert_size) / 64);
         P.w2x8 = o;
-        o += ((size_t)L.n_experts * (L.d_model / 32) * 2048 + 255) / 256 * 256;
+        o += (units * (L.d_model / 32) * 2048 + 255) / 256 * 256;
         P.wsc8 = o;
-        o += ((size_t)L.n_experts + 255) / 256 * 256;
+        o += (units + 255) / 256 * 256;
     }
     P.total = o;
     return P;
@@ -324,7 +326,7 @@ void launch_quantize_x(const dmoe_layer& L, const void* x, int T, uint8_t* x8, f
                        void* xhat, hipStream_t s);
 void launch_pack_x8(const dmoe_layer& L, void* packed, hipStream_t s);
 // Up-projection on 8-bit operands; same work items, lists and H rows as launch_up_bf16.
-// H8 / hs8 non-null (gated experts in rows of 64 only): the rows go out quantised for the 8-bit
+// H8 / hs8 non-null: the rows go out quantised for the 8-bit
 // down-projection instead of as bf16 rows in H.
 void launch_up_x8(const dmoe_layer& L, const uint8_t* x8, const float* xscale, int T,
                   const int32_t* witem, const int32_t* wfirst, const int32_t* alist, void* H,

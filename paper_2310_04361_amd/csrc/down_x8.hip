@@ -12,6 +12,8 @@
 //             v_mfma_scale_f32_32x32x64_f8f6f4: one instruction per expert, token tile and column
 //             tile, the row scale of H and the expert's weight scale as the instruction's block
 //             scales.  Half the operand bytes and half the matrix-pipe time of the bf16 kernel.
+//             H rows of 128 neurons are two such units of 64 per expert (UPE = 2): the same
+//             pipeline walks units, and the selection of an expert is worked out at its first.
 #include "dmoe_internal.h"
 #include "mfma.h"
 
@@ -113,30 +115,32 @@ __global__ __launch_bounds__(256) void h_rows_quantize_kernel(__bf16* __restrict
     }
 }
 
-// w_down (E4M3 codes) [E][m][d] -> w2x8[E][d/32][64][32]: lane (h, r) of block (e, column tile)
-// holds the neurons 32h .. 32h+31 of output column 32*tile + 16*((r>>2)&1) + 4*(r>>3) + (r&3)
-// (the column order that makes a lane's 16 accumulators 16 consecutive columns); wsc8[e] = the
-// E8M0 byte of the magnitude of the expert's (power-of-two) down scale -- a negative scale flips
+// w_down (E4M3 codes) [E][m][d] -> w2x8[E * UPE][d/32][64][32], a unit being 64 consecutive neurons
+// of an expert: lane (h, r) of block (unit, column tile) holds the unit's neurons 32h .. 32h+31 of
+// output column 32*tile + 16*((r>>2)&1) + 4*(r>>3) + (r&3)
+// (the column order that makes a lane's 16 accumulators 16 consecutive columns); wsc8[unit] = the
+// E8M0 byte of the magnitude of its expert's (power-of-two) down scale -- a negative scale flips
 // the sign bit of the expert's codes instead, a zero scale zeroes them.
 __global__ void pack_down_x8_kernel(const uint8_t* __restrict__ w, const float* __restrict__ scales,
                                     uint8_t* __restrict__ out, uint8_t* __restrict__ wsc8, int E,
-                                    int m, int d) {
-    const size_t n = (size_t)E * (d / 32) * 2048;
+                                    int m, int d, int UPE) {
+    const size_t n = (size_t)E * UPE * (d / 32) * 2048;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    if (i < (size_t)E) {
+    if (i < (size_t)E * UPE) {
         int ex = 1;
-        (void)frexpf(fabsf(scales[3 * i + 2]), &ex);  // |scale| = 0.5 * 2^ex exactly (a power of two)
+        (void)frexpf(fabsf(scales[3 * (i / UPE) + 2]), &ex);  // |scale| = 0.5 * 2^ex exactly (a power of two)
         wsc8[i] = (uint8_t)min(max(127 + ex - 1, 0), 254);
     }
     for (; i < n; i += stride) {
         const int j = (int)(i & 31), lane = (int)((i >> 5) & 63);
         size_t f = i >> 11;
         const int ct = (int)(f % (d / 32));
-        const int e = (int)(f / (d / 32));
+        const int unit = (int)(f / (d / 32));
+        const int e = unit / UPE;
         const int h = lane >> 5, r = lane & 31;
         const int col = 32 * ct + 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
-        const int neuron = 32 * h + j;
+        const int neuron = 64 * (unit % UPE) + 32 * h + j;
         const float sc = scales[3 * e + 2];
         uint8_t b = neuron < m ? w[((size_t)e * m + neuron) * d + col] : (uint8_t)0;
         if (sc < 0.0f) b ^= 0x80;
@@ -150,6 +154,8 @@ constexpr int kD8Image = kD8Tiles * 64 * 32;   // the four B tiles of one expert
 constexpr int kD8Buf = kD8Image + kD8Tokens;   // + one scale byte per token
 constexpr int kD8Lds = 2 * kD8Buf;
 
+// UPE = units of 64 neurons per expert (H rows of 64 * UPE bytes).
+template <int UPE>
 __global__ __launch_bounds__(256) void down_x8_kernel(
     const uint8_t* __restrict__ w2x8, const uint8_t* __restrict__ wsc8,
     const __bf16* __restrict__ b_down, const int32_t* __restrict__ item_start,
@@ -180,7 +186,8 @@ __global__ __launch_bounds__(256) void down_x8_kernel(
     const __amdgpu_buffer_rsrc_t h_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)H8, 0, (int)h_bytes, kRawBuffer);
     const __amdgpu_buffer_rsrc_t s_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)hs8, 0, (int)hs_bytes, kRawBuffer);
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)w2x8, 0, (int)w_bytes, kRawBuffer);
-    const __amdgpu_buffer_rsrc_t ws_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)wsc8, 0, E, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t ws_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)wsc8, 0, E * UPE, kRawBuffer);
+    const int n_units = E * UPE;
 
     uint32_t mw = 0, mw_next;
     int rowv = 0, is_next, go_next;
@@ -192,11 +199,11 @@ __global__ __launch_bounds__(256) void down_x8_kernel(
         go_next = grow[ec];
     };
     load_batch(0);
-    // fetch state of the next expert in order; the fetches run FOUR experts ahead of the MFMAs, so
-    // a batch of 32 experts starts between two quads of the loop below, which keeps the quad's
+    // fetch state of the next unit in order; the fetches run FOUR units ahead of the MFMAs, so a
+    // batch of 32 experts starts between two quads of the loop below, which keeps the quad's
     // body free of branches (with a branch inside, the compiler moved all MFMAs of a quad behind
     // its memory operations)
-    int fe = 0;  // next expert to fetch
+    int fe = 0;  // next unit to fetch
     int fbatch = 0;
     auto next_batch = [&]() {
         mw = (tok_ok && fbatch < n_batches) ? mw_next : 0u;
@@ -205,20 +212,26 @@ __global__ __launch_bounds__(256) void down_x8_kernel(
         load_batch(fbatch);
     };
     next_batch();
-    auto fetch = [&](u32x4 (&hb)[2], uint32_t& hsc) {
-        const bool sel = (mw & 1u) != 0u;
-        mw >>= 1;
-        const uint64_t bal = __ballot(sel);
-        const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
-        const uint32_t row = (uint32_t)__builtin_amdgcn_readlane(rowv, fe & 31) + rank;
-        const uint32_t oob = sel ? 0u : 0x80000000u;
-        const uint32_t voff = (row * 64u + 32u * (uint32_t)bh) | oob;
+    // first: the unit opens an expert (its selection, rank and row are worked out); a second
+    // unit reads the next 64 bytes of the same row
+    uint32_t voff_expert = 0, srow_expert = 0;
+    auto fetch = [&](bool first, u32x4 (&hb)[2], uint32_t& hsc) {
+        if (first) {  // compile-time at every call
+            const bool sel = (mw & 1u) != 0u;
+            mw >>= 1;
+            const uint64_t bal = __ballot(sel);
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            const uint32_t row = (uint32_t)__builtin_amdgcn_readlane(rowv, (fe / UPE) & 31) + rank;
+            const uint32_t oob = sel ? 0u : 0x80000000u;
+            voff_expert = (row * (64u * UPE) + 32u * (uint32_t)bh) | oob;
+            srow_expert = row | oob;
+        }
+        const uint32_t voff = voff_expert + 64u * (uint32_t)(fe % UPE);
         hb[0] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, voff, 0, 0);
         hb[1] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, voff, 16, 0);
-        hsc = __builtin_amdgcn_raw_buffer_load_b8(s_rsrc, row | oob, 0, 0);
+        hsc = __builtin_amdgcn_raw_buffer_load_b8(s_rsrc, srow_expert, 0, 0);
         ++fe;
     };
-    // lane = token 32*(lane>>5) + (lane&31) of the group: tile 2bg + (lane>>5), operand lane (bh, c)
     // a tile is two planes of 1 KiB: plane p holds bytes 16p .. 16p+15 of every operand lane, so
     // a 16-byte access of a wavefront covers consecutive addresses (no bank conflicts)
     char* const wdst = img + (2 * bg + h) * 2048 + (32 * bh + c) * 16;
@@ -235,17 +248,17 @@ __global__ __launch_bounds__(256) void down_x8_kernel(
 #pragma unroll
     for (int ct = 0; ct < kD8CT; ++ct) a_voff[ct] = (uint32_t)(((col_w / 32 + ct) * 64 + lane) * 32);
     const uint32_t w_expert_bytes = (uint32_t)(d / 32) * 2048;
-    int we = 0;  // next expert whose weights are requested
+    int we = 0;  // next unit whose weights are requested
     auto load_w = [&](i32x8 (&a)[kD8CT], int& sa) {
 #pragma unroll
         for (int ct = 0; ct < kD8CT; ++ct) {
             // (past the last expert: its weights again, against all-zero tiles)
-            const uint32_t so = (uint32_t)min(we, E - 1) * w_expert_bytes;
+            const uint32_t so = (uint32_t)min(we, n_units - 1) * w_expert_bytes;
             const u32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, a_voff[ct], so, 0);
             const u32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, a_voff[ct] + 16u, so, 0);
             a[ct] = i32x8{(int)v0[0], (int)v0[1], (int)v0[2], (int)v0[3], (int)v1[0], (int)v1[1], (int)v1[2], (int)v1[3]};
         }
-        sa = (int)__builtin_amdgcn_raw_buffer_load_b8(ws_rsrc, 0u, (uint32_t)min(we, E - 1), 0);
+        sa = (int)__builtin_amdgcn_raw_buffer_load_b8(ws_rsrc, 0u, (uint32_t)min(we, n_units - 1), 0);
         ++we;
     };
 
@@ -286,7 +299,7 @@ __global__ __launch_bounds__(256) void down_x8_kernel(
     i32x8 aw[4][kD8CT];
     int sa[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fetch(hb[i], hs[i]);
+    for (int i = 0; i < 4; ++i) fetch(i % UPE == 0, hb[i], hs[i]);
 #pragma unroll
     for (int i = 0; i < 3; ++i) load_w(aw[i], sa[i]);
     park(0, hb[0], hs[0]);
@@ -296,11 +309,13 @@ __global__ __launch_bounds__(256) void down_x8_kernel(
     int sb[2][kD8Tiles];
 #pragma unroll
     for (int j = 0; j < kD8Tiles; ++j) read_b(0, j, bb[0][j], sb[0][j]);
-    const int n_quads = (E + 3) >> 2;
+    const int n_quads = (n_units + 3) >> 2;
+    constexpr int kQuadsPerBatch = 8 * UPE;  // 32 experts
     for (int qd = 0; qd < n_quads; ++qd) {
-        if ((qd & 7) == 7) next_batch();  // this quad fetches the first four experts of the next batch
+        // the last quad of a batch fetches the first four units of the next batch
+        if ((qd & (kQuadsPerBatch - 1)) == kQuadsPerBatch - 1) next_batch();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {  // expert e = 4 qd + i: LDS buffer / B set i & 1, register sets i
+        for (int i = 0; i < 4; ++i) {  // unit u = 4 qd + i: LDS buffer / B set i & 1, register sets i
             const int buf = i & 1, n3 = (i + 3) & 3, n1 = (i + 1) & 3;
             __builtin_amdgcn_sched_barrier(0);
             acc[0][0] = mfma64(aw[i][0], bb[buf][0], acc[0][0], sa[i], sb[buf][0]);
@@ -309,7 +324,7 @@ __global__ __launch_bounds__(256) void down_x8_kernel(
             __builtin_amdgcn_sched_barrier(0);
             acc[0][1] = mfma64(aw[i][1], bb[buf][0], acc[0][1], sa[i], sb[buf][0]);
             __builtin_amdgcn_sched_barrier(0);
-            fetch(hb[i], hs[i]);             // expert e + 4 (this set was parked one expert ago)
+            fetch(i % UPE == 0, hb[i], hs[i]);  // unit u + 4 (this set was parked one unit ago)
             __builtin_amdgcn_sched_barrier(0);
             acc[1][0] = mfma64(aw[i][0], bb[buf][1], acc[1][0], sa[i], sb[buf][1]);
             __builtin_amdgcn_sched_barrier(0);
@@ -362,21 +377,26 @@ void launch_pack_down_x8(const dmoe_layer& L, void* packed, hipStream_t s) {
     char* pk = static_cast<char*>(packed);
     launch_kernel(pack_down_x8_kernel, 2048, 256, 0, s, (const uint8_t*)L.w_down,
                   (const float*)(pk + P.scales), (uint8_t*)(pk + P.w2x8), (uint8_t*)(pk + P.wsc8),
-                  L.n_experts, L.expert_size, L.d_model);
+                  L.n_experts, L.expert_size, L.d_model, m_pad_of(L.expert_size) / 64);
 }
 
 // The kernel reaches the packed weights and H8 through 32-bit buffer offsets, and marks
 // unselected tokens with offsets from 2^31 up.
 bool down_x8_addressable(const dmoe_layer& L, int T) {
-    return (size_t)L.n_experts * (L.d_model / 32) * 2048 < (1ull << 32) &&
-           h_fragments(L, T) * 16 * 64 < (1ull << 31);
+    const size_t mp = m_pad_of(L.expert_size);
+    return (size_t)L.n_experts * (mp / 64) * (L.d_model / 32) * 2048 < (1ull << 32) &&
+           h_fragments(L, T) * 16 * mp < (1ull << 31);
 }
 
 void launch_h_rows_to_e4m3(const dmoe_layer& L, const int32_t* item_start, const void* H,
                            uint8_t* H8, uint8_t* hs8, hipStream_t s) {
     LaunchTimer tm(kSlotQuantH, s);
-    launch_kernel(h_rows_quantize_kernel<64, true>, 2048, 256, 0, s, (__bf16*)const_cast<void*>(H),
-                  item_start, L.n_experts, up_rows_bf16(L), H8, hs8);
+    if (m_pad_of(L.expert_size) == 64)
+        launch_kernel(h_rows_quantize_kernel<64, true>, 2048, 256, 0, s, (__bf16*)const_cast<void*>(H),
+                      item_start, L.n_experts, up_rows_bf16(L), H8, hs8);
+    else
+        launch_kernel(h_rows_quantize_kernel<128, true>, 2048, 256, 0, s, (__bf16*)const_cast<void*>(H),
+                      item_start, L.n_experts, up_rows_bf16(L), H8, hs8);
 }
 
 void launch_h_rows_quantize(const dmoe_layer& L, const int32_t* item_start, void* H, hipStream_t s) {
@@ -401,13 +421,15 @@ void launch_down_x8(const dmoe_layer& L, int T, const int32_t* item_start, const
     const char* pk = static_cast<const char*>(L.packed);
     const int E = L.n_experts, d = L.d_model;
     const size_t rows = h_fragments(L, T) * 16;
-    const size_t w_bytes = (size_t)E * (d / 32) * 2048;
+    const int upe = m_pad_of(L.expert_size) / 64;
+    const size_t w_bytes = (size_t)E * upe * (d / 32) * 2048;
     const int NG = div_up(T, kGroup), NC = div_up(T, kD8Tokens), NS = d / (kD8CT * 128);
-    launch_kernel(down_x8_kernel, round_up(NC, 8) * NS, 256, kD8Lds, s, (const uint8_t*)(pk + P.w2x8),
+    auto* kernel = upe == 1 ? down_x8_kernel<1> : down_x8_kernel<2>;
+    launch_kernel(kernel, round_up(NC, 8) * NS, 256, kD8Lds, s, (const uint8_t*)(pk + P.w2x8),
                   (const uint8_t*)(pk + P.wsc8), (const __bf16*)L.b_down, item_start, group_off,
                   reinterpret_cast<const uint32_t*>(mask), H8, hs8, (__bf16*)y, T, d, E, NG,
-                  2 * div_up(E, 64), up_rows_bf16(L), (uint32_t)w_bytes, (uint32_t)(rows * 64),
-                  (uint32_t)rows);
+                  2 * div_up(E, 64), up_rows_bf16(L), (uint32_t)w_bytes,
+                  (uint32_t)(rows * 64 * upe), (uint32_t)rows);
 }
 
 }  // namespace dmoe

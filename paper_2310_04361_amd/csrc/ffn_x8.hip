@@ -369,6 +369,7 @@ void launch_up_x8(const dmoe_layer& L, const uint8_t* x8, const float* xscale, i
         (int)std::min<long long>((long long)T * L.n_experts / 256 + L.n_experts, 512), 8);
     if (L.gated && H8) launch_up_x8_t<4, true, 4, true>(L, P, x8, xscale, witem, wfirst, alist, H, H8, hs8, grid, s);
     else if (L.gated) launch_up_x8_t<4, true, 4, false>(L, P, x8, xscale, witem, wfirst, alist, H, nullptr, nullptr, grid, s);
+    else if (H8) launch_up_x8_t<8, false, 4, true>(L, P, x8, xscale, witem, wfirst, alist, H, H8, hs8, grid, s);
     else launch_up_x8_t<8, false, 4, false>(L, P, x8, xscale, witem, wfirst, alist, H, nullptr, nullptr, grid, s);
 }
 

@@ -44,12 +44,12 @@ def _check(oracle, layer, x, mask, got, dtype):
 
 
 # 8-bit down-projection: gated experts of 64 (ragged token counts, expert counts that are not a
-# multiple of the four-expert rotation or of the 32-expert mask batch), experts of 48 in rows of
-# 64, plain experts of 64; in-place quantisation + bf16 kernels: rows of 32, of 128, one-tile
-# experts; batches of at most 16 tokens
+# multiple of the four-unit rotation or of the 32-expert mask batch), experts of 48 in rows of
+# 64, plain experts of 64, plain experts of 128 (two units of 64 per expert); in-place
+# quantisation + bf16 kernels: rows of 32, one-tile experts; batches of at most 16 tokens
 SHAPES = [("cfg4", 300, 16), ("cfg4", 700, 8), ("cfg4", 129, 37), ("cfg4", 1000, 70), ("cfg4", 17, 16),
           ("cfg4", 16, 64), ("cfg4", 5, 16), ("cfg4", 1, 16), ("cfg4", 200, 600), ("cfg4", 70, 1),
-          ("cfg2", 300, 32), ("paper", 260, 8), ("gemma_paper", 200, 64), ("cfg5b", 9, None)]
+          ("cfg2", 300, 32), ("paper", 260, 8), ("paper", 1000, None), ("paper", 130, 37), ("paper", 9, 5), ("gemma_paper", 200, 64), ("cfg5b", 9, None)]
 
 
 @pytest.mark.parametrize("name,T,E", SHAPES)

@@ -10,7 +10,7 @@ and the output of sampled tokens against the oracle's experts on that mask."""
 import numpy as np
 import pytest
 
-from helpers import TOL, oracle_ffn, tokenwise_rel_err
+from helpers import TOL, check_fully_8bit, oracle_ffn, tokenwise_rel_err
 from paper_2310_04361_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -84,6 +84,44 @@ def test_random_layer_matches_oracle(B, oracle, i):
     err = tokenwise_rel_err(got[idx], ref_y)
     print(f"  density={ref_mask.mean():.3f} err={err:.3e}", flush=True)
     assert err <= TOL[cfg.dtype]
+
+
+@pytest.mark.parametrize("fmt", ["x8", "a8"])
+@pytest.mark.parametrize("i", range(0, N_CASES, 3))
+def test_random_layer_with_8bit_activations(B, oracle, i, fmt):
+    """Every third draw again with 8-bit expert inputs (x8) and with 8-bit hidden activations as
+    well (a8): whatever kernels the shape selects, the layer must compute the format's
+    definition -- the oracle's experts on the oracle's quantised rows."""
+    import torch
+    cfg, tau, k, _ = draw_case(i + 1)   # the ragged few-hundred-token draws, mostly
+    print(f"random 8-bit layer {i + 1} ({fmt}): T={cfg.T} d={cfg.d} E={cfg.E} m={cfg.m} gated={cfg.gated} "
+          f"act={cfg.act} tau={tau} k={k}", flush=True)
+    layer = wl.quantize_experts_e4m3(wl.make_layer(cfg, i))
+    layer["x8"] = True
+    if fmt == "a8":
+        layer["a8"] = True
+    x = wl.make_input(cfg, i)
+    L = B.Layer(layer, cfg.dtype)
+    y, ex = B.dmoe_forward(L, B.to_device(x, cfg.dtype), tau, want_scores=True, want_mask=True, top_k=k)
+    torch.cuda.synchronize()
+    s = ex["scores"].cpu().numpy().astype(np.float64)
+    ref_mask = oracle.select(s, tau)[0] if k is None else oracle.select_topk(s, k)
+    assert np.array_equal(B.mask_bits_to_bool(ex["mask_bits"], cfg.E), ref_mask)
+    got = B.from_device(y, cfg.dtype)
+    assert np.isfinite(got).all()
+    rng = np.random.default_rng(i)
+    idx = np.unique(np.concatenate([[t for t in (0, 15, 16, 63, 64, cfg.T - 1) if t < cfg.T],
+                                    rng.choice(cfg.T, min(32, cfg.T), replace=False)]))
+    xq, _ = oracle.quantize_rows_e4m3(x[idx])
+    ref = oracle_ffn(oracle, layer, xq, ref_mask[idx], quantize_h=(fmt == "a8"))
+    if fmt == "a8":
+        err, n_allow = check_fully_8bit(oracle, layer, xq, ref_mask[idx], got[idx], ref, TOL[cfg.dtype],
+                                        max_share=0.05)
+        print(f"  density={ref_mask.mean():.3f} err={err:.3e} tokens on the one-step allowance: {n_allow}", flush=True)
+    else:
+        err = tokenwise_rel_err(got[idx], ref)
+        print(f"  density={ref_mask.mean():.3f} err={err:.3e}", flush=True)
+        assert err <= TOL[cfg.dtype]
 
 
 @pytest.mark.parametrize("T,d,E,m,gated", [(300, 4096, 16, 64, True), (9, 4096, 16, 64, True),

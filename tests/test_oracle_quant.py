@@ -163,3 +163,39 @@ def test_recomposed_from_the_pinned_pieces(oracle):
     # the quantisation is visible against the unquantised layer
     plain = oracle.expert_ffn(x, w_up, w_gate, None, w_down, None, mask, "gelu_tanh", True)
     assert np.abs(got - plain).max() > 1e-3 * np.abs(plain).max()
+
+
+def test_the_one_step_allowance_accepts_a_planted_step_and_rejects_more(oracle):
+    """The bar for 8-bit hidden activations (helpers.check_fully_8bit) on the CPU: a result that
+    differs from the oracle's by ONE E4M3 step of one hidden activation passes although it misses
+    the plain tolerance; five steps on the same activation, or a one-step difference on every
+    token, do not."""
+    from helpers import check_fully_8bit, oracle_ffn, quantised_hidden_row
+    rng = np.random.default_rng(5)
+    E, m, d, T = 3, 8, 16, 40
+    layer = dict(w_up=rng.standard_normal((E, m, d)), w_gate=rng.standard_normal((E, m, d)), b_up=None,
+                 w_down=rng.standard_normal((E, m, d)), b_down=None, act="gelu_tanh", gated=True)
+    x = rng.standard_normal((T, d))
+    xq, _ = oracle.quantize_rows_e4m3(x)
+    mask = np.zeros((T, E), np.uint8)
+    mask[:, 1] = 1                                   # one expert per token: a step weighs most
+    ref = oracle_ffn(oracle, layer, xq, mask, quantize_h=True)
+    # token 7: its largest hidden activation one E4M3 step up (the spacing at that magnitude)
+    hq = quantised_hidden_row(oracle, layer, xq[7], 1)
+    j = int(np.abs(hq).argmax())
+    step = np.exp2(np.floor(np.log2(abs(hq[j]))) - 3)
+    tol = 1e-3
+    planted = ref.copy()
+    planted[7] += step * layer["w_down"][1, j]
+    assert np.abs(planted[7] - ref[7]).max() / np.abs(ref[7]).max() > tol      # misses the plain bar
+    err, n_allow = check_fully_8bit(oracle, layer, xq, mask, planted, ref, tol, max_share=0.05)
+    assert n_allow == 1 and err > tol
+    worse = ref.copy()
+    worse[7] += 5 * step * layer["w_down"][1, j]
+    with pytest.raises(AssertionError):
+        check_fully_8bit(oracle, layer, xq, mask, worse, ref, tol, max_share=0.05)
+    everywhere = ref.copy()
+    for t in range(T):
+        everywhere[t] += 0.01 * np.abs(ref[t]).max()
+    with pytest.raises(AssertionError):              # too many tokens would need the allowance
+        check_fully_8bit(oracle, layer, xq, mask, everywhere, ref, tol, max_share=0.05)

@@ -444,11 +444,17 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
 // kernel a weight stream.  Here a workgroup of four wavefronts owns 4 x 16*TT consecutive list
 // rows of one expert and shares each K block of the weight fragments through LDS (double
 // buffered, one barrier per block); the x rows stay private to their wavefront as above.
+//
+// The K blocks of all the items of a workgroup form one stream: while block k is multiplied,
+// block k+1 waits in LDS or is on its way there and the loads of block k+2 are in flight -- also
+// across the end of an item, so that the first blocks of the next item arrive during the
+// activation epilogue of the current one instead of after it (an item is only 12 to 32 blocks
+// long, and a round trip beyond L2 takes as long as two or three blocks).
 template <int MT, bool GATED, int TT>
 __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
     const __bf16* __restrict__ x, const __bf16* __restrict__ wupf,
     const __bf16* __restrict__ wgatef, const __bf16* __restrict__ b_up,
-    const int32_t* __restrict__ witem, const int32_t* __restrict__ wfirst, int NW,
+    const int32_t* __restrict__ witem, const int32_t* __restrict__ wfirst,
     const int32_t* __restrict__ alist, __bf16* __restrict__ Hf, int d, int E, int m, int act) {
     constexpr int BR = GATED ? 2 : 1;
     constexpr int KS = MT / 2;
@@ -457,85 +463,102 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
     constexpr int UR = 4 * WR;          // rows per work item
     constexpr int NL = TT * 2;          // x load instructions per K block
     constexpr int NWF = 2 * NT;         // weight fragments (1 KiB each) per K block
-    static_assert(NWF % 4 == 0, "weight fragments are copied four at a time");
+    constexpr int NWL = NWF / 4;        // ... of which each wavefront copies every fourth
+    static_assert(NWF % 4 == 0 && MT % 2 == 0, "weight fragments are copied four at a time");
     extern __shared__ char smem[];
     char* wbuf = smem;                                   // [2][NWF][1024]
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15, w = threadIdx.x >> 6;
     char* xs = smem + 2 * NWF * 1024 + w * (WR * kUpRowBytes);   // [WR][kUpRowBytes], private
-    float* sbias = reinterpret_cast<float*>(smem + 2 * NWF * 1024 + 4 * (WR * kUpRowBytes));  // [MT * 16]
-    const int NK32 = d / 32, NKB = d / 64;
+    float* sbias = reinterpret_cast<float*>(smem + 2 * NWF * 1024 + 4 * (WR * kUpRowBytes));  // [2][MT * 16]
+    const int NK32 = d / 32, NKB = d / 64;   // NKB >= 2
     const int ld_row = lane >> 3, ld_piece = lane & 7;
-    // windows as in the kernel above: XCD k takes the windows k, k+8, ...; a single window is
-    // shared by all workgroups
-    const bool windowed = NW > 1;
-    const int wg = windowed ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
-    const int n_wg = windowed ? (int)(gridDim.x >> 3) : (int)gridDim.x;
-    for (int wdx = windowed ? (int)(blockIdx.x & 7) : 0; wdx < NW; wdx += 8) {
-    const int32_t* wit = witem + (size_t)wdx * (E + 1);
-    const int total = wit[E];
-    for (int j = wg; j < total; j += n_wg) {
-        // expert of this item: the last e with wit[e] <= j (uniform binary search)
+    const int total = witem[E];
+    int j = blockIdx.x;
+    if (j >= total) return;
+
+    // item j: its expert is the last e with witem[e] <= j (uniform binary search)
+    auto locate = [&](int jj, int& e, int& item) {
         int lo = 0, hi = E;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (wit[mid] <= j) lo = mid; else hi = mid;
+            if (witem[mid] <= jj) lo = mid; else hi = mid;
         }
-        const int e = lo;
-        const int item = wfirst[(size_t)wdx * E + e] + (j - wit[e]);
-        const int32_t* tl = alist + (size_t)item * UR + w * WR + ld_row;
-        const bool active = alist[(size_t)item * UR + w * WR] >= 0;  // valid rows are a prefix
-        const __bf16* xrow[NL];
+        e = lo;
+        item = wfirst[lo] + (jj - witem[lo]);
+    };
+    // tokens of the x rows this lane fetches; padding rows (-1) read token 0 and produce H rows
+    // that nobody merges
+    auto rows_of = [&](int item, uint32_t (&xoff)[NL], bool& active) {
+        const int32_t* tl = alist + (size_t)item * UR + w * WR;
+        active = tl[0] >= 0;  // valid rows are a prefix
 #pragma unroll
-        for (int i = 0; i < NL; ++i) xrow[i] = x + (size_t)max(tl[8 * i], 0) * d + 8 * ld_piece;
-        // weight fragment f = (br*MT + mt)*2 + ks of K block kb; thread copies piece (f % 4 == w)
-        const __bf16* wsrc[NWF / 4];
+        for (int i = 0; i < NL; ++i)
+            xoff[i] = (uint32_t)max(tl[ld_row + 8 * i], 0);
+    };
+    // Weight fragment f = (br * MT + mt) * 2 + ks of a K block; this wavefront copies the
+    // fragments f = 4 i + w: ks = w & 1, mt = (2 i) % MT + (w >> 1), br = (2 i) / MT.
+    const uint32_t woff = (uint32_t)(((w >> 1) * NK32 + (w & 1)) * 512 + lane * 8);
+    bf16x8 xr[NL], wr[NWL];
+    auto issue = [&](int e, const uint32_t (&xoff)[NL], bool active, int kb) {
+        const size_t we = (size_t)e * MT * NK32 * 512 + (size_t)kb * 1024 + woff;
 #pragma unroll
-        for (int i = 0; i < NWF / 4; ++i) {
-            const int f = 4 * i + w, ks = f & 1, tile = f >> 1, br = tile / MT, mt = tile % MT;
-            const __bf16* base = (GATED && br == BR - 1) ? wgatef : wupf;
-            wsrc[i] = base + (((size_t)e * MT + mt) * NK32 + ks) * 512 + lane * 8;
+        for (int i = 0; i < NWL; ++i) {
+            const __bf16* base = (GATED && (2 * i) / MT == BR - 1) ? wgatef : wupf;
+            wr[i] = load8(base + we + (size_t)((2 * i) % MT) * NK32 * 512);
         }
+        if (active) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                xr[i] = load8(x + ((size_t)xoff[i] * (uint32_t)d + (uint32_t)(8 * ld_piece + 64 * kb)));
+        }
+    };
+    auto park = [&](int buf, bool active) {
+#pragma unroll
+        for (int i = 0; i < NWL; ++i)
+            *reinterpret_cast<bf16x8*>(wbuf + buf * NWF * 1024 + (4 * i + w) * 1024 + lane * 16) = wr[i];
+        if (active) {
+            char* dst = xs + ld_row * kUpRowBytes + ld_piece * 16;
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
+        }
+    };
+    auto park_bias = [&](int e, int par) {  // plain experts: the item's biases, by neuron
+        if (!GATED && (int)threadIdx.x < MT * 16)
+            sbias[par * MT * 16 + threadIdx.x] =
+                b_up ? (float)b_up[(size_t)e * m + min((int)threadIdx.x, m - 1)] : 0.0f;
+    };
+
+    int e, item;
+    uint32_t xoff[NL];
+    bool active;
+    locate(j, e, item);
+    rows_of(item, xoff, active);
+    issue(e, xoff, active, 0);
+    park(0, active);
+    park_bias(e, 0);
+    __syncthreads();
+    issue(e, xoff, active, 1);
+    int buf = 0, par = 0;
+    for (;;) {
+        // the item after this one (the last item names itself: its first blocks are read again
+        // and never used)
+        const int jn = j + (int)gridDim.x;
+        const bool more = jn < total;
+        int en = e, itemn = item;
+        if (more) locate(jn, en, itemn);
+        uint32_t xoffn[NL];
+        bool activen;
+        rows_of(itemn, xoffn, activen);
 
         f32x4 acc[NT][TT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) acc[nt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        // bias of neuron threadIdx.x of a plain expert: requested with the first loads, parked in
-        // LDS once they have arrived, read back in the epilogue (no registers held for it)
-        float bias_reg = 0.0f;
-        if (!GATED && b_up && (int)threadIdx.x < MT * 16)
-            bias_reg = (float)b_up[(size_t)e * m + min((int)threadIdx.x, m - 1)];
-
-        bf16x8 xr[NL], wr[NWF / 4];
-        auto load_next = [&](int kb) {
-#pragma unroll
-            for (int i = 0; i < NWF / 4; ++i) wr[i] = load8(wsrc[i] + (size_t)kb * 1024);
+        auto multiply = [&]() {
             if (active) {
-#pragma unroll
-                for (int i = 0; i < NL; ++i) xr[i] = load8(xrow[i] + 64 * kb);
-            }
-        };
-        auto store_next = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < NWF / 4; ++i)
-                *reinterpret_cast<bf16x8*>(wbuf + buf * NWF * 1024 + (4 * i + w) * 1024 + lane * 16) = wr[i];
-            if (active) {
-                char* dst = xs + ld_row * kUpRowBytes + ld_piece * 16;
-#pragma unroll
-                for (int i = 0; i < NL; ++i)
-                    *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
-            }
-        };
-        __syncthreads();  // the previous item's last K block has been consumed by every wavefront
-        load_next(0);
-        store_next(0);
-        if (!GATED && (int)threadIdx.x < MT * 16) sbias[threadIdx.x] = bias_reg;
-        __syncthreads();
-        for (int kb = 0; kb < NKB; ++kb) {
-            load_next(min(kb + 1, NKB - 1));  // the last trip re-reads a block it will not use
-            if (active) {
-                const char* wsrc_l = wbuf + (kb & 1) * NWF * 1024 + lane * 16;
+                const char* wsrc_l = wbuf + buf * NWF * 1024 + lane * 16;
                 const char* xsrc = xs + c * kUpRowBytes + q * 16;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
@@ -551,11 +574,29 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
                     }
                 }
             }
-            store_next((kb + 1) & 1);
+        };
+        // block kb is in LDS buffer `buf`, block kb + 1 in flight to the registers
+        for (int kb = 0; kb < NKB - 2; ++kb) {
+            multiply();
+            park(buf ^ 1, active);
             __syncthreads();
+            buf ^= 1;
+            issue(e, xoff, active, kb + 2);
         }
+        multiply();                    // block NKB - 2
+        park(buf ^ 1, active);
+        __syncthreads();
+        buf ^= 1;
+        issue(en, xoffn, activen, 0);
+        multiply();                    // block NKB - 1; the next item's block 0 arrives
+        park(buf ^ 1, activen);
+        park_bias(en, par ^ 1);
+        __syncthreads();
+        buf ^= 1;
+        issue(en, xoffn, activen, 1);
 
         if (active) {
+            const float* sb = sbias + par * MT * 16;
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 __bf16* dst = Hf + ((size_t)item * UR + w * WR + 16 * tt + c) * (KS * 32) + 8 * q;
@@ -569,7 +610,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
                         for (int r = 0; r < 4; ++r) {
                             float v;
                             if (GATED) v = activate_fast(act, acc[MT + mt][tt][r]) * acc[mt][tt][r];
-                            else v = activate_fast(act, acc[mt][tt][r] + sbias[neuron_of_slot(mt, 4 * q + r)]);
+                            else v = activate_fast(act, acc[mt][tt][r] + sb[neuron_of_slot(mt, 4 * q + r)]);
                             if (neuron_of_slot(mt, 4 * q + r) >= m) v = 0.0f;
                             hv[half * 4 + r] = (__bf16)v;
                         }
@@ -578,8 +619,15 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
                 }
             }
         }
+        if (!more) break;
+        j = jn;
+        e = en;
+        item = itemn;
+        active = activen;
+        par ^= 1;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) xoff[i] = xoffn[i];
     }
-    }  // windows
 }
 
 // ---- launchers ---------------------------------------------------------------------------------------
@@ -603,10 +651,10 @@ void launch_up_t(const dmoe_layer& L, const void* x, const PackedLayout& P, cons
 
 template <int MT, bool GATED, int TT>
 void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
-                      const int32_t* witem, const int32_t* wfirst, int NW, const int32_t* alist,
+                      const int32_t* witem, const int32_t* wfirst, const int32_t* alist,
                       void* H, int grid, hipStream_t s) {
     constexpr int NWF = 2 * (GATED ? 2 : 1) * MT;
-    const size_t lds = 2 * NWF * 1024 + 4 * (size_t)TT * 16 * kUpRowBytes + MT * 16 * sizeof(float);
+    const size_t lds = 2 * NWF * 1024 + 4 * (size_t)TT * 16 * kUpRowBytes + 2 * MT * 16 * sizeof(float);
     static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
     std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_wide_bf16_kernel<MT, GATED, TT>),
@@ -615,7 +663,7 @@ void launch_up_wide_t(const dmoe_layer& L, const void* x, const PackedLayout& P,
     const char* pk = static_cast<const char*>(L.packed);
     launch_kernel(up_wide_bf16_kernel<MT, GATED, TT>, grid, 256, lds, s, 
         (const __bf16*)x, (const __bf16*)(pk + P.wupf), (const __bf16*)(pk + P.wgatef),
-        (const __bf16*)L.b_up, witem, wfirst, NW, alist, (__bf16*)H, L.d_model, L.n_experts,
+        (const __bf16*)L.b_up, witem, wfirst, alist, (__bf16*)H, L.d_model, L.n_experts,
         L.expert_size, L.act);
 }
 
@@ -701,8 +749,8 @@ void launch_up_bf16(const dmoe_layer& L, const void* x, int T, const int32_t* wi
     if (up_rows_bf16(L) == 256) {  // wide experts: weights shared through LDS
         const int wgrid = round_up(
             (int)std::min<long long>((long long)T * L.n_experts / 256 + L.n_experts, 512), 8);
-        if (L.gated) launch_up_wide_t<4, true, 4>(L, x, P, witem, wfirst, NW, alist, H, wgrid, s);
-        else launch_up_wide_t<8, false, 4>(L, x, P, witem, wfirst, NW, alist, H, wgrid, s);
+        if (L.gated) launch_up_wide_t<4, true, 4>(L, x, P, witem, wfirst, alist, H, wgrid, s);
+        else launch_up_wide_t<8, false, 4>(L, x, P, witem, wfirst, alist, H, wgrid, s);
         return;
     }
     if (up_tiny_supported(L)) {

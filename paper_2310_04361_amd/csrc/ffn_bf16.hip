@@ -547,9 +547,6 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
         const bool more = jn < total;
         int en = e, itemn = item;
         if (more) locate(jn, en, itemn);
-        uint32_t xoffn[NL];
-        bool activen;
-        rows_of(itemn, xoffn, activen);
 
         f32x4 acc[NT][TT];
 #pragma unroll
@@ -583,6 +580,12 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
             buf ^= 1;
             issue(e, xoff, active, kb + 2);
         }
+        // The next item's rows are requested here, two blocks before the end: vector loads return
+        // in order, so requested any later they would queue behind the next item's first blocks,
+        // and any earlier their wait would hold up this item's start.
+        uint32_t xoffn[NL];
+        bool activen;
+        rows_of(itemn, xoffn, activen);
         multiply();                    // block NKB - 2
         park(buf ^ 1, active);
         __syncthreads();

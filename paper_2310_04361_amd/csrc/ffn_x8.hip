@@ -166,76 +166,98 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
     char* wbuf = smem;                                            // [2][NT][64][32]
     const int lane = threadIdx.x & 63, q = lane >> 4, c = lane & 15, w = threadIdx.x >> 6;
     char* xs = smem + 2 * NT * 2048 + w * (WR * kX8RowBytes);     // [WR][kX8RowBytes], private
-    float* sbias = reinterpret_cast<float*>(smem + 2 * NT * 2048 + 4 * (WR * kX8RowBytes));  // [MT * 16]
-    const int NKB = d / 128;
+    float* sbias = reinterpret_cast<float*>(smem + 2 * NT * 2048 + 4 * (WR * kX8RowBytes));  // [2][MT * 16]
+    const int NKB = d / 128;   // >= 2
     const int ld_row = lane >> 3, ld_piece = lane & 7;
     const int total = witem[E];
-    for (int j = blockIdx.x; j < total; j += gridDim.x) {
-        // expert of this item: the last e with witem[e] <= j (uniform binary search)
+    int j = blockIdx.x;
+    if (j >= total) return;
+
+    // item j: its expert is the last e with witem[e] <= j (uniform binary search)
+    auto locate = [&](int jj, int& e, int& item) {
         int lo = 0, hi = E;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (witem[mid] <= j) lo = mid; else hi = mid;
+            if (witem[mid] <= jj) lo = mid; else hi = mid;
         }
-        const int e = lo;
-        const int item = wfirst[e] + (j - witem[e]);
+        e = lo;
+        item = wfirst[lo] + (jj - witem[lo]);
+    };
+    // tokens of the x rows this lane fetches; padding rows (-1) read token 0 and produce H rows
+    // that nobody merges
+    auto rows_of = [&](int item, uint32_t (&xtok)[NL], bool& active) {
         const int32_t* tl = alist + (size_t)item * UR + w * WR;
-        const bool active = tl[0] >= 0;  // valid rows are a prefix
-        // x rows as offsets in 16-byte units (T * d / 16 fits 32 bits); padding rows (-1) read
-        // token 0 and produce H rows that nobody merges
-        uint32_t xoff[NL];
+        active = tl[0] >= 0;  // valid rows are a prefix
 #pragma unroll
-        for (int i = 0; i < NL; ++i)
-            xoff[i] = (uint32_t)(((size_t)max(tl[ld_row + 8 * i], 0) * d) >> 4) + ld_piece;
-        // The K block's weights are NT tiles of 2 KiB; this thread copies the 16-byte pieces
-        // tid, tid + 256, ...: piece 256 i + tid belongs to tile 2i + (tid >> 7), the first MT of
-        // which are up rows and the rest gate rows -- one base per matrix plus i times a stride.
-        const size_t wpiece = ((size_t)e * MT + (threadIdx.x >> 7)) * NKB * 2048 + (threadIdx.x & 127) * 16;
-        const uint8_t* wbase_up = wupx + wpiece;
-        const uint8_t* wbase_gate = GATED ? wgatex + wpiece : wupx;
-        const size_t wstride = (size_t)2 * NKB * 2048;   // two neuron tiles on
+        for (int i = 0; i < NL; ++i) xtok[i] = (uint32_t)max(tl[ld_row + 8 * i], 0);
+    };
+    // The K block's weights are NT tiles of 2 KiB; this thread copies the 16-byte pieces
+    // tid, tid + 256, ...: piece 256 i + tid belongs to tile 2i + (tid >> 7), the first MT of
+    // which are up rows and the rest gate rows -- one base per matrix plus i times a stride.
+    const uint32_t wlane = (uint32_t)((threadIdx.x >> 7) * NKB * 2048 + (threadIdx.x & 127) * 16);
+    const size_t wstride = (size_t)2 * NKB * 2048;   // two neuron tiles on
+    i32x4 xr[NL], wr[NWL];
+    auto issue = [&](int e, const uint32_t (&xtok)[NL], bool active, int kb) {
+        const size_t we = (size_t)e * MT * NKB * 2048 + (size_t)kb * 2048 + wlane;
+#pragma unroll
+        for (int i = 0; i < NWL; ++i)
+            wr[i] = *reinterpret_cast<const i32x4*>(((GATED && i >= MT / 2) ? wgatex : wupx) + we +
+                                                    (i % (MT / 2)) * wstride);
+        if (active) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                xr[i] = *reinterpret_cast<const i32x4*>(
+                    x8 + ((size_t)xtok[i] * (uint32_t)d + (uint32_t)(16 * ld_piece + 128 * kb)));
+        }
+    };
+    auto park = [&](int buf, bool active) {
+#pragma unroll
+        for (int i = 0; i < NWL; ++i)
+            *reinterpret_cast<i32x4*>(wbuf + buf * NT * 2048 + (256 * i + threadIdx.x) * 16) = wr[i];
+        if (active) {
+            char* dst = xs + ld_row * kX8RowBytes + ld_piece * 16;
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                *reinterpret_cast<i32x4*>(dst + 8 * i * kX8RowBytes) = xr[i];
+        }
+    };
+    auto park_bias = [&](int e, int par) {  // plain experts: the item's biases, by neuron
+        if (!GATED && (int)threadIdx.x < MT * 16)
+            sbias[par * MT * 16 + threadIdx.x] =
+                b_up ? (float)b_up[(size_t)e * m + min((int)threadIdx.x, m - 1)] : 0.0f;
+    };
+
+    // The K blocks of all the items of the workgroup form one stream: block k is multiplied while
+    // block k + 1 waits in LDS or is on its way there and block k + 2 is in flight, also across
+    // the end of an item -- the next item's first blocks arrive during this item's epilogue.
+    int e, item;
+    uint32_t xtok[NL];
+    bool active;
+    locate(j, e, item);
+    rows_of(item, xtok, active);
+    issue(e, xtok, active, 0);
+    park(0, active);
+    park_bias(e, 0);
+    __syncthreads();
+    issue(e, xtok, active, 1);
+    int buf = 0, par = 0;
+    for (;;) {
+        // the item after this one (the last item names itself: its first blocks are read again
+        // and never used)
+        const int jn = j + (int)gridDim.x;
+        const bool more = jn < total;
+        int en = e, itemn = item;
+        if (more) locate(jn, en, itemn);
+        const int32_t* tl = alist + (size_t)item * UR + w * WR;
 
         f32x4 acc[NT][TT];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) acc[nt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        float bias_reg = 0.0f;
-        if (!GATED && b_up && (int)threadIdx.x < MT * 16)
-            bias_reg = (float)b_up[(size_t)e * m + min((int)threadIdx.x, m - 1)];
-
-        i32x4 xr[NL], wr[NWL];
-        auto load_next = [&](int kb) {
-#pragma unroll
-            for (int i = 0; i < NWL; ++i)
-                wr[i] = *reinterpret_cast<const i32x4*>((i < MT / 2 ? wbase_up : wbase_gate) +
-                                                        (i % (MT / 2)) * wstride + (size_t)kb * 2048);
+        auto multiply = [&]() {
             if (active) {
-#pragma unroll
-                for (int i = 0; i < NL; ++i)
-                    xr[i] = *reinterpret_cast<const i32x4*>(x8 + (((size_t)xoff[i] + 8 * kb) << 4));
-            }
-        };
-        auto store_next = [&](int buf) {
-#pragma unroll
-            for (int i = 0; i < NWL; ++i)
-                *reinterpret_cast<i32x4*>(wbuf + buf * NT * 2048 + (256 * i + threadIdx.x) * 16) = wr[i];
-            if (active) {
-                char* dst = xs + ld_row * kX8RowBytes + ld_piece * 16;
-#pragma unroll
-                for (int i = 0; i < NL; ++i)
-                    *reinterpret_cast<i32x4*>(dst + 8 * i * kX8RowBytes) = xr[i];
-            }
-        };
-        __syncthreads();  // the previous item's last K block has been consumed by every wavefront
-        load_next(0);
-        store_next(0);
-        if (!GATED && (int)threadIdx.x < MT * 16) sbias[threadIdx.x] = bias_reg;
-        __syncthreads();
-        for (int kb = 0; kb < NKB; ++kb) {
-            load_next(min(kb + 1, NKB - 1));  // the last trip re-reads a block it will not use
-            if (active) {
-                const char* wsrc_l = wbuf + (kb & 1) * NT * 2048 + lane * 32;
+                const char* wsrc_l = wbuf + buf * NT * 2048 + lane * 32;
                 const char* xsrc = xs + c * kX8RowBytes + q * 32;
                 i32x8 b[TT];
 #pragma unroll
@@ -253,9 +275,38 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
                     for (int tt = 0; tt < TT; ++tt) acc[nt][tt] = mfma128(a, b[tt], acc[nt][tt]);
                 }
             }
-            store_next((kb + 1) & 1);
+        };
+        // block kb is in LDS buffer `buf`, block kb + 1 in flight to the registers
+        for (int kb = 0; kb < NKB - 2; ++kb) {
+            multiply();
+            park(buf ^ 1, active);
             __syncthreads();
+            buf ^= 1;
+            issue(e, xtok, active, kb + 2);
         }
+        // The next item's rows and this item's row scales are requested here, two blocks before
+        // the end: vector loads return in order, so requested any later they would queue behind
+        // the next item's first blocks, and any earlier their wait would hold up this item's start.
+        uint32_t xtokn[NL];
+        bool activen;
+        rows_of(itemn, xtokn, activen);
+        int tok_c[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) tok_c[tt] = max(tl[16 * tt + c], 0);
+        multiply();                    // block NKB - 2
+        park(buf ^ 1, active);
+        __syncthreads();
+        buf ^= 1;
+        float s_xr[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) s_xr[tt] = xscale[tok_c[tt]];
+        issue(en, xtokn, activen, 0);
+        multiply();                    // block NKB - 1; the next item's block 0 arrives
+        park(buf ^ 1, activen);
+        park_bias(en, par ^ 1);
+        __syncthreads();
+        buf ^= 1;
+        issue(en, xtokn, activen, 1);
 
         if (active) {
             // lane (q, c) of tile (mt, tt): neurons neuron_of_slot(mt, 4q + r) of list row 16tt + c.
@@ -264,7 +315,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
             const float s_up = w_scales[3 * e + 0], s_gate = w_scales[3 * e + 1];
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                const float s_x = xscale[max(tl[16 * tt + c], 0)];
+                const float s_x = s_xr[tt];
                 const size_t row = (size_t)item * UR + w * WR + 16 * tt + c;
                 bf16x8 hv[KS];
 #pragma unroll
@@ -280,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
                                     (acc[mt][tt][r] * (s_x * s_up));
                             else
                                 v = activate_fast(act, acc[mt][tt][r] * (s_x * s_up) +
-                                                           sbias[neuron_of_slot(mt, 4 * q + r)]);
+                                                           sbias[par * MT * 16 + neuron_of_slot(mt, 4 * q + r)]);
                             if (neuron_of_slot(mt, 4 * q + r) >= m) v = 0.0f;
                             hv[ks][half * 4 + r] = (__bf16)v;
                         }
@@ -318,6 +369,14 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
                 }
             }
         }
+        if (!more) break;
+        j = jn;
+        e = en;
+        item = itemn;
+        active = activen;
+        par ^= 1;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) xtok[i] = xtokn[i];
     }
 }
 
@@ -327,7 +386,7 @@ void launch_up_x8_t(const dmoe_layer& L, const PackedLayout& P, const uint8_t* x
                     const int32_t* alist, void* H, uint8_t* H8, uint8_t* hs8, int grid,
                     hipStream_t s) {
     constexpr int NT = (GATED ? 2 : 1) * MT;
-    const size_t lds = 2 * NT * 2048 + 4 * (size_t)TT * 16 * kX8RowBytes + MT * 16 * sizeof(float);
+    const size_t lds = 2 * NT * 2048 + 4 * (size_t)TT * 16 * kX8RowBytes + 2 * MT * 16 * sizeof(float);
     static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
     std::call_once(attr_once, [&] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&up_wide_x8_kernel<MT, GATED, TT, H8OUT>),

@@ -104,7 +104,8 @@ typedef struct {
  *                                   its exponent is clamped to -100 .. 100),
  * where e4m3(.) rounds to the nearest E4M3 value, ties to the even mantissa (the largest
  * element of a row lands in (224, 448], so nothing overflows; magnitudes below 2^-10 s_t become
- * zero).  Every xq element is a bf16 number, so the layer computes what a bf16 layer with the
+ * zero; a row with an element beyond 448 * 2^100, or a non-finite one, is outside the format and
+ * its quantised values are unspecified).  Every xq element is a bf16 number, so the layer computes what a bf16 layer with the
  * same weights computes on the input xq, up to the summation: the 8-bit matrix-core instruction
  * adds the products of a 32-wide block with less than fp32 precision (measured: within 3e-4 of
  * the block's largest product).  The hidden activations and the down-projection are as in

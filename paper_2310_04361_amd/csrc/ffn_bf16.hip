@@ -563,11 +563,18 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
 #pragma unroll
                     for (int tt = 0; tt < TT; ++tt)
                         b[tt] = *reinterpret_cast<const bf16x8*>(xsrc + tt * 16 * kUpRowBytes + ks * 64);
+                    // the weight tile of the next four MFMAs is read while the current four run
+                    bf16x8 a_next = *reinterpret_cast<const bf16x8*>(wsrc_l + ks * 1024);
+                    __builtin_amdgcn_sched_group_barrier(0x100, TT + 1, 0);  // the reads so far
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt) {
-                        const bf16x8 a = *reinterpret_cast<const bf16x8*>(wsrc_l + (nt * 2 + ks) * 1024);
+                        const bf16x8 a = a_next;
+                        if (nt + 1 < NT)
+                            a_next = *reinterpret_cast<const bf16x8*>(wsrc_l + ((nt + 1) * 2 + ks) * 1024);
 #pragma unroll
                         for (int tt = 0; tt < TT; ++tt) acc[nt][tt] = mfma16(a, b[tt], acc[nt][tt]);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read ...
+                        __builtin_amdgcn_sched_group_barrier(0x008, TT, 0); // ... then the MFMAs
                     }
                 }
             }

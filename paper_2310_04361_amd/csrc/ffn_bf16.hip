@@ -167,46 +167,42 @@ __global__ __launch_bounds__(256, NBUF == 1 ? 3 : 1) void up_bf16_kernel(
         s_wit[i] = i <= E ? witem[(size_t)wdx * (E + 1) + i] : wfirst[(size_t)wdx * E + (i - E - 1)];
     __syncthreads();
     const int total = s_wit[E];
-    for (int j = wave; j < total; j += n_waves) {
-        int lo = 0, hi = E;  // last e with s_wit[e] <= j
+    // item jj: its expert is the last e with s_wit[e] <= jj
+    auto locate = [&](int jj, int& e, int& item) {
+        int lo = 0, hi = E;
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
-            if (s_wit[mid] <= j) lo = mid; else hi = mid;
+            if (s_wit[mid] <= jj) lo = mid; else hi = mid;
         }
-        const int e = lo;
-        const int item = s_wf[e] + (j - s_wit[e]);
-        // rows of the aligned list past the expert's last token hold -1: they read token 0 and
-        // produce H rows that nobody merges
-        const int32_t* tl = alist + (size_t)item * UR + ld_row;
-        // x rows as 32-bit offsets in 16-byte units (T * d / 8 fits): half the registers of pointers
+        e = lo;
+        item = s_wf[lo] + (jj - s_wit[lo]);
+    };
+    int j = wave;
+    if (j < total) {
+        int e, item;
+        locate(j, e, item);
+        // x rows as 32-bit offsets in 16-byte units (T * d / 8 fits): half the registers of
+        // pointers.  Rows of the aligned list past the expert's last token hold -1: they read
+        // token 0 and produce H rows that nobody merges.
         uint32_t xoff[NL];
+        auto rows_from = [&](const int (&tok)[NL]) {
 #pragma unroll
-        for (int i = 0; i < NL; ++i) {
-            const int tok = max(tl[8 * i], 0);
-            xoff[i] = (uint32_t)(((size_t)tok * d) >> 3) + ld_piece;
-        }
+            for (int i = 0; i < NL; ++i)
+                xoff[i] = (uint32_t)(((size_t)max(tok[i], 0) * d) >> 3) + ld_piece;
+        };
         const __bf16* wf[BR];
-        wf[0] = wupf + (size_t)e * MT * NK32 * 512 + lane * 8;
-        if (GATED) wf[BR - 1] = wgatef + (size_t)e * MT * NK32 * 512 + lane * 8;
-
-        // the accumulators start at the biases of this lane's neurons (no registers held for them
-        // through the K loop)
-        f32x4 acc[BR][MT][TT];
+        auto weights_of = [&](int ee) {
+            wf[0] = wupf + (size_t)ee * MT * NK32 * 512 + lane * 8;
+            if (GATED) wf[BR - 1] = wgatef + (size_t)ee * MT * NK32 * 512 + lane * 8;
+        };
+        {
+            const int32_t* tl = alist + (size_t)item * UR + ld_row;
+            int tok[NL];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            f32x4 bias = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (!GATED && b_up) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int n = neuron_of_slot(mt, 4 * q + r);
-                    bias[r] = (float)b_up[(size_t)e * m + min(n, m - 1)];
-                }
-            }
-#pragma unroll
-            for (int br = 0; br < BR; ++br)
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) acc[br][mt][tt] = br == 0 ? bias : f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int i = 0; i < NL; ++i) tok[i] = tl[8 * i];
+            rows_from(tok);
         }
+        weights_of(e);
 
         bf16x8 xr[NL];
         bf16x8 a0[2][BR][MT], a1[2][BR][MT];
@@ -229,65 +225,112 @@ __global__ __launch_bounds__(256, NBUF == 1 ? 3 : 1) void up_bf16_kernel(
             for (int i = 0; i < NL; ++i)
                 *reinterpret_cast<bf16x8*>(dst + 8 * i * kUpRowBytes) = xr[i];
         };
-        auto compute = [&](int buf, const bf16x8 (&a)[2][BR][MT]) {
-            const char* src = xs + (buf % NBUF) * (UR * kUpRowBytes) + c * kUpRowBytes + q * 16;
+        // The first block of an item is requested before the epilogue of the item before it (here:
+        // before anything else), so an item starts with its block 0 on the way.
+        load_x(0);
+        load_a(0, a0);
+        for (;;) {
+            // the accumulators start at the biases of this lane's neurons (no registers held for
+            // them through the K loop)
+            f32x4 acc[BR][MT][TT];
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                bf16x8 b[TT];
+            for (int mt = 0; mt < MT; ++mt) {
+                f32x4 bias = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (!GATED && b_up) {
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    b[tt] = *reinterpret_cast<const bf16x8*>(src + tt * 16 * kUpRowBytes + ks * 64);
+                    for (int r = 0; r < 4; ++r) {
+                        const int n = neuron_of_slot(mt, 4 * q + r);
+                        bias[r] = (float)b_up[(size_t)e * m + min(n, m - 1)];
+                    }
+                }
 #pragma unroll
                 for (int br = 0; br < BR; ++br)
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                        for (int tt = 0; tt < TT; ++tt)
-                            acc[br][mt][tt] = mfma16(a[ks][br][mt], b[tt], acc[br][mt][tt]);
+                    for (int tt = 0; tt < TT; ++tt) acc[br][mt][tt] = br == 0 ? bias : f32x4{0.f, 0.f, 0.f, 0.f};
             }
-        };
+            auto compute = [&](int buf, const bf16x8 (&a)[2][BR][MT]) {
+                const char* src = xs + (buf % NBUF) * (UR * kUpRowBytes) + c * kUpRowBytes + q * 16;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    bf16x8 b[TT];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        b[tt] = *reinterpret_cast<const bf16x8*>(src + tt * 16 * kUpRowBytes + ks * 64);
+#pragma unroll
+                    for (int br = 0; br < BR; ++br)
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int tt = 0; tt < TT; ++tt)
+                                acc[br][mt][tt] = mfma16(a[ks][br][mt], b[tt], acc[br][mt][tt]);
+                }
+            };
 
-        load_x(0);
-        load_a(0, a0);
-        store_x(0);
-        // two K blocks per trip so that the two weight-fragment register sets simply alternate
-        for (int kb = 0; kb < NKB; kb += 2) {
-            load_x(kb + 1);
-            load_a(kb + 1, a1);
+            store_x(0);
+            // two K blocks per trip so that the two weight-fragment register sets simply alternate
+            for (int kb = 0; kb < NKB - 2; kb += 2) {
+                load_x(kb + 1);
+                load_a(kb + 1, a1);
+                compute(0, a0);
+                store_x(1);
+                load_x(kb + 2);
+                load_a(kb + 2, a0);
+                compute(1, a1);
+                store_x(0);
+            }
+            // Last trip: its second set of requests is block 0 of the wavefront's NEXT item (the
+            // last item names itself: the block is read and never used), whose list rows are
+            // requested together with this item's last block, once its own offsets are done with.
+            load_x(NKB - 1);
+            load_a(NKB - 1, a1);
+            const int jn = j + n_waves;
+            const bool more = jn < total;
+            int en = e, itemn = item;
+            if (more) locate(jn, en, itemn);
+            int tokn[NL];
+            {
+                const int32_t* tl = alist + (size_t)itemn * UR + ld_row;
+#pragma unroll
+                for (int i = 0; i < NL; ++i) tokn[i] = tl[8 * i];
+            }
             compute(0, a0);
             store_x(1);
-            const int nb = min(kb + 2, NKB - 1);  // the last trip re-reads a block it will not use
-            load_x(nb);
-            load_a(nb, a0);
+            rows_from(tokn);
+            weights_of(en);
+            load_x(0);
+            load_a(0, a0);
             compute(1, a1);
-            store_x(0);
-        }
 
-        // lane (q, c) of tile (mt, tt): neurons 16mt + 4q + r of list row 16tt + c
+            // lane (q, c) of tile (mt, tt): neurons 16mt + 4q + r of list row 16tt + c
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            __bf16* dst = Hf + ((size_t)item * UR + 16 * tt + c) * (KS * 32) + 8 * q;
+            for (int tt = 0; tt < TT; ++tt) {
+                __bf16* dst = Hf + ((size_t)item * UR + 16 * tt + c) * (KS * 32) + 8 * q;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                bf16x8 hv;
+                for (int ks = 0; ks < KS; ++ks) {
+                    bf16x8 hv;
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int mt = 2 * ks + half;
-                    const int n0 = neuron_of_slot(mt, 4 * q);  // + r: consecutive
+                    for (int half = 0; half < 2; ++half) {
+                        const int mt = 2 * ks + half;
+                        const int n0 = neuron_of_slot(mt, 4 * q);  // + r: consecutive
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float v;
-                        if (GATED) {
-                            v = activate_fast(act, acc[BR - 1][mt][tt][r]) * acc[0][mt][tt][r];
-                        } else {
-                            v = activate_fast(act, acc[0][mt][tt][r]);
+                        for (int r = 0; r < 4; ++r) {
+                            float v;
+                            if (GATED) {
+                                v = activate_fast(act, acc[BR - 1][mt][tt][r]) * acc[0][mt][tt][r];
+                            } else {
+                                v = activate_fast(act, acc[0][mt][tt][r]);
+                            }
+                            if (n0 + r >= m) v = 0.0f;
+                            hv[half * 4 + r] = (__bf16)v;
                         }
-                        if (n0 + r >= m) v = 0.0f;
-                        hv[half * 4 + r] = (__bf16)v;
                     }
+                    *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
                 }
-                *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
             }
+            if (!more) break;
+            j = jn;
+            e = en;
+            item = itemn;
         }
     }
     }  // windows

@@ -595,7 +595,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
     issue(e, xoff, active, 0);
     park(0, active);
     park_bias(e, 0);
-    __syncthreads();
+    lds_barrier();
     issue(e, xoff, active, 1);
     int buf = 0, par = 0;
     for (;;) {
@@ -641,7 +641,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
         for (int kb = 0; kb < NKB - 2; ++kb) {
             multiply();
             park(buf ^ 1, active);
-            __syncthreads();
+            lds_barrier();
             buf ^= 1;
             issue(e, xoff, active, kb + 2);
         }
@@ -653,13 +653,13 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
         rows_of(itemn, xoffn, activen);
         multiply();                    // block NKB - 2
         park(buf ^ 1, active);
-        __syncthreads();
+        lds_barrier();
         buf ^= 1;
         issue(en, xoffn, activen, 0);
         multiply();                    // block NKB - 1; the next item's block 0 arrives
         park(buf ^ 1, activen);
         park_bias(en, par ^ 1);
-        __syncthreads();
+        lds_barrier();
         buf ^= 1;
         issue(en, xoffn, activen, 1);
 

@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
     issue(e, xtok, active, 0);
     park(0, active);
     park_bias(e, 0);
-    __syncthreads();
+    lds_barrier();
     issue(e, xtok, active, 1);
     int buf = 0, par = 0;
     for (;;) {
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
         for (int kb = 0; kb < NKB - 2; ++kb) {
             multiply();
             park(buf ^ 1, active);
-            __syncthreads();
+            lds_barrier();
             buf ^= 1;
             issue(e, xtok, active, kb + 2);
         }
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
         for (int tt = 0; tt < TT; ++tt) tok_c[tt] = max(tl[16 * tt + c], 0);
         multiply();                    // block NKB - 2
         park(buf ^ 1, active);
-        __syncthreads();
+        lds_barrier();
         buf ^= 1;
         float s_xr[TT];
 #pragma unroll
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
         multiply();                    // block NKB - 1; the next item's block 0 arrives
         park(buf ^ 1, activen);
         park_bias(en, par ^ 1);
-        __syncthreads();
+        lds_barrier();
         buf ^= 1;
         issue(en, xtokn, activen, 1);
 

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
             *reinterpret_cast<bf16x8*>(hid + row * kHRow + piece * 16) = hr[j];
         }
     }
-    __syncthreads();
+    lds_barrier();  // the hidden tile is in LDS (a full barrier would also wait for global stores)
 
     // ---------------------------------------------------------------- stage 2
     // scores of expert tile et for the group's 64 tokens: |R2 hid + c2| to `scores` and to o
@@ -272,7 +272,8 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         m = fmaxf(m, __shfl_xor(m, 32, 64));
         if (q == 0) pmax[w * 64 + 16 * tt + c] = m;
     }
-    __syncthreads();
+    lds_barrier();  // LDS only: the scores' stores to global memory need not have landed
+    const uint32_t keep_all = tau == 0.0f ? 1u : 0u;
     double thr[TT];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
@@ -292,8 +293,11 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
                 uint32_t bits = 0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const bool keep = (tau == 0.0f) || ((double)sc[j][tt][r] >= thr[tt]);
-                    bits |= (uint32_t)(keep && et < NE && e0 + r < E) << (4 * q + r);
+                    // integer logic, no short circuit: as `a || b`, `c && d` this became a
+                    // branch around every one of the 64-bit comparisons
+                    const uint32_t ge = (double)sc[j][tt][r] >= thr[tt] ? 1u : 0u;
+                    const uint32_t in = (et < NE ? 1u : 0u) & (e0 + r < E ? 1u : 0u);
+                    bits |= ((keep_all | ge) & in) << (4 * q + r);
                 }
                 bits |= __shfl_xor(bits, 16, 64);
                 bits |= __shfl_xor(bits, 32, 64);  // 16 bits: experts 16et .. 16et+15 of token c
@@ -301,7 +305,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
             }
         }
     }
-    __syncthreads();
+    lds_barrier();
     if (tid < 64) {
         const int t = t0 + tid;
         const bool mine = tid < TOK && t < T;  // lanes from TOK up: no token, an all-zero row
@@ -317,7 +321,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
         if (mine && k_per_token) k_per_token[t] = kt;
     }
-    __syncthreads();
+    lds_barrier();
     // ballot transpose: lane = token; wavefront w handles the experts 64wi + 16w .. +15 of every
     // word wi (sixteen ballots per word and wavefront)
     for (int wi = 0; wi < W; ++wi) {

@@ -663,7 +663,8 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
         buf ^= 1;
         issue(en, xoffn, activen, 1);
 
-        if (active) {
+        if (active) with_activation(act, [&](auto act_c) {
+            constexpr int ACT = decltype(act_c)::value;
             const float* sb = sbias + par * MT * 16;
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
@@ -677,16 +678,19 @@ __global__ __launch_bounds__(256, 2) void up_wide_bf16_kernel(
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             float v;
-                            if (GATED) v = activate_fast(act, acc[MT + mt][tt][r]) * acc[mt][tt][r];
-                            else v = activate_fast(act, acc[mt][tt][r] + sb[neuron_of_slot(mt, 4 * q + r)]);
+                            if (GATED) v = activate_fast(ACT, acc[MT + mt][tt][r]) * acc[mt][tt][r];
+                            else v = activate_fast(ACT, acc[mt][tt][r] + sb[neuron_of_slot(mt, 4 * q + r)]);
                             if (neuron_of_slot(mt, 4 * q + r) >= m) v = 0.0f;
                             hv[half * 4 + r] = (__bf16)v;
                         }
                     }
                     *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
+                    // eight values at a time: interleaving more of them costs registers the
+                    // requests in flight are using
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-        }
+        });
         if (!more) break;
         j = jn;
         e = en;

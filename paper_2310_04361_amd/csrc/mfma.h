@@ -150,4 +150,18 @@ __device__ __forceinline__ float activate_fast(int act, float v) {
     return 0.5f * v * (1.0f + th);
 }
 
+// The activation as a compile-time constant for an epilogue that applies it to a hundred values
+// per lane: with the layer's `act` tested per value the compiler kept two scalar branches around
+// every one of them.  with_activation(act, f) calls f(ActTag<act>{}) once, under one test.
+template <int ACT>
+struct ActTag {
+    static constexpr int value = ACT;
+};
+template <class F>
+__device__ __forceinline__ void with_activation(int act, F&& f) {
+    if (act == DMOE_ACT_RELU) f(ActTag<DMOE_ACT_RELU>{});
+    else if (act == DMOE_ACT_GELU_ERF) f(ActTag<DMOE_ACT_GELU_ERF>{});
+    else f(ActTag<DMOE_ACT_GELU_TANH>{});
+}
+
 }  // namespace dmoe

@@ -302,31 +302,35 @@ __global__ __launch_bounds__(256, NBUF == 1 ? 3 : 1) void up_bf16_kernel(
             compute(1, a1);
 
             // lane (q, c) of tile (mt, tt): neurons 16mt + 4q + r of list row 16tt + c
+            with_activation(act, [&](auto act_c) {
+                constexpr int ACT = decltype(act_c)::value;
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                __bf16* dst = Hf + ((size_t)item * UR + 16 * tt + c) * (KS * 32) + 8 * q;
+                for (int tt = 0; tt < TT; ++tt) {
+                    __bf16* dst = Hf + ((size_t)item * UR + 16 * tt + c) * (KS * 32) + 8 * q;
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    bf16x8 hv;
+                    for (int ks = 0; ks < KS; ++ks) {
+                        bf16x8 hv;
 #pragma unroll
-                    for (int half = 0; half < 2; ++half) {
-                        const int mt = 2 * ks + half;
-                        const int n0 = neuron_of_slot(mt, 4 * q);  // + r: consecutive
+                        for (int half = 0; half < 2; ++half) {
+                            const int mt = 2 * ks + half;
+                            const int n0 = neuron_of_slot(mt, 4 * q);  // + r: consecutive
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            float v;
-                            if (GATED) {
-                                v = activate_fast(act, acc[BR - 1][mt][tt][r]) * acc[0][mt][tt][r];
-                            } else {
-                                v = activate_fast(act, acc[0][mt][tt][r]);
+                            for (int r = 0; r < 4; ++r) {
+                                float v;
+                                if (GATED) {
+                                    v = activate_fast(ACT, acc[BR - 1][mt][tt][r]) * acc[0][mt][tt][r];
+                                } else {
+                                    v = activate_fast(ACT, acc[0][mt][tt][r]);
+                                }
+                                if (n0 + r >= m) v = 0.0f;
+                                hv[half * 4 + r] = (__bf16)v;
                             }
-                            if (n0 + r >= m) v = 0.0f;
-                            hv[half * 4 + r] = (__bf16)v;
                         }
+                        *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
+                        __builtin_amdgcn_sched_barrier(0);  // eight values at a time
                     }
-                    *reinterpret_cast<bf16x8*>(dst + ks * 32) = hv;
                 }
-            }
+            });
             if (!more) break;
             j = jn;
             e = en;
@@ -462,6 +466,8 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
 #pragma unroll
             for (int r = 0; r < 4; ++r) bias[r] = (float)b_up[(size_t)e * m + min(4 * q + r, m - 1)];
         }
+        with_activation(act, [&](auto act_c) {
+        constexpr int ACT = decltype(act_c)::value;
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             float v[4], w[4];
@@ -471,10 +477,10 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
                     const float other = __shfl_xor(acc[tt][r], 32, 64);  // q <-> q ^ 2
                     const float up = q < 2 ? acc[tt][r] : other;
                     const float gate = q < 2 ? other : acc[tt][r];
-                    v[r] = activate_fast(act, gate) * up;
+                    v[r] = activate_fast(ACT, gate) * up;
                     if (4 * (q & 1) + r >= m) v[r] = 0.0f;
                 } else {
-                    v[r] = activate_fast(act, acc[tt][r] + bias[r]);
+                    v[r] = activate_fast(ACT, acc[tt][r] + bias[r]);
                     if (4 * q + r >= m) v[r] = 0.0f;
                 }
             }
@@ -493,6 +499,7 @@ __global__ __launch_bounds__(256) void up_tiny_kernel(
             }
             *reinterpret_cast<bf16x8*>(Hf + ((size_t)item * UR + 16 * tt + c) * 32 + 8 * piece) = hv;
         }
+        });
     }
     }  // windows
 }

@@ -308,7 +308,8 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
         buf ^= 1;
         issue(en, xtokn, activen, 1);
 
-        if (active) {
+        if (active) with_activation(act, [&](auto act_c) {
+            constexpr int ACT = decltype(act_c)::value;
             // lane (q, c) of tile (mt, tt): neurons neuron_of_slot(mt, 4q + r) of list row 16tt + c.
             // The accumulators are sums of code products: times the row's scale and the
             // matrix's scale they are the pre-activations.
@@ -327,10 +328,10 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
                         for (int r = 0; r < 4; ++r) {
                             float v;
                             if (GATED)
-                                v = activate_fast(act, acc[MT + mt][tt][r] * (s_x * s_gate)) *
+                                v = activate_fast(ACT, acc[MT + mt][tt][r] * (s_x * s_gate)) *
                                     (acc[mt][tt][r] * (s_x * s_up));
                             else
-                                v = activate_fast(act, acc[mt][tt][r] * (s_x * s_up) +
+                                v = activate_fast(ACT, acc[mt][tt][r] * (s_x * s_up) +
                                                            sbias[par * MT * 16 + neuron_of_slot(mt, 4 * q + r)]);
                             if (neuron_of_slot(mt, 4 * q + r) >= m) v = 0.0f;
                             hv[ks][half * 4 + r] = (__bf16)v;
@@ -368,7 +369,7 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
                     if (q == 0) hs8[row] = (uint8_t)(127 + s_exp);
                 }
             }
-        }
+        });
         if (!more) break;
         j = jn;
         e = en;

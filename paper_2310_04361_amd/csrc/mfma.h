@@ -60,8 +60,12 @@ __device__ __forceinline__ float4 router_scores4(const f32x4& acc, const __bf16*
                                                  int e0, int E) {
     float v[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-        v[r] = e0 + r < E ? fabsf(acc[r] + (r_b2 ? (float)r_b2[e0 + r] : 0.0f)) : 0.0f;
+    for (int r = 0; r < 4; ++r) {
+        // the load is unconditional (clamped index): under the bound test each of the four would
+        // be a block of its own that waits for its value
+        const float bias = r_b2 ? (float)r_b2[min(e0 + r, E - 1)] : 0.0f;
+        v[r] = e0 + r < E ? fabsf(acc[r] + bias) : 0.0f;
+    }
     return make_float4(v[0], v[1], v[2], v[3]);
 }
 // ... and their store to row[e0 .. e0+3] of a [.][E] array: 16 bytes at once where the rows keep

@@ -214,11 +214,15 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
         }
         const int e0 = 16 * et + 4 * q;  // this lane: experts e0 .. e0+3
         // the second-layer biases as an accumulator-shaped vector (0 for experts from E on)
+        // (every load unconditional, from a clamped index: under `if (e0 + r < E)` each of them
+        // became a block of its own that waited for its value before the next one was requested)
         f32x4 b2 = f32x4{0.f, 0.f, 0.f, 0.f};
         if (r_b2) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (e0 + r < E) b2[r] = (float)r_b2[e0 + r];
+            for (int r = 0; r < 4; ++r) {
+                const float bv = (float)r_b2[min(e0 + r, E - 1)];
+                b2[r] = e0 + r < E ? bv : 0.0f;
+            }
         }
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {

@@ -368,6 +368,9 @@ __global__ __launch_bounds__(256, 2) void up_wide_x8_kernel(
                     }
                     if (q == 0) hs8[row] = (uint8_t)(127 + s_exp);
                 }
+                // one list row at a time: interleaving more of them costs registers that the
+                // requests in flight are using
+                __builtin_amdgcn_sched_barrier(0);
             }
         });
         if (!more) break;

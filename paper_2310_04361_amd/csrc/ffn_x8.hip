@@ -4,8 +4,10 @@
 //
 //   quantise  one wavefront per token: the row maximum, the power-of-two scale
 //             s_t = 2^ceil(log2(max / 448)), and every element rounded to the nearest E4M3 value
-//             of x / s_t (ties to the even mantissa) by integer arithmetic on the fp32 bits -- no
-//             converter instruction, so the codes do not depend on a rounding or saturation mode.
+//             of x / s_t (ties to the even mantissa): by integer arithmetic on the fp32 bits where
+//             the quantised value is wanted as well, by the hardware converter where only the
+//             code is (it gives that arithmetic's code for every input it can meet here; see
+//             e4m3_codes8).
 //   up        the wide-expert kernel of ffn_bf16.hip (a workgroup owns 256 list rows of one
 //             expert, the weights of a K block go through LDS once per workgroup, every
 //             wavefront stages its own 64 gathered x rows) on v_mfma_f32_16x16x128_f8f6f4: a K block

@@ -202,7 +202,8 @@ int32_t dmoe_expert_ffn(const dmoe_layer *layer, const void *x, int32_t n_tokens
  * top of b_down (Sec. 3.2; gated experts Appendix G) -- what dmoe_router, dmoe_select and
  * dmoe_expert_ffn compute one after the other.  Optional outputs (each nullable):
  * scores_out [T][E] fp32, mask_out [T][ceil(E/64)], offsets_out [E+1] and token_lists_out
- * (capacity T*E; both or neither).
+ * (capacity T*E; both or neither).  An output that is not asked for may never be written at all
+ * (the fused router and gate keep the scores in registers), so NULL is also the faster call.
  */
 int32_t dmoe_forward(const dmoe_layer *layer, const void *x, int32_t n_tokens, float tau,
                      void *y, float *scores_out, uint64_t *mask_out, int32_t *offsets_out,

@@ -548,7 +548,9 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
         // workgroups per group, each with its own row of counts)
         if (!colmask) split = router_fused_split(*layer, n_tokens);
         int32_t* cnt = split > 1 ? reinterpret_cast<int32_t*>(ws + w.sub_cnt) : group_off;
-        launch_router_fused(*layer, x, n_tokens, split, scores, tau, mask, nullptr, cnt, colmask, s);
+        // (the gate works on the scores in registers: they go to memory only for a caller who
+        // asked for them)
+        launch_router_fused(*layer, x, n_tokens, split, scores_out, tau, mask, nullptr, cnt, colmask, s);
     } else if (fused_router && colmask && gate.top_k < 0 &&
                layer->n_experts <= kSmallFusedSelectMaxE) {
         SmallGroup G{};

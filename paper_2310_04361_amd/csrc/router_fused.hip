@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256) void router_fused_kernel(
             // padding experts (from E on) score 0
             const float4 out = e0 < E ? router_scores4(a2[tt] + b2, nullptr, e0, E)
                                       : make_float4(0.f, 0.f, 0.f, 0.f);
-            if (t < T && e0 < E) store_scores4(scores + (size_t)t * E, e0, E, out);
+            if (scores && t < T && e0 < E) store_scores4(scores + (size_t)t * E, e0, E, out);
             o[tt][0] = out.x; o[tt][1] = out.y; o[tt][2] = out.z; o[tt][3] = out.w;
         }
     };

@@ -270,8 +270,7 @@ SmallMod small_mod(const dmoe_layer& L, char* ws, const LayerWs& w, float* score
 // the counts are then outputs of that kernel, described by gate_mod).
 int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const LayerWs& w,
                 const uint64_t* mask, int32_t* offsets_out, int32_t* lists_out, void* y,
-                hipStream_t s, int split = 1, const SmallMod* gate_mod = nullptr,
-                int gate_mode = kGateDone) {
+                hipStream_t s, int split = 1, const SmallMod* gate_mod = nullptr) {
     // split > 1: the counts are in sub_cnt, split rows per group (bf16 prefill path only)
     int32_t* group_off = reinterpret_cast<int32_t*>(ws + w.group_off);
     const int32_t* sub_cnt = split > 1 ? reinterpret_cast<const int32_t*>(ws + w.sub_cnt) : nullptr;
@@ -300,7 +299,7 @@ int run_experts(const dmoe_layer& L, const void* x, int T, char* ws, const Layer
     } else if (use_small_path(L, T)) {
         SmallGroup G{};
         G.m[0] = gate_mod ? *gate_mod : small_mod(L, ws, w, nullptr, nullptr, y, 0.0f);
-        launch_small_bf16(L, G, 1, x, T, gate_mod ? gate_mode : kGateDone, s);
+        launch_small_bf16(L, G, 1, x, T, gate_mod != nullptr, s);
         if (offsets_out)  // after the experts: with the gate folded in, they write mask and counts
             launch_scan_and_fill(mask, T, L.n_experts, group_off, counts, offsets, nullptr, 64,
                                  lists_out, nullptr, 1, nullptr, nullptr, s);
@@ -560,13 +559,10 @@ int forward_impl(const dmoe_layer* layer, const void* x, int32_t n_tokens, Gate 
             // the hidden product here; the second product and the gate ride in the up-projection
             launch_router_small_hidden(*layer, G, 1, x, n_tokens, s);
             return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s,
-                               1, &G.m[0], kGateFromHidden);
+                               1, &G.m[0]);
         }
-        // both router products as launches over many workgroups; the gate rides in the
-        // up-projection, on the stored scores
-        launch_router_small(*layer, G, 1, x, n_tokens, s);
-        return run_experts(*layer, x, n_tokens, ws, w, mask, offsets_out, token_lists_out, y, s, 1,
-                           &G.m[0], kGateFromScores);
+        // hidden product, then scores + gate in one workgroup
+        launch_router_select_small(*layer, G, 1, x, n_tokens, s);
     } else {
         if (fused_router && n_tokens <= kSmallTokens) {
             SmallGroup G{};
@@ -694,18 +690,16 @@ int32_t dmoe_forward_group(const dmoe_layer* const* layers, int32_t n_layers, co
         G.m[i] = small_mod(*layers[i], wsi, w, reinterpret_cast<float*>(wsi + w.scores),
                            reinterpret_cast<uint64_t*>(wsi + w.mask), host_ys[i], host_taus[i]);
     }
-    int gate_mode = kGateDone;
-    if (small_gate_in_up(L0)) {
+    const bool gate_in_up = small_gate_in_up(L0);
+    if (gate_in_up) {
         launch_router_small_hidden(L0, G, n_layers, x, n_tokens, s);
-        gate_mode = kGateFromHidden;
     } else if (L0.n_experts <= kSmallFusedSelectMaxE) {
-        launch_router_small(L0, G, n_layers, x, n_tokens, s);
-        gate_mode = kGateFromScores;
+        launch_router_select_small(L0, G, n_layers, x, n_tokens, s);
     } else {
         launch_router_small(L0, G, n_layers, x, n_tokens, s);
         launch_select_small_group(L0, G, n_layers, n_tokens, s);
     }
-    launch_small_bf16(L0, G, n_layers, x, n_tokens, gate_mode, s);
+    launch_small_bf16(L0, G, n_layers, x, n_tokens, gate_in_up, s);
     return check_launch("group kernels");
 }
 

@@ -254,14 +254,15 @@ void launch_router_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
                          int T, hipStream_t s);
 void launch_router_small_hidden(const dmoe_layer& L, const SmallGroup& G, int n_layers,
                                 const void* x, int T, hipStream_t s);
-// Up to this many experts the gate of the small-token path rides in the up-projection (the 16
-// score rows fit its LDS next to the mask words): no gate launch.
+// The same with the second product and the dynamic-k gate of every layer (M.tau) in ONE
+// workgroup, which also writes mask, colmask and group_cnt; for E <= kSmallFusedSelectMaxE.
 constexpr int kSmallFusedSelectMaxE = 1024;
-// Where the second router matrix is small the up-projection's workgroups repeat that product
-// themselves from the hidden rows (launch_small_bf16 with kGateFromHidden); with a larger matrix
-// the repeated product costs each workgroup more than a launch (256 experts, d_h = 256: the
-// up-projection grew by 10 us), so the scores come from launch_router_small and the workgroups
-// read them (kGateFromScores: 16 KB each instead of 128 KB of matrix).
+void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
+                                const void* x, int T, hipStream_t s);
+// Where the second router matrix is small the up-projection's workgroups repeat that product and
+// the gate themselves (launch_small_bf16 with gate = true) and the gate launch goes away; with a
+// larger matrix the repeated product costs each workgroup more than the launch (256 experts,
+// d_h = 256: the up-projection grew by 10 us for a gate kernel of 8).
 inline bool small_gate_in_up(const dmoe_layer& L) {
     return L.n_experts <= 64 && (size_t)L.n_experts * L.router_hidden <= 16384;
 }
@@ -274,14 +275,11 @@ constexpr int kSmallTokens = 16;
 constexpr int kSmallMaxGroups = 32;   // expert groups whose partial outputs are summed at the end
 bool small_bf16_supported(const dmoe_layer& L);
 // Hs: E * (m_pad/32) KiB of fragments; partial: kSmallMaxGroups * 16 * d floats.
-// gate: kGateFromHidden -- the up-projection computes the scores and the dynamic-k gate (M.tau)
-// itself from the router's hidden rows (M.hid, written by launch_router_small_hidden) and writes
-// M.scores, M.mask, M.colmask and M.group_cnt on the way; kGateFromScores -- the same gate on
-// the scores that launch_router_small stored in M.scores (it writes M.mask, M.colmask and
-// M.group_cnt); kGateDone -- it reads M.colmask.
-enum { kGateDone = 0, kGateFromHidden = 1, kGateFromScores = 2 };
+// gate: the up-projection computes the scores and the dynamic-k gate (M.tau) itself from the
+// router's hidden rows (M.hid, written by launch_router_small_hidden) and writes M.scores, M.mask,
+// M.colmask and M.group_cnt on the way; otherwise it reads M.colmask.
 void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
-                       int gate, hipStream_t s);
+                       bool gate, hipStream_t s);
 
 // ---- experts ----------------------------------------------------------------------------------
 void launch_ffn_f32(const dmoe_layer& L, const float* x, int T, const uint64_t* mask, float* y,

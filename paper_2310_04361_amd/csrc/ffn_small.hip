@@ -7,11 +7,7 @@
 //               the router's hidden rows -- 128 KB of router matrix out of L2 and a handful of
 //               MFMAs per wavefront -- and so knows its own expert's tokens without a gate kernel
 //               in front of it; one extra workgroup writes the scores, the mask and the
-//               per-expert token sets for the kernels and callers that follow.  With a larger
-//               router matrix (gate_dh < 0) the second product is a launch of its own over many
-//               workgroups and every workgroup here reads the stored scores (16 rows of E) for
-//               the same threshold test: still no gate kernel, which as ONE workgroup pulled the
-//               whole second matrix through one CU.  The 16 x rows sit in LDS; wavefront (tile, slice)
+//               per-expert token sets for the kernels and callers that follow.  The 16 x rows sit in LDS; wavefront (tile, slice)
 //               streams a K slice of one neuron tile of the up (and gate) fragments -- 1 KiB
 //               contiguous per load, 8 to 16 loads in flight per wavefront -- the slices are added
 //               through LDS and h (zero for tokens that did not select the expert) goes out as an
@@ -59,13 +55,13 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
     auto x_piece = [&](int i) {
         return load8(x + (size_t)min(i / pieces, T - 1) * d + (i % pieces) * 8);
     };
-    if (gate_dh != 0 && e < E) {
+    if (gate_dh > 0 && e < E) {
 #pragma unroll
         for (int k = 0; k < kPre; ++k)
             if (tid + k * kThreads < 16 * pieces) xpre[k] = x_piece(tid + k * kThreads);
     }
     uint64_t cm;
-    if (gate_dh != 0) {
+    if (gate_dh > 0) {
         // scores of all experts in LDS, then this expert's column against every token's threshold
         const int W = (E + 63) >> 6;
         // (all in the dynamic block: a static array next to a 160 KB dynamic limit is refused)
@@ -73,11 +69,7 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
         uint64_t* mw = reinterpret_cast<uint64_t*>(smem + 64);        // [16][W], output workgroup only
         float* sc = reinterpret_cast<float*>(mw + 16 * W);            // [16][E]
         const bool out_wg = e == E;  // the extra workgroup: scores, mask, token sets to memory
-        if (gate_dh > 0) {
-            small_scores_to_lds(M, T, gate_dh, E, sc, out_wg);
-        } else {  // the scores were computed by a launch before this one: T rows of E
-            for (int i = tid; i < T * E; i += kThreads) sc[i] = M.scores[i];
-        }
+        small_scores_to_lds(M, T, gate_dh, E, sc, out_wg);
         __syncthreads();
         if (out_wg) {
             select_small_body(sc, mw, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
@@ -105,7 +97,7 @@ __global__ __launch_bounds__(64 * kUpSmallWaves) void up_small_kernel(
         *reinterpret_cast<bf16x8*>(xs + (i / pieces) * row_bytes + (i % pieces) * 16) = v;
     };
     int i_first = tid;
-    if (gate_dh != 0) {
+    if (gate_dh > 0) {
 #pragma unroll
         for (int k = 0; k < kPre; ++k)
             if (tid + k * kThreads < 16 * pieces) x_park(tid + k * kThreads, xpre[k]);
@@ -270,7 +262,7 @@ __global__ void finish_small_kernel(const SmallGroup G, int T, int d, int EG) {
 
 template <int MT, bool GATED, bool W8>
 void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
-                       int gate, hipStream_t s) {
+                       bool gate, hipStream_t s) {
     const int E = L.n_experts;
     size_t lds = std::max(16 * (2 * (size_t)L.d_model + 16),
                           sizeof(float) * kUpSmallWaves * (GATED ? 2 : 1) * 64 * 4);
@@ -285,12 +277,12 @@ void launch_up_small_t(const dmoe_layer& L, const SmallGroup& G, int n_layers, c
     while (KQ > 1 && (L.d_model / 32) % KQ != 0) KQ >>= 1;
     launch_kernel(up_small_kernel<MT, GATED, W8>, dim3(E + (gate ? 1 : 0), 1, n_layers),
                   64 * kUpSmallWaves, lds, s, G, (const __bf16*)x, T, L.d_model, L.expert_size, L.act,
-                  KQ, E, gate == kGateFromHidden ? L.router_hidden : (gate == kGateFromScores ? -1 : 0));
+                  KQ, E, gate ? L.router_hidden : 0);
 }
 
 template <int MT, bool GATED>
 void launch_up_small_w(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
-                       int gate, hipStream_t s) {
+                       bool gate, hipStream_t s) {
     if (weights_fp8(L)) launch_up_small_t<MT, GATED, true>(L, G, n_layers, x, T, gate, s);
     else launch_up_small_t<MT, GATED, false>(L, G, n_layers, x, T, gate, s);
 }
@@ -307,7 +299,7 @@ bool small_bf16_supported(const dmoe_layer& L) {
 }
 
 void launch_small_bf16(const dmoe_layer& L, const SmallGroup& G, int n_layers, const void* x, int T,
-                       int gate, hipStream_t s) {
+                       bool gate, hipStream_t s) {
     const int mt = m_pad_of(L.expert_size) / 16;
     {
         LaunchTimer tm(kSlotSmallUp, s);

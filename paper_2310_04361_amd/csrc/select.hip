@@ -160,6 +160,19 @@ __global__ __launch_bounds__(1024) void select_small_kernel(const float* __restr
     select_small_body(scores, mw, mask, k_per_token, group_cnt, colmask, T, E, W, tau);
 }
 
+// Second router product and the gate in one workgroup per layer (T <= 16, E <= 1024): the scores
+// go to global memory and to LDS, and after one barrier the gate runs on the LDS copy.  One
+// launch less than scores + gate, which is what counts at this size.
+__global__ __launch_bounds__(1024) void router_scores_select_small_kernel(const SmallGroup G, int T,
+                                                                          int dh, int E, int W) {
+    extern __shared__ uint64_t mw[];  // [16][W] mask words, then [16][E] fp32 scores
+    const SmallMod& M = G.m[blockIdx.z];
+    float* sc = reinterpret_cast<float*>(mw + 16 * W);
+    small_scores_to_lds(M, T, dh, E, sc, true);
+    __syncthreads();
+    select_small_body(sc, mw, M.mask, nullptr, M.group_cnt, M.colmask, T, E, W, M.tau);
+}
+
 // the same gate for every layer of a group (blockIdx.z = layer), each with its own tau
 __global__ __launch_bounds__(1024) void select_small_group_kernel(const SmallGroup G, int T, int E,
                                                                   int W) {
@@ -419,6 +432,21 @@ void launch_select_small_group(const dmoe_layer& L, const SmallGroup& G, int n_l
     const int E = L.n_experts, W = div_up(E, 64);
     LaunchTimer tm(kSlotMask, s);
     launch_kernel(select_small_group_kernel, dim3(1, 1, n_layers), 1024, sizeof(uint64_t) * 16 * W, s, G, T, E, W);
+}
+
+void launch_router_select_small(const dmoe_layer& L, const SmallGroup& G, int n_layers,
+                                const void* x, int T, hipStream_t s) {
+    // first product: the many-workgroup hidden kernel; second product + gate: one workgroup
+    const int E = L.n_experts, W = div_up(E, 64);
+    launch_router_small_hidden(L, G, n_layers, x, T, s);
+    LaunchTimer tm(kSlotMask, s);
+    const size_t lds = sizeof(uint64_t) * 16 * W + sizeof(float) * 16 * (size_t)E;
+    static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
+    std::call_once(attr_once, [&] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&router_scores_select_small_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+    });
+    launch_kernel(router_scores_select_small_kernel, dim3(1, 1, n_layers), 1024, lds, s, G, T, L.router_hidden, E, W);
 }
 
 void launch_mask_from_lists(const int32_t* offsets, const int32_t* lists, int T, int E,

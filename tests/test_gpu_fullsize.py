@@ -189,6 +189,48 @@ def test_paper_shape_full_size_bernoulli(B, oracle):
     assert np.array_equal(yh[777], layer["b_down"])
 
 
+@pytest.mark.parametrize("fmt", ["x8", "a8"])
+def test_paper_shape_full_size_bernoulli_8bit(B, oracle, fmt):
+    """The same shape and decisions with 8-bit expert inputs (x8) and with 8-bit hidden
+    activations as well (a8): plain experts of 128 neurons, several work items per workgroup of
+    the 8-bit up-projection, two 64-neuron units per expert in the 8-bit down-projection.  Four
+    tokens of every 128-token chunk against the oracle's experts on the oracle's quantised rows."""
+    import torch
+    cfg = wl.CONFIGS["paper"]
+    print(f"paper shape T={cfg.T} E={cfg.E} m={cfg.m} Bernoulli(0.5), {fmt}", flush=True)
+    layer = wl.quantize_experts_e4m3(wl.make_layer(cfg, 0))
+    layer["x8"] = True
+    if fmt == "a8":
+        layer["a8"] = True
+    x = wl.make_input(cfg, 0)
+    L = B.Layer(layer, cfg.dtype)
+    mask = wl.bernoulli_mask(cfg.T, cfg.E, 0.5, seed=3)
+    mask[777] = 0                                                     # a token with no expert
+    offs, lst = lists_from_mask(mask)
+    y = B.dmoe_expert_ffn(L, B.to_device(x, cfg.dtype), torch.from_numpy(offs).cuda(),
+                          torch.from_numpy(np.concatenate([lst, np.zeros(1, np.int32)])).cuda())
+    torch.cuda.synchronize()
+    yh = B.from_device(y, cfg.dtype)
+    assert np.isfinite(yh).all()
+    rng = np.random.default_rng(9)
+    starts = np.arange(0, cfg.T, 128)
+    idx = np.unique(np.concatenate([starts, np.minimum(starts + 127, cfg.T - 1),
+                                    np.minimum(starts + rng.integers(1, 127, len(starts)), cfg.T - 1),
+                                    np.minimum(starts + rng.integers(1, 127, len(starts)), cfg.T - 1),
+                                    [777]]))
+    xq, _ = oracle.quantize_rows_e4m3(x[idx])
+    ref = oracle_ffn(oracle, layer, xq, mask[idx], quantize_h=(fmt == "a8"))
+    if fmt == "a8":
+        err, n_allow = check_fully_8bit(oracle, layer, xq, mask[idx], yh[idx], ref, TOL[cfg.dtype])
+        print(f"  pairs={offs[-1]} tokens compared={len(idx)} err={err:.3e} "
+              f"tokens on the one-step allowance: {n_allow}", flush=True)
+    else:
+        err = tokenwise_rel_err(yh[idx], ref)
+        print(f"  pairs={offs[-1]} tokens compared={len(idx)} err={err:.3e}", flush=True)
+        assert err <= TOL[cfg.dtype]
+    assert np.array_equal(yh[777], layer["b_down"])
+
+
 def test_sizes_beyond_32bit_offsets_take_the_pair_kernel(B, oracle):
     """The matrix-core merge addresses H through 32-bit buffer offsets (below 2 GiB); a layer
     whose worst-case H is larger -- 8200 tokens x 4096 experts of 32-neuron rows -- must go to the

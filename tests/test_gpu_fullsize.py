@@ -48,7 +48,11 @@ def B():
                                                ("gemma_paper:600", 0.5, 32),
                                                # ... and of its text classifier: 512 experts of 6
                                                ("bert_paper:700", 0.5, 48),
-                                               ("gemma_paper:12", 0.5, 12)])
+                                               ("gemma_paper:12", 0.5, 12),
+                                               # both at the sizes bench.py times (windows of the
+                                               # up-projection, part-filled work items, several
+                                               # items per wavefront)
+                                               ("gemma_paper", 0.5, 64), ("bert_paper", 0.5, 96)])
 def test_full_size_sampled(B, oracle, name, tau, n_sample):
     import torch
     cfg = wl.CONFIGS[name.split(":")[0]]

@@ -55,11 +55,16 @@ constexpr int kDnTokens = 128;  // tokens per workgroup: 4 tiles of 32 = 2 selec
 constexpr int kDnTiles = 4;
 constexpr int kDnColStep = 128;  // a workgroup covers CT * 128 columns: 4 wavefronts x CT tiles of 32
 
-// Pieces per expert (padded up to a supported count), experts per stage, k-steps per stage.
+// Pieces per unit (padded up to a supported count), units per stage, k-steps per stage, units per
+// expert.  A unit is an expert -- except that an expert of exactly 128 neurons is walked as two
+// units of 64 (its weights ARE two experts of 64 laid end to end, its H rows two half rows): with
+// 4 k-steps per stage instead of 8 the LDS tiles of a workgroup halve, two workgroups share a CU
+// and one's start-up and output hide behind the other's loop.
 struct DownPacking {
-    int PG, G, KSP;
+    int PG, G, KSP, UPE;
 };
 DownPacking down_packing(int m) {
+    if (m == 128) return DownPacking{8, 1, 4, 2};
     static const int kCounts[] = {1, 2, 3, 4, 6, 8, 16};  // H rows are 32, 64 or 128 neurons wide
     int pg = div_up(m, 8);
     for (int v : kCounts)
@@ -69,13 +74,13 @@ DownPacking down_packing(int m) {
         }
     // an even number of pieces, at least two k-steps
     const int g = pg == 1 ? 4 : ((pg == 2 || (pg & 1)) ? 2 : 1);
-    return DownPacking{pg, g, g * pg / 2};
+    return DownPacking{pg, g, g * pg / 2, 1};
 }
 
 __global__ void pack_down32_kernel(const void* __restrict__ w_down, const float* __restrict__ scales,
                                    int fp8, __bf16* __restrict__ w2g, int E, int m, int d, int PG,
-                                   int G, int KSP) {
-    const int n_stages = (E + G - 1) / G;
+                                   int G, int KSP, int UPE) {
+    const int n_stages = (E * UPE + G - 1) / G;
     const size_t n = (size_t)n_stages * (d / 32) * KSP * 512;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -89,7 +94,8 @@ __global__ void pack_down32_kernel(const void* __restrict__ w_down, const float*
         const int h = lane >> 5, r = lane & 31;
         const int col = 32 * ct + 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);
         const int pi = 2 * s + h;                   // piece of the stage
-        const int e = st * G + pi / PG, neuron = 8 * (pi % PG) + s8;
+        const int u = st * G + pi / PG;             // unit; unit u of expert e holds its neurons 8 PG u' ..
+        const int e = u / UPE, neuron = 8 * PG * (u % UPE) + 8 * (pi % PG) + s8;
         w2g[i] = (e < E && neuron < m)
                      ? expert_weight(w_down, scales, fp8, 2, e, ((size_t)e * m + neuron) * d + col)
                      : (__bf16)0.0f;
@@ -116,7 +122,7 @@ constexpr int kDnTrip = 4;  // stages per loop trip = LDS buffers = H register s
 // expert and replaced once per 32 experts BETWEEN two runs of the loop, by the word requested a
 // run earlier; the MFMAs of a phase start with the operands that were requested last, so that
 // one wait covers the phase.
-template <int KSP, int G, int R, int WPS, int CT>
+template <int KSP, int G, int R, int WPS, int CT, int UPE = 1>
 __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     const __bf16* __restrict__ w2g, const __bf16* __restrict__ b_down,
     const int32_t* __restrict__ item_start, const int32_t* __restrict__ group_off,
@@ -125,11 +131,13 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     int rows_per_item, int row_shift, uint32_t w_bytes, uint32_t h_bytes,
     long long max_pairs_sparse) {
     static_assert((kDnTrip * KSP) % R == 0 && 32 % (kDnTrip * G) == 0, "loop trip");
+    static_assert(UPE == 1 || (UPE == 2 && G == 1), "two units per expert: one unit per stage");
     if (offsets[E] <= max_pairs_sparse) return;  // sparse enough for the pair-proportional kernel
     constexpr int PG = 2 * KSP / G;                  // pieces per expert
     constexpr int kImage = kDnTiles * KSP * 1024;    // the B tiles of one stage
     constexpr int PH = kDnTrip * KSP;                // phases per loop trip
-    constexpr int kTripsPerBatch = 32 / (kDnTrip * G);
+    constexpr int kExpertsPerTrip = kDnTrip * G / UPE;
+    constexpr int kTripsPerBatch = 32 / kExpertsPerTrip;
     extern __shared__ __attribute__((aligned(16))) char img[];  // [kDnTrip][kImage]
     // The column slices of one chunk share its H rows: keep them on one XCD (workgroups are dealt
     // round-robin to the 8 XCDs) and next to each other in launch order.
@@ -143,7 +151,7 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane >> 5, c = lane & 31;
     const int col_w = slice * kDnCols + wave * (32 * CT);
-    const int n_trips = (E + kDnTrip * G - 1) / (kDnTrip * G);
+    const int n_trips = (E * UPE + kDnTrip * G - 1) / (kDnTrip * G);
 
     // ---- tile-building role: select group bg of the chunk (lane = token), lane half bh
     const int bg = wave & 1, bh = wave >> 1;
@@ -186,14 +194,15 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
     uint32_t p_soff[KSP];
 #pragma unroll
     for (int s = 0; s < KSP; ++s) p_soff[s] = 16u * (uint32_t)((2 * s + bh) % PG);
-    auto fetch_piece = [&](int s, u32x4 (&br)[KSP]) {
+    // half: the unit of the expert (0, or 1 with two units per expert: the second half of the row)
+    auto fetch_piece = [&](int s, u32x4 (&br)[KSP], int half) {
         const int eo0 = G == 1 ? 0 : (2 * s) / PG, eo1 = G == 1 ? 0 : (2 * s + 1) / PG;
         const uint32_t v = eo0 == eo1 ? b_voff[eo0] : (bh ? b_voff[eo1] : b_voff[eo0]);
-        br[s] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, v, p_soff[s], 0);
+        br[s] = __builtin_amdgcn_raw_buffer_load_b128(h_rsrc, v, p_soff[s] + (uint32_t)(half * PG * 16), 0);
     };
-    auto build_fetch = [&](u32x4 (&br)[KSP]) {
+    auto build_fetch = [&](u32x4 (&br)[KSP], int half) {
 #pragma unroll
-        for (int s = 0; s < KSP; ++s) fetch_piece(s, br);
+        for (int s = 0; s < KSP; ++s) fetch_piece(s, br, half);
     };
     // lane = token 32h + c of the group: tile 2bg + h of the chunk, operand lane (bh, c)
     char* const wdst = img + (((2 * bg + h) * KSP) * 64 + 32 * bh + c) * 16;
@@ -245,13 +254,19 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
         rowv = is0 * rows_per_item + go0;
         mw = tok_ok ? mw : 0u;
     }
+    // (two units per expert: stage i is unit i & 1 of expert i / 2 of the trip, and the offsets
+    // of an expert are computed once, before its first unit)
 #pragma unroll
     for (int i = 0; i < kDnTrip; ++i) {
+        if (UPE == 1) {
 #pragma unroll
-        for (int eo = 0; eo < G; ++eo) build_prepare(i * G + eo, eo);
-        build_fetch(breg[i]);
+            for (int eo = 0; eo < G; ++eo) build_prepare(i * G + eo, eo);
+        } else if ((i & 1) == 0) {
+            build_prepare(i / 2, 0);
+        }
+        build_fetch(breg[i], UPE == 1 ? 0 : (i & 1));
     }
-    sh_base = (kDnTrip * G) & 31;
+    sh_base = kExpertsPerTrip & 31;
 #pragma unroll
     for (int q = 0; q < R - 1; ++q) load_phase(q % KSP, aw[q]);
     // every accumulator starts at the output bias: lane (h, c) holds columns 16h .. 16h + 15 of
@@ -315,15 +330,20 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
                     acc[j][ct] = mfma32(aw[q % R][ct], bb[q & 1][j], acc[j][ct]);
                     __builtin_amdgcn_sched_barrier(0);
                     if (ks == 0) {
+                        if (UPE == 1) {
 #pragma unroll
-                        for (int eo = 0; eo < G; ++eo)  // G <= 4: before the first fetch below
-                            if (n == eo) build_prepare(sh_base + i * G + eo, eo);
+                            for (int eo = 0; eo < G; ++eo)  // G <= 4: before the first fetch below
+                                if (n == eo) build_prepare(sh_base + i * G + eo, eo);
+                        } else if ((i & 1) == 0 && n == 0) {
+                            build_prepare(sh_base + i / 2, 0);
+                        }
 #pragma unroll
                         for (int s = 1; s < KSP; ++s)
                             if (n == (s - 1) % 2) write_piece(ni, s, breg[ni]);
 #pragma unroll
                         for (int s = 0; s < KSP; ++s)
-                            if (n == (2 + CT + s < kLast ? 2 + CT + s : kLast)) fetch_piece(s, breg[i]);
+                            if (n == (2 + CT + s < kLast ? 2 + CT + s : kLast))
+                                fetch_piece(s, breg[i], UPE == 1 ? 0 : (i & 1));
                     }
                     if (n >= 2 && n < 2 + CT) load_block((q + R - 1) % KSP, n - 2, aw[(q + R - 1) % R]);
                     if (n == 2) {
@@ -337,7 +357,7 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
                 }
                 if (ks == (KSP >> 1) - 1) lds_barrier();  // every wavefront has written its part of st + 1
             }
-            sh_base += kDnTrip * G;
+            sh_base += kExpertsPerTrip;
         } while (++trip < trip_end);
         if (trip >= n_trips) break;
         // the next trip computes the offsets of the first experts of the next batch: its mask
@@ -375,13 +395,13 @@ __global__ __launch_bounds__(256, WPS) void down_bf16_kernel(
 // through 32-bit buffer offsets.
 size_t down_w_bytes(const dmoe_layer& L) {
     const DownPacking dp = down_packing(L.expert_size);
-    return (size_t)div_up(L.n_experts, dp.G) * (L.d_model / 32) * dp.KSP * 1024;
+    return (size_t)div_up(L.n_experts * dp.UPE, dp.G) * (L.d_model / 32) * dp.KSP * 1024;
 }
 size_t down_h_bytes(const dmoe_layer& L, int T) {
     return (size_t)h_fragments(L, T) * 16 * 2 * m_pad_of(L.expert_size);
 }
 
-template <int KSP, int G, int R, int WPS, int CT>
+template <int KSP, int G, int R, int WPS, int CT, int UPE = 1>
 void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int32_t* item_start,
                    const int32_t* group_off, const uint64_t* mask, const int32_t* offsets,
                    const void* H, void* y, long long max_pairs_sparse, hipStream_t s) {
@@ -389,14 +409,14 @@ void launch_down_t(const dmoe_layer& L, const PackedLayout& P, int T, const int3
     constexpr size_t lds = (size_t)kDnTrip * kDnTiles * KSP * 1024;
     static std::once_flag attr_once;  // kernel attributes: once per process, thread-safe
     std::call_once(attr_once, [&] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KSP, G, R, WPS, CT>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&down_bf16_kernel<KSP, G, R, WPS, CT, UPE>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     const char* pk = static_cast<const char*>(L.packed);
     const int row_bytes = 2 * m_pad_of(L.expert_size);
     int row_shift = 0;
     while ((1 << row_shift) < row_bytes) ++row_shift;
-    launch_kernel(down_bf16_kernel<KSP, G, R, WPS, CT>, round_up(NC, 8) * NS, 256, lds, s, 
+    launch_kernel(down_bf16_kernel<KSP, G, R, WPS, CT, UPE>, round_up(NC, 8) * NS, 256, lds, s, 
         (const __bf16*)(pk + P.w2g), (const __bf16*)L.b_down, item_start, group_off,
         reinterpret_cast<const uint32_t*>(mask), offsets, (const __bf16*)H, (__bf16*)y, T,
         L.d_model, L.n_experts, NG, 2 * div_up(L.n_experts, 64), up_rows_bf16(L), row_shift,
@@ -424,7 +444,7 @@ void launch_pack_down_bf16(const dmoe_layer& L, void* w2g, hipStream_t s) {
                               : nullptr;
     launch_kernel(pack_down32_kernel, 2048, 256, 0, s, L.w_down, scales,
                                             weights_fp8(L), (__bf16*)w2g,
-                                            L.n_experts, L.expert_size, L.d_model, dp.PG, dp.G, dp.KSP);
+                                            L.n_experts, L.expert_size, L.d_model, dp.PG, dp.G, dp.KSP, dp.UPE);
 }
 
 void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
@@ -461,7 +481,12 @@ void launch_down_bf16(const dmoe_layer& L, int T, const int32_t* item_start,
         if (wide) DMOE_DOWN(KSP_, G_, RW_, 1, 3); \
         else DMOE_DOWN(KSP_, G_, R1_, 1, 2);      \
     } while (0)
-    if (dp.KSP == 2 && dp.G == 4) DMOE_DOWN_BY_GRID(2, 4, 8, 8, 4);
+    if (dp.UPE == 2) {  // experts of exactly 128 neurons as two units of 64
+        if (wide) launch_down_t<4, 1, 8, 1, 3, 2>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
+        else if (one_per_cu) launch_down_t<4, 1, 16, 1, 2, 2>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
+        else launch_down_t<4, 1, 4, 2, 2, 2>(L, P, T, item_start, group_off, mask, offsets, H, y, max_pairs_sparse, s);
+    }
+    else if (dp.KSP == 2 && dp.G == 4) DMOE_DOWN_BY_GRID(2, 4, 8, 8, 4);
     else if (dp.KSP == 2 && dp.G == 2) DMOE_DOWN_BY_GRID(2, 2, 8, 8, 4);
     else if (dp.KSP == 2) DMOE_DOWN_BY_GRID(2, 1, 8, 8, 4);
     else if (dp.KSP == 3 && dp.G == 2) DMOE_DOWN_BY_GRID(3, 2, 12, 12, 4);

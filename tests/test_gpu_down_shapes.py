@@ -32,12 +32,14 @@ def _cfg(T, d, E, m, gated):
 
 # one narrow workgroup per CU (few tokens): every k-step packing, plain and gated; expert counts
 # from 1 up, not multiples of the 32-expert mask batch or of the 4-stage loop trip, and beyond
-# several batches
+# several batches (an expert of exactly 128 neurons is walked as two units of 64: two stages and
+# one mask bit per expert)
 ONE_PER_CU = [(300, 256, 20, m, False) for m in (8, 16, 24, 32, 40, 48, 64, 72, 96, 100, 128)] + \
              [(300, 256, 37, m, True) for m in (16, 32, 48, 64)] + \
              [(200, 256, 70, 24, False)] + \
              [(200, 256, E, 24, False) for E in (1, 3, 5, 33, 65, 130, 300)] + \
              [(200, 256, E, 64, False) for E in (1, 33, 100)] + \
+             [(200, 256, E, 128, False) for E in (1, 3, 17, 33, 70)] + \
              [(128, 256, 2048, 8, False), (96, 512, 4096, 16, True)] + \
              [(300, 256, 37, m, True) for m in (1, 3, 5, 8)] + \
              [(1000, 512, 600, 8, True)]
